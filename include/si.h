@@ -1,0 +1,193 @@
+/*
+ * si.h -- C ABI of the Streamlined-Inference hot path on MI355X (gfx950).
+ *
+ * Two operations of "Fast and Memory-Efficient Video Diffusion Using
+ * Streamlined Inference" (arXiv 2411.01171):
+ *
+ *   - the Feature Slicer + Operator Grouping forward of one video-UNet
+ *     transformer block (Sec. 4.1, Sec. 4.2.1, Eq. 1): the input feature is cut
+ *     into windows along an axis the block's operators do not mix, every window
+ *     runs through the whole operator group, and its result lands in place in
+ *     a preallocated output, so that live intermediates are those of one slice;
+ *   - Step Rehash's reuse-or-recompute test (Sec. 4.3, Appendix B): the
+ *     similarity of a feature with its cached counterpart against a threshold,
+ *     and the key-step search of Algorithm 1 over a similarity map.
+ *
+ * Conventions common to all entry points
+ *   - Every pointer named *device* is GPU memory owned by the caller; the
+ *     library never allocates or frees device memory.  Pointers named *host*
+ *     are ordinary process memory.  Descriptor structs themselves live in host
+ *     memory and are read before the call returns.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the call returns without waiting, unless stated.
+ *   - Errors are returned as si_status; nothing aborts or throws.  All
+ *     argument validation happens before the first GPU call, so every error
+ *     other than SI_ERR_HIP can be provoked on a machine without a GPU.
+ *   - Device base pointers must be 16-byte aligned.
+ */
+#ifndef SI_H_
+#define SI_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SI_OK = 0,
+  SI_ERR_NULL = 1,      /* a required pointer is NULL */
+  SI_ERR_SHAPE = 2,     /* inconsistent or unsupported sizes */
+  SI_ERR_DTYPE = 3,     /* unknown or mismatching element types */
+  SI_ERR_SLICE = 4,     /* slice axis illegal for the block kind, or slice_len < 1 */
+  SI_ERR_ALIGN = 5,     /* a device pointer is not 16-byte aligned */
+  SI_ERR_WORKSPACE = 6, /* workspace / scratch too small */
+  SI_ERR_ARG = 7,       /* other invalid argument (aliasing, NaN threshold, ...) */
+  SI_ERR_HIP = 8        /* a HIP runtime call or kernel launch failed */
+} si_status;
+
+typedef enum { SI_F32 = 0, SI_BF16 = 1 } si_dtype;
+
+/* Temporal blocks attend over the F frames of one spatial position; spatial
+ * blocks attend over the H*W positions of one frame and cross-attend to the
+ * context tokens (Sec. 3, "temporal layers ... after every spatial layer"). */
+typedef enum { SI_BLOCK_TEMPORAL = 0, SI_BLOCK_SPATIAL = 1 } si_block_kind;
+
+/* Slice axis (Sec. 4.1).  SI_AXIS_F: windows of frames, legal for spatial
+ * blocks only (the spatial-layer slicer; both batch entries of a frame index
+ * travel together).  SI_AXIS_HW: windows of flattened positions p = h*W + w,
+ * legal for temporal blocks only (the temporal-layer slicer never cuts the
+ * frame axis, because that would change the result). */
+typedef enum { SI_AXIS_F = 2, SI_AXIS_HW = 3 } si_axis;
+
+/* Contiguous 5-D feature [B, C, F, H, W] in device memory (W fastest). */
+typedef struct {
+  void* ptr;      /* device */
+  int32_t dtype;  /* si_dtype */
+  int64_t B, C, F, H, W;
+} si_tensor5;
+
+/* Contiguous context tokens [B, M, Cc] in device memory; spatial blocks only.
+ * The same context row block serves every frame of batch entry b. */
+typedef struct {
+  const void* ptr; /* device */
+  int32_t dtype;   /* si_dtype, must equal the feature's */
+  int64_t B, M, Cc;
+} si_context;
+
+/* Parameters of one block.  All pointers are device memory in the feature's
+ * element type, read-only.  Matrices are row-major [in, out]; D = heads *
+ * dim_head is the inner width.  A NULL bias means zero; a NULL norm gain means
+ * one and a NULL norm shift means zero.
+ *
+ *   GroupNorm(gn_groups, gn_eps; gn_g, gn_b [C]) per (batch, frame, group)
+ *   h  = tokens w_in [C,D] + b_in [D]
+ *   h += Attn(LN(h; ln1_g, ln1_b) (+ frame embedding if add_sin_pe)) wo [D,D] + bo [D]
+ *        with q,k,v = a wq, a wk, a wv ([D,D] each, no bias), scale 1/sqrt(dim_head)
+ *   spatial only:
+ *   h += Attn(q = LN(h; ln2_g, ln2_b) wq2 [D,D]; k,v = ctx wk2, ctx wv2 [Cc,D]) wo2 [D,D] + bo2 [D]
+ *   u  = LN(h; ln3_g, ln3_b) w1 [D,8D] + b1 [8D];  h += (u[:4D] * gelu_erf(u[4D:])) w2 [4D,D] + b2 [D]
+ *   out = x + h w_out [D,C] + b_out [C]
+ *
+ * The frame embedding is the sinusoidal table PE[f,2i] = sin(f/10000^(2i/D)),
+ * PE[f,2i+1] = cos(f/10000^(2i/D)), f = 0..F-1, and applies to temporal
+ * blocks only. */
+typedef struct {
+  int32_t kind; /* si_block_kind */
+  int32_t heads, dim_head, gn_groups;
+  float gn_eps, ln_eps;
+  int32_t add_sin_pe;
+  const void *gn_g, *gn_b, *w_in, *b_in;
+  const void *ln1_g, *ln1_b, *wq, *wk, *wv, *wo, *bo;
+  const void *ln2_g, *ln2_b, *wq2, *wk2, *wv2, *wo2, *bo2; /* spatial only, else ignored */
+  const void *ln3_g, *ln3_b, *w1, *b1, *w2, *b2;
+  const void *w_out, *b_out;
+} si_block_weights;
+
+/* Bytes of device workspace si_block_forward needs for these arguments: the
+ * intermediates of ONE slice (Sec. 4.2.1, "only ... a single sliced
+ * sub-feature") plus slice-independent items (GroupNorm statistics, the
+ * re-laid-out weights, the context keys/values).  `ctx` may be NULL for
+ * temporal blocks.  Returns 0 if the arguments are invalid (the same checks
+ * as si_block_forward, pointers excepted).  Host-only; touches no GPU. */
+size_t si_workspace_bytes(const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
+                          int32_t axis, int64_t slice_len);
+
+/* Of si_workspace_bytes, the part that holds activation-derived data (slice
+ * intermediates, GroupNorm statistics, context keys/values); the remainder is
+ * re-laid-out weights.  Same arguments, same validity rule. */
+size_t si_live_activation_bytes(const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
+                                int32_t axis, int64_t slice_len);
+
+/* Sliced block forward (Sec. 4.1, 4.2.1, Eq. 1).
+ *
+ *   x, out     [B,C,F,H,W], same shape and dtype; `out` must not overlap `x`
+ *              (x is re-read for the residual).  Every element of out is written.
+ *   w          block parameters (see si_block_weights); ctx: context or NULL.
+ *   axis       si_axis; slice_len >= 1 in units of that axis.  Window i covers
+ *              [i*slice_len, min((i+1)*slice_len, extent)); the last may be
+ *              ragged.  slice_len >= extent runs the block unsliced.
+ *   workspace  device memory of at least si_workspace_bytes(...) bytes, 256-byte
+ *              aligned; contents on entry are ignored and on exit unspecified.
+ *
+ * GroupNorm statistics are taken per (batch, frame, group) over the whole
+ * H*W extent before the first slice; they are the only quantity that crosses
+ * position windows.  Supported: C and D multiples of 8, dim_head a multiple
+ * of 8 and <= 128, C divisible by gn_groups, H*W*F*B*C < 2^40.
+ * Returns SI_ERR_* on invalid arguments (nothing enqueued) or SI_ERR_HIP. */
+si_status si_block_forward(const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
+                           si_tensor5* out, int32_t axis, int64_t slice_len,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Scratch bytes si_rehash_check needs for n elements (partial sums). */
+size_t si_rehash_scratch_bytes(int64_t n);
+
+/* Step Rehash similarity test (Sec. 4.3.1, Appendix B: "S_ij >= gamma").
+ *
+ * Computes cos = <a,b> / (|a||b|) over the n elements of feat_t and feat_prev
+ * (device, dtype `dtype`, any shape flattened) with float64 accumulation in a
+ * fixed order, and decision = 1 (reuse the cached feature) if cos >= thresh,
+ * else 0 (recompute).  The decision is taken as dot >= thresh*sqrt(na*nb) in
+ * float64.  Both inputs all-zero: cos = 1; exactly one all-zero: cos = 0; a
+ * non-finite sum: cos = NaN, decision 0.
+ *
+ *   cos_dev       device double*, may be NULL
+ *   decision_dev  device int32_t*, required
+ *   scratch       device, >= si_rehash_scratch_bytes(n), 16-byte aligned
+ * n == 0 is legal (both all-zero).  thresh NaN -> SI_ERR_ARG. */
+si_status si_rehash_check(const void* feat_t, const void* feat_prev, int64_t n, int32_t dtype,
+                          float thresh, double* cos_dev, int32_t* decision_dev,
+                          void* scratch, void* stream);
+
+/* As si_rehash_check, then waits for `stream` and returns the results in host
+ * memory.  result_dev: device memory of at least 16 bytes (holds cos, decision). */
+si_status si_rehash_check_sync(const void* feat_t, const void* feat_prev, int64_t n, int32_t dtype,
+                               float thresh, void* scratch, void* result_dev, void* stream,
+                               double* cos_host, int32_t* decision_host);
+
+/* Key-step search, Algorithm 1 (Appendix B).  Host only.
+ *   S      host, row-major K x K similarity map; only S[i][anchor] entries are read
+ *   gamma  threshold, must satisfy gamma <= 1 and gamma <= S[i][i] where visited
+ *   G_out  host, capacity K; receives the key steps in ascending order, no duplicates
+ * Returns |G| (>= 1), or -1 on invalid arguments (K < 1, NULL, gamma NaN or > 1,
+ * a visited diagonal entry below gamma). */
+int32_t si_key_step_search(const float* S, int32_t K, float gamma, int32_t* G_out);
+
+/* Optional per-stage timing for measurement.  When enabled, si_block_forward
+ * and si_rehash_check record a HIP event pair around every kernel launch on
+ * the caller's stream (this serialises nothing but adds event overhead).
+ * si_stage_timing_read waits for the recorded events, adds each pair's
+ * duration to its stage, writes up to `cap` entries (stage name, total
+ * milliseconds, launches) and clears the record.  Returns the number of stages,
+ * or -1 on a HIP error.  Not thread-safe; host pointers. */
+void si_stage_timing_enable(int32_t on);
+int32_t si_stage_timing_read(const char** names, double* total_ms, int64_t* launches, int32_t cap);
+
+const char* si_status_str(int32_t status);
+int32_t si_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SI_H_ */

@@ -1,0 +1,13 @@
+"""Streamlined-Inference hot path on MI355X: Python binding of the C-ABI library.
+
+Argument marshalling only; every step of the path runs in the HIP kernels of
+libsi.so.  There is no CPU fallback: if the library is missing, importing the
+binding's entry points raises.
+"""
+from .binding import (  # noqa: F401
+    SI_F32, SI_BF16, SI_BLOCK_TEMPORAL, SI_BLOCK_SPATIAL, SI_AXIS_F, SI_AXIS_HW,
+    SiError, lib, library_path, BlockWeights,
+    si_workspace_bytes, si_live_activation_bytes, si_block_forward,
+    si_rehash_scratch_bytes, si_rehash_check, si_rehash_check_sync, si_key_step_search,
+    si_stage_timing_enable, si_stage_timing_read, si_status_str, si_abi_version,
+)

@@ -1,0 +1,205 @@
+// Normalisation and layout kernels of the staged (general-shape) path:
+//   gn_stats_kernel        GroupNorm statistics per (batch, frame, group)     [HBM bound]
+//   window_to_tokens_kernel  slice window -> GroupNorm -> token-major rows     [HBM bound]
+//   layer_norm_kernel      row LayerNorm (+ frame embedding), fp32 -> T        [HBM/L2 bound]
+//   pe_table_kernel        sinusoidal frame embedding table
+//   pack_transpose_kernel  [in,out] weight -> [out,in] (k-contiguous) layout
+#pragma once
+#include "si_common.h"
+
+namespace si {
+
+// One block per (b, f, g).  Reduces the n_g * P values x[b, g*n_g:(g+1)*n_g, f, :].
+// Sums are taken relative to the group's first element so that a large common
+// offset does not cancel in fp32; per-thread fp32 partials are merged in fp64.
+// stats[((b*F + f)*G + g)*2 + {0,1}] = {mean, 1/sqrt(var + eps)}.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void gn_stats_kernel(const T* __restrict__ x, float* __restrict__ stats,
+                                                       int C, int F, int64_t P, int G, float eps) {
+  const int g = blockIdx.x % G;
+  const int f = (blockIdx.x / G) % F;
+  const int b = blockIdx.x / (G * F);
+  const int ng = C / G;
+  const int pv = (int)(P / VEC);  // vectors per channel row (VEC divides P; ng*P < 2^31 is checked by the host)
+  const int total = ng * pv;
+  const T* base = x + (((int64_t)b * C + (int64_t)g * ng) * F + f) * P;
+  const int64_t cstride = (int64_t)F * P;
+  const float shift = to_float(base[0]);
+
+  float s1 = 0.f, s2 = 0.f;
+  for (int e = threadIdx.x; e < total; e += blockDim.x) {
+    const int c = e / pv, v = e - c * pv;
+    const T* p = base + c * cstride + (int64_t)v * VEC;
+    if constexpr (VEC == 1) {
+      const float d = to_float(p[0]) - shift;
+      s1 += d;
+      s2 += d * d;
+    } else if constexpr (sizeof(T) == 2) {  // 8 x bf16 = 16 bytes
+      const uint4 raw = *reinterpret_cast<const uint4*>(p);
+      const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float d0 = __uint_as_float(w[i] << 16) - shift;
+        const float d1 = __uint_as_float(w[i] & 0xffff0000u) - shift;
+        s1 += d0 + d1;
+        s2 += d0 * d0 + d1 * d1;
+      }
+    } else {  // 4 x f32 = 16 bytes
+      const float4 raw = *reinterpret_cast<const float4*>(p);
+      const float d0 = raw.x - shift, d1 = raw.y - shift, d2 = raw.z - shift, d3 = raw.w - shift;
+      s1 += (d0 + d1) + (d2 + d3);
+      s2 += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+    }
+  }
+  double a1 = wave_sum((double)s1), a2 = wave_sum((double)s2);
+  __shared__ double sh[2][4];
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  if (lane == 0) {
+    sh[0][wave] = a1;
+    sh[1][wave] = a2;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const double n = (double)ng * (double)P;
+    const double m1 = (sh[0][0] + sh[0][1] + sh[0][2] + sh[0][3]) / n;
+    const double m2 = (sh[1][0] + sh[1][1] + sh[1][2] + sh[1][3]) / n;
+    double var = m2 - m1 * m1;
+    if (var < 0.0) var = 0.0;
+    stats[(int64_t)blockIdx.x * 2 + 0] = (float)((double)shift + m1);
+    stats[(int64_t)blockIdx.x * 2 + 1] = (float)(1.0 / sqrt(var + (double)eps));
+  }
+}
+
+// Geometry of one slice window and of the token order used inside a slice:
+// token m = (b*Fw + (f - f0))*Pw + (p - p0).
+struct Window {
+  int B, C, F;   // full tensor
+  int64_t P;     // H*W
+  int f0, Fw;    // frame window
+  int64_t p0;    // first position
+  int Pw;        // positions in the window
+  int G;         // GroupNorm groups
+};
+
+// Slice-in: a0[m, c] = GN(x)[b, c, f, p] for the window's tokens.  64 x 64
+// (position x channel) tiles are transposed through LDS so that both the read
+// (along positions) and the write (along channels) are contiguous.
+template <typename T>
+__global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restrict__ x, const float* __restrict__ stats,
+                                                               const T* __restrict__ gamma, const T* __restrict__ beta,
+                                                               T* __restrict__ a0, Window w) {
+  __shared__ float tile[64][65];
+  const int bf = blockIdx.z;  // b*Fw + fl
+  const int b = bf / w.Fw, fl = bf % w.Fw, f = w.f0 + fl;
+  const int pt = blockIdx.x * 64, ct = blockIdx.y * 64;
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+  const int ng = w.C / w.G;
+#pragma unroll 4
+  for (int cl = ty; cl < 64; cl += 4) {
+    const int c = ct + cl, pl = pt + tx;
+    float v = 0.f;
+    if (c < w.C && pl < w.Pw) {
+      const int g = c / ng;
+      const float mean = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 0];
+      const float rstd = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 1];
+      const float xv = to_float(x[(((int64_t)b * w.C + c) * w.F + f) * w.P + w.p0 + pl]);
+      v = (xv - mean) * rstd * param_or(gamma, c, 1.f) + param_or(beta, c, 0.f);
+    }
+    tile[cl][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll 4
+  for (int pl = ty; pl < 64; pl += 4) {
+    const int c = ct + tx, p = pt + pl;
+    if (c < w.C && p < w.Pw) {
+      const int64_t m = (int64_t)bf * w.Pw + p;
+      a0[m * w.C + c] = from_float<T>(tile[tx][pl]);
+    }
+  }
+}
+
+// PE[f, 2i] = sin(f / 10000^(2i/D)), PE[f, 2i+1] = cos(same), evaluated in fp64.
+__global__ void pe_table_kernel(float* __restrict__ pe, int F, int D) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= F * D) return;
+  const int f = idx / D, i = idx % D;
+  const int even = i - (i & 1);
+  const double angle = (double)f / pow(10000.0, (double)even / (double)D);
+  pe[idx] = (float)((i & 1) ? cos(angle) : sin(angle));
+}
+
+// Row LayerNorm of the fp32 residual stream; one wavefront per row, the row is
+// held in registers (D <= 2048, D % 4 == 0).  Optional frame embedding: row m
+// belongs to frame f0 + (m / Pw) % Fw.
+template <typename T>
+__global__ __launch_bounds__(256) void layer_norm_kernel(const float* __restrict__ h, T* __restrict__ a, int64_t M, int D,
+                                                         const T* __restrict__ gamma, const T* __restrict__ beta, float eps,
+                                                         const float* __restrict__ pe, int Pw, int Fw, int f0) {
+  const int lane = threadIdx.x % kWave;
+  const int64_t m = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (m >= M) return;
+  const float4* row = reinterpret_cast<const float4*>(h + m * D);
+  const int nv = D / 4;
+  float4 r[8];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int v = lane + i * kWave;
+    if (v < nv) {
+      r[i] = row[v];
+      s += (r[i].x + r[i].y) + (r[i].z + r[i].w);
+    }
+  }
+  const float mean = wave_sum(s) / (float)D;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int v = lane + i * kWave;
+    if (v < nv) {
+      const float dx = r[i].x - mean, dy = r[i].y - mean, dz = r[i].z - mean, dw = r[i].w - mean;
+      q += (dx * dx + dy * dy) + (dz * dz + dw * dw);
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(q) / (float)D + eps);
+  const float* perow = nullptr;
+  if (pe) perow = pe + (int64_t)(f0 + (int)((m / Pw) % Fw)) * D;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int v = lane + i * kWave;
+    if (v < nv) {
+      const float in[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int c = v * 4 + e;
+        float y = (in[e] - mean) * rstd * param_or(gamma, c, 1.f) + param_or(beta, c, 0.f);
+        if (perow) y += perow[c];
+        a[m * D + c] = from_float<T>(y);
+      }
+    }
+  }
+}
+
+// dst[r * K + k] = src[k * ld_src + col(r)] for r in [0, rows): the k-contiguous
+// layout the GEMM kernels read.  col(r) = col0 + r, or, with `interleave` > 0
+// (GEGLU projection), even r -> value column r/2, odd r -> gate column interleave + r/2.
+template <typename T>
+__global__ __launch_bounds__(256) void pack_transpose_kernel(const T* __restrict__ src, T* __restrict__ dst, int K, int ld_src,
+                                                             int rows, int col0, int interleave) {
+  __shared__ T tile[32][33];
+  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
+  const int r0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+  for (int kk = ty; kk < 32; kk += 8) {
+    const int r = r0 + tx, k = k0 + kk;
+    if (r < rows && k < K) {
+      const int col = interleave > 0 ? ((r & 1) ? interleave + (r >> 1) : (r >> 1)) : col0 + r;
+      tile[kk][tx] = src[(int64_t)k * ld_src + col];
+    }
+  }
+  __syncthreads();
+  for (int rr = ty; rr < 32; rr += 8) {
+    const int r = r0 + rr, k = k0 + tx;
+    if (r < rows && k < K) dst[(int64_t)r * K + k] = tile[tx][rr];
+  }
+}
+
+}  // namespace si

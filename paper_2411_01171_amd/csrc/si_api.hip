@@ -1,0 +1,547 @@
+// C ABI of the Streamlined-Inference hot path (see include/si.h): argument
+// validation, workspace layout, the host slice loop (Feature Slicer windows,
+// Sec. 4.1; one operator group per window, Sec. 4.2.1) and kernel launches.
+#include "../../include/si.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "k_attn.h"
+#include "k_cosine.h"
+#include "k_gemm.h"
+#include "k_norm.h"
+#include "si_common.h"
+
+namespace si {
+
+// ----------------------------------------------------------------------------- stage timing
+
+struct StageEvent {
+  int stage;
+  hipEvent_t a, b;
+};
+static bool g_timing = false;
+static std::vector<std::string> g_stage_names;
+static std::vector<StageEvent> g_events;
+
+static int stage_id(const char* name) {
+  for (size_t i = 0; i < g_stage_names.size(); ++i)
+    if (g_stage_names[i] == name) return (int)i;
+  g_stage_names.emplace_back(name);
+  return (int)g_stage_names.size() - 1;
+}
+
+struct StageScope {
+  hipStream_t st;
+  StageEvent ev;
+  bool on;
+  StageScope(const char* name, hipStream_t s) : st(s), on(g_timing) {
+    if (!on) return;
+    ev.stage = stage_id(name);
+    if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) {
+      on = false;
+      return;
+    }
+    (void)hipEventRecord(ev.a, st);
+  }
+  ~StageScope() {
+    if (!on) return;
+    (void)hipEventRecord(ev.b, st);
+    g_events.push_back(ev);
+  }
+};
+
+// ----------------------------------------------------------------------------- plan
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Plan {
+  int kind, dtype, esize;
+  int B, C, F, H, W, G, heads, d, D;
+  int64_t P;
+  int Mc, Cc;    // context tokens / width (spatial)
+  int axis;
+  int64_t extent, slice_len;
+  int64_t Mmax;  // tokens of the largest window
+  bool pe;
+  // workspace offsets (bytes)
+  size_t off_stats, off_pe, off_ctxkv;
+  size_t off_w_in, off_wqkv, off_wo, off_wq2, off_wkv2, off_wo2, off_w1, off_w2, off_w_out;
+  size_t off_a, off_h, off_big;
+  size_t weights_bytes, total_bytes;
+};
+
+static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, int32_t axis,
+                           int64_t slice_len, Plan* p) {
+  if (!x || !w) return SI_ERR_NULL;
+  if (x->dtype != SI_F32 && x->dtype != SI_BF16) return SI_ERR_DTYPE;
+  if (w->kind != SI_BLOCK_TEMPORAL && w->kind != SI_BLOCK_SPATIAL) return SI_ERR_ARG;
+  if (x->B < 1 || x->C < 1 || x->F < 1 || x->H < 1 || x->W < 1) return SI_ERR_SHAPE;
+  if (w->heads < 1 || w->dim_head < 8 || w->dim_head > 128 || w->dim_head % 8) return SI_ERR_SHAPE;
+  if (w->gn_groups < 1 || x->C % w->gn_groups || x->C % 8) return SI_ERR_SHAPE;
+  const int64_t D = (int64_t)w->heads * w->dim_head;
+  if (D > 2048 || x->C > 8192) return SI_ERR_SHAPE;
+  const int64_t P = x->H * x->W;
+  if (x->B > 65535 || x->F > 65535 || P > (1 << 24)) return SI_ERR_SHAPE;
+  if ((double)x->B * x->C * x->F * (double)P >= 1099511627776.0) return SI_ERR_SHAPE;
+  if ((int64_t)(x->C / w->gn_groups) * P >= (1LL << 31)) return SI_ERR_SHAPE;
+  if (!(w->gn_eps >= 0.f) || !(w->ln_eps >= 0.f)) return SI_ERR_ARG;
+  p->kind = w->kind;
+  p->dtype = x->dtype;
+  p->esize = x->dtype == SI_F32 ? 4 : 2;
+  p->B = (int)x->B; p->C = (int)x->C; p->F = (int)x->F; p->H = (int)x->H; p->W = (int)x->W;
+  p->P = P; p->G = w->gn_groups; p->heads = w->heads; p->d = w->dim_head; p->D = (int)D;
+  p->Mc = 0; p->Cc = 0;
+  if (w->kind == SI_BLOCK_SPATIAL) {
+    if (!ctx) return SI_ERR_NULL;
+    if (ctx->dtype != x->dtype) return SI_ERR_DTYPE;
+    if (ctx->B != x->B || ctx->M < 1 || ctx->M > 65535 || ctx->Cc < 1 || ctx->Cc > 65536) return SI_ERR_SHAPE;
+    if (ctx->Cc % 8) return SI_ERR_SHAPE;
+    if (w->add_sin_pe) return SI_ERR_ARG;
+    p->Mc = (int)ctx->M;
+    p->Cc = (int)ctx->Cc;
+  }
+  p->pe = w->kind == SI_BLOCK_TEMPORAL && w->add_sin_pe != 0;
+  if (axis != SI_AXIS_F && axis != SI_AXIS_HW) return SI_ERR_SLICE;
+  if ((axis == SI_AXIS_F) != (w->kind == SI_BLOCK_SPATIAL)) return SI_ERR_SLICE;
+  if (slice_len < 1) return SI_ERR_SLICE;
+  p->axis = axis;
+  p->extent = axis == SI_AXIS_F ? x->F : P;
+  p->slice_len = slice_len < p->extent ? slice_len : p->extent;
+  p->Mmax = axis == SI_AXIS_F ? (int64_t)x->B * p->slice_len * P : (int64_t)x->B * x->F * p->slice_len;
+  if (p->Mmax >= (1LL << 31) / 16) return SI_ERR_SHAPE;
+
+  const size_t es = (size_t)p->esize;
+  const size_t C = (size_t)p->C, Dz = (size_t)D;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  // slice-independent activation-derived items
+  p->off_stats = take((size_t)p->B * p->F * p->G * 2 * sizeof(float));
+  p->off_pe = take(p->pe ? (size_t)p->F * Dz * sizeof(float) : 0);
+  p->off_ctxkv = take((size_t)p->B * p->Mc * 2 * Dz * es);
+  // one slice's intermediates
+  p->off_a = take((size_t)p->Mmax * (C > Dz ? C : Dz) * es);
+  p->off_h = take((size_t)p->Mmax * Dz * sizeof(float));
+  p->off_big = take((size_t)p->Mmax * 4 * Dz * es);
+  const size_t act_end = off;
+  // re-laid-out weights
+  p->off_w_in = take(Dz * C * es);
+  p->off_wqkv = take(3 * Dz * Dz * es);
+  p->off_wo = take(Dz * Dz * es);
+  const bool sp = p->kind == SI_BLOCK_SPATIAL;
+  p->off_wq2 = take(sp ? Dz * Dz * es : 0);
+  p->off_wkv2 = take(sp ? 2 * Dz * (size_t)p->Cc * es : 0);
+  p->off_wo2 = take(sp ? Dz * Dz * es : 0);
+  p->off_w1 = take(8 * Dz * Dz * es);
+  p->off_w2 = take(4 * Dz * Dz * es);
+  p->off_w_out = take(C * Dz * es);
+  p->weights_bytes = off - act_end;
+  p->total_bytes = off;
+  return SI_OK;
+}
+
+// ----------------------------------------------------------------------------- launches
+
+#define SI_CHECK_LAUNCH()                         \
+  do {                                            \
+    if (hipGetLastError() != hipSuccess) return SI_ERR_HIP; \
+  } while (0)
+
+template <typename T, class Epi>
+static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T* Wp, int64_t M, int N, int K, Epi epi,
+                             hipStream_t st) {
+  if (M <= 0) return SI_OK;
+  StageScope scope(stage, st);
+  if constexpr (sizeof(T) == 4) {
+    dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 63) / 64));
+    gemm_f32_kernel<Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+  } else {
+    if (N % 128 == 0) {
+      dim3 grid((unsigned)((M + 127) / 128), (unsigned)(N / 128));
+      gemm_bf16_kernel<128, 128, 2, 2, Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+    } else {
+      dim3 grid((unsigned)((M + 127) / 128), (unsigned)((N + 63) / 64));
+      gemm_bf16_kernel<128, 64, 4, 1, Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+    }
+  }
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+
+template <typename T>
+static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, int col0, int interleave, hipStream_t st) {
+  dim3 grid((unsigned)((rows + 31) / 32), (unsigned)((K + 31) / 32));
+  pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, dst, K, ld_src, rows, col0, interleave);
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+
+template <typename T>
+static si_status launch_attention(const char* stage, const AttnArgs& a, hipStream_t st) {
+  if (a.S <= 0 || a.Nq <= 0) return SI_OK;
+  StageScope scope(stage, st);
+  constexpr int QB = 4;
+  dim3 grid((unsigned)((a.Nq + 4 * QB - 1) / (4 * QB)), (unsigned)a.heads, (unsigned)a.S);
+  attn_valu_kernel<T, QB><<<grid, 256, 0, st>>>(a);
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+
+template <typename T>
+static si_status launch_layer_norm(const char* stage, const float* h, T* a, int64_t M, int D, const void* g, const void* b,
+                                   float eps, const float* pe, int Pw, int Fw, int f0, hipStream_t st) {
+  StageScope scope(stage, st);
+  layer_norm_kernel<T><<<(unsigned)((M + 3) / 4), 256, 0, st>>>(h, a, M, D, static_cast<const T*>(g), static_cast<const T*>(b),
+                                                                   eps, pe, Pw, Fw, f0);
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+
+#define SI_TRY(expr)                  \
+  do {                                \
+    si_status st__ = (expr);          \
+    if (st__ != SI_OK) return st__;   \
+  } while (0)
+
+template <typename T>
+static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
+                           si_tensor5* out, char* ws, hipStream_t st) {
+  const T* X = static_cast<const T*>(x->ptr);
+  T* OUT = static_cast<T*>(out->ptr);
+  float* stats = reinterpret_cast<float*>(ws + p.off_stats);
+  float* pe = p.pe ? reinterpret_cast<float*>(ws + p.off_pe) : nullptr;
+  T* ctxkv = reinterpret_cast<T*>(ws + p.off_ctxkv);
+  T* a = reinterpret_cast<T*>(ws + p.off_a);
+  float* h = reinterpret_cast<float*>(ws + p.off_h);
+  T* big = reinterpret_cast<T*>(ws + p.off_big);
+  T* w_in = reinterpret_cast<T*>(ws + p.off_w_in);
+  T* wqkv = reinterpret_cast<T*>(ws + p.off_wqkv);
+  T* wo = reinterpret_cast<T*>(ws + p.off_wo);
+  T* wq2 = reinterpret_cast<T*>(ws + p.off_wq2);
+  T* wkv2 = reinterpret_cast<T*>(ws + p.off_wkv2);
+  T* wo2 = reinterpret_cast<T*>(ws + p.off_wo2);
+  T* w1 = reinterpret_cast<T*>(ws + p.off_w1);
+  T* w2 = reinterpret_cast<T*>(ws + p.off_w2);
+  T* w_out = reinterpret_cast<T*>(ws + p.off_w_out);
+  const int C = p.C, D = p.D;
+  const bool spatial = p.kind == SI_BLOCK_SPATIAL;
+  auto cT = [](const void* q) { return static_cast<const T*>(q); };
+
+  // ---- once per call: weight re-layout, frame embedding table, GroupNorm statistics, context K/V
+  {
+    StageScope scope("pack_weights", st);
+    SI_TRY(launch_pack<T>(cT(w->w_in), w_in, C, D, D, 0, 0, st));
+    SI_TRY(launch_pack<T>(cT(w->wq), wqkv, D, D, D, 0, 0, st));
+    SI_TRY(launch_pack<T>(cT(w->wk), wqkv + (size_t)D * D, D, D, D, 0, 0, st));
+    SI_TRY(launch_pack<T>(cT(w->wv), wqkv + (size_t)2 * D * D, D, D, D, 0, 0, st));
+    SI_TRY(launch_pack<T>(cT(w->wo), wo, D, D, D, 0, 0, st));
+    if (spatial) {
+      SI_TRY(launch_pack<T>(cT(w->wq2), wq2, D, D, D, 0, 0, st));
+      SI_TRY(launch_pack<T>(cT(w->wk2), wkv2, p.Cc, D, D, 0, 0, st));
+      SI_TRY(launch_pack<T>(cT(w->wv2), wkv2 + (size_t)D * p.Cc, p.Cc, D, D, 0, 0, st));
+      SI_TRY(launch_pack<T>(cT(w->wo2), wo2, D, D, D, 0, 0, st));
+    }
+    SI_TRY(launch_pack<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 0, 4 * D, st));
+    SI_TRY(launch_pack<T>(cT(w->w2), w2, 4 * D, D, D, 0, 0, st));
+    SI_TRY(launch_pack<T>(cT(w->w_out), w_out, D, C, C, 0, 0, st));
+    if (pe) {
+      pe_table_kernel<<<(p.F * D + 255) / 256, 256, 0, st>>>(pe, p.F, D);
+      SI_CHECK_LAUNCH();
+    }
+  }
+  {
+    StageScope scope("gn_stats", st);
+    constexpr int VEC = 16 / sizeof(T);
+    const unsigned blocks = (unsigned)(p.B * p.F * p.G);
+    if (p.P % VEC == 0)
+      gn_stats_kernel<T, VEC><<<blocks, 256, 0, st>>>(X, stats, C, p.F, p.P, p.G, w->gn_eps);
+    else
+      gn_stats_kernel<T, 1><<<blocks, 256, 0, st>>>(X, stats, C, p.F, p.P, p.G, w->gn_eps);
+    SI_CHECK_LAUNCH();
+  }
+  if (spatial) {
+    EpiStore<T> epi{ctxkv, (int64_t)2 * D, nullptr};
+    SI_TRY(launch_gemm<T>("ctx_kv", cT(ctx->ptr), (int64_t)p.Cc, wkv2, (int64_t)p.B * p.Mc, 2 * D, p.Cc, epi, st));
+  }
+
+  // ---- Feature Slicer windows; one operator group per window (Eq. 1)
+  const float scale = 1.0f / sqrtf((float)p.d);
+  for (int64_t s0 = 0; s0 < p.extent; s0 += p.slice_len) {
+    const int64_t s1 = s0 + p.slice_len < p.extent ? s0 + p.slice_len : p.extent;
+    Window win;
+    win.B = p.B; win.C = C; win.F = p.F; win.P = p.P; win.G = p.G;
+    if (p.axis == SI_AXIS_F) {
+      win.f0 = (int)s0; win.Fw = (int)(s1 - s0); win.p0 = 0; win.Pw = (int)p.P;
+    } else {
+      win.f0 = 0; win.Fw = p.F; win.p0 = s0; win.Pw = (int)(s1 - s0);
+    }
+    const int64_t M = (int64_t)p.B * win.Fw * win.Pw;
+
+    {  // slice-in: window -> GroupNorm -> token rows
+      StageScope scope("slice_in", st);
+      dim3 grid((unsigned)((win.Pw + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * win.Fw));
+      window_to_tokens_kernel<T><<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
+      SI_CHECK_LAUNCH();
+    }
+    {
+      EpiResidual<T> epi{h, (int64_t)D, cT(w->b_in), 0, nullptr};
+      SI_TRY(launch_gemm<T>("proj_in", a, (int64_t)C, w_in, M, D, C, epi, st));
+    }
+    SI_TRY(launch_layer_norm<T>("ln1", h, a, M, D, w->ln1_g, w->ln1_b, w->ln_eps, pe, win.Pw, win.Fw, win.f0, st));
+    {
+      EpiStore<T> epi{big, (int64_t)3 * D, nullptr};
+      SI_TRY(launch_gemm<T>("qkv", a, (int64_t)D, wqkv, M, 3 * D, D, epi, st));
+    }
+    {
+      AttnArgs at;
+      at.q = big; at.k = big + D; at.v = big + 2 * D; at.o = a;
+      at.ldq = at.ldk = at.ldv = (int64_t)3 * D; at.ldo = D;
+      at.heads = p.heads; at.d = p.d; at.scale = scale;
+      if (spatial) {
+        at.S = p.B * win.Fw; at.Nq = at.Nk = win.Pw;
+        at.qmap = SeqMap{1, (int64_t)win.Pw, 0, 1};
+      } else {
+        at.S = p.B * win.Pw; at.Nq = at.Nk = p.F;
+        at.qmap = SeqMap{win.Pw, (int64_t)p.F * win.Pw, 1, (int64_t)win.Pw};
+      }
+      at.kmap = at.qmap;
+      SI_TRY(launch_attention<T>("self_attn", at, st));
+    }
+    {
+      EpiResidual<T> epi{h, (int64_t)D, cT(w->bo), 1, nullptr};
+      SI_TRY(launch_gemm<T>("attn_out", a, (int64_t)D, wo, M, D, D, epi, st));
+    }
+    if (spatial) {
+      SI_TRY(launch_layer_norm<T>("ln2", h, a, M, D, w->ln2_g, w->ln2_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st));
+      {
+        EpiStore<T> epi{big, (int64_t)D, nullptr};
+        SI_TRY(launch_gemm<T>("q2", a, (int64_t)D, wq2, M, D, D, epi, st));
+      }
+      {
+        AttnArgs at;
+        at.q = big; at.k = ctxkv; at.v = ctxkv + D; at.o = a;
+        at.ldq = D; at.ldk = at.ldv = (int64_t)2 * D; at.ldo = D;
+        at.heads = p.heads; at.d = p.d; at.scale = scale;
+        at.S = p.B * win.Fw; at.Nq = win.Pw; at.Nk = p.Mc;
+        at.qmap = SeqMap{1, (int64_t)win.Pw, 0, 1};
+        at.kmap = SeqMap{win.Fw, (int64_t)p.Mc, 0, 1};
+        SI_TRY(launch_attention<T>("cross_attn", at, st));
+      }
+      {
+        EpiResidual<T> epi{h, (int64_t)D, cT(w->bo2), 1, nullptr};
+        SI_TRY(launch_gemm<T>("cross_out", a, (int64_t)D, wo2, M, D, D, epi, st));
+      }
+    }
+    SI_TRY(launch_layer_norm<T>("ln3", h, a, M, D, w->ln3_g, w->ln3_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st));
+    {
+      EpiGeglu<T> epi{big, (int64_t)4 * D, cT(w->b1), 4 * D};
+      SI_TRY(launch_gemm<T>("ff1_geglu", a, (int64_t)D, w1, M, 8 * D, D, epi, st));
+    }
+    {
+      EpiResidual<T> epi{h, (int64_t)D, cT(w->b2), 1, a};  // also leaves the final h as T in `a`
+      SI_TRY(launch_gemm<T>("ff2", big, (int64_t)4 * D, w2, M, D, 4 * D, epi, st));
+    }
+    {
+      EpiSliceOut<T> epi{X, OUT, cT(w->b_out), win};
+      SI_TRY(launch_gemm<T>("proj_out", a, (int64_t)D, w_out, M, C, D, epi, st));
+    }
+  }
+  return SI_OK;
+}
+
+static bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+  return a0 < b0 + nb && b0 < a0 + na;
+}
+
+}  // namespace si
+
+// ============================================================================= C ABI
+
+extern "C" {
+
+int32_t si_abi_version(void) { return 1; }
+
+const char* si_status_str(int32_t s) {
+  switch (s) {
+    case SI_OK: return "ok";
+    case SI_ERR_NULL: return "required pointer is NULL";
+    case SI_ERR_SHAPE: return "inconsistent or unsupported shape";
+    case SI_ERR_DTYPE: return "unknown or mismatching dtype";
+    case SI_ERR_SLICE: return "illegal slice axis or length";
+    case SI_ERR_ALIGN: return "misaligned device pointer";
+    case SI_ERR_WORKSPACE: return "workspace too small";
+    case SI_ERR_ARG: return "invalid argument";
+    case SI_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+size_t si_workspace_bytes(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, int32_t axis,
+                          int64_t slice_len) {
+  si::Plan p;
+  if (si::make_plan(x, w, ctx, axis, slice_len, &p) != SI_OK) return 0;
+  return p.total_bytes;
+}
+
+size_t si_live_activation_bytes(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, int32_t axis,
+                                int64_t slice_len) {
+  si::Plan p;
+  if (si::make_plan(x, w, ctx, axis, slice_len, &p) != SI_OK) return 0;
+  return p.total_bytes - p.weights_bytes;
+}
+
+si_status si_block_forward(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, si_tensor5* out,
+                           int32_t axis, int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || !w || !out) return SI_ERR_NULL;
+  si::Plan p;
+  si_status s = si::make_plan(x, w, ctx, axis, slice_len, &p);
+  if (s != SI_OK) return s;
+  if (out->dtype != x->dtype) return SI_ERR_DTYPE;
+  if (out->B != x->B || out->C != x->C || out->F != x->F || out->H != x->H || out->W != x->W) return SI_ERR_SHAPE;
+  if (!x->ptr || !out->ptr || !workspace) return SI_ERR_NULL;
+  const void* req[] = {w->w_in, w->wq, w->wk, w->wv, w->wo, w->w1, w->w2, w->w_out};
+  for (const void* q : req)
+    if (!q) return SI_ERR_NULL;
+  const bool spatial = w->kind == SI_BLOCK_SPATIAL;
+  if (spatial) {
+    if (!ctx->ptr || !w->wq2 || !w->wk2 || !w->wv2 || !w->wo2) return SI_ERR_NULL;
+  }
+  const void* all[] = {x->ptr, out->ptr, w->gn_g, w->gn_b, w->w_in, w->b_in, w->ln1_g, w->ln1_b, w->wq, w->wk, w->wv,
+                       w->wo, w->bo, w->ln3_g, w->ln3_b, w->w1, w->b1, w->w2, w->b2, w->w_out, w->b_out};
+  for (const void* q : all)
+    if (q && !si::aligned16(q)) return SI_ERR_ALIGN;
+  if (spatial) {
+    const void* sp[] = {ctx->ptr, w->ln2_g, w->ln2_b, w->wq2, w->wk2, w->wv2, w->wo2, w->bo2};
+    for (const void* q : sp)
+      if (q && !si::aligned16(q)) return SI_ERR_ALIGN;
+  }
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SI_ERR_ALIGN;
+  if (workspace_bytes < p.total_bytes) return SI_ERR_WORKSPACE;
+  const size_t xbytes = (size_t)p.B * p.C * p.F * (size_t)p.P * p.esize;
+  if (si::ranges_overlap(x->ptr, xbytes, out->ptr, xbytes)) return SI_ERR_ARG;
+  if (si::ranges_overlap(workspace, p.total_bytes, out->ptr, xbytes) ||
+      si::ranges_overlap(workspace, p.total_bytes, x->ptr, xbytes))
+    return SI_ERR_ARG;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  if (p.dtype == SI_F32) return si::run_block<float>(p, x, w, ctx, out, ws, st);
+  return si::run_block<si::bf16>(p, x, w, ctx, out, ws, st);
+}
+
+static int rehash_blocks(int64_t n) {
+  // one 16-byte vector per thread per trip, at least 4 trips per thread before adding blocks
+  const int64_t vecs = n / 4 + 1;
+  int64_t blocks = (vecs + (int64_t)si::kCosBlock * 4 - 1) / ((int64_t)si::kCosBlock * 4);
+  if (blocks < 1) blocks = 1;
+  if (blocks > si::kCosMaxBlocks) blocks = si::kCosMaxBlocks;
+  return (int)blocks;
+}
+
+size_t si_rehash_scratch_bytes(int64_t n) {
+  if (n < 0) return 0;
+  return (size_t)rehash_blocks(n) * 3 * sizeof(double);
+}
+
+si_status si_rehash_check(const void* feat_t, const void* feat_prev, int64_t n, int32_t dtype, float thresh,
+                          double* cos_dev, int32_t* decision_dev, void* scratch, void* stream) {
+  if (n < 0) return SI_ERR_SHAPE;
+  if (dtype != SI_F32 && dtype != SI_BF16) return SI_ERR_DTYPE;
+  if (std::isnan(thresh)) return SI_ERR_ARG;
+  if (!decision_dev || !scratch) return SI_ERR_NULL;
+  if (n > 0 && (!feat_t || !feat_prev)) return SI_ERR_NULL;
+  if (!si::aligned16(feat_t) || !si::aligned16(feat_prev) || !si::aligned16(scratch)) return SI_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(cos_dev) & 7u) || (reinterpret_cast<uintptr_t>(decision_dev) & 3u)) return SI_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int blocks = rehash_blocks(n);
+  double* partial = static_cast<double*>(scratch);
+  {
+    si::StageScope scope("cosine_partial", st);
+    if (dtype == SI_F32)
+      si::cosine_partial_kernel<float><<<blocks, si::kCosBlock, 0, st>>>(static_cast<const float*>(feat_t),
+                                                                         static_cast<const float*>(feat_prev), n, partial);
+    else
+      si::cosine_partial_kernel<si::bf16><<<blocks, si::kCosBlock, 0, st>>>(static_cast<const si::bf16*>(feat_t),
+                                                                            static_cast<const si::bf16*>(feat_prev), n, partial);
+    if (hipGetLastError() != hipSuccess) return SI_ERR_HIP;
+  }
+  {
+    si::StageScope scope("cosine_finish", st);
+    si::cosine_finish_kernel<<<1, si::kCosBlock, 0, st>>>(partial, blocks, (double)thresh, cos_dev, decision_dev);
+    if (hipGetLastError() != hipSuccess) return SI_ERR_HIP;
+  }
+  return SI_OK;
+}
+
+si_status si_rehash_check_sync(const void* feat_t, const void* feat_prev, int64_t n, int32_t dtype, float thresh,
+                               void* scratch, void* result_dev, void* stream, double* cos_host, int32_t* decision_host) {
+  if (!result_dev || !cos_host || !decision_host) return SI_ERR_NULL;
+  if (!si::aligned16(result_dev)) return SI_ERR_ALIGN;
+  double* cos_dev = static_cast<double*>(result_dev);
+  int32_t* dec_dev = reinterpret_cast<int32_t*>(static_cast<char*>(result_dev) + 8);
+  si_status s = si_rehash_check(feat_t, feat_prev, n, dtype, thresh, cos_dev, dec_dev, scratch, stream);
+  if (s != SI_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  struct { double c; int32_t d; int32_t pad; } host;
+  if (hipMemcpyAsync(&host, result_dev, 16, hipMemcpyDeviceToHost, st) != hipSuccess) return SI_ERR_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return SI_ERR_HIP;
+  *cos_host = host.c;
+  *decision_host = host.d;
+  return SI_OK;
+}
+
+int32_t si_key_step_search(const float* S, int32_t K, float gamma, int32_t* G_out) {
+  if (!S || !G_out || K < 1 || std::isnan(gamma) || gamma > 1.0f) return -1;
+  // Algorithm 1: i walks upward, j is the last key step (the anchor).
+  int32_t count = 0;
+  G_out[count++] = 0;
+  int32_t i = 0, j = 0;
+  while (i < K) {
+    if (S[(int64_t)i * K + j] >= gamma) {
+      ++i;
+    } else {
+      if (!(S[(int64_t)i * K + i] >= gamma)) return -1;  // the walk could not advance
+      if (G_out[count - 1] != i) G_out[count++] = i;
+      j = i;
+    }
+  }
+  if (G_out[count - 1] != K - 1) G_out[count++] = K - 1;
+  return count;
+}
+
+void si_stage_timing_enable(int32_t on) { si::g_timing = on != 0; }
+
+int32_t si_stage_timing_read(const char** names, double* total_ms, int64_t* launches, int32_t cap) {
+  const int ns = (int)si::g_stage_names.size();
+  std::vector<double> ms(ns, 0.0);
+  std::vector<int64_t> cnt(ns, 0);
+  bool bad = false;
+  for (auto& e : si::g_events) {
+    float t = 0.f;
+    if (hipEventSynchronize(e.b) != hipSuccess || hipEventElapsedTime(&t, e.a, e.b) != hipSuccess) bad = true;
+    ms[e.stage] += t;
+    cnt[e.stage] += 1;
+    (void)hipEventDestroy(e.a);
+    (void)hipEventDestroy(e.b);
+  }
+  si::g_events.clear();
+  if (bad) return -1;
+  for (int i = 0; i < ns && i < cap; ++i) {
+    if (names) names[i] = si::g_stage_names[i].c_str();
+    if (total_ms) total_ms[i] = ms[i];
+    if (launches) launches[i] = cnt[i];
+  }
+  return ns;
+}
+
+}  // extern "C"

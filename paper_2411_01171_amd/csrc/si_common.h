@@ -1,0 +1,68 @@
+// Shared device helpers: storage types, conversions, wavefront reductions.
+// gfx950 only: 64-wide wavefronts are assumed throughout.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace si {
+
+constexpr int kWave = 64;
+
+// bf16 storage: upper 16 bits of an IEEE float.
+struct bf16 {
+  unsigned short v;
+};
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
+  return __uint_as_float(((unsigned)b) << 16);
+}
+
+// Round-to-nearest-even; NaN stays NaN (quiet), overflow goes to infinity as IEEE does.
+__device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16 v) { return bf16_bits_to_float(v.v); }
+
+template <typename T> __device__ __forceinline__ T from_float(float f);
+template <> __device__ __forceinline__ float from_float<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16 from_float<bf16>(float f) {
+  bf16 r;
+  r.v = float_to_bf16_bits(f);
+  return r;
+}
+
+// Optional parameter vectors: NULL gain = 1, NULL shift / bias = 0.
+template <typename T> __device__ __forceinline__ float param_or(const T* p, int64_t i, float dflt) {
+  return p ? to_float(p[i]) : dflt;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+__device__ __forceinline__ float gelu_erf(float u) {
+  return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f));
+}
+
+}  // namespace si

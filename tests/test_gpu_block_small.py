@@ -1,0 +1,119 @@
+"""HIP block forward vs the CPU oracle, element by element, on shapes the oracle
+finishes in seconds: config 1 itself (fp32) and small bf16 blocks spanning
+several tiles with ragged slice tails."""
+import numpy as np
+import pytest
+
+import oracle
+import si_workloads as wl
+from helpers import tiny_spec
+
+pytestmark = pytest.mark.gpu
+
+BF16_MAX_ABS, BF16_REL_L2 = 2e-2, 5e-3      # tolerances for bf16 paths
+F32_REL = 1e-4                              # relative tolerance for fp32 paths
+
+
+def _check(spec, x, w, ctx, slice_len=None, branch_tol=None):
+    from gpu_helpers import errors, run_block
+    ref = oracle.block_forward_ref(x, w, spec, ctx)
+    out = run_block(spec, x, w, ctx, slice_len)
+    assert np.all(np.isfinite(out)), "output has NaN/Inf or unwritten elements"
+    e = errors(out, ref, x)
+    print(spec.name, spec.kind, spec.dtype, "slice", slice_len, e)
+    if spec.dtype == "f32":
+        assert e["rel_l2"] <= F32_REL and e["max_abs"] <= F32_REL * e["max_ref"]
+        assert e["rel_l2_branch"] <= 10 * F32_REL
+    else:
+        assert e["max_abs"] <= BF16_MAX_ABS and e["rel_l2"] <= BF16_REL_L2
+        assert e["rel_l2_branch"] <= (branch_tol or 2e-2)
+    return e
+
+
+@pytest.mark.parametrize("slice_len", [16, 64, 7])
+def test_cfg1_fp32(slice_len):
+    spec = wl.CONFIGS["cfg1"]
+    x, w = wl.make_x(spec), wl.make_weights(spec)
+    _check(spec, x, w, None, slice_len)
+
+
+def test_cfg1_fp32_random_affine_and_pe():
+    spec = wl.scaled(wl.CONFIGS["cfg1"], add_sin_pe=True)
+    x, w = wl.make_x(spec), wl.make_weights(spec, randomize_affine=True, matrix_std=0.08)
+    _check(spec, x, w, None, 16)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("slice_len", [20, 1000])
+def test_small_temporal(dtype, slice_len):
+    spec = tiny_spec(wl.TEMPORAL, B=2, C=64, F=5, H=7, W=9, heads=2, dim_head=32, groups=8, pe=True, dtype=dtype)
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, None, slice_len)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("slice_len", [2, 1, 3])
+def test_small_spatial(dtype, slice_len):
+    spec = tiny_spec(wl.SPATIAL, B=2, C=64, F=3, H=12, W=13, heads=2, dim_head=32, groups=8, M=5, Cc=16, dtype=dtype)
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, ctx, slice_len)
+
+
+def test_head_dim_40_and_25_frames_bf16():
+    spec = tiny_spec(wl.TEMPORAL, B=1, C=80, F=25, H=6, W=6, heads=2, dim_head=40, groups=4, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, None, 10)
+
+
+def test_peaky_softmax_bf16():
+    """Queries and keys scaled up so that the softmax is far from uniform."""
+    spec = tiny_spec(wl.SPATIAL, B=1, C=64, F=2, H=10, W=10, heads=2, dim_head=32, groups=8, M=7, Cc=16, dtype="bf16")
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, matrix_std=0.05)
+    for k in ("wq", "wk", "wq2", "wk2"):
+        w[k] = wl.round_to_storage(w[k] * 8.0, "bf16")
+    _check(spec, x, w, ctx, 1, branch_tol=4e-2)
+
+
+def test_large_mean_groupnorm():
+    """Input mean far from zero: statistics must not cancel catastrophically."""
+    for dtype, mean in (("f32", 200.0), ("bf16", 30.0)):
+        spec = tiny_spec(wl.TEMPORAL, B=1, C=64, F=4, H=8, W=8, heads=2, dim_head=32, groups=8, dtype=dtype)
+        x = wl.make_x(spec, mean=mean)
+        w = wl.make_weights(spec, matrix_std=0.05)
+        from gpu_helpers import run_block
+        ref = oracle.block_forward_ref(x, w, spec)
+        out = run_block(spec, x, w, None, 16)
+        branch = ref - x
+        err = np.linalg.norm((out - x) - branch) / np.linalg.norm(branch)
+        print(dtype, "large-mean branch rel err", err)
+        # the output itself is dominated by x; compare the computed branch where storage allows
+        if dtype == "f32":
+            assert err < 2e-3
+        else:
+            assert np.max(np.abs(out - ref)) <= 0.5 * 2 ** -7 * np.max(np.abs(ref)) + 2e-2
+
+
+def test_slicing_is_lossless_on_gpu():
+    """Eq. (1): any slice length gives the same output, up to reduction order (here: bit-identical,
+    because per-token arithmetic does not depend on the window)."""
+    from gpu_helpers import run_block
+    spec = tiny_spec(wl.TEMPORAL, B=2, C=64, F=4, H=8, W=8, heads=2, dim_head=32, groups=8, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, matrix_std=0.05)
+    full = run_block(spec, x, w, None, 64)
+    for sl in (1, 5, 16, 63):
+        assert np.array_equal(run_block(spec, x, w, None, sl), full)
+
+
+def test_deterministic():
+    from gpu_helpers import run_block
+    spec = tiny_spec(wl.SPATIAL, B=1, C=64, F=2, H=8, W=8, heads=2, dim_head=32, groups=8, M=5, Cc=16, dtype="bf16")
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, matrix_std=0.05)
+    a = run_block(spec, x, w, ctx, 1)
+    b = run_block(spec, x, w, ctx, 1)
+    assert np.array_equal(a, b)
