@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the Streamlined-Inference hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+GroupNorm statistics, every slice of the sliced block forward (slice-in,
+proj_in, LN+QKV, attention, out-proj, GEGLU FFN, proj_out + residual into the
+preallocated output) and the Step Rehash similarity test of the new output
+against a cached one.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-step throughput in algorithmic TFLOP/s, the
+roofline record of the dominant kernel (per-launch duration from HIP events
+recorded by the library around each launch), and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+PEAK_F32_VALU_TFLOPS = 157.3
+
+
+def stage_work(spec, stage, M, window_tokens_per_seq=None):
+    """Algorithmic work of one launch of `stage` on a window of M tokens.
+
+    Returns (kind, amount): kind "flop" for contractions (2mnk; attention
+    4*Nq*Nk*d per head), "byte" for HBM-bound stages."""
+    import si_workloads as wl
+    C, D = spec.C, spec.D
+    es = 4 if spec.dtype == "f32" else 2
+    P = spec.H * spec.W
+    gemm = {
+        "proj_in": 2.0 * M * C * D, "qkv": 2.0 * M * D * 3 * D, "attn_out": 2.0 * M * D * D,
+        "q2": 2.0 * M * D * D, "cross_out": 2.0 * M * D * D,
+        "ff1_geglu": 2.0 * M * D * 8 * D, "ff2": 2.0 * M * 4 * D * D, "proj_out": 2.0 * M * D * C,
+        "ctx_kv": 2.0 * spec.B * spec.ctx_tokens * spec.ctx_dim * 2 * D,
+    }
+    if stage in gemm:
+        return "flop", gemm[stage]
+    if stage == "self_attn":
+        nk = spec.F if spec.kind == wl.TEMPORAL else P
+        return "flop", 4.0 * M * nk * D
+    if stage == "cross_attn":
+        return "flop", 4.0 * M * spec.ctx_tokens * D
+    if stage == "temporal_fused":
+        return "flop", 2.0 * M * (C * D + 3 * D * D + D * D + 8 * D * D + 4 * D * D + D * C) + 4.0 * M * spec.F * D
+    if stage == "gn_stats":
+        return "byte", float(spec.tokens * C * es)
+    if stage == "slice_in":
+        return "byte", 2.0 * M * C * es
+    if stage in ("ln1", "ln2", "ln3"):
+        return "byte", M * D * (4.0 + es)
+    if stage == "cosine_partial":
+        return "byte", 2.0 * spec.tokens * C * es
+    return "none", 0.0
+
+
+def cpu_baseline(spec, seconds_target=20.0):
+    """The fp64 NumPy oracle, as it stands, on a bounded sample of the workload."""
+    import numpy as np
+    import oracle
+    import si_workloads as wl
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    if spec.kind == wl.TEMPORAL:
+        npos = min(spec.H * spec.W, 2048)
+        sub = wl.scaled(spec, H=1, W=npos)
+        what = f"{npos} of {spec.H * spec.W} positions (all {spec.F} frames, B={spec.B}), GroupNorm over the sample"
+    else:
+        sub = wl.scaled(spec, F=1)
+        what = f"1 of {spec.F} frames (B={spec.B})"
+    x, w, ctx = wl.make_x(sub), wl.make_weights(sub), wl.make_context(sub)
+    t0 = time.perf_counter()
+    oracle.block_forward_ref(x, w, sub, ctx)
+    out = oracle.block_forward_ref(x, w, sub, ctx) if time.perf_counter() - t0 < seconds_target / 4 else None
+    dt = time.perf_counter() - t0
+    reps = 2 if out is not None else 1
+    tflops = sub.flops() * reps / dt / 1e12
+    return {"value": tflops, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{what}; fp64 NumPy; {reps} pass(es) in {dt:.1f} s",
+            "host_cpus": len(os.sched_getaffinity(0))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2", help="cfg2 (default, the metric's configuration), cfg3, cfg4s, cfg4t, cfg5s, cfg5t")
+    ap.add_argument("--slice-len", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards without changing the kernel; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2411_01171_amd as si
+    import si_workloads as wl
+    from gpu_helpers import AXIS, device_weights, to_dev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    spec = wl.CONFIGS[args.workload]
+    slice_len = args.slice_len or spec.slice_len
+    axis = AXIS[spec.slice_axis]
+    extent = spec.F if spec.slice_axis == wl.AXIS_F else spec.H * spec.W
+
+    x_np = wl.make_x(spec)
+    x = to_dev(x_np, spec.dtype)
+    x_prev = to_dev(wl.cfg5_step_input(x_np, 5, spec.dtype), spec.dtype)   # a drifted earlier input
+    ctx_np = wl.make_context(spec)
+    ctx = None if ctx_np is None else to_dev(ctx_np, spec.dtype)
+    wts = device_weights(spec, wl.make_weights(spec))
+    ws_bytes = si.si_workspace_bytes(x, wts, ctx, axis, slice_len)
+    live_sliced = si.si_live_activation_bytes(x, wts, ctx, axis, slice_len)
+    live_unsliced = si.si_live_activation_bytes(x, wts, ctx, axis, extent)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(x)
+    cached = torch.empty_like(x)
+    scratch = torch.empty(si.si_rehash_scratch_bytes(x.numel()), dtype=torch.uint8, device="cuda")
+    cos = torch.zeros(1, dtype=torch.float64, device="cuda")
+    dec = torch.zeros(1, dtype=torch.int32, device="cuda")
+    gamma = wl.CFG5_GAMMA
+
+    # cached feature: the block output of the drifted input (what a previous key step would have stored)
+    si.si_block_forward(x_prev, wts, ctx, cached, axis, slice_len, ws)
+    torch.cuda.synchronize()
+
+    def step():
+        si.si_block_forward(x, wts, ctx, out, axis, slice_len, ws)
+        si.si_rehash_check(out, cached, gamma, cos, dec, scratch)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    dev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall_ms / args.steps
+    flops = spec.flops()
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel durations: the same K steps with an event pair around every launch
+    si.si_stage_timing_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    stages = si.si_stage_timing_read()
+    si.si_stage_timing_enable(False)
+
+    n_slices = -(-extent // slice_len)
+    M_slice = spec.tokens // extent * min(slice_len, extent)
+    stage_report = {}
+    for name, (ms, cnt) in stages.items():
+        avg_ms = ms / cnt
+        kind, work = stage_work(spec, name, M_slice)
+        rec = {"avg_us": round(avg_ms * 1e3, 2), "launches_per_step": cnt / args.steps,
+               "ms_per_step": round(ms / args.steps, 4)}
+        if kind == "flop":
+            rec["TFLOP/s"] = round(work / (avg_ms * 1e-3) / 1e12, 2)
+        elif kind == "byte":
+            rec["GB/s"] = round(work / (avg_ms * 1e-3) / 1e9, 1)
+        stage_report[name] = rec
+    dominant = max(stages.items(), key=lambda kv: kv[1][0])[0]
+    d_ms, d_cnt = stages[dominant]
+    d_kind, d_work = stage_work(spec, dominant, M_slice)
+    if d_kind == "flop":
+        ach = d_work / (d_ms / d_cnt * 1e-3) / 1e12
+        peak = PEAK_BF16_TFLOPS if spec.dtype == "bf16" else PEAK_F32_VALU_TFLOPS
+        bound = "mfma" if spec.dtype == "bf16" else "alu"
+        # the vector-ALU attention fallback is priced against the MFMA peak too: it is a dense contraction
+        roof = {"bound": bound, "kernel": dominant, "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                "frac": ach / peak}
+    else:
+        ach = d_work / (d_ms / d_cnt * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": dominant, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS}
+    roof["avg_launch_us"] = d_ms / d_cnt * 1e3
+    roof["traffic"] = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            roof["traffic"] = json.load(open(tpath)).get(args.workload, {}).get(dominant)
+        except Exception:
+            pass
+
+    result = {
+        "metric": "sliced block-forward TFLOP/s (% MFMA peak) + peak live activation bytes vs unsliced",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "device_ms_per_step": dev_ms / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": spec.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {spec.kind} block x[B={spec.B},C={spec.C},F={spec.F},H={spec.H},W={spec.W}], "
+                               f"{spec.heads} heads x {spec.dim_head}, sliced along {spec.slice_axis} in windows of {slice_len} "
+                               f"({n_slices} slices) + rehash check of the output (threshold {gamma})",
+                   "algorithmic_flop_per_step": flops, "tokens": spec.tokens},
+        "frac_mfma_peak": value / PEAK_BF16_TFLOPS,
+        "live_activation_bytes": {"sliced": live_sliced, "unsliced_same_kernels": live_unsliced,
+                                  "ratio": live_sliced / live_unsliced, "workspace_bytes": ws_bytes,
+                                  "x_bytes": x.numel() * x.element_size()},
+        "rehash": {"cos": float(cos.item()), "decision": int(dec.item())},
+        "roofline": roof,
+        "stages": stage_report,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(spec)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -47,7 +47,9 @@ struct EpiStore {
 };
 
 // Residual stream (fp32): h[m, n] = (accumulate ? h[m, n] : 0) + acc + bias[n];
-// optionally the new value is also stored as T in copy[m, n] (operand of the next GEMM).
+// optionally the new value is also stored as T in copy (operand of the next GEMM):
+// fp32 storage as is; bf16 storage as a (high, low) pair, high parts in columns
+// [0, ld), low parts in [ld, 2*ld) of a row of 2*ld elements.
 template <typename T>
 struct EpiResidual {
   float* h;
@@ -64,11 +66,20 @@ struct EpiResidual {
     o.w += v[3] + param_or(bias, n0 + 3, 0.f);
     *p = o;
     if (copy) {
-      T* c = copy + m * ld + n0;
-      c[0] = from_float<T>(o.x);
-      c[1] = from_float<T>(o.y);
-      c[2] = from_float<T>(o.z);
-      c[3] = from_float<T>(o.w);
+      const float ov[4] = {o.x, o.y, o.z, o.w};
+      if constexpr (sizeof(T) == 2) {
+        T* c = copy + m * (2 * ld) + n0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const T hi = from_float<T>(ov[i]);
+          c[i] = hi;
+          c[ld + i] = from_float<T>(ov[i] - to_float(hi));
+        }
+      } else {
+        T* c = copy + m * ld + n0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] = from_float<T>(ov[i]);
+      }
     }
   }
 };

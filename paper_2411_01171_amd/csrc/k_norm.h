@@ -83,7 +83,9 @@ struct Window {
 
 // Slice-in: a0[m, c] = GN(x)[b, c, f, p] for the window's tokens.  64 x 64
 // (position x channel) tiles are transposed through LDS so that both the read
-// (along positions) and the write (along channels) are contiguous.
+// (along positions) and the write (along channels) are contiguous.  For bf16
+// storage the normalised value is kept as a (high, low) bf16 pair -- row m holds
+// C high parts followed by C low parts -- so that proj_in sees it to ~16 bits.
 template <typename T>
 __global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restrict__ x, const float* __restrict__ stats,
                                                                const T* __restrict__ gamma, const T* __restrict__ beta,
@@ -113,7 +115,13 @@ __global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restri
     const int c = ct + tx, p = pt + pl;
     if (c < w.C && p < w.Pw) {
       const int64_t m = (int64_t)bf * w.Pw + p;
-      a0[m * w.C + c] = from_float<T>(tile[tx][pl]);
+      if constexpr (sizeof(T) == 2) {
+        const T hi = from_float<T>(tile[tx][pl]);
+        a0[m * (2 * w.C) + c] = hi;
+        a0[m * (2 * w.C) + w.C + c] = from_float<T>(tile[tx][pl] - to_float(hi));
+      } else {
+        a0[m * w.C + c] = from_float<T>(tile[tx][pl]);
+      }
     }
   }
 }
@@ -179,12 +187,13 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float* __restrict
   }
 }
 
-// dst[r * K + k] = src[k * ld_src + col(r)] for r in [0, rows): the k-contiguous
-// layout the GEMM kernels read.  col(r) = col0 + r, or, with `interleave` > 0
+// dst[r * ld_dst + k] = src[k * ld_src + col(r)] for r in [0, rows): the k-contiguous
+// layout the GEMM kernels read (ld_dst > K lets two copies sit side by side for
+// operands that arrive as high/low pairs).  col(r) = col0 + r, or, with `interleave` > 0
 // (GEGLU projection), even r -> value column r/2, odd r -> gate column interleave + r/2.
 template <typename T>
 __global__ __launch_bounds__(256) void pack_transpose_kernel(const T* __restrict__ src, T* __restrict__ dst, int K, int ld_src,
-                                                             int rows, int col0, int interleave) {
+                                                             int rows, int col0, int interleave, int ld_dst) {
   __shared__ T tile[32][33];
   const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
   const int r0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
@@ -198,7 +207,7 @@ __global__ __launch_bounds__(256) void pack_transpose_kernel(const T* __restrict
   __syncthreads();
   for (int rr = ty; rr < 32; rr += 8) {
     const int r = r0 + rr, k = k0 + tx;
-    if (r < rows && k < K) dst[(int64_t)r * K + k] = tile[tx][rr];
+    if (r < rows && k < K) dst[(int64_t)r * ld_dst + k] = tile[tx][rr];
   }
 }
 

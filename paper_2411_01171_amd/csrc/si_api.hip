@@ -129,12 +129,13 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_pe = take(p->pe ? (size_t)p->F * Dz * sizeof(float) : 0);
   p->off_ctxkv = take((size_t)p->B * p->Mc * 2 * Dz * es);
   // one slice's intermediates
-  p->off_a = take((size_t)p->Mmax * (C > Dz ? C : Dz) * es);
+  const size_t split = es == 2 ? 2 : 1;  // bf16: proj_in / proj_out operands travel as (high, low) pairs
+  p->off_a = take((size_t)p->Mmax * (C > Dz ? C : Dz) * split * es);
   p->off_h = take((size_t)p->Mmax * Dz * sizeof(float));
   p->off_big = take((size_t)p->Mmax * 4 * Dz * es);
   const size_t act_end = off;
   // re-laid-out weights
-  p->off_w_in = take(Dz * C * es);
+  p->off_w_in = take(split * Dz * C * es);
   p->off_wqkv = take(3 * Dz * Dz * es);
   p->off_wo = take(Dz * Dz * es);
   const bool sp = p->kind == SI_BLOCK_SPATIAL;
@@ -143,7 +144,7 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_wo2 = take(sp ? Dz * Dz * es : 0);
   p->off_w1 = take(8 * Dz * Dz * es);
   p->off_w2 = take(4 * Dz * Dz * es);
-  p->off_w_out = take(C * Dz * es);
+  p->off_w_out = take(split * C * Dz * es);
   p->weights_bytes = off - act_end;
   p->total_bytes = off;
   return SI_OK;
@@ -178,9 +179,10 @@ static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T
 }
 
 template <typename T>
-static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, int col0, int interleave, hipStream_t st) {
+static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, int col0, int interleave, hipStream_t st,
+                             int ld_dst = 0) {
   dim3 grid((unsigned)((rows + 31) / 32), (unsigned)((K + 31) / 32));
-  pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, dst, K, ld_src, rows, col0, interleave);
+  pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, dst, K, ld_src, rows, col0, interleave, ld_dst ? ld_dst : K);
   SI_CHECK_LAUNCH();
   return SI_OK;
 }
@@ -234,12 +236,16 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   T* w_out = reinterpret_cast<T*>(ws + p.off_w_out);
   const int C = p.C, D = p.D;
   const bool spatial = p.kind == SI_BLOCK_SPATIAL;
+  constexpr int kSplit = sizeof(T) == 2 ? 2 : 1;
   auto cT = [](const void* q) { return static_cast<const T*>(q); };
 
   // ---- once per call: weight re-layout, frame embedding table, GroupNorm statistics, context K/V
   {
     StageScope scope("pack_weights", st);
-    SI_TRY(launch_pack<T>(cT(w->w_in), w_in, C, D, D, 0, 0, st));
+    for (int h2 = 0; h2 < kSplit; ++h2) {
+      SI_TRY(launch_pack<T>(cT(w->w_in), w_in + (size_t)h2 * C, C, D, D, 0, 0, st, kSplit * C));
+      SI_TRY(launch_pack<T>(cT(w->w_out), w_out + (size_t)h2 * D, D, C, C, 0, 0, st, kSplit * D));
+    }
     SI_TRY(launch_pack<T>(cT(w->wq), wqkv, D, D, D, 0, 0, st));
     SI_TRY(launch_pack<T>(cT(w->wk), wqkv + (size_t)D * D, D, D, D, 0, 0, st));
     SI_TRY(launch_pack<T>(cT(w->wv), wqkv + (size_t)2 * D * D, D, D, D, 0, 0, st));
@@ -252,7 +258,6 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     }
     SI_TRY(launch_pack<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 0, 4 * D, st));
     SI_TRY(launch_pack<T>(cT(w->w2), w2, 4 * D, D, D, 0, 0, st));
-    SI_TRY(launch_pack<T>(cT(w->w_out), w_out, D, C, C, 0, 0, st));
     if (pe) {
       pe_table_kernel<<<(p.F * D + 255) / 256, 256, 0, st>>>(pe, p.F, D);
       SI_CHECK_LAUNCH();
@@ -294,7 +299,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     }
     {
       EpiResidual<T> epi{h, (int64_t)D, cT(w->b_in), 0, nullptr};
-      SI_TRY(launch_gemm<T>("proj_in", a, (int64_t)C, w_in, M, D, C, epi, st));
+      SI_TRY(launch_gemm<T>("proj_in", a, (int64_t)kSplit * C, w_in, M, D, kSplit * C, epi, st));
     }
     SI_TRY(launch_layer_norm<T>("ln1", h, a, M, D, w->ln1_g, w->ln1_b, w->ln_eps, pe, win.Pw, win.Fw, win.f0, st));
     {
@@ -352,7 +357,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     }
     {
       EpiSliceOut<T> epi{X, OUT, cT(w->b_out), win};
-      SI_TRY(launch_gemm<T>("proj_out", a, (int64_t)D, w_out, M, C, D, epi, st));
+      SI_TRY(launch_gemm<T>("proj_out", a, (int64_t)kSplit * D, w_out, M, C, kSplit * D, epi, st));
     }
   }
   return SI_OK;
