@@ -1,0 +1,507 @@
+// Register-resident fused kernels for blocks whose inner width D = 32*NB fits a
+// wavefront's register file (D <= 320, C == D, bf16 storage).
+//
+// Idea.  In v_mfma_f32_32x32x16_bf16 the row operand and the column operand
+// have the same register shape: lane l supplies 8 k-values (slot g = l/32) of
+// row / column l%32.  The result gives lane l column l%32 and, in register
+// quad q, rows 8q + 4g + {0..3}.  If tokens are the COLUMNS, a lane's 16 result
+// registers of a 32-row block, converted to bf16, are exactly the column
+// operand of the next contraction for the two 16-wide k-steps of that block --
+// provided the weight fragments of the next contraction list their k-values in
+// the order k(g, e) = 16s + (e < 4 ? 4g + e : 8 + 4g + e - 4).  The weights are
+// re-laid-out once per call into that order ("fragment stream": 1 KiB per
+// (32-row block, k-step), in exactly the order the kernel consumes them).
+//
+// So one wavefront carries 32 tokens through a whole operator chain without
+// its activations ever leaving registers; the only LDS traffic is the weight
+// stream, loaded once per workgroup (4 wavefronts x 32 tokens) into a ring of
+// sub-chunks of 2*NB fragments and read by all four wavefronts.
+//
+//   ffn_half_kernel   h (fp32 rows) -> LN3 -> W1 -> GEGLU -> W2 (+h) -> W_out
+//                     -> + x -> out window.  The 8D-wide FFN intermediate and
+//                     the final h exist only in registers.  The FFN runs as a
+//                     three-stage software pipeline over 32-column chunks so
+//                     that the GELU arithmetic of chunk t issues between the
+//                     MFMAs of chunks t+1 (W1) and t-1 (W2).
+#pragma once
+#include <type_traits>
+
+#include "si_common.h"
+#include "k_norm.h"
+
+namespace si {
+
+// Compile-time loop: f(std::integral_constant<int, I>) for I in [0, N).
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
+// Logical k offset inside a 16-wide k-step of hardware slot (g, e).
+__host__ __device__ __forceinline__ int frag_k(int g, int e) { return e < 4 ? 4 * g + e : 8 + 4 * g + (e - 4); }
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bf16 pair, round-to-nearest-even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
+
+// 8 consecutive result registers (two quads) -> column operand of one k-step.
+__device__ __forceinline__ bf16x8_t to_operand(const float* v) {
+  uint4 u;
+  u.x = pack_bf16x2(v[0], v[1]);
+  u.y = pack_bf16x2(v[2], v[3]);
+  u.z = pack_bf16x2(v[4], v[5]);
+  u.w = pack_bf16x2(v[6], v[7]);
+  return __builtin_bit_cast(bf16x8_t, u);
+}
+
+// GELU(x) = x * Phi(x), Phi(x) = 0.5 (1 + erf(x / sqrt 2)).  Phi(x) - 0.5 is evaluated as an odd
+// polynomial xc * R(xc^2), xc = clamp(x, -4.2, 4.2), degree 8 in xc^2 (minimax fit of
+// erf(x / sqrt 2) / x on [0, 4.2], |erf error| <= 2.2e-5 everywhere, coefficients pre-halved).
+// No transcendental instructions: the FFN's GELUs share the issue port with the MFMAs.
+constexpr float kGeluClamp = 4.2f;
+constexpr int kGeluDeg = 8;
+__device__ constexpr float kGeluC[kGeluDeg + 1] = {
+    0.5f * 0.7978148460388184f,     0.5f * -0.1327207386493683f,    0.5f * 0.019660256803035736f,
+    0.5f * -0.0022282942663878202f, 0.5f * 0.00018914842803496867f, 0.5f * -1.1521495252964087e-05f,
+    0.5f * 4.6873191195118125e-07f, 0.5f * -1.1266531707576632e-08f, 0.5f * 1.199598614887165e-10f};
+
+// GEGLU of G result registers [E0, E0+G) of one chunk, cut into stages of G independent
+// vector-ALU instructions each, so that one stage can be issued behind every MFMA.
+//   value = UV[e] + bv[off(e)], gate = UG[e] + bg[off(e)], gv[e] = value * gate * Phi(gate)
+// off(e): column of result register e relative to the lane's first column (see frag_k).
+__host__ __device__ constexpr int reg_col(int e) { return 16 * (e / 8) + ((e % 8) < 4 ? (e % 8) : (e % 8) + 4); }
+constexpr int kGeluStages = kGeluDeg + 9;
+
+template <int E0, int G>
+struct GegluGroup {
+  float x[G], v[G], xc[G], t[G], p[G];
+  __device__ __forceinline__ void stage(int s, const f32x16_t& UV, const f32x16_t& UG, const float* bv, const float* bg,
+                                        float* gv) {
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+      const int e = E0 + i;
+      if (s == 0) x[i] = UG[e];
+      else if (s == 1) v[i] = UV[e];
+      else if (s == 2) x[i] += bg[reg_col(e)];
+      else if (s == 3) v[i] += bv[reg_col(e)];
+      else if (s == 4) xc[i] = __builtin_amdgcn_fmed3f(x[i], -kGeluClamp, kGeluClamp);
+      else if (s == 5) t[i] = xc[i] * xc[i];
+      else if (s == 6) p[i] = fmaf(kGeluC[kGeluDeg], t[i], kGeluC[kGeluDeg - 1]);
+      else if (s >= 7 && s < 6 + kGeluDeg) p[i] = fmaf(p[i], t[i], kGeluC[kGeluDeg + 5 - s]);
+      else if (s == 6 + kGeluDeg) p[i] = fmaf(p[i], xc[i], 0.5f);  // Phi(gate)
+      else if (s == 7 + kGeluDeg) x[i] = x[i] * v[i];
+      else if (s == 8 + kGeluDeg) gv[e] = x[i] * p[i];
+    }
+  }
+};
+
+// ----------------------------------------------------------------------------- weight stream layout
+
+// Placement of the fragment stream in memory.  Every workgroup reads the same
+// fragments at about the same time, so the fragments of one sub-chunk are kept
+// out of a single L2 channel: fragment f of sub-chunk i lives at 16-byte index
+// f * pitch + i * 64 (+ lane), pitch an odd number of KiB (in 16-byte units)
+// congruent to 5 mod 16.
+__host__ __device__ inline int64_t stream_pitch_u4(int total_sub) {
+  int kib = total_sub;
+  while (kib % 16 != 5) ++kib;
+  return (int64_t)kib * 64;
+}
+__host__ __device__ inline int64_t stream_bytes(int total_sub, int sub) { return stream_pitch_u4(total_sub) * 16 * sub; }
+
+// Fragment stream of the FFN half, in consumption order.  A sub-chunk is 2*NB
+// fragments (fragment = 64 lanes x 8 bf16); with NC = 4*NB chunks of 32 inner columns:
+//   V(c): W1 value rows 32c..32c+31, k-steps 0..2NB-1      G(c): the gate rows likewise
+//   W2(c): for nb in [0, NB): k-steps (inner 32c..32c+15), (32c+16..32c+31)
+//   O(nb): W_out rows 32nb..32nb+31, k-steps 0..2NB-1
+// order: V0 G0 V1 G1 | for t in 1..NC-2: V(t+1) G(t+1) W2(t-1) | W2(NC-2) W2(NC-1) | O(0..NB-1)
+// One thread per (fragment, lane).  Sources are row-major [in, out].
+template <int NB>
+__global__ __launch_bounds__(256) void pack_ffn_stream_kernel(const bf16* __restrict__ w1, const bf16* __restrict__ w2,
+                                                              const bf16* __restrict__ w_out, u32x4_t* __restrict__ dst) {
+  constexpr int D = 32 * NB, SUB = 2 * NB, NC = 4 * NB;
+  constexpr int TOTAL_SUB = 3 * NC + NB;
+  const int fidx = blockIdx.x * 4 + threadIdx.x / kWave;
+  if (fidx >= TOTAL_SUB * SUB) return;
+  const int lane = threadIdx.x % kWave, r = lane % 32, g = lane / 32;
+  const int sub = fidx / SUB, idx = fidx % SUB;
+  int kind, c;  // kind 0: V, 1: G, 2: W2, 3: O
+  if (sub < 4) {
+    kind = sub % 2; c = sub / 2;
+  } else if (sub < 4 + 3 * (NC - 2)) {
+    const int rr = sub - 4, t = 1 + rr / 3, k = rr % 3;
+    kind = k; c = k == 2 ? t - 1 : t + 1;
+  } else if (sub < 3 * NC) {
+    kind = 2; c = NC - 2 + (sub - (4 + 3 * (NC - 2)));
+  } else {
+    kind = 3; c = sub - 3 * NC;
+  }
+  const bf16* src;
+  int ld, n, k0;
+  if (kind < 2) {
+    src = w1; ld = 8 * D; n = (kind ? 4 * D : 0) + 32 * c + r; k0 = 16 * idx;
+  } else if (kind == 2) {
+    src = w2; ld = D; n = 32 * (idx / 2) + r; k0 = 32 * c + 16 * (idx % 2);
+  } else {
+    src = w_out; ld = D; n = 32 * c + r; k0 = 16 * idx;
+  }
+  unsigned short e[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) e[i] = src[(int64_t)(k0 + frag_k(g, i)) * ld + n].v;
+  u32x4_t o;
+  o.x = e[0] | ((unsigned)e[1] << 16);
+  o.y = e[2] | ((unsigned)e[3] << 16);
+  o.z = e[4] | ((unsigned)e[5] << 16);
+  o.w = e[6] | ((unsigned)e[7] << 16);
+  dst[idx * stream_pitch_u4(TOTAL_SUB) + (int64_t)sub * kWave + lane] = o;
+}
+
+// ----------------------------------------------------------------------------- weight stream pipeline
+
+// The workgroup's 256 threads move the fragment stream through a ring of three
+// LDS slots of SUB fragments.  Global loads run two sub-chunks ahead of their
+// use, through two alternating register sets: in step i (parity P = i % 2) the
+// loads of sub-chunk i+3 are issued into set P, the MFMAs of sub-chunk i read
+// ring slot i % 3, then set 1-P (sub-chunk i+2, loaded during step i-1) is
+// stored into slot (i+2) % 3 -- the slot read in step i-1 -- and one barrier
+// closes the step.  Each wavefront keeps the next SUB/2 fragments in a register
+// FIFO that it refills right after each use (from slot i % 3, then from slot
+// (i+1) % 3, which was published before the previous barrier), so LDS latency
+// stays off the MFMA chain.
+template <int SUB>
+struct WeightPipe {
+  static constexpr int PER_THREAD = SUB * kWave / 256;
+  static constexpr int NSLOT = 3;
+  template <int N>
+  static __device__ __forceinline__ void fetch(u32x4_t (&pre)[N], const u32x4_t* stream, int next, int total, int tid) {
+    if (next < total) {
+      const int64_t pitch = stream_pitch_u4(total);
+      const u32x4_t* src = stream + (int64_t)next * kWave + (tid % kWave);
+#pragma unroll
+      for (int i = 0; i < N; ++i) pre[i] = src[(tid / kWave + 4 * i) * pitch];
+    }
+  }
+  template <int N>
+  static __device__ __forceinline__ void commit(const u32x4_t (&pre)[N], u32x4_t* ring0, int next, int total, int tid) {
+    if (next < total) {
+      u32x4_t* dstp = ring0 + (next % NSLOT) * (SUB * kWave);
+#pragma unroll
+      for (int i = 0; i < N; ++i) dstp[tid + i * 256] = pre[i];
+    }
+  }
+};
+
+// ----------------------------------------------------------------------------- FFN half
+
+struct FfnHalfArgs {
+  const float* h;         // [M, D] residual stream after the attention part
+  int64_t M;
+  const u32x4_t* stream;  // fragment stream (pack_ffn_stream_kernel)
+  const bf16 *ln_g, *ln_b, *b1, *b2, *b_out;
+  float ln_eps;
+  const bf16* x;
+  bf16* out;
+  Window win;
+};
+
+template <int NB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void ffn_half_kernel(FfnHalfArgs a) {
+  constexpr int D = 32 * NB, SUB = 2 * NB, NC = 4 * NB;  // SUB fragments per sub-chunk (= k-steps over D)
+  constexpr int NSLOT = 3, FIFO = NB;
+  constexpr int TOTAL_SUB = 3 * NC + NB;
+  static_assert(NB % 2 == 0, "NB must be even");  // whole 16-byte loads per thread; even number of pipeline slots
+  __shared__ u32x4_t ring[NSLOT][SUB * kWave];
+  __shared__ float t_g[D], t_b[D], t_b2[D], t_bout[D], t_b1[8 * D];
+  __shared__ __attribute__((aligned(16))) float stage[4][32][36];  // slice-out transpose, one patch per wavefront
+
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int tcol = lane % 32, g = lane / 32;
+  const int64_t m = (int64_t)blockIdx.x * 128 + wave * 32 + tcol;
+  const bool live = m < a.M;
+
+  // ---- residual rows into result-layout registers: hacc[nb][4q + j] = h[m][32nb + 8q + 4g + j]
+  f32x16_t hacc[NB];
+  {
+    const float* hrow = a.h + (live ? m : 0) * D;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live) v = *reinterpret_cast<const float4*>(hrow + 32 * nb + 8 * q + 4 * g);
+        hacc[nb][4 * q + 0] = v.x; hacc[nb][4 * q + 1] = v.y; hacc[nb][4 * q + 2] = v.z; hacc[nb][4 * q + 3] = v.w;
+      }
+  }
+  for (int i = tid; i < D; i += 256) {
+    t_g[i] = param_or(a.ln_g, i, 1.f);
+    t_b[i] = param_or(a.ln_b, i, 0.f);
+    t_b2[i] = param_or(a.b2, i, 0.f);
+    t_bout[i] = param_or(a.b_out, i, 0.f);
+  }
+  for (int i = tid; i < 8 * D; i += 256) t_b1[i] = param_or(a.b1, i, 0.f);
+
+  // ---- weight stream: sub-chunks 0 and 1 straight into the ring, sub-chunk 2 into register set 1
+  // (as if loaded in a step -1)
+  using Pipe = WeightPipe<SUB>;
+  u32x4_t pre0[Pipe::PER_THREAD], pre1[Pipe::PER_THREAD];
+  int cur = 0;  // sub-chunk being consumed; loads run at cur + 3, ring stores at cur + 2
+  Pipe::fetch(pre0, a.stream, 0, TOTAL_SUB, tid);
+  Pipe::fetch(pre1, a.stream, 1, TOTAL_SUB, tid);
+  Pipe::commit(pre0, ring[0], 0, TOTAL_SUB, tid);
+  Pipe::commit(pre1, ring[0], 1, TOTAL_SUB, tid);
+  Pipe::fetch(pre1, a.stream, 2, TOTAL_SUB, tid);
+
+  __syncthreads();  // tables and the first two sub-chunks are in LDS
+
+  // ---- LN3 over the row (this lane holds half of it, lane ^ 32 the other half)
+  bf16x8_t aop[SUB];
+  {
+    float s = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s += hacc[nb][e];
+    s += __shfl_xor(s, 32, kWave);
+    const float mean = s * (1.0f / D);
+    float qv = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float dlt = hacc[nb][e] - mean;
+        qv = fmaf(dlt, dlt, qv);
+      }
+    qv += __shfl_xor(qv, 32, kWave);
+    const float rstd = rsqrtf(qv * (1.0f / D) + a.ln_eps);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int n = 32 * nb + 16 * hf + frag_k(g, e);
+          v[e] = (hacc[nb][8 * hf + e] - mean) * rstd * t_g[n] + t_b[n];
+        }
+        aop[2 * nb + hf] = to_operand(v);
+      }
+  }
+
+  // ---- fragment FIFO: the first FIFO fragments of sub-chunk 0
+  bf16x8_t fifo[FIFO];
+#pragma unroll
+  for (int i = 0; i < FIFO; ++i) fifo[i] = __builtin_bit_cast(bf16x8_t, ring[0][i * kWave + lane]);
+
+  // One pipeline step around the MFMAs of sub-chunk `cur`; P is the step's parity (compile time).
+#define SI_STEP_OPEN(P)                                                         \
+  __builtin_amdgcn_sched_barrier(0);                                            \
+  if constexpr ((P) == 0) Pipe::fetch(pre0, a.stream, cur + 3, TOTAL_SUB, tid); \
+  else Pipe::fetch(pre1, a.stream, cur + 3, TOTAL_SUB, tid);                    \
+  const u32x4_t* slot_c = ring[cur % NSLOT];                                    \
+  const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                              \
+  (void)slot_c; (void)slot_n
+#define SI_STEP_CLOSE(P)                                                        \
+  __builtin_amdgcn_sched_barrier(0);                                            \
+  if constexpr ((P) == 0) Pipe::commit(pre1, ring[0], cur + 2, TOTAL_SUB, tid); \
+  else Pipe::commit(pre0, ring[0], cur + 2, TOTAL_SUB, tid);                    \
+  ++cur;                                                                        \
+  __syncthreads()
+  // fragment f of the current sub-chunk, and its replacement FIFO fragments further down the stream
+#define SI_FRAG(f) fifo[(f) % FIFO]
+#define SI_REFILL(f)                                                                                 \
+  fifo[(f) % FIFO] = __builtin_bit_cast(bf16x8_t, (f) < FIFO ? slot_c[((f) + FIFO) * kWave + lane]   \
+                                                             : slot_n[((f)-FIFO) * kWave + lane])
+  // A step issues, per fragment: one MFMA, the fragment's FIFO refill, and one stage of the GEGLU
+  // group that rides along (a handful of independent vector-ALU instructions that execute while
+  // the matrix pipe works); sched_barrier pins that order.  Stages that do not fit behind the
+  // SUB MFMAs run after them.
+#define SI_GEGLU_TAIL(GRP, UVC, UGC) \
+  _Pragma("unroll") for (int s = SUB; s < kGeluStages; ++s) GRP.stage(s, UVC, UGC, bvp, bgp, gv)
+  // W1 sub-chunk into one accumulator block (value or gate rows of a chunk)
+#define SI_RUN_W1(ACC, STAGE_STMT)                                                          \
+  _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                         \
+    if (s == 0) { _Pragma("unroll") for (int e = 0; e < 16; ++e) ACC[e] = 0.f; }            \
+    ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), aop[s], ACC, 0, 0, 0);        \
+    SI_REFILL(s);                                                                           \
+    STAGE_STMT;                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                      \
+  }
+  // W2 sub-chunk: the chunk's GEGLU output times W2, accumulated into the residual blocks
+#define SI_RUN_W2(GOP, STAGE_STMT)                                                                       \
+  _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                                      \
+    hacc[s / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), GOP[s % 2], hacc[s / 2], 0, 0, 0); \
+    SI_REFILL(s);                                                                                        \
+    STAGE_STMT;                                                                                          \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+  }
+#define SI_GELU_PACK(GOP)          \
+  GOP[0] = to_operand(&gv[0]);     \
+  GOP[1] = to_operand(&gv[8])
+
+  // Pipeline slot t: MFMAs of W1(t+1) and W2(t-1), GEGLU of chunk t in three groups of result
+  // registers.  Chunk c keeps its W1 results in register set c % 2, its operand in gop set c % 2.
+#define SI_SLOT(t, P0, UVC, UGC, UVN, UGN, GOPP, GOPC)                                              \
+  {                                                                                                 \
+    const float* bvp = t_b1 + 32 * (t) + 4 * g;                                                     \
+    const float* bgp = bvp + 4 * D;                                                                 \
+    GegluGroup<0, 6> ga;                                                                            \
+    GegluGroup<6, 5> gb;                                                                            \
+    GegluGroup<11, 5> gc;                                                                           \
+    { SI_STEP_OPEN(P0); SI_RUN_W1(UVN, ga.stage(s, UVC, UGC, bvp, bgp, gv)) SI_GEGLU_TAIL(ga, UVC, UGC); SI_STEP_CLOSE(P0); } \
+    { SI_STEP_OPEN(1 - (P0)); SI_RUN_W1(UGN, gb.stage(s, UVC, UGC, bvp, bgp, gv)) SI_GEGLU_TAIL(gb, UVC, UGC); SI_STEP_CLOSE(1 - (P0)); } \
+    { SI_STEP_OPEN(P0); SI_RUN_W2(GOPP, gc.stage(s, UVC, UGC, bvp, bgp, gv)) SI_GEGLU_TAIL(gc, UVC, UGC); SI_GELU_PACK(GOPC); SI_STEP_CLOSE(P0); } \
+  }
+
+  f32x16_t uvA, ugA, uvB, ugB;
+  bf16x8_t gopA[2], gopB[2];
+  float gv[16];
+  // prologue: W1(0), then W1(1) with the GEGLU of chunk 0
+  { SI_STEP_OPEN(0); SI_RUN_W1(uvA, (void)0) SI_STEP_CLOSE(0); }
+  { SI_STEP_OPEN(1); SI_RUN_W1(ugA, (void)0) SI_STEP_CLOSE(1); }
+  {
+    const float* bvp = t_b1 + 4 * g;
+    const float* bgp = bvp + 4 * D;
+    GegluGroup<0, 8> ga;
+    GegluGroup<8, 8> gb;
+    { SI_STEP_OPEN(0); SI_RUN_W1(uvB, ga.stage(s, uvA, ugA, bvp, bgp, gv)) SI_GEGLU_TAIL(ga, uvA, ugA); SI_STEP_CLOSE(0); }
+    { SI_STEP_OPEN(1); SI_RUN_W1(ugB, gb.stage(s, uvA, ugA, bvp, bgp, gv)) SI_GEGLU_TAIL(gb, uvA, ugA); SI_GELU_PACK(gopA); SI_STEP_CLOSE(1); }
+  }
+  // steady state, two slots per trip (odd chunk in set B, even chunk in set A)
+#pragma unroll 1
+  for (int t = 1; t <= NC - 2; t += 2) {
+    SI_SLOT(t, 0, uvB, ugB, uvA, ugA, gopA, gopB)
+    SI_SLOT(t + 1, 1, uvA, ugA, uvB, ugB, gopB, gopA)
+  }
+  // drain: W2(NC-2) with the GEGLU of the last chunk (set B), then W2(NC-1)
+  {
+    const float* bvp = t_b1 + 32 * (NC - 1) + 4 * g;
+    const float* bgp = bvp + 4 * D;
+    GegluGroup<0, 8> ga;
+    GegluGroup<8, 8> gb;
+#pragma unroll
+    for (int s = 0; s < kGeluStages; ++s) ga.stage(s, uvB, ugB, bvp, bgp, gv);
+#pragma unroll
+    for (int s = 0; s < kGeluStages; ++s) gb.stage(s, uvB, ugB, bvp, bgp, gv);
+    SI_GELU_PACK(gopB);
+    { SI_STEP_OPEN(0); SI_RUN_W2(gopA, (void)0) SI_STEP_CLOSE(0); }
+    { SI_STEP_OPEN(1); SI_RUN_W2(gopB, (void)0) SI_STEP_CLOSE(1); }
+  }
+
+  // ---- final h (+ b2) as bf16 operands; proj_out one 32-channel block at a time
+  bf16x8_t hop[SUB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      float vh[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vh[e] = hacc[nb][8 * hf + e] + t_b2[32 * nb + 16 * hf + frag_k(g, e)];
+      hop[2 * nb + hf] = to_operand(vh);
+    }
+
+  // Slice-out.  Fast path (window rows, window start and frame size multiples of 8 positions):
+  // each wavefront transposes its 32 tokens x 32 channels through a private LDS patch so that a lane
+  // owns 8 consecutive positions of one channel -- one 16-byte load of x and one 16-byte store of
+  // out; the x loads are issued two blocks ahead of their use.  Otherwise: element-wise.
+  const Window& w = a.win;
+  const int64_t cs = (int64_t)w.F * w.P;
+  const bool vec_ok = (w.Pw % 8 == 0) && (w.p0 % 8 == 0) && (w.P % 8 == 0);
+  // element-wise path: this lane's token
+  const int64_t mm = live ? m : 0;
+  const int64_t off0 = ((int64_t)(mm / w.Pw / w.Fw) * w.C * w.F + (w.f0 + (int)((mm / w.Pw) % w.Fw))) * w.P + w.p0 +
+                       (int)(mm % w.Pw);
+  // vector path: lane-op i in {0,1} -> channel row r_i of the block, token group tg_i (8 tokens)
+  int vr[2];
+  int64_t voff[2];
+  bool vlive[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int idx = lane + kWave * i, tg = idx % 4;
+    vr[i] = idx / 4;
+    const int64_t m8 = (int64_t)blockIdx.x * 128 + wave * 32 + 8 * tg;
+    vlive[i] = vec_ok && m8 < a.M;
+    const int64_t mq = vlive[i] ? m8 : 0;
+    voff[i] = ((int64_t)(mq / w.Pw / w.Fw) * w.C * w.F + (w.f0 + (int)((mq / w.Pw) % w.Fw))) * w.P + w.p0 + (int)(mq % w.Pw) +
+              (int64_t)vr[i] * cs;
+  }
+  u32x4_t xq[3][2];
+#define SI_X_PREFETCH(nb)                                                                                  \
+  if ((nb) < NB) {                                                                                         \
+    _Pragma("unroll") for (int i = 0; i < 2; ++i) if (vlive[i])                                            \
+        xq[(nb) % 3][i] = *reinterpret_cast<const u32x4_t*>(a.x + voff[i] + (int64_t)(32 * (nb)) * cs);    \
+  }
+  SI_X_PREFETCH(0)
+  SI_X_PREFETCH(1)
+
+  // 3*NC pipeline steps precede (an even number), so block nb runs at parity nb % 2
+#define SI_PROJ_OUT_BLOCK(nb, P)                                                                 \
+  {                                                                                              \
+    f32x16_t y;                                                                                  \
+    _Pragma("unroll") for (int e = 0; e < 16; ++e) y[e] = 0.f;                                   \
+    SI_X_PREFETCH((nb) + 2)                                                                      \
+    {                                                                                            \
+      SI_STEP_OPEN(P);                                                                           \
+      _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                          \
+        y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), hop[s], y, 0, 0, 0);             \
+        SI_REFILL(s);                                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                       \
+      }                                                                                          \
+      SI_STEP_CLOSE(P);                                                                          \
+    }                                                                                            \
+    if (vec_ok) {                                                                                \
+      float(*patch)[36] = stage[wave];                                                           \
+      _Pragma("unroll") for (int q = 0; q < 4; ++q)                                              \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j)                                              \
+        patch[8 * q + 4 * g + j][tcol] = y[4 * q + j] + t_bout[32 * (nb) + 8 * q + 4 * g + j];   \
+      __builtin_amdgcn_wave_barrier();                                                           \
+      _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                            \
+        const float4 y0 = *reinterpret_cast<const float4*>(&patch[vr[i]][8 * ((lane + kWave * i) % 4)]);     \
+        const float4 y1 = *reinterpret_cast<const float4*>(&patch[vr[i]][8 * ((lane + kWave * i) % 4) + 4]); \
+        if (vlive[i]) {                                                                          \
+          const u32x4_t xv = xq[(nb) % 3][i];                                                    \
+          u32x4_t o;                                                                             \
+          o.x = pack_bf16x2(__uint_as_float(xv.x << 16) + y0.x, __uint_as_float(xv.x & 0xffff0000u) + y0.y); \
+          o.y = pack_bf16x2(__uint_as_float(xv.y << 16) + y0.z, __uint_as_float(xv.y & 0xffff0000u) + y0.w); \
+          o.z = pack_bf16x2(__uint_as_float(xv.z << 16) + y1.x, __uint_as_float(xv.z & 0xffff0000u) + y1.y); \
+          o.w = pack_bf16x2(__uint_as_float(xv.w << 16) + y1.z, __uint_as_float(xv.w & 0xffff0000u) + y1.w); \
+          *reinterpret_cast<u32x4_t*>(a.out + voff[i] + (int64_t)(32 * (nb)) * cs) = o;          \
+        }                                                                                        \
+      }                                                                                          \
+      __builtin_amdgcn_wave_barrier();                                                           \
+    } else if (live) {                                                                           \
+      _Pragma("unroll") for (int q = 0; q < 4; ++q)                                              \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                            \
+        const int n = 32 * (nb) + 8 * q + 4 * g + j;                                             \
+        const int64_t off = off0 + n * cs;                                                       \
+        const float r = bf16_bits_to_float(a.x[off].v) + (y[4 * q + j] + t_bout[n]);             \
+        a.out[off].v = float_to_bf16_bits(r);                                                    \
+      }                                                                                          \
+    }                                                                                            \
+  }
+#pragma unroll
+  for (int nb2 = 0; nb2 < NB; nb2 += 2) {
+    SI_PROJ_OUT_BLOCK(nb2, 0)
+    SI_PROJ_OUT_BLOCK(nb2 + 1, 1)
+  }
+#undef SI_X_PREFETCH
+#undef SI_PROJ_OUT_BLOCK
+#undef SI_SLOT
+#undef SI_GELU_PACK
+#undef SI_RUN_W2
+#undef SI_RUN_W1
+#undef SI_GEGLU_TAIL
+#undef SI_REFILL
+#undef SI_FRAG
+#undef SI_STEP_CLOSE
+#undef SI_STEP_OPEN
+}
+
+}  // namespace si

@@ -12,6 +12,7 @@
 
 #include "k_attn.h"
 #include "k_cosine.h"
+#include "k_fused.h"
 #include "k_gemm.h"
 #include "k_norm.h"
 #include "si_common.h"
@@ -69,10 +70,11 @@ struct Plan {
   int64_t extent, slice_len;
   int64_t Mmax;  // tokens of the largest window
   bool pe;
+  int fused_nb;  // > 0: register-resident FFN half with D = 32*fused_nb
   // workspace offsets (bytes)
   size_t off_stats, off_pe, off_ctxkv;
   size_t off_w_in, off_wqkv, off_wo, off_wq2, off_wkv2, off_wo2, off_w1, off_w2, off_w_out;
-  size_t off_a, off_h, off_big;
+  size_t off_a, off_h, off_big, off_ffn_stream;
   size_t weights_bytes, total_bytes;
 };
 
@@ -145,6 +147,9 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_w1 = take(8 * Dz * Dz * es);
   p->off_w2 = take(4 * Dz * Dz * es);
   p->off_w_out = take(split * C * Dz * es);
+  p->fused_nb = 0;
+  if (p->dtype == SI_BF16 && p->C == p->D && (D == 64 || D == 320)) p->fused_nb = (int)(D / 32);
+  p->off_ffn_stream = take(p->fused_nb ? (size_t)stream_bytes(13 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->weights_bytes = off - act_end;
   p->total_bytes = off;
   return SI_OK;
@@ -244,7 +249,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     StageScope scope("pack_weights", st);
     for (int h2 = 0; h2 < kSplit; ++h2) {
       SI_TRY(launch_pack<T>(cT(w->w_in), w_in + (size_t)h2 * C, C, D, D, 0, 0, st, kSplit * C));
-      SI_TRY(launch_pack<T>(cT(w->w_out), w_out + (size_t)h2 * D, D, C, C, 0, 0, st, kSplit * D));
+      if (p.fused_nb == 0) SI_TRY(launch_pack<T>(cT(w->w_out), w_out + (size_t)h2 * D, D, C, C, 0, 0, st, kSplit * D));
     }
     SI_TRY(launch_pack<T>(cT(w->wq), wqkv, D, D, D, 0, 0, st));
     SI_TRY(launch_pack<T>(cT(w->wk), wqkv + (size_t)D * D, D, D, D, 0, 0, st));
@@ -256,8 +261,18 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       SI_TRY(launch_pack<T>(cT(w->wv2), wkv2 + (size_t)D * p.Cc, p.Cc, D, D, 0, 0, st));
       SI_TRY(launch_pack<T>(cT(w->wo2), wo2, D, D, D, 0, 0, st));
     }
-    SI_TRY(launch_pack<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 0, 4 * D, st));
-    SI_TRY(launch_pack<T>(cT(w->w2), w2, 4 * D, D, D, 0, 0, st));
+    if (p.fused_nb == 0) {
+      SI_TRY(launch_pack<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 0, 4 * D, st));
+      SI_TRY(launch_pack<T>(cT(w->w2), w2, 4 * D, D, D, 0, 0, st));
+    } else if constexpr (sizeof(T) == 2) {
+      u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + p.off_ffn_stream);
+      const int frags = 26 * p.fused_nb * p.fused_nb;
+      if (p.fused_nb == 2)
+        pack_ffn_stream_kernel<2><<<(frags + 3) / 4, 256, 0, st>>>(cT(w->w1), cT(w->w2), cT(w->w_out), stream);
+      else
+        pack_ffn_stream_kernel<10><<<(frags + 3) / 4, 256, 0, st>>>(cT(w->w1), cT(w->w2), cT(w->w_out), stream);
+      SI_CHECK_LAUNCH();
+    }
     if (pe) {
       pe_table_kernel<<<(p.F * D + 255) / 256, 256, 0, st>>>(pe, p.F, D);
       SI_CHECK_LAUNCH();
@@ -344,6 +359,22 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       {
         EpiResidual<T> epi{h, (int64_t)D, cT(w->bo2), 1, nullptr};
         SI_TRY(launch_gemm<T>("cross_out", a, (int64_t)D, wo2, M, D, D, epi, st));
+      }
+    }
+    if constexpr (sizeof(T) == 2) {
+      if (p.fused_nb) {
+        StageScope scope("ffn_half_fused", st);
+        FfnHalfArgs fa;
+        fa.h = h; fa.M = M; fa.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_ffn_stream);
+        fa.ln_g = cT(w->ln3_g); fa.ln_b = cT(w->ln3_b); fa.b1 = cT(w->b1); fa.b2 = cT(w->b2); fa.b_out = cT(w->b_out);
+        fa.ln_eps = w->ln_eps; fa.x = X; fa.out = OUT; fa.win = win;
+        const unsigned blocks = (unsigned)((M + 127) / 128);
+        if (p.fused_nb == 2)
+          ffn_half_kernel<2><<<blocks, 256, 0, st>>>(fa);
+        else
+          ffn_half_kernel<10><<<blocks, 256, 0, st>>>(fa);
+        SI_CHECK_LAUNCH();
+        continue;
       }
     }
     SI_TRY(launch_layer_norm<T>("ln3", h, a, M, D, w->ln3_g, w->ln3_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st));

@@ -16,17 +16,15 @@ struct bf16 {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));  // 16-byte register staging (a plain vector, not a struct)
 
 __device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
   return __uint_as_float(((unsigned)b) << 16);
 }
 
-// Round-to-nearest-even; NaN stays NaN (quiet), overflow goes to infinity as IEEE does.
+// Round-to-nearest-even via the hardware conversion (v_cvt_pk_bf16_f32); NaN stays NaN.
 __device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {
-  unsigned u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x0040u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (unsigned short)(u >> 16);
+  return __builtin_bit_cast(unsigned short, (__bf16)f);
 }
 
 __device__ __forceinline__ float to_float(float v) { return v; }
