@@ -121,37 +121,32 @@ __host__ __device__ inline int64_t stream_bytes(int total_sub, int sub) { return
 // fragments (fragment = 64 lanes x 8 bf16); with NC = 4*NB chunks of 32 inner columns:
 //   V(c): W1 value rows 32c..32c+31, k-steps 0..2NB-1      G(c): the gate rows likewise
 //   W2(c): for nb in [0, NB): k-steps (inner 32c..32c+15), (32c+16..32c+31)
-//   O(nb): W_out rows 32nb..32nb+31, k-steps 0..2NB-1
-// order: V0 G0 V1 G1 | for t in 1..NC-2: V(t+1) G(t+1) W2(t-1) | W2(NC-2) W2(NC-1) | O(0..NB-1)
+// order: V0 G0 V1 G1 | for t in 1..NC-2: V(t+1) G(t+1) W2(t-1) | W2(NC-2) W2(NC-1)
+// written at sub-chunks [sub0, sub0 + 3*NC) of a stream of total_sub sub-chunks.
 // One thread per (fragment, lane).  Sources are row-major [in, out].
 template <int NB>
 __global__ __launch_bounds__(256) void pack_ffn_stream_kernel(const bf16* __restrict__ w1, const bf16* __restrict__ w2,
-                                                              const bf16* __restrict__ w_out, u32x4_t* __restrict__ dst) {
+                                                              u32x4_t* __restrict__ dst, int sub0, int total_sub) {
   constexpr int D = 32 * NB, SUB = 2 * NB, NC = 4 * NB;
-  constexpr int TOTAL_SUB = 3 * NC + NB;
   const int fidx = blockIdx.x * 4 + threadIdx.x / kWave;
-  if (fidx >= TOTAL_SUB * SUB) return;
+  if (fidx >= 3 * NC * SUB) return;
   const int lane = threadIdx.x % kWave, r = lane % 32, g = lane / 32;
   const int sub = fidx / SUB, idx = fidx % SUB;
-  int kind, c;  // kind 0: V, 1: G, 2: W2, 3: O
+  int kind, c;  // kind 0: V, 1: G, 2: W2
   if (sub < 4) {
     kind = sub % 2; c = sub / 2;
   } else if (sub < 4 + 3 * (NC - 2)) {
     const int rr = sub - 4, t = 1 + rr / 3, k = rr % 3;
     kind = k; c = k == 2 ? t - 1 : t + 1;
-  } else if (sub < 3 * NC) {
-    kind = 2; c = NC - 2 + (sub - (4 + 3 * (NC - 2)));
   } else {
-    kind = 3; c = sub - 3 * NC;
+    kind = 2; c = NC - 2 + (sub - (4 + 3 * (NC - 2)));
   }
   const bf16* src;
   int ld, n, k0;
   if (kind < 2) {
     src = w1; ld = 8 * D; n = (kind ? 4 * D : 0) + 32 * c + r; k0 = 16 * idx;
-  } else if (kind == 2) {
-    src = w2; ld = D; n = 32 * (idx / 2) + r; k0 = 32 * c + 16 * (idx % 2);
   } else {
-    src = w_out; ld = D; n = 32 * c + r; k0 = 16 * idx;
+    src = w2; ld = D; n = 32 * (idx / 2) + r; k0 = 32 * c + 16 * (idx % 2);
   }
   unsigned short e[8];
 #pragma unroll
@@ -161,7 +156,37 @@ __global__ __launch_bounds__(256) void pack_ffn_stream_kernel(const bf16* __rest
   o.y = e[2] | ((unsigned)e[3] << 16);
   o.z = e[4] | ((unsigned)e[5] << 16);
   o.w = e[6] | ((unsigned)e[7] << 16);
-  dst[idx * stream_pitch_u4(TOTAL_SUB) + (int64_t)sub * kWave + lane] = o;
+  dst[idx * stream_pitch_u4(total_sub) + (int64_t)(sub0 + sub) * kWave + lane] = o;
+}
+
+// Sub-chunks that are one 32-column block of a [D, ld] row-major matrix, k-steps 0..2NB-1 over
+// its D rows (proj_in, q/k/v, attention out-projection, proj_out): block i of the list goes to
+// sub-chunk sub0 + i.
+struct BlockDesc {
+  const bf16* src;
+  int ld, col0;
+};
+struct BlockList {
+  BlockDesc b[48];
+};
+template <int NB>
+__global__ __launch_bounds__(256) void pack_blocks_kernel(BlockList list, int n_blocks, u32x4_t* __restrict__ dst, int sub0,
+                                                          int total_sub) {
+  constexpr int SUB = 2 * NB;
+  const int fidx = blockIdx.x * 4 + threadIdx.x / kWave;
+  if (fidx >= n_blocks * SUB) return;
+  const int lane = threadIdx.x % kWave, r = lane % 32, g = lane / 32;
+  const int blk = fidx / SUB, idx = fidx % SUB;
+  const BlockDesc d = list.b[blk];
+  unsigned short e[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) e[i] = d.src[(int64_t)(16 * idx + frag_k(g, i)) * d.ld + d.col0 + r].v;
+  u32x4_t o;
+  o.x = e[0] | ((unsigned)e[1] << 16);
+  o.y = e[2] | ((unsigned)e[3] << 16);
+  o.z = e[4] | ((unsigned)e[5] << 16);
+  o.w = e[6] | ((unsigned)e[7] << 16);
+  dst[idx * stream_pitch_u4(total_sub) + (int64_t)(sub0 + blk) * kWave + lane] = o;
 }
 
 // ----------------------------------------------------------------------------- weight stream pipeline
@@ -202,10 +227,11 @@ struct WeightPipe {
 // ----------------------------------------------------------------------------- FFN half
 
 struct FfnHalfArgs {
-  const float* h;         // [M, D] residual stream after the attention part
+  const float* h;         // [M, D] residual stream before the last attention output projection
+  const bf16* o;          // [M, D] attention output (heads concatenated); h += o W_o + b_o comes first
   int64_t M;
-  const u32x4_t* stream;  // fragment stream (pack_ffn_stream_kernel)
-  const bf16 *ln_g, *ln_b, *b1, *b2, *b_out;
+  const u32x4_t* stream;  // fragment stream: W_o blocks, FFN (pack_ffn_stream_kernel), W_out blocks
+  const bf16 *b_o, *ln_g, *ln_b, *b1, *b2, *b_out;
   float ln_eps;
   const bf16* x;
   bf16* out;
@@ -216,10 +242,10 @@ template <int NB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void ffn_half_kernel(FfnHalfArgs a) {
   constexpr int D = 32 * NB, SUB = 2 * NB, NC = 4 * NB;  // SUB fragments per sub-chunk (= k-steps over D)
   constexpr int NSLOT = 3, FIFO = NB;
-  constexpr int TOTAL_SUB = 3 * NC + NB;
+  constexpr int TOTAL_SUB = NB + 3 * NC + NB;
   static_assert(NB % 2 == 0, "NB must be even");  // whole 16-byte loads per thread; even number of pipeline slots
   __shared__ u32x4_t ring[NSLOT][SUB * kWave];
-  __shared__ float t_g[D], t_b[D], t_b2[D], t_bout[D], t_b1[8 * D];
+  __shared__ float t_g[D], t_b[D], t_b2[D], t_bout[D], t_bo[D], t_b1[8 * D];
   __shared__ __attribute__((aligned(16))) float stage[4][32][36];  // slice-out transpose, one patch per wavefront
 
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -240,11 +266,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         hacc[nb][4 * q + 0] = v.x; hacc[nb][4 * q + 1] = v.y; hacc[nb][4 * q + 2] = v.z; hacc[nb][4 * q + 3] = v.w;
       }
   }
+  // attention output rows as column operands: k-step s holds o[m][16s + {4g..4g+3, 8+4g..8+4g+3}]
+  bf16x8_t aop[SUB];
+  {
+    const bf16* orow = a.o + (live ? m : 0) * D;
+#pragma unroll
+    for (int s2 = 0; s2 < SUB; ++s2) {
+      uint2 lo = make_uint2(0, 0), hi = make_uint2(0, 0);
+      if (live) {
+        lo = *reinterpret_cast<const uint2*>(orow + 16 * s2 + 4 * g);
+        hi = *reinterpret_cast<const uint2*>(orow + 16 * s2 + 8 + 4 * g);
+      }
+      u32x4_t u;
+      u.x = lo.x; u.y = lo.y; u.z = hi.x; u.w = hi.y;
+      aop[s2] = __builtin_bit_cast(bf16x8_t, u);
+    }
+  }
   for (int i = tid; i < D; i += 256) {
     t_g[i] = param_or(a.ln_g, i, 1.f);
     t_b[i] = param_or(a.ln_b, i, 0.f);
     t_b2[i] = param_or(a.b2, i, 0.f);
     t_bout[i] = param_or(a.b_out, i, 0.f);
+    t_bo[i] = param_or(a.b_o, i, 0.f);
   }
   for (int i = tid; i < 8 * D; i += 256) t_b1[i] = param_or(a.b1, i, 0.f);
 
@@ -261,8 +304,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   __syncthreads();  // tables and the first two sub-chunks are in LDS
 
-  // ---- LN3 over the row (this lane holds half of it, lane ^ 32 the other half)
-  bf16x8_t aop[SUB];
+  // ---- fragment FIFO: the first FIFO fragments of sub-chunk 0
+  bf16x8_t fifo[FIFO];
+#pragma unroll
+  for (int i = 0; i < FIFO; ++i) fifo[i] = __builtin_bit_cast(bf16x8_t, ring[0][i * kWave + lane]);
+
+  // One pipeline step around the MFMAs of sub-chunk `cur`; P is the step's parity (compile time).
+#define SI_STEP_OPEN(P)                                                         \
+  __builtin_amdgcn_sched_barrier(0);                                            \
+  if constexpr ((P) == 0) Pipe::fetch(pre0, a.stream, cur + 3, TOTAL_SUB, tid); \
+  else Pipe::fetch(pre1, a.stream, cur + 3, TOTAL_SUB, tid);                    \
+  const u32x4_t* slot_c = ring[cur % NSLOT];                                    \
+  const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                              \
+  (void)slot_c; (void)slot_n
+#define SI_STEP_CLOSE(P)                                                        \
+  __builtin_amdgcn_sched_barrier(0);                                            \
+  if constexpr ((P) == 0) Pipe::commit(pre1, ring[0], cur + 2, TOTAL_SUB, tid); \
+  else Pipe::commit(pre0, ring[0], cur + 2, TOTAL_SUB, tid);                    \
+  ++cur;                                                                        \
+  __syncthreads()
+  // fragment f of the current sub-chunk, and its replacement FIFO fragments further down the stream
+#define SI_FRAG(f) fifo[(f) % FIFO]
+#define SI_REFILL(f)                                                                                 \
+  fifo[(f) % FIFO] = __builtin_bit_cast(bf16x8_t, (f) < FIFO ? slot_c[((f) + FIFO) * kWave + lane]   \
+                                                             : slot_n[((f)-FIFO) * kWave + lane])
+  // ---- h += o W_o + b_o: NB steps, one 32-column block of the residual each
+#define SI_WO_BLOCK(nb, P)                                                                          \
+  {                                                                                                 \
+    SI_STEP_OPEN(P);                                                                                \
+    _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                               \
+      hacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), aop[s], hacc[nb], 0, 0, 0);    \
+      SI_REFILL(s);                                                                                 \
+      __builtin_amdgcn_sched_barrier(0);                                                            \
+    }                                                                                               \
+    SI_STEP_CLOSE(P);                                                                               \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                   \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) hacc[nb][4 * q + j] += t_bo[32 * (nb) + 8 * q + 4 * g + j]; \
+  }
+#pragma unroll
+  for (int nb2 = 0; nb2 < NB; nb2 += 2) {
+    SI_WO_BLOCK(nb2, 0)
+    SI_WO_BLOCK(nb2 + 1, 1)
+  }
+#undef SI_WO_BLOCK
+
+  // ---- LN3 over the row (this lane holds half of it, lane ^ 32 the other half); aop becomes its output
   {
     float s = 0.f;
 #pragma unroll
@@ -295,30 +381,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
   }
 
-  // ---- fragment FIFO: the first FIFO fragments of sub-chunk 0
-  bf16x8_t fifo[FIFO];
-#pragma unroll
-  for (int i = 0; i < FIFO; ++i) fifo[i] = __builtin_bit_cast(bf16x8_t, ring[0][i * kWave + lane]);
-
-  // One pipeline step around the MFMAs of sub-chunk `cur`; P is the step's parity (compile time).
-#define SI_STEP_OPEN(P)                                                         \
-  __builtin_amdgcn_sched_barrier(0);                                            \
-  if constexpr ((P) == 0) Pipe::fetch(pre0, a.stream, cur + 3, TOTAL_SUB, tid); \
-  else Pipe::fetch(pre1, a.stream, cur + 3, TOTAL_SUB, tid);                    \
-  const u32x4_t* slot_c = ring[cur % NSLOT];                                    \
-  const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                              \
-  (void)slot_c; (void)slot_n
-#define SI_STEP_CLOSE(P)                                                        \
-  __builtin_amdgcn_sched_barrier(0);                                            \
-  if constexpr ((P) == 0) Pipe::commit(pre1, ring[0], cur + 2, TOTAL_SUB, tid); \
-  else Pipe::commit(pre0, ring[0], cur + 2, TOTAL_SUB, tid);                    \
-  ++cur;                                                                        \
-  __syncthreads()
-  // fragment f of the current sub-chunk, and its replacement FIFO fragments further down the stream
-#define SI_FRAG(f) fifo[(f) % FIFO]
-#define SI_REFILL(f)                                                                                 \
-  fifo[(f) % FIFO] = __builtin_bit_cast(bf16x8_t, (f) < FIFO ? slot_c[((f) + FIFO) * kWave + lane]   \
-                                                             : slot_n[((f)-FIFO) * kWave + lane])
   // A step issues, per fragment: one MFMA, the fragment's FIFO refill, and one stage of the GEGLU
   // group that rides along (a handful of independent vector-ALU instructions that execute while
   // the matrix pipe works); sched_barrier pins that order.  Stages that do not fit behind the
@@ -441,7 +503,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   SI_X_PREFETCH(0)
   SI_X_PREFETCH(1)
 
-  // 3*NC pipeline steps precede (an even number), so block nb runs at parity nb % 2
+  // NB + 3*NC pipeline steps precede (an even number), so block nb runs at parity nb % 2
 #define SI_PROJ_OUT_BLOCK(nb, P)                                                                 \
   {                                                                                              \
     f32x16_t y;                                                                                  \

@@ -13,6 +13,7 @@
 #include "k_attn.h"
 #include "k_cosine.h"
 #include "k_fused.h"
+#include "k_fused_attn.h"
 #include "k_gemm.h"
 #include "k_norm.h"
 #include "si_common.h"
@@ -70,11 +71,12 @@ struct Plan {
   int64_t extent, slice_len;
   int64_t Mmax;  // tokens of the largest window
   bool pe;
-  int fused_nb;  // > 0: register-resident FFN half with D = 32*fused_nb
+  int fused_nb;     // > 0: register-resident FFN half with D = 32*fused_nb
+  bool fused_attn;  // register-resident attention half as well (temporal blocks)
   // workspace offsets (bytes)
   size_t off_stats, off_pe, off_ctxkv;
   size_t off_w_in, off_wqkv, off_wo, off_wq2, off_wkv2, off_wo2, off_w1, off_w2, off_w_out;
-  size_t off_a, off_h, off_big, off_ffn_stream;
+  size_t off_a, off_h, off_big, off_ffn_stream, off_attn_stream;
   size_t weights_bytes, total_bytes;
 };
 
@@ -130,11 +132,27 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_stats = take((size_t)p->B * p->F * p->G * 2 * sizeof(float));
   p->off_pe = take(p->pe ? (size_t)p->F * Dz * sizeof(float) : 0);
   p->off_ctxkv = take((size_t)p->B * p->Mc * 2 * Dz * es);
+  // which path: register-resident kernels need bf16, C == D = 64 or 320 (instantiated widths)
+  p->fused_nb = 0;
+  p->fused_attn = false;
+  if (p->dtype == SI_BF16 && p->C == p->D && (D == 64 || D == 320)) {
+    p->fused_nb = (int)(D / 32);
+    const int tp = p->F <= 32 ? 32 / p->F : 0;
+    const bool dh_ok = (D == 320 && (p->d == 40 || p->d == 64)) || (D == 64 && p->d == 32);
+    p->fused_attn = p->kind == SI_BLOCK_TEMPORAL && tp >= 1 && dh_ok && (int64_t)p->F * p->G <= kAttnMaxStats &&
+                    (p->B <= 2 || p->slice_len >= 128);
+  }
   // one slice's intermediates
-  const size_t split = es == 2 ? 2 : 1;  // bf16: proj_in / proj_out operands travel as (high, low) pairs
-  p->off_a = take((size_t)p->Mmax * (C > Dz ? C : Dz) * split * es);
-  p->off_h = take((size_t)p->Mmax * Dz * sizeof(float));
-  p->off_big = take((size_t)p->Mmax * 4 * Dz * es);
+  const size_t split = es == 2 ? 2 : 1;  // bf16 staged path: proj_in / proj_out operands travel as (high, low) pairs
+  if (p->fused_attn) {
+    p->off_a = take((size_t)p->Mmax * Dz * es);  // attention output o
+    p->off_h = take((size_t)p->Mmax * Dz * sizeof(float));
+    p->off_big = take(0);
+  } else {
+    p->off_a = take((size_t)p->Mmax * (C > Dz ? C : Dz) * split * es);
+    p->off_h = take((size_t)p->Mmax * Dz * sizeof(float));
+    p->off_big = take((size_t)p->Mmax * 4 * Dz * es);
+  }
   const size_t act_end = off;
   // re-laid-out weights
   p->off_w_in = take(split * Dz * C * es);
@@ -147,9 +165,8 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_w1 = take(8 * Dz * Dz * es);
   p->off_w2 = take(4 * Dz * Dz * es);
   p->off_w_out = take(split * C * Dz * es);
-  p->fused_nb = 0;
-  if (p->dtype == SI_BF16 && p->C == p->D && (D == 64 || D == 320)) p->fused_nb = (int)(D / 32);
-  p->off_ffn_stream = take(p->fused_nb ? (size_t)stream_bytes(13 * p->fused_nb, 2 * p->fused_nb) : 0);
+  p->off_ffn_stream = take(p->fused_nb ? (size_t)stream_bytes(14 * p->fused_nb, 2 * p->fused_nb) : 0);
+  p->off_attn_stream = take(p->fused_attn ? (size_t)stream_bytes(4 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->weights_bytes = off - act_end;
   p->total_bytes = off;
   return SI_OK;
@@ -219,6 +236,43 @@ static si_status launch_layer_norm(const char* stage, const float* h, T* a, int6
     if (st__ != SI_OK) return st__;   \
   } while (0)
 
+// Fragment streams of the register-resident kernels (bf16 only).
+template <int NB>
+static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, char* ws, hipStream_t st) {
+  const int D = p.D;
+  auto cB = [](const void* q) { return static_cast<const bf16*>(q); };
+  const bool spatial = p.kind == SI_BLOCK_SPATIAL;
+  {  // FFN half: out-projection of the last attention, FFN, proj_out
+    u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + p.off_ffn_stream);
+    const int total = 14 * NB;
+    BlockList list;
+    for (int nb = 0; nb < NB; ++nb) list.b[nb] = BlockDesc{cB(spatial ? w->wo2 : w->wo), D, 32 * nb};
+    pack_blocks_kernel<NB><<<(NB * 2 * NB + 3) / 4, 256, 0, st>>>(list, NB, stream, 0, total);
+    SI_CHECK_LAUNCH();
+    pack_ffn_stream_kernel<NB><<<(12 * NB * 2 * NB + 3) / 4, 256, 0, st>>>(cB(w->w1), cB(w->w2), stream, NB, total);
+    SI_CHECK_LAUNCH();
+    for (int nb = 0; nb < NB; ++nb) list.b[nb] = BlockDesc{cB(w->w_out), p.C, 32 * nb};
+    pack_blocks_kernel<NB><<<(NB * 2 * NB + 3) / 4, 256, 0, st>>>(list, NB, stream, 13 * NB, total);
+    SI_CHECK_LAUNCH();
+  }
+  if (p.fused_attn) {  // attention half: W_in blocks, then per head group q, k, v blocks
+    u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + p.off_attn_stream);
+    const int total = 4 * NB;
+    const int gw = lcm_int(p.d, 32), nbg = gw / 32, ng = D / gw;
+    BlockList list;
+    int n = 0;
+    for (int nb = 0; nb < NB; ++nb) list.b[n++] = BlockDesc{cB(w->w_in), D, 32 * nb};
+    for (int gi = 0; gi < ng; ++gi) {
+      const void* mats[3] = {w->wq, w->wk, w->wv};
+      for (int kind = 0; kind < 3; ++kind)
+        for (int blk = 0; blk < nbg; ++blk) list.b[n++] = BlockDesc{cB(mats[kind]), D, gi * gw + 32 * blk};
+    }
+    pack_blocks_kernel<NB><<<(n * 2 * NB + 3) / 4, 256, 0, st>>>(list, n, stream, 0, total);
+    SI_CHECK_LAUNCH();
+  }
+  return SI_OK;
+}
+
 template <typename T>
 static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
                            si_tensor5* out, char* ws, hipStream_t st) {
@@ -241,37 +295,35 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   T* w_out = reinterpret_cast<T*>(ws + p.off_w_out);
   const int C = p.C, D = p.D;
   const bool spatial = p.kind == SI_BLOCK_SPATIAL;
+  const bool fused_ffn = p.fused_nb > 0, fused_attn = p.fused_attn;
   constexpr int kSplit = sizeof(T) == 2 ? 2 : 1;
   auto cT = [](const void* q) { return static_cast<const T*>(q); };
 
   // ---- once per call: weight re-layout, frame embedding table, GroupNorm statistics, context K/V
   {
     StageScope scope("pack_weights", st);
-    for (int h2 = 0; h2 < kSplit; ++h2) {
-      SI_TRY(launch_pack<T>(cT(w->w_in), w_in + (size_t)h2 * C, C, D, D, 0, 0, st, kSplit * C));
-      if (p.fused_nb == 0) SI_TRY(launch_pack<T>(cT(w->w_out), w_out + (size_t)h2 * D, D, C, C, 0, 0, st, kSplit * D));
+    if (!fused_attn) {
+      for (int h2 = 0; h2 < kSplit; ++h2)
+        SI_TRY(launch_pack<T>(cT(w->w_in), w_in + (size_t)h2 * C, C, D, D, 0, 0, st, kSplit * C));
+      SI_TRY(launch_pack<T>(cT(w->wq), wqkv, D, D, D, 0, 0, st));
+      SI_TRY(launch_pack<T>(cT(w->wk), wqkv + (size_t)D * D, D, D, D, 0, 0, st));
+      SI_TRY(launch_pack<T>(cT(w->wv), wqkv + (size_t)2 * D * D, D, D, D, 0, 0, st));
+      if (spatial || !fused_ffn) SI_TRY(launch_pack<T>(cT(w->wo), wo, D, D, D, 0, 0, st));
     }
-    SI_TRY(launch_pack<T>(cT(w->wq), wqkv, D, D, D, 0, 0, st));
-    SI_TRY(launch_pack<T>(cT(w->wk), wqkv + (size_t)D * D, D, D, D, 0, 0, st));
-    SI_TRY(launch_pack<T>(cT(w->wv), wqkv + (size_t)2 * D * D, D, D, D, 0, 0, st));
-    SI_TRY(launch_pack<T>(cT(w->wo), wo, D, D, D, 0, 0, st));
     if (spatial) {
       SI_TRY(launch_pack<T>(cT(w->wq2), wq2, D, D, D, 0, 0, st));
       SI_TRY(launch_pack<T>(cT(w->wk2), wkv2, p.Cc, D, D, 0, 0, st));
       SI_TRY(launch_pack<T>(cT(w->wv2), wkv2 + (size_t)D * p.Cc, p.Cc, D, D, 0, 0, st));
-      SI_TRY(launch_pack<T>(cT(w->wo2), wo2, D, D, D, 0, 0, st));
+      if (!fused_ffn) SI_TRY(launch_pack<T>(cT(w->wo2), wo2, D, D, D, 0, 0, st));
     }
-    if (p.fused_nb == 0) {
+    if (!fused_ffn) {
+      for (int h2 = 0; h2 < kSplit; ++h2)
+        SI_TRY(launch_pack<T>(cT(w->w_out), w_out + (size_t)h2 * D, D, C, C, 0, 0, st, kSplit * D));
       SI_TRY(launch_pack<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 0, 4 * D, st));
       SI_TRY(launch_pack<T>(cT(w->w2), w2, 4 * D, D, D, 0, 0, st));
     } else if constexpr (sizeof(T) == 2) {
-      u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + p.off_ffn_stream);
-      const int frags = 26 * p.fused_nb * p.fused_nb;
-      if (p.fused_nb == 2)
-        pack_ffn_stream_kernel<2><<<(frags + 3) / 4, 256, 0, st>>>(cT(w->w1), cT(w->w2), cT(w->w_out), stream);
-      else
-        pack_ffn_stream_kernel<10><<<(frags + 3) / 4, 256, 0, st>>>(cT(w->w1), cT(w->w2), cT(w->w_out), stream);
-      SI_CHECK_LAUNCH();
+      if (p.fused_nb == 2) SI_TRY(pack_fused_streams<2>(p, w, ws, st));
+      else SI_TRY(pack_fused_streams<10>(p, w, ws, st));
     }
     if (pe) {
       pe_table_kernel<<<(p.F * D + 255) / 256, 256, 0, st>>>(pe, p.F, D);
@@ -306,73 +358,90 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     }
     const int64_t M = (int64_t)p.B * win.Fw * win.Pw;
 
-    {  // slice-in: window -> GroupNorm -> token rows
-      StageScope scope("slice_in", st);
-      dim3 grid((unsigned)((win.Pw + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * win.Fw));
-      window_to_tokens_kernel<T><<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
-      SI_CHECK_LAUNCH();
-    }
-    {
-      EpiResidual<T> epi{h, (int64_t)D, cT(w->b_in), 0, nullptr};
-      SI_TRY(launch_gemm<T>("proj_in", a, (int64_t)kSplit * C, w_in, M, D, kSplit * C, epi, st));
-    }
-    SI_TRY(launch_layer_norm<T>("ln1", h, a, M, D, w->ln1_g, w->ln1_b, w->ln_eps, pe, win.Pw, win.Fw, win.f0, st));
-    {
-      EpiStore<T> epi{big, (int64_t)3 * D, nullptr};
-      SI_TRY(launch_gemm<T>("qkv", a, (int64_t)D, wqkv, M, 3 * D, D, epi, st));
-    }
-    {
-      AttnArgs at;
-      at.q = big; at.k = big + D; at.v = big + 2 * D; at.o = a;
-      at.ldq = at.ldk = at.ldv = (int64_t)3 * D; at.ldo = D;
-      at.heads = p.heads; at.d = p.d; at.scale = scale;
-      if (spatial) {
-        at.S = p.B * win.Fw; at.Nq = at.Nk = win.Pw;
-        at.qmap = SeqMap{1, (int64_t)win.Pw, 0, 1};
-      } else {
-        at.S = p.B * win.Pw; at.Nq = at.Nk = p.F;
-        at.qmap = SeqMap{win.Pw, (int64_t)p.F * win.Pw, 1, (int64_t)win.Pw};
+    if constexpr (sizeof(T) == 2) {
+      if (fused_attn) {  // slice-in .. attention in one kernel: h0 -> h, attention output -> a
+        StageScope scope("attn_half_fused", st);
+        AttnHalfArgs aa;
+        aa.x = X; aa.stats = stats; aa.gn_g = cT(w->gn_g); aa.gn_b = cT(w->gn_b); aa.b_in = cT(w->b_in);
+        aa.ln_g = cT(w->ln1_g); aa.ln_b = cT(w->ln1_b); aa.pe = pe;
+        aa.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_attn_stream);
+        aa.h0 = h; aa.o = a; aa.ln_eps = w->ln_eps; aa.scale = scale; aa.win = win;
+        const int npos = 4 * (32 / p.F);
+        const unsigned blocks = (unsigned)(((int64_t)p.B * win.Pw + npos - 1) / npos);
+        if (p.fused_nb == 2) attn_half_kernel<2, 32><<<blocks, 256, 0, st>>>(aa);
+        else if (p.d == 40) attn_half_kernel<10, 40><<<blocks, 256, 0, st>>>(aa);
+        else attn_half_kernel<10, 64><<<blocks, 256, 0, st>>>(aa);
+        SI_CHECK_LAUNCH();
       }
-      at.kmap = at.qmap;
-      SI_TRY(launch_attention<T>("self_attn", at, st));
     }
-    {
-      EpiResidual<T> epi{h, (int64_t)D, cT(w->bo), 1, nullptr};
-      SI_TRY(launch_gemm<T>("attn_out", a, (int64_t)D, wo, M, D, D, epi, st));
-    }
-    if (spatial) {
-      SI_TRY(launch_layer_norm<T>("ln2", h, a, M, D, w->ln2_g, w->ln2_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st));
+    if (!fused_attn) {
+      {  // slice-in: window -> GroupNorm -> token rows
+        StageScope scope("slice_in", st);
+        dim3 grid((unsigned)((win.Pw + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * win.Fw));
+        window_to_tokens_kernel<T><<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
+        SI_CHECK_LAUNCH();
+      }
       {
-        EpiStore<T> epi{big, (int64_t)D, nullptr};
-        SI_TRY(launch_gemm<T>("q2", a, (int64_t)D, wq2, M, D, D, epi, st));
+        EpiResidual<T> epi{h, (int64_t)D, cT(w->b_in), 0, nullptr};
+        SI_TRY(launch_gemm<T>("proj_in", a, (int64_t)kSplit * C, w_in, M, D, kSplit * C, epi, st));
+      }
+      SI_TRY(launch_layer_norm<T>("ln1", h, a, M, D, w->ln1_g, w->ln1_b, w->ln_eps, pe, win.Pw, win.Fw, win.f0, st));
+      {
+        EpiStore<T> epi{big, (int64_t)3 * D, nullptr};
+        SI_TRY(launch_gemm<T>("qkv", a, (int64_t)D, wqkv, M, 3 * D, D, epi, st));
       }
       {
         AttnArgs at;
-        at.q = big; at.k = ctxkv; at.v = ctxkv + D; at.o = a;
-        at.ldq = D; at.ldk = at.ldv = (int64_t)2 * D; at.ldo = D;
+        at.q = big; at.k = big + D; at.v = big + 2 * D; at.o = a;
+        at.ldq = at.ldk = at.ldv = (int64_t)3 * D; at.ldo = D;
         at.heads = p.heads; at.d = p.d; at.scale = scale;
-        at.S = p.B * win.Fw; at.Nq = win.Pw; at.Nk = p.Mc;
-        at.qmap = SeqMap{1, (int64_t)win.Pw, 0, 1};
-        at.kmap = SeqMap{win.Fw, (int64_t)p.Mc, 0, 1};
-        SI_TRY(launch_attention<T>("cross_attn", at, st));
+        if (spatial) {
+          at.S = p.B * win.Fw; at.Nq = at.Nk = win.Pw;
+          at.qmap = SeqMap{1, (int64_t)win.Pw, 0, 1};
+        } else {
+          at.S = p.B * win.Pw; at.Nq = at.Nk = p.F;
+          at.qmap = SeqMap{win.Pw, (int64_t)p.F * win.Pw, 1, (int64_t)win.Pw};
+        }
+        at.kmap = at.qmap;
+        SI_TRY(launch_attention<T>("self_attn", at, st));
       }
-      {
-        EpiResidual<T> epi{h, (int64_t)D, cT(w->bo2), 1, nullptr};
-        SI_TRY(launch_gemm<T>("cross_out", a, (int64_t)D, wo2, M, D, D, epi, st));
+      if (spatial || !fused_ffn) {  // otherwise the FFN-half kernel applies W_o itself
+        EpiResidual<T> epi{h, (int64_t)D, cT(w->bo), 1, nullptr};
+        SI_TRY(launch_gemm<T>("attn_out", a, (int64_t)D, wo, M, D, D, epi, st));
+      }
+      if (spatial) {
+        SI_TRY(launch_layer_norm<T>("ln2", h, a, M, D, w->ln2_g, w->ln2_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st));
+        {
+          EpiStore<T> epi{big, (int64_t)D, nullptr};
+          SI_TRY(launch_gemm<T>("q2", a, (int64_t)D, wq2, M, D, D, epi, st));
+        }
+        {
+          AttnArgs at;
+          at.q = big; at.k = ctxkv; at.v = ctxkv + D; at.o = a;
+          at.ldq = D; at.ldk = at.ldv = (int64_t)2 * D; at.ldo = D;
+          at.heads = p.heads; at.d = p.d; at.scale = scale;
+          at.S = p.B * win.Fw; at.Nq = win.Pw; at.Nk = p.Mc;
+          at.qmap = SeqMap{1, (int64_t)win.Pw, 0, 1};
+          at.kmap = SeqMap{win.Fw, (int64_t)p.Mc, 0, 1};
+          SI_TRY(launch_attention<T>("cross_attn", at, st));
+        }
+        if (!fused_ffn) {
+          EpiResidual<T> epi{h, (int64_t)D, cT(w->bo2), 1, nullptr};
+          SI_TRY(launch_gemm<T>("cross_out", a, (int64_t)D, wo2, M, D, D, epi, st));
+        }
       }
     }
     if constexpr (sizeof(T) == 2) {
-      if (p.fused_nb) {
+      if (fused_ffn) {  // h += a W_o + b_o, LN3, GEGLU FFN, proj_out, residual, slice-out
         StageScope scope("ffn_half_fused", st);
         FfnHalfArgs fa;
-        fa.h = h; fa.M = M; fa.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_ffn_stream);
+        fa.h = h; fa.o = a; fa.M = M; fa.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_ffn_stream);
+        fa.b_o = cT(spatial ? w->bo2 : w->bo);
         fa.ln_g = cT(w->ln3_g); fa.ln_b = cT(w->ln3_b); fa.b1 = cT(w->b1); fa.b2 = cT(w->b2); fa.b_out = cT(w->b_out);
         fa.ln_eps = w->ln_eps; fa.x = X; fa.out = OUT; fa.win = win;
         const unsigned blocks = (unsigned)((M + 127) / 128);
-        if (p.fused_nb == 2)
-          ffn_half_kernel<2><<<blocks, 256, 0, st>>>(fa);
-        else
-          ffn_half_kernel<10><<<blocks, 256, 0, st>>>(fa);
+        if (p.fused_nb == 2) ffn_half_kernel<2><<<blocks, 256, 0, st>>>(fa);
+        else ffn_half_kernel<10><<<blocks, 256, 0, st>>>(fa);
         SI_CHECK_LAUNCH();
         continue;
       }
