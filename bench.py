@@ -52,8 +52,10 @@ def stage_work(spec, stage, M, window_tokens_per_seq=None):
         return "flop", 4.0 * M * nk * D
     if stage == "cross_attn":
         return "flop", 4.0 * M * spec.ctx_tokens * D
-    if stage == "temporal_fused":
-        return "flop", 2.0 * M * (C * D + 3 * D * D + D * D + 8 * D * D + 4 * D * D + D * C) + 4.0 * M * spec.F * D
+    if stage == "attn_half_fused":      # proj_in, q/k/v, attention over F frames
+        return "flop", 2.0 * M * (C * D + 3 * D * D) + 4.0 * M * spec.F * D
+    if stage == "ffn_half_fused":       # attention out-projection, W1, W2, proj_out
+        return "flop", 2.0 * M * (D * D + 8 * D * D + 4 * D * D + D * C)
     if stage == "gn_stats":
         return "byte", float(spec.tokens * C * es)
     if stage == "slice_in":

@@ -37,6 +37,66 @@ struct AttnHalfArgs {
 
 constexpr int kAttnMaxStats = 1024;  // F * G entries per batch entry held in LDS
 
+// Cooperative slice-in of one workgroup tile (see attn_half_kernel).  NPOS consecutive sequences
+// (b, position) starting at seq_wg; xs row of (sequence j, frame f) = (j / TP) * 32 + (j % TP) * F + f.
+template <int U, int D, int XLD>
+__device__ __forceinline__ void stage_window(const bf16* __restrict__ x, unsigned short* xs, const float2* t_stats,
+                                             const float* t_gng, const float* t_gnb, const Window& w, int64_t seq_wg,
+                                             int64_t nseq, int b_first, int TP, int NPOS, int tid) {
+  const int F = w.F;
+  const int runs = NPOS / U, pairs = runs * F;  // <= 128
+  int PP = 1;
+  while (PP < pairs) PP *= 2;
+  const int CL = 256 / PP;  // channel lanes
+  const int pair = tid % PP, cl = tid / PP;
+  const int run = pair % runs, f = pair / runs;
+  const int j0 = run * U;
+  const int64_t seq = seq_wg + j0;
+  if (pair >= pairs || seq >= nseq) return;  // runs never straddle the end: nseq % U == 0 when U > 1
+  const int b = (int)(seq / w.Pw), pl = (int)(seq % w.Pw);
+  const int ng = w.C / w.G;
+  const float2* st = t_stats + (b - b_first) * kAttnMaxStats + f * w.G;
+  const bf16* xp = x + (((int64_t)b * w.C + cl) * F + f) * w.P + w.p0 + pl;
+  const int64_t cstep = (int64_t)CL * F * w.P;
+  int rows[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) rows[u] = ((j0 + u) / TP) * 32 + ((j0 + u) % TP) * F + f;
+  int grp = cl / ng, left = ng - (cl % ng);
+  constexpr int BATCH = 8;
+  for (int c0 = cl; c0 < D; c0 += BATCH * CL) {
+    uint2 raw[BATCH];
+#pragma unroll
+    for (int k = 0; k < BATCH; ++k) {
+      if (c0 + k * CL < D) {
+        if constexpr (U == 4) raw[k] = *reinterpret_cast<const uint2*>(xp + k * cstep);
+        else raw[k].x = xp[k * cstep].v;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < BATCH; ++k) {
+      const int c = c0 + k * CL;
+      if (c < D) {
+        const float2 ms = st[grp];
+        const float sc = ms.y * t_gng[c], sh = t_gnb[c] - ms.x * sc;
+        if constexpr (U == 4) {
+          xs[rows[0] * XLD + c] = float_to_bf16_bits(fmaf(__uint_as_float(raw[k].x << 16), sc, sh));
+          xs[rows[1] * XLD + c] = float_to_bf16_bits(fmaf(__uint_as_float(raw[k].x & 0xffff0000u), sc, sh));
+          xs[rows[2] * XLD + c] = float_to_bf16_bits(fmaf(__uint_as_float(raw[k].y << 16), sc, sh));
+          xs[rows[3] * XLD + c] = float_to_bf16_bits(fmaf(__uint_as_float(raw[k].y & 0xffff0000u), sc, sh));
+        } else {
+          xs[rows[0] * XLD + c] = float_to_bf16_bits(fmaf(bf16_bits_to_float((unsigned short)raw[k].x), sc, sh));
+        }
+        left -= CL;
+        while (left <= 0) {
+          ++grp;
+          left += ng;
+        }
+      }
+    }
+    xp += BATCH * cstep;
+  }
+}
+
 template <int NB, int DH>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_half_kernel(AttnHalfArgs a) {
   constexpr int D = 32 * NB, SUB = 2 * NB, NSLOT = 3, FIFO = NB;
@@ -59,7 +119,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const Window& w = a.win;
   const int F = w.F, TP = 32 / F, NPOS = 4 * TP;  // positions per workgroup
   const int64_t nseq = (int64_t)w.B * w.Pw;       // sequences (b, position) of the window
-  const int64_t seq_wg = (int64_t)blockIdx.x * NPOS;
+  // Eight consecutive tiles share the cache lines of x (runs of 64 positions).  Workgroups are
+  // handed to the 8 XCDs round-robin, so tile = f(blockIdx) is chosen to put such a run of tiles
+  // on one XCD (one L2), in consecutive dispatch rounds: tile = 64*(b/64) + 8*(b%8) + (b/8)%8.
+  const unsigned bid = blockIdx.x, full = gridDim.x / 64 * 64;
+  const unsigned tile = bid < full ? (bid / 64) * 64 + (bid % 8) * 8 + (bid / 8) % 8 : bid;
+  const int64_t seq_wg = (int64_t)tile * NPOS;
 
   // this lane's token: sequence, frame, row of the window's token order m = (b*F + f)*Pw + pl
   const int my_pp = tcol / F, my_f = tcol % F;
@@ -94,36 +159,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   for (int i = tid; i < XS_BYTES / 16; i += 256) reinterpret_cast<u32x4_t*>(arena)[i] = u32x4_t{0, 0, 0, 0};
   __syncthreads();
 
-  // ---- slice-in: x[b, c, f, p0 + pl] -> GroupNorm -> xs[row][c].  Thread = one (position, frame)
-  // pair, positions fastest so that a wavefront reads runs of consecutive positions; two threads
-  // per pair take even / odd channels.
-  {
-    const int pairs = NPOS * F;  // <= 128
-    const int pair = tid % 128, cpar = tid / 128;
-    const int j = pair % NPOS, f = pair / NPOS;
-    const int64_t seq = seq_wg + j;
-    if (pair < pairs && seq < nseq) {
-      const int b = (int)(seq / w.Pw), pl = (int)(seq % w.Pw);
-      const int row = (j / TP) * 32 + (j % TP) * F + f;
-      const int ng = w.C / w.G;
-      const float2* st = t_stats[b - b_first] + f * w.G;
-      const bf16* xp = a.x + (((int64_t)b * w.C + cpar) * F + f) * w.P + w.p0 + pl;
-      const int64_t cstep = 2 * (int64_t)F * w.P;
-      unsigned short* xrow = xs + row * XLD;
-      int grp = cpar / ng, left = ng - (cpar % ng);  // channels left in the current group (stepping by 2)
-      for (int c = cpar; c < D; c += 2) {
-        const float2 ms = st[grp];
-        const float v = (bf16_bits_to_float(xp->v) - ms.x) * ms.y * t_gng[c] + t_gnb[c];
-        xrow[c] = float_to_bf16_bits(v);
-        xp += cstep;
-        left -= 2;
-        while (left <= 0) {
-          ++grp;
-          left += ng;
-        }
-      }
-    }
-  }
+  // ---- slice-in: x[b, c, f, p0 + pl] -> GroupNorm -> xs[row][c].  A thread owns one (frame,
+  // run of U consecutive positions) pair and walks the channels with stride 256 / PP; loads are
+  // issued in batches ahead of their use.  U = 4 (8-byte loads) when rows, window start and frame
+  // size are multiples of 4 positions, else U = 1.
+  if ((w.Pw % 4 == 0) && (w.p0 % 4 == 0) && (w.P % 4 == 0))
+    stage_window<4, D, XLD>(a.x, xs, t_stats[0], t_gng, t_gnb, w, seq_wg, nseq, b_first, TP, NPOS, tid);
+  else
+    stage_window<1, D, XLD>(a.x, xs, t_stats[0], t_gng, t_gnb, w, seq_wg, nseq, b_first, TP, NPOS, tid);
   __syncthreads();
 
   // ---- this wavefront's GroupNorm'ed tokens as column operands
@@ -268,7 +311,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
       bf16x8_t qop[2 * NBG], kop[2 * NBG], vop[2 * NBG];
-      f32x16_t og[NBG];
 #pragma unroll
       for (int kind = 0; kind < 3; ++kind) {
 #pragma unroll
@@ -347,25 +389,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               const int col = 32 * blk + 8 * q;  // quad q: columns [col, col+8) of the group
-              if (col >= c0 && col < c1) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) og[blk][4 * q + j] = ot[4 * q + j] * inv;
+              if (col >= c0 && col < c1 && live) {
+                // attention output, heads concatenated: o[m][gi*GW + 32 blk + 8q + 4g + j]
+                uint2 pk;
+                pk.x = pack_bf16x2(ot[4 * q + 0] * inv, ot[4 * q + 1] * inv);
+                pk.y = pack_bf16x2(ot[4 * q + 2] * inv, ot[4 * q + 3] * inv);
+                *reinterpret_cast<uint2*>(a.o + my_m * D + gi * GW + col + 4 * g) = pk;
               }
             }
           }
         }
-      }
-      // attention output of the group, heads concatenated: o[m][gi*GW + 32 blk + 8q + 4g + j]
-      if (live) {
-#pragma unroll
-        for (int blk = 0; blk < NBG; ++blk)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            uint2 pk;
-            pk.x = pack_bf16x2(og[blk][4 * q + 0], og[blk][4 * q + 1]);
-            pk.y = pack_bf16x2(og[blk][4 * q + 2], og[blk][4 * q + 3]);
-            *reinterpret_cast<uint2*>(a.o + my_m * D + gi * GW + 32 * blk + 8 * q + 4 * g) = pk;
-          }
       }
     }
   }
