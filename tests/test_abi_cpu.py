@@ -1,0 +1,126 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, validates arguments before any GPU call, and runs Algorithm 1 on the host."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2411_01171_amd as si
+from paper_2411_01171_amd import binding as B
+from test_oracle_rehash import _golden_cases, _rule_matrix
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "si.h")
+
+
+def _declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(si_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"si_block_forward", "si_rehash_check", "si_workspace_bytes", "si_key_step_search"} <= set(names)
+    lib = si.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert si.si_abi_version() >= 1
+    assert si.si_status_str(0) == "ok" and "slice" in si.si_status_str(4)
+
+
+def _descs(kind=B.SI_BLOCK_TEMPORAL, dtype=B.SI_BF16, Bn=2, Cn=64, F=4, H=8, W=8, heads=2, dh=32, groups=8, fake=0x10000):
+    x = B._Tensor5(fake, dtype, Bn, Cn, F, H, W)
+    out = B._Tensor5(fake + (1 << 30), dtype, Bn, Cn, F, H, W)
+    w = B._Weights()
+    w.kind, w.heads, w.dim_head, w.gn_groups, w.gn_eps, w.ln_eps, w.add_sin_pe = kind, heads, dh, groups, 1e-6, 1e-5, 0
+    for name in B.WEIGHT_FIELDS:
+        setattr(w, name, fake + (2 << 30))
+    ctx = B._Context(fake + (3 << 30), dtype, Bn, 5, 16)
+    return x, w, ctx, out
+
+
+def _forward(x, w, ctx, out, axis, slice_len, ws=0x7000000000, ws_bytes=1 << 40):
+    return si.lib().si_block_forward(C.byref(x), C.byref(w), C.byref(ctx) if ctx is not None else None, C.byref(out),
+                                     axis, slice_len, ws, ws_bytes, None)
+
+
+def _wsbytes(x, w, ctx, axis, slice_len):
+    return si.lib().si_workspace_bytes(C.byref(x), C.byref(w), C.byref(ctx) if ctx is not None else None, axis, slice_len)
+
+
+def test_argument_validation_returns_codes_without_touching_the_gpu():
+    x, w, ctx, out = _descs()
+    assert _wsbytes(x, w, None, B.SI_AXIS_HW, 16) > 0
+    # slicing a temporal block along frames is not lossless -> refused; same for spatial along positions
+    assert _forward(x, w, None, out, B.SI_AXIS_F, 1) == 4
+    assert _wsbytes(x, w, None, B.SI_AXIS_F, 1) == 0
+    xs, ws_, cs, os_ = _descs(kind=B.SI_BLOCK_SPATIAL)
+    assert _forward(xs, ws_, cs, os_, B.SI_AXIS_HW, 16) == 4
+    assert _forward(xs, ws_, None, os_, B.SI_AXIS_F, 1) == 1          # spatial block without context
+    assert _forward(x, w, None, out, B.SI_AXIS_HW, 0) == 4           # slice_len < 1
+    assert _forward(x, w, None, out, 7, 4) == 4                      # unknown axis
+    bad = B._Tensor5(x.ptr, 5, 2, 64, 4, 8, 8)
+    assert _forward(bad, w, None, out, B.SI_AXIS_HW, 4) == 3          # unknown dtype
+    o32 = B._Tensor5(out.ptr, B.SI_F32, 2, 64, 4, 8, 8)
+    assert _forward(x, w, None, o32, B.SI_AXIS_HW, 4) == 3            # dtype mismatch
+    o2 = B._Tensor5(out.ptr, B.SI_BF16, 2, 64, 4, 8, 9)
+    assert _forward(x, w, None, o2, B.SI_AXIS_HW, 4) == 2             # shape mismatch
+    x3, w3, _, out3 = _descs(Cn=60)
+    assert _forward(x3, w3, None, out3, B.SI_AXIS_HW, 4) == 2         # C not divisible by groups / 8
+    x4, w4, _, out4 = _descs(dh=20)
+    assert _forward(x4, w4, None, out4, B.SI_AXIS_HW, 4) == 2         # dim_head not a multiple of 8
+    xn = B._Tensor5(None, B.SI_BF16, 2, 64, 4, 8, 8)
+    assert _forward(xn, w, None, out, B.SI_AXIS_HW, 4) == 1           # NULL feature
+    w5 = _descs()[1]; w5.w1 = None
+    assert _forward(x, w5, None, out, B.SI_AXIS_HW, 4) == 1           # NULL required matrix
+    xm = B._Tensor5(x.ptr + 2, B.SI_BF16, 2, 64, 4, 8, 8)
+    assert _forward(xm, w, None, out, B.SI_AXIS_HW, 4) == 5           # misaligned
+    assert _forward(x, w, None, out, B.SI_AXIS_HW, 4, ws_bytes=1024) == 6   # workspace too small
+    alias = B._Tensor5(x.ptr + 4096, B.SI_BF16, 2, 64, 4, 8, 8)
+    assert _forward(x, w, None, alias, B.SI_AXIS_HW, 4) == 7          # out overlaps x
+    assert si.lib().si_block_forward(None, None, None, None, 3, 1, None, 0, None) == 1
+
+
+def test_workspace_scales_with_the_slice():
+    x, w, _, _ = _descs(Cn=320, heads=8, dh=40, groups=32, F=16, H=64, W=64)
+    lib = si.lib()
+    full = lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 4096)
+    quarter = lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 1024)
+    assert 0 < quarter < full and quarter / full < 0.2502
+    assert lib.si_workspace_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 1024) > quarter
+    # slice_len beyond the extent behaves as unsliced
+    assert lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 10**9) == full
+
+
+def test_rehash_check_validation():
+    lib = si.lib()
+    fake = 0x10000
+    assert lib.si_rehash_check(fake, fake, 16, 7, 0.9, None, fake, fake, None) == 3
+    assert lib.si_rehash_check(fake, fake, -1, B.SI_BF16, 0.9, None, fake, fake, None) == 2
+    assert lib.si_rehash_check(fake, fake, 16, B.SI_BF16, float("nan"), None, fake, fake, None) == 7
+    assert lib.si_rehash_check(fake, fake, 16, B.SI_BF16, 0.9, None, None, fake, None) == 1
+    assert lib.si_rehash_check(fake + 2, fake, 16, B.SI_BF16, 0.9, None, fake, fake, None) == 5
+    assert si.si_rehash_scratch_bytes(0) >= 24 and si.si_rehash_scratch_bytes(1 << 30) <= 2048 * 24
+
+
+@pytest.mark.parametrize("name,K,gamma,rule,G", list(_golden_cases()))
+def test_key_step_search_matches_hand_worked_cases_and_oracle(name, K, gamma, rule, G):
+    S = _rule_matrix(rule, K)
+    assert si.si_key_step_search(S.tolist(), gamma) == G
+    assert si.si_key_step_search(S.tolist(), gamma) == oracle.key_step_search_ref(S.astype(np.float32), np.float32(gamma), K)
+
+
+def test_key_step_search_random_maps_and_errors():
+    rng = np.random.default_rng(0)
+    for K in (1, 2, 5, 10, 25):
+        for _ in range(20):
+            S = rng.uniform(0.8, 1.0, (K, K)).astype(np.float32)
+            np.fill_diagonal(S, 1.0)
+            g = float(np.float32(rng.uniform(0.85, 0.99)))
+            assert si.si_key_step_search(S.tolist(), g) == oracle.key_step_search_ref(S, g, K)
+    with pytest.raises(si.SiError):
+        si.si_key_step_search([[1.0]], 1.5)
+    with pytest.raises(si.SiError):
+        si.si_key_step_search([[0.2, 0.1], [0.1, 0.2]], 0.5)     # diagonal below the threshold

@@ -1,0 +1,109 @@
+"""Config 5: Step Rehash over a 10-step trajectory of 4 spatial+temporal block pairs (C = 1280).
+
+Protocol (two passes): pass 1 runs every step in full and keeps each pair's output Y_t^p; the
+similarity map S^p[i][j] = cos(Y_i^p, Y_j^p) is filled by si_rehash_check; Algorithm 1 walks it
+(si_key_step_search) to the key-step set G_p; pass 2 replays the trajectory recomputing pair p at
+step t only if t is in G_p and handing back its cached output otherwise.
+
+Checked against the oracle: every cosine and every >= 0.95 decision on the identical stored
+outputs (bit-exact decisions), the key-step sets, and the replay's hand-back rule.  The block
+outputs themselves are covered by the sampled parity tests of cfg5s / cfg5t.
+"""
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import si_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg5_trajectory_decisions_and_key_steps():
+    import torch
+    import paper_2411_01171_amd as si
+    from gpu_helpers import AXIS, device_weights, to_dev
+
+    K, NP, gamma = wl.CFG5_STEPS, wl.CFG5_PAIRS, wl.CFG5_GAMMA
+    sp, tp = wl.CONFIGS["cfg5s"], wl.CONFIGS["cfg5t"]
+    ctx = to_dev(wl.make_context(sp), "bf16")
+    pairs = [(device_weights(sp, wl.make_weights(sp, seed=sp.seed + 100 * p)),
+              device_weights(tp, wl.make_weights(tp, seed=tp.seed + 100 * p))) for p in range(NP)]
+    x_np = wl.make_x(sp)
+    xs = [to_dev(x_np, "bf16")]
+    for t in range(1, K):
+        x_np = wl.cfg5_step_input(x_np, t)
+        xs.append(to_dev(x_np, "bf16"))
+    ws_s = torch.empty(si.si_workspace_bytes(xs[0], pairs[0][0], ctx, AXIS[sp.slice_axis], sp.slice_len), dtype=torch.uint8, device="cuda")
+    ws_t = torch.empty(si.si_workspace_bytes(xs[0], pairs[0][1], None, AXIS[tp.slice_axis], tp.slice_len), dtype=torch.uint8, device="cuda")
+    scratch = torch.empty(si.si_rehash_scratch_bytes(xs[0].numel()), dtype=torch.uint8, device="cuda")
+    res = torch.empty(16, dtype=torch.uint8, device="cuda")
+    mid = torch.empty_like(xs[0])
+
+    def run_pair(p, inp, out):
+        si.si_block_forward(inp, pairs[p][0], ctx, mid, AXIS[sp.slice_axis], sp.slice_len, ws_s)
+        si.si_block_forward(mid, pairs[p][1], None, out, AXIS[tp.slice_axis], tp.slice_len, ws_t)
+
+    # pass 1: full computation
+    t0 = time.perf_counter()
+    Y = [[torch.empty_like(xs[0]) for _ in range(NP)] for _ in range(K)]
+    for t in range(K):
+        cur = xs[t]
+        for p in range(NP):
+            run_pair(p, cur, Y[t][p])
+            cur = Y[t][p]
+    torch.cuda.synchronize()
+    t_full = time.perf_counter() - t0
+    assert all(bool(torch.isfinite(Y[t][p].float()).all()) for t in range(K) for p in range(NP))
+
+    # similarity maps on the GPU vs the oracle on the identical stored outputs
+    t0 = time.perf_counter()
+    S = np.ones((NP, K, K))
+    D = np.ones((NP, K, K), dtype=int)
+    for p in range(NP):
+        for i in range(K):
+            for j in range(i):
+                c, d = si.si_rehash_check_sync(Y[i][p], Y[j][p], gamma, scratch, res)
+                S[p, i, j] = S[p, j, i] = c
+                D[p, i, j] = D[p, j, i] = d
+    t_checks = time.perf_counter() - t0
+    min_margin = 1.0
+    G_all = []
+    for p in range(NP):
+        host = [Y[t][p].float().cpu().numpy() for t in range(K)]
+        S_ref = np.ones((K, K))
+        for i in range(K):
+            for j in range(i):
+                S_ref[i, j] = S_ref[j, i] = oracle.cosine_ref(host[i], host[j])
+                assert D[p, i, j] == oracle.rehash_decision_ref(host[i], host[j], gamma), (p, i, j)
+                assert abs(S[p, i, j] - S_ref[i, j]) < 1e-12
+                min_margin = min(min_margin, abs(S_ref[i, j] - float(np.float32(gamma))))
+        G = si.si_key_step_search(S[p].tolist(), gamma)
+        assert G == oracle.key_step_search_ref(S_ref, float(np.float32(gamma)), K) or min_margin < 1e-6
+        assert G[0] == 0 and G[-1] == K - 1
+        G_all.append(G)
+
+    # pass 2: replay with the hand-back rule; recomputed outputs of the first pair equal pass 1
+    t0 = time.perf_counter()
+    cache = [None] * NP
+    recomputed = 0
+    out_buf = [[torch.empty_like(xs[0]) for _ in range(NP)] for _ in range(2)]
+    for t in range(K):
+        cur = xs[t]
+        for p in range(NP):
+            if t in G_all[p] or cache[p] is None:
+                dst = out_buf[t % 2][p]
+                run_pair(p, cur, dst)
+                cache[p] = dst.clone()
+                recomputed += 1
+                if p == 0:
+                    assert torch.equal(dst, Y[t][0])       # same input, deterministic kernels
+            cur = cache[p]
+    torch.cuda.synchronize()
+    t_replay = time.perf_counter() - t0
+    skips = K * NP - recomputed
+    assert skips == sum(K - len(G) for G in G_all) and skips > 0
+    print(f"cfg5: key steps per pair {G_all}; skipped {skips} of {K * NP} pair evaluations; "
+          f"full pass {t_full * 1e3:.1f} ms, {NP * K * (K - 1) // 2} checks {t_checks * 1e3:.1f} ms, "
+          f"replay {t_replay * 1e3:.1f} ms; min |cos - gamma| = {min_margin:.2e}")
