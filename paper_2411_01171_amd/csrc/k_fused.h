@@ -191,35 +191,34 @@ __global__ __launch_bounds__(256) void pack_blocks_kernel(BlockList list, int n_
 
 // ----------------------------------------------------------------------------- weight stream pipeline
 
-// The workgroup's 256 threads move the fragment stream through a ring of three
-// LDS slots of SUB fragments.  Global loads run two sub-chunks ahead of their
-// use, through two alternating register sets: in step i (parity P = i % 2) the
-// loads of sub-chunk i+3 are issued into set P, the MFMAs of sub-chunk i read
-// ring slot i % 3, then set 1-P (sub-chunk i+2, loaded during step i-1) is
-// stored into slot (i+2) % 3 -- the slot read in step i-1 -- and one barrier
-// closes the step.  Each wavefront keeps the next SUB/2 fragments in a register
-// FIFO that it refills right after each use (from slot i % 3, then from slot
-// (i+1) % 3, which was published before the previous barrier), so LDS latency
-// stays off the MFMA chain.
+// The workgroup moves the fragment stream through a ring of kRingSlots LDS slots of SUB fragments
+// with direct global-to-LDS loads (global_load_lds_dwordx4: lane i of a wavefront deposits its 16
+// bytes at LDS address M0 + 16 i, i.e. one fragment per instruction, no staging registers).  At the
+// start of step i the loads of sub-chunk i+3 are issued into slot (i+3) % 4 -- the slot read in
+// step i-1; the MFMAs of sub-chunk i read slot i % 4 and, through the register FIFO's refills,
+// slot (i+1) % 4.  Before the barrier that closes step i every wavefront waits until at most its
+// newest batch of loads is outstanding (loads return in issue order), so sub-chunk i+2 is in LDS
+// for everybody two steps before it becomes the FIFO's refill source.
+constexpr int kRingSlots = 4;
 template <int SUB>
 struct WeightPipe {
-  static constexpr int PER_THREAD = SUB * kWave / 256;
-  static constexpr int NSLOT = 3;
-  template <int N>
-  static __device__ __forceinline__ void fetch(u32x4_t (&pre)[N], const u32x4_t* stream, int next, int total, int tid) {
-    if (next < total) {
-      const int64_t pitch = stream_pitch_u4(total);
-      const u32x4_t* src = stream + (int64_t)next * kWave + (tid % kWave);
+  static constexpr int PER_THREAD = SUB * kWave / 256;  // loads per lane per sub-chunk
+  // s_waitcnt immediate (gfx9 encoding): vmcnt <= n, other counters unconstrained
+  static constexpr int wait_imm(int n) { return (n & 0xF) | 0x70 | 0xF00 | ((n >> 4) << 14); }
+  static __device__ __forceinline__ void issue(const u32x4_t* stream, u32x4_t* ring0, int sub, int total, int64_t pitch,
+                                               int lane, int wave) {
+    if (sub < total) {
+      const u32x4_t* src = stream + (int64_t)sub * kWave + lane;
+      // LDS byte address of the slot, wave-uniform (goes to M0)
+      const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(ring0 + (sub % kRingSlots) * (SUB * kWave));
 #pragma unroll
-      for (int i = 0; i < N; ++i) pre[i] = src[(tid / kWave + 4 * i) * pitch];
-    }
-  }
-  template <int N>
-  static __device__ __forceinline__ void commit(const u32x4_t (&pre)[N], u32x4_t* ring0, int next, int total, int tid) {
-    if (next < total) {
-      u32x4_t* dstp = ring0 + (next % NSLOT) * (SUB * kWave);
-#pragma unroll
-      for (int i = 0; i < N; ++i) dstp[tid + i * 256] = pre[i];
+      for (int i = 0; i < PER_THREAD; ++i) {
+        const u32x4_t* g = src + (wave + 4 * i) * pitch;
+        const unsigned l = __builtin_amdgcn_readfirstlane(dst + (unsigned)((wave + 4 * i) * kWave * 16));
+        // Issued as assembly so that the compiler's wait-count pass does not place a full vector-memory
+        // wait in front of every later LDS read; completion is awaited explicitly when a step closes.
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory", "m0");
+      }
     }
   }
 };
@@ -241,9 +240,9 @@ struct FfnHalfArgs {
 template <int NB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void ffn_half_kernel(FfnHalfArgs a) {
   constexpr int D = 32 * NB, SUB = 2 * NB, NC = 4 * NB;  // SUB fragments per sub-chunk (= k-steps over D)
-  constexpr int NSLOT = 3, FIFO = NB;
+  constexpr int NSLOT = kRingSlots, FIFO = NB;
   constexpr int TOTAL_SUB = NB + 3 * NC + NB;
-  static_assert(NB % 2 == 0, "NB must be even");  // whole 16-byte loads per thread; even number of pipeline slots
+  static_assert(NB % 2 == 0, "NB must be even");  // whole fragments per wavefront per sub-chunk
   __shared__ u32x4_t ring[NSLOT][SUB * kWave];
   __shared__ float t_g[D], t_b[D], t_b2[D], t_bout[D], t_bo[D], t_b1[8 * D];
   __shared__ __attribute__((aligned(16))) float stage[4][32][36];  // slice-out transpose, one patch per wavefront
@@ -291,37 +290,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   for (int i = tid; i < 8 * D; i += 256) t_b1[i] = param_or(a.b1, i, 0.f);
 
-  // ---- weight stream: sub-chunks 0 and 1 straight into the ring, sub-chunk 2 into register set 1
-  // (as if loaded in a step -1)
+  // ---- weight stream: the first three sub-chunks go straight into the ring
   using Pipe = WeightPipe<SUB>;
-  u32x4_t pre0[Pipe::PER_THREAD], pre1[Pipe::PER_THREAD];
-  int cur = 0;  // sub-chunk being consumed; loads run at cur + 3, ring stores at cur + 2
-  Pipe::fetch(pre0, a.stream, 0, TOTAL_SUB, tid);
-  Pipe::fetch(pre1, a.stream, 1, TOTAL_SUB, tid);
-  Pipe::commit(pre0, ring[0], 0, TOTAL_SUB, tid);
-  Pipe::commit(pre1, ring[0], 1, TOTAL_SUB, tid);
-  Pipe::fetch(pre1, a.stream, 2, TOTAL_SUB, tid);
-
-  __syncthreads();  // tables and the first two sub-chunks are in LDS
+  const int64_t pitch = stream_pitch_u4(TOTAL_SUB);
+  int cur = 0;  // sub-chunk being consumed; loads run at cur + 3
+  Pipe::issue(a.stream, ring[0], 0, TOTAL_SUB, pitch, lane, wave);
+  Pipe::issue(a.stream, ring[0], 1, TOTAL_SUB, pitch, lane, wave);
+  Pipe::issue(a.stream, ring[0], 2, TOTAL_SUB, pitch, lane, wave);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): also the residual / attention rows loaded above
+  __syncthreads();  // tables and the first three sub-chunks are in LDS
 
   // ---- fragment FIFO: the first FIFO fragments of sub-chunk 0
   bf16x8_t fifo[FIFO];
 #pragma unroll
   for (int i = 0; i < FIFO; ++i) fifo[i] = __builtin_bit_cast(bf16x8_t, ring[0][i * kWave + lane]);
 
-  // One pipeline step around the MFMAs of sub-chunk `cur`; P is the step's parity (compile time).
-#define SI_STEP_OPEN(P)                                                         \
-  __builtin_amdgcn_sched_barrier(0);                                            \
-  if constexpr ((P) == 0) Pipe::fetch(pre0, a.stream, cur + 3, TOTAL_SUB, tid); \
-  else Pipe::fetch(pre1, a.stream, cur + 3, TOTAL_SUB, tid);                    \
-  const u32x4_t* slot_c = ring[cur % NSLOT];                                    \
-  const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                              \
+  // One pipeline step around the MFMAs of sub-chunk `cur` (see WeightPipe).
+#define SI_STEP_OPEN()                                                           \
+  __builtin_amdgcn_sched_barrier(0);                                             \
+  Pipe::issue(a.stream, ring[0], cur + 3, TOTAL_SUB, pitch, lane, wave);         \
+  const u32x4_t* slot_c = ring[cur % NSLOT];                                     \
+  const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                               \
   (void)slot_c; (void)slot_n
-#define SI_STEP_CLOSE(P)                                                        \
-  __builtin_amdgcn_sched_barrier(0);                                            \
-  if constexpr ((P) == 0) Pipe::commit(pre1, ring[0], cur + 2, TOTAL_SUB, tid); \
-  else Pipe::commit(pre0, ring[0], cur + 2, TOTAL_SUB, tid);                    \
-  ++cur;                                                                        \
+#define SI_STEP_CLOSE()                                                          \
+  __builtin_amdgcn_sched_barrier(0);                                             \
+  __builtin_amdgcn_s_waitcnt(Pipe::wait_imm(Pipe::PER_THREAD));                  \
+  ++cur;                                                                         \
+  __syncthreads()
+  // as above when EXTRA (0 or 2) further loads were issued after this step's weight loads
+#define SI_STEP_CLOSE_EXTRA(EXTRA)                                               \
+  __builtin_amdgcn_sched_barrier(0);                                             \
+  if ((EXTRA) == 2) __builtin_amdgcn_s_waitcnt(Pipe::wait_imm(Pipe::PER_THREAD + 2)); \
+  else __builtin_amdgcn_s_waitcnt(Pipe::wait_imm(Pipe::PER_THREAD));             \
+  ++cur;                                                                         \
   __syncthreads()
   // fragment f of the current sub-chunk, and its replacement FIFO fragments further down the stream
 #define SI_FRAG(f) fifo[(f) % FIFO]
@@ -329,23 +330,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   fifo[(f) % FIFO] = __builtin_bit_cast(bf16x8_t, (f) < FIFO ? slot_c[((f) + FIFO) * kWave + lane]   \
                                                              : slot_n[((f)-FIFO) * kWave + lane])
   // ---- h += o W_o + b_o: NB steps, one 32-column block of the residual each
-#define SI_WO_BLOCK(nb, P)                                                                          \
+#define SI_WO_BLOCK(nb)                                                                          \
   {                                                                                                 \
-    SI_STEP_OPEN(P);                                                                                \
+    SI_STEP_OPEN();                                                                                \
     _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                               \
       hacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), aop[s], hacc[nb], 0, 0, 0);    \
       SI_REFILL(s);                                                                                 \
       __builtin_amdgcn_sched_barrier(0);                                                            \
     }                                                                                               \
-    SI_STEP_CLOSE(P);                                                                               \
+    SI_STEP_CLOSE();                                                                               \
     _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                   \
     _Pragma("unroll") for (int j = 0; j < 4; ++j) hacc[nb][4 * q + j] += t_bo[32 * (nb) + 8 * q + 4 * g + j]; \
   }
 #pragma unroll
-  for (int nb2 = 0; nb2 < NB; nb2 += 2) {
-    SI_WO_BLOCK(nb2, 0)
-    SI_WO_BLOCK(nb2 + 1, 1)
-  }
+  for (int nb = 0; nb < NB; ++nb) SI_WO_BLOCK(nb)
 #undef SI_WO_BLOCK
 
   // ---- LN3 over the row (this lane holds half of it, lane ^ 32 the other half); aop becomes its output
@@ -410,37 +408,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   // Pipeline slot t: MFMAs of W1(t+1) and W2(t-1), GEGLU of chunk t in three groups of result
   // registers.  Chunk c keeps its W1 results in register set c % 2, its operand in gop set c % 2.
-#define SI_SLOT(t, P0, UVC, UGC, UVN, UGN, GOPP, GOPC)                                              \
+#define SI_SLOT(t, UVC, UGC, UVN, UGN, GOPP, GOPC)                                              \
   {                                                                                                 \
     const float* bvp = t_b1 + 32 * (t) + 4 * g;                                                     \
     const float* bgp = bvp + 4 * D;                                                                 \
     GegluGroup<0, 6> ga;                                                                            \
     GegluGroup<6, 5> gb;                                                                            \
     GegluGroup<11, 5> gc;                                                                           \
-    { SI_STEP_OPEN(P0); SI_RUN_W1(UVN, ga.stage(s, UVC, UGC, bvp, bgp, gv)) SI_GEGLU_TAIL(ga, UVC, UGC); SI_STEP_CLOSE(P0); } \
-    { SI_STEP_OPEN(1 - (P0)); SI_RUN_W1(UGN, gb.stage(s, UVC, UGC, bvp, bgp, gv)) SI_GEGLU_TAIL(gb, UVC, UGC); SI_STEP_CLOSE(1 - (P0)); } \
-    { SI_STEP_OPEN(P0); SI_RUN_W2(GOPP, gc.stage(s, UVC, UGC, bvp, bgp, gv)) SI_GEGLU_TAIL(gc, UVC, UGC); SI_GELU_PACK(GOPC); SI_STEP_CLOSE(P0); } \
+    { SI_STEP_OPEN(); SI_RUN_W1(UVN, ga.stage(s, UVC, UGC, bvp, bgp, gv)) SI_GEGLU_TAIL(ga, UVC, UGC); SI_STEP_CLOSE(); } \
+    { SI_STEP_OPEN(); SI_RUN_W1(UGN, gb.stage(s, UVC, UGC, bvp, bgp, gv)) SI_GEGLU_TAIL(gb, UVC, UGC); SI_STEP_CLOSE(); } \
+    { SI_STEP_OPEN(); SI_RUN_W2(GOPP, gc.stage(s, UVC, UGC, bvp, bgp, gv)) SI_GEGLU_TAIL(gc, UVC, UGC); SI_GELU_PACK(GOPC); SI_STEP_CLOSE(); } \
   }
 
   f32x16_t uvA, ugA, uvB, ugB;
   bf16x8_t gopA[2], gopB[2];
   float gv[16];
   // prologue: W1(0), then W1(1) with the GEGLU of chunk 0
-  { SI_STEP_OPEN(0); SI_RUN_W1(uvA, (void)0) SI_STEP_CLOSE(0); }
-  { SI_STEP_OPEN(1); SI_RUN_W1(ugA, (void)0) SI_STEP_CLOSE(1); }
+  { SI_STEP_OPEN(); SI_RUN_W1(uvA, (void)0) SI_STEP_CLOSE(); }
+  { SI_STEP_OPEN(); SI_RUN_W1(ugA, (void)0) SI_STEP_CLOSE(); }
   {
     const float* bvp = t_b1 + 4 * g;
     const float* bgp = bvp + 4 * D;
     GegluGroup<0, 8> ga;
     GegluGroup<8, 8> gb;
-    { SI_STEP_OPEN(0); SI_RUN_W1(uvB, ga.stage(s, uvA, ugA, bvp, bgp, gv)) SI_GEGLU_TAIL(ga, uvA, ugA); SI_STEP_CLOSE(0); }
-    { SI_STEP_OPEN(1); SI_RUN_W1(ugB, gb.stage(s, uvA, ugA, bvp, bgp, gv)) SI_GEGLU_TAIL(gb, uvA, ugA); SI_GELU_PACK(gopA); SI_STEP_CLOSE(1); }
+    { SI_STEP_OPEN(); SI_RUN_W1(uvB, ga.stage(s, uvA, ugA, bvp, bgp, gv)) SI_GEGLU_TAIL(ga, uvA, ugA); SI_STEP_CLOSE(); }
+    { SI_STEP_OPEN(); SI_RUN_W1(ugB, gb.stage(s, uvA, ugA, bvp, bgp, gv)) SI_GEGLU_TAIL(gb, uvA, ugA); SI_GELU_PACK(gopA); SI_STEP_CLOSE(); }
   }
   // steady state, two slots per trip (odd chunk in set B, even chunk in set A)
 #pragma unroll 1
   for (int t = 1; t <= NC - 2; t += 2) {
-    SI_SLOT(t, 0, uvB, ugB, uvA, ugA, gopA, gopB)
-    SI_SLOT(t + 1, 1, uvA, ugA, uvB, ugB, gopB, gopA)
+    SI_SLOT(t, uvB, ugB, uvA, ugA, gopA, gopB)
+    SI_SLOT(t + 1, uvA, ugA, uvB, ugB, gopB, gopA)
   }
   // drain: W2(NC-2) with the GEGLU of the last chunk (set B), then W2(NC-1)
   {
@@ -453,8 +451,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
     for (int s = 0; s < kGeluStages; ++s) gb.stage(s, uvB, ugB, bvp, bgp, gv);
     SI_GELU_PACK(gopB);
-    { SI_STEP_OPEN(0); SI_RUN_W2(gopA, (void)0) SI_STEP_CLOSE(0); }
-    { SI_STEP_OPEN(1); SI_RUN_W2(gopB, (void)0) SI_STEP_CLOSE(1); }
+    { SI_STEP_OPEN(); SI_RUN_W2(gopA, (void)0) SI_STEP_CLOSE(); }
+    { SI_STEP_OPEN(); SI_RUN_W2(gopB, (void)0) SI_STEP_CLOSE(); }
   }
 
   // ---- final h (+ b2) as bf16 operands; proj_out one 32-channel block at a time
@@ -495,28 +493,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
               (int64_t)vr[i] * cs;
   }
   u32x4_t xq[3][2];
+  // every wavefront issues both loads (dead lanes read the tensor's first bytes): the step-closing
+  // wait counts outstanding loads
 #define SI_X_PREFETCH(nb)                                                                                  \
   if ((nb) < NB) {                                                                                         \
-    _Pragma("unroll") for (int i = 0; i < 2; ++i) if (vlive[i])                                            \
-        xq[(nb) % 3][i] = *reinterpret_cast<const u32x4_t*>(a.x + voff[i] + (int64_t)(32 * (nb)) * cs);    \
+    _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                          \
+        xq[(nb) % 3][i] = *reinterpret_cast<const u32x4_t*>(a.x + (vlive[i] ? voff[i] + (int64_t)(32 * (nb)) * cs : 0)); \
   }
   SI_X_PREFETCH(0)
   SI_X_PREFETCH(1)
 
-  // NB + 3*NC pipeline steps precede (an even number), so block nb runs at parity nb % 2
-#define SI_PROJ_OUT_BLOCK(nb, P)                                                                 \
+#define SI_PROJ_OUT_BLOCK(nb)                                                                    \
   {                                                                                              \
     f32x16_t y;                                                                                  \
     _Pragma("unroll") for (int e = 0; e < 16; ++e) y[e] = 0.f;                                   \
-    SI_X_PREFETCH((nb) + 2)                                                                      \
     {                                                                                            \
-      SI_STEP_OPEN(P);                                                                           \
+      SI_STEP_OPEN();                                                                            \
+      SI_X_PREFETCH((nb) + 2)                                                                    \
       _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                          \
         y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), hop[s], y, 0, 0, 0);             \
         SI_REFILL(s);                                                                            \
         __builtin_amdgcn_sched_barrier(0);                                                       \
       }                                                                                          \
-      SI_STEP_CLOSE(P);                                                                          \
+      SI_STEP_CLOSE_EXTRA((nb) + 2 < NB ? 2 : 0);                                                \
     }                                                                                            \
     if (vec_ok) {                                                                                \
       float(*patch)[36] = stage[wave];                                                           \
@@ -549,10 +548,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }                                                                                            \
   }
 #pragma unroll
-  for (int nb2 = 0; nb2 < NB; nb2 += 2) {
-    SI_PROJ_OUT_BLOCK(nb2, 0)
-    SI_PROJ_OUT_BLOCK(nb2 + 1, 1)
-  }
+  for (int nb = 0; nb < NB; ++nb) SI_PROJ_OUT_BLOCK(nb)
 #undef SI_X_PREFETCH
 #undef SI_PROJ_OUT_BLOCK
 #undef SI_SLOT
@@ -562,6 +558,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #undef SI_GEGLU_TAIL
 #undef SI_REFILL
 #undef SI_FRAG
+#undef SI_STEP_CLOSE_EXTRA
 #undef SI_STEP_CLOSE
 #undef SI_STEP_OPEN
 }

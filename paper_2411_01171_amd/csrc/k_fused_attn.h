@@ -99,20 +99,21 @@ __device__ __forceinline__ void stage_window(const bf16* __restrict__ x, unsigne
 
 template <int NB, int DH>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_half_kernel(AttnHalfArgs a) {
-  constexpr int D = 32 * NB, SUB = 2 * NB, NSLOT = 3, FIFO = NB;
+  constexpr int D = 32 * NB, SUB = 2 * NB, NSLOT = kRingSlots, FIFO = NB;
   constexpr int GW = lcm_int(DH, 32);        // columns per head group
   constexpr int NBG = GW / 32, HG = GW / DH;  // blocks / heads per group
   constexpr int NG = D / GW;
   constexpr int TOTAL_SUB = NB + 3 * NB;
   constexpr int XLD = D + 8;  // padded row of the staged x tile (bf16 elements)
   static_assert(NB % 2 == 0 && D % GW == 0 && DH % 8 == 0, "shape");
-  constexpr int RING_BYTES = NSLOT * SUB * kWave * 16, XS_BYTES = 128 * XLD * 2;
-  // the staged x tile is dead before the weight ring is first written: they share LDS
-  __shared__ __attribute__((aligned(16))) unsigned char arena[RING_BYTES > XS_BYTES ? RING_BYTES : XS_BYTES];
+  constexpr int SLOT_BYTES = SUB * kWave * 16, XS_BYTES = 128 * XLD * 2;
+  // ring slots 0 and 1 are loaded while the staged x tile is in use; the tile shares LDS with slots 2, 3
+  constexpr int TAIL_BYTES = 2 * SLOT_BYTES > XS_BYTES ? 2 * SLOT_BYTES : XS_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char arena[2 * SLOT_BYTES + TAIL_BYTES];
   __shared__ float2 t_stats[2][kAttnMaxStats];
   __shared__ __attribute__((aligned(16))) float t_gng[D], t_gnb[D], t_bin[D], t_lg[D], t_lb[D];
   u32x4_t(*ring)[SUB * kWave] = reinterpret_cast<u32x4_t(*)[SUB * kWave]>(arena);
-  unsigned short* xs = reinterpret_cast<unsigned short*>(arena);
+  unsigned short* xs = reinterpret_cast<unsigned short*>(arena + 2 * SLOT_BYTES);
 
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int tcol = lane % 32, g = lane / 32;
@@ -133,12 +134,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int my_b = live ? (int)(my_seq / w.Pw) : 0, my_pl = live ? (int)(my_seq % w.Pw) : 0;
   const int64_t my_m = ((int64_t)my_b * F + my_f) * w.Pw + my_pl;
 
-  // ---- weight stream: the first sub-chunks wait in registers until the x tile has left LDS
+  // ---- weight stream (see WeightPipe): sub-chunks 0 and 1 now, sub-chunk 2 once the x tile has left LDS
   using Pipe = WeightPipe<SUB>;
-  u32x4_t pre0[Pipe::PER_THREAD], pre1[Pipe::PER_THREAD];
+  const int64_t pitch = stream_pitch_u4(TOTAL_SUB);
   int cur = 0;
-  Pipe::fetch(pre0, a.stream, 0, TOTAL_SUB, tid);
-  Pipe::fetch(pre1, a.stream, 1, TOTAL_SUB, tid);
+  Pipe::issue(a.stream, ring[0], 0, TOTAL_SUB, pitch, lane, wave);
+  Pipe::issue(a.stream, ring[0], 1, TOTAL_SUB, pitch, lane, wave);
 
   // ---- tables; the staged tile starts as zeros (padding rows and columns stay zero)
   const int b_first = (int)(seq_wg / w.Pw);
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (bb < w.B) st = *reinterpret_cast<const float2*>(a.stats + ((int64_t)bb * F * w.G + r) * 2);
     t_stats[bs][r] = st;
   }
-  for (int i = tid; i < XS_BYTES / 16; i += 256) reinterpret_cast<u32x4_t*>(arena)[i] = u32x4_t{0, 0, 0, 0};
+  for (int i = tid; i < XS_BYTES / 16; i += 256) reinterpret_cast<u32x4_t*>(xs)[i] = u32x4_t{0, 0, 0, 0};
   __syncthreads();
 
   // ---- slice-in: x[b, c, f, p0 + pl] -> GroupNorm -> xs[row][c].  A thread owns one (frame,
@@ -182,62 +183,59 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       aop[s] = __builtin_bit_cast(bf16x8_t, u);
     }
   }
-  __syncthreads();  // every wavefront has its operands: the arena becomes the weight ring
-  Pipe::commit(pre0, ring[0], 0, TOTAL_SUB, tid);
-  Pipe::commit(pre1, ring[0], 1, TOTAL_SUB, tid);
-  Pipe::fetch(pre1, a.stream, 2, TOTAL_SUB, tid);
+  __syncthreads();  // every wavefront has its operands: the tile's LDS becomes ring slots 2 and 3
+  Pipe::issue(a.stream, ring[0], 2, TOTAL_SUB, pitch, lane, wave);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
 
   bf16x8_t fifo[FIFO];
 #pragma unroll
   for (int i = 0; i < FIFO; ++i) fifo[i] = __builtin_bit_cast(bf16x8_t, ring[0][i * kWave + lane]);
 
-#define SI_STEP_OPEN(P)                                                         \
-  __builtin_amdgcn_sched_barrier(0);                                            \
-  if constexpr ((P) == 0) Pipe::fetch(pre0, a.stream, cur + 3, TOTAL_SUB, tid); \
-  else Pipe::fetch(pre1, a.stream, cur + 3, TOTAL_SUB, tid);                    \
-  const u32x4_t* slot_c = ring[cur % NSLOT];                                    \
-  const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                              \
+#define SI_STEP_OPEN()                                                           \
+  __builtin_amdgcn_sched_barrier(0);                                             \
+  Pipe::issue(a.stream, ring[0], cur + 3, TOTAL_SUB, pitch, lane, wave);         \
+  const u32x4_t* slot_c = ring[cur % NSLOT];                                     \
+  const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                               \
   (void)slot_c; (void)slot_n
-#define SI_STEP_CLOSE(P)                                                        \
-  __builtin_amdgcn_sched_barrier(0);                                            \
-  if constexpr ((P) == 0) Pipe::commit(pre1, ring[0], cur + 2, TOTAL_SUB, tid); \
-  else Pipe::commit(pre0, ring[0], cur + 2, TOTAL_SUB, tid);                    \
-  ++cur;                                                                        \
+#define SI_STEP_CLOSE()                                                          \
+  __builtin_amdgcn_sched_barrier(0);                                             \
+  __builtin_amdgcn_s_waitcnt(Pipe::wait_imm(Pipe::PER_THREAD));                  \
+  ++cur;                                                                         \
   __syncthreads()
 #define SI_FRAG(f) fifo[(f) % FIFO]
 #define SI_REFILL(f)                                                                                 \
   fifo[(f) % FIFO] = __builtin_bit_cast(bf16x8_t, (f) < FIFO ? slot_c[((f) + FIFO) * kWave + lane]   \
                                                              : slot_n[((f)-FIFO) * kWave + lane])
   // one 32-column block: weights as rows (result: lane = token) or as columns (result: lane = column)
-#define SI_BLOCK_WROWS(ACC, P)                                                              \
+#define SI_BLOCK_WROWS(ACC)                                                                 \
   {                                                                                         \
-    SI_STEP_OPEN(P);                                                                        \
+    SI_STEP_OPEN();                                                                         \
     _Pragma("unroll") for (int e = 0; e < 16; ++e) ACC[e] = 0.f;                            \
     _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                       \
       ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), aop[s], ACC, 0, 0, 0);      \
       SI_REFILL(s);                                                                         \
       __builtin_amdgcn_sched_barrier(0);                                                    \
     }                                                                                       \
-    SI_STEP_CLOSE(P);                                                                       \
+    SI_STEP_CLOSE();                                                                        \
   }
-#define SI_BLOCK_WCOLS(ACC, P)                                                              \
+#define SI_BLOCK_WCOLS(ACC)                                                                 \
   {                                                                                         \
-    SI_STEP_OPEN(P);                                                                        \
+    SI_STEP_OPEN();                                                                         \
     _Pragma("unroll") for (int e = 0; e < 16; ++e) ACC[e] = 0.f;                            \
     _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                       \
       ACC = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[s], SI_FRAG(s), ACC, 0, 0, 0);      \
       SI_REFILL(s);                                                                         \
       __builtin_amdgcn_sched_barrier(0);                                                    \
     }                                                                                       \
-    SI_STEP_CLOSE(P);                                                                       \
+    SI_STEP_CLOSE();                                                                        \
   }
 
   // ---- proj_in, h0 to memory
   f32x16_t hacc[NB];
-#define SI_PROJ_IN_BLOCK(nb, P)                                                                      \
+#define SI_PROJ_IN_BLOCK(nb)                                                                         \
   {                                                                                                  \
-    SI_BLOCK_WROWS(hacc[nb], P)                                                                      \
+    SI_BLOCK_WROWS(hacc[nb])                                                                         \
     _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                  \
       const float4 bb = *reinterpret_cast<const float4*>(&t_bin[32 * (nb) + 8 * q + 4 * g]);         \
       hacc[nb][4 * q + 0] += bb.x; hacc[nb][4 * q + 1] += bb.y;                                      \
@@ -248,10 +246,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }                                                                                                \
   }
 #pragma unroll
-  for (int nb2 = 0; nb2 < NB; nb2 += 2) {
-    SI_PROJ_IN_BLOCK(nb2, 0)
-    SI_PROJ_IN_BLOCK(nb2 + 1, 1)
-  }
+  for (int nb = 0; nb < NB; ++nb) SI_PROJ_IN_BLOCK(nb)
 #undef SI_PROJ_IN_BLOCK
 
   // ---- LN1 (+ frame embedding): aop becomes its output
@@ -307,7 +302,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   // ---- groups of heads
   {
-    constexpr int STEPS_PER_GROUP = 3 * NBG;
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
       bf16x8_t qop[2 * NBG], kop[2 * NBG], vop[2 * NBG];
@@ -316,13 +310,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
         for (int blk = 0; blk < NBG; ++blk) {
           f32x16_t acc;
-          // step parity: NB (even) + gi*3*NBG + kind*NBG + blk
-          const int par = (gi * STEPS_PER_GROUP + kind * NBG + blk) % 2;
-          if (kind < 2) {
-            if (par == 0) SI_BLOCK_WROWS(acc, 0) else SI_BLOCK_WROWS(acc, 1)
-          } else {
-            if (par == 0) SI_BLOCK_WCOLS(acc, 0) else SI_BLOCK_WCOLS(acc, 1)
-          }
+          if (kind < 2) SI_BLOCK_WROWS(acc) else SI_BLOCK_WCOLS(acc)
           float lo[8], hi[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
