@@ -56,6 +56,8 @@ def stage_work(spec, stage, M, window_tokens_per_seq=None):
         return "flop", 2.0 * M * (C * D + 3 * D * D) + 4.0 * M * spec.F * D
     if stage == "ffn_half_fused":       # attention out-projection, W1, W2, proj_out
         return "flop", 2.0 * M * (D * D + 8 * D * D + 4 * D * D + D * C)
+    if stage == "temporal_block_fused":  # the whole operator group of a window in one kernel
+        return "flop", 2.0 * M * (C * D + 3 * D * D + D * D + 8 * D * D + 4 * D * D + D * C) + 4.0 * M * spec.F * D
     if stage == "gn_stats":
         return "byte", float(spec.tokens * C * es)
     if stage == "slice_in":
@@ -104,6 +106,9 @@ def main():
     ap.add_argument("--workload", default="cfg2", help="cfg2 (default, the metric's configuration), cfg3, cfg4s, cfg4t, cfg5s, cfg5t")
     ap.add_argument("--slice-len", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of x (known bytes) so that hardware byte counters "
+                         "collected around this command can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards without changing the kernel; "
@@ -148,6 +153,9 @@ def main():
         si.si_block_forward(x, wts, ctx, out, axis, slice_len, ws)
         si.si_rehash_check(out, cached, gamma, cos, dec, scratch)
 
+    if args.calibration_copy:
+        torch.empty_like(x).copy_(x)       # reads and writes x.numel() * element_size bytes
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -13,6 +13,8 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 instruction forms are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the fused kernels rely on full unrolling so that every register array keeps constant indices
+    "-mllvm", "-pragma-unroll-threshold=262144",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes",
 ]
 

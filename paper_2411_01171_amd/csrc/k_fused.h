@@ -199,12 +199,35 @@ __global__ __launch_bounds__(256) void pack_blocks_kernel(BlockList list, int n_
 // slot (i+1) % 4.  Before the barrier that closes step i every wavefront waits until at most its
 // newest batch of loads is outstanding (loads return in issue order), so sub-chunk i+2 is in LDS
 // for everybody two steps before it becomes the FIFO's refill source.
-constexpr int kRingSlots = 4;
+#ifndef SI_RING_SLOTS
+#define SI_RING_SLOTS 4
+#endif
+constexpr int kRingSlots = SI_RING_SLOTS;
+static_assert(kRingSlots >= 4 && kRingSlots <= 6, "ring depth");
 template <int SUB>
 struct WeightPipe {
   static constexpr int PER_THREAD = SUB * kWave / 256;  // loads per lane per sub-chunk
   // s_waitcnt immediate (gfx9 encoding): vmcnt <= n, other counters unconstrained
   static constexpr int wait_imm(int n) { return (n & 0xF) | 0x70 | 0xF00 | ((n >> 4) << 14); }
+  // Closing wait of step `cur`: sub-chunk cur + 2 must have landed.  Younger batches (up to
+  // kRingSlots - 3 of them, fewer at the stream's tail) and EXTRA loads issued after them may stay
+  // in flight.
+  template <int EXTRA = 0>
+  static __device__ __forceinline__ void wait_step(int cur, int total) {
+    int n = total - 3 - cur;
+    n = n < kRingSlots - 3 ? n : kRingSlots - 3;
+    if (n <= 0) __builtin_amdgcn_s_waitcnt(wait_imm(EXTRA));
+    else if (n == 1) __builtin_amdgcn_s_waitcnt(wait_imm(PER_THREAD + EXTRA));
+    else if (n == 2) __builtin_amdgcn_s_waitcnt(wait_imm(2 * PER_THREAD + EXTRA));
+    else __builtin_amdgcn_s_waitcnt(wait_imm(3 * PER_THREAD + EXTRA));
+  }
+  // same with a run-time count (rounded down to a multiple of 4, at most 12; constant after unrolling)
+  static __device__ __forceinline__ void wait_step_n(int cur, int total, int extra) {
+    if (extra >= 12) wait_step<12>(cur, total);
+    else if (extra >= 8) wait_step<8>(cur, total);
+    else if (extra >= 4) wait_step<4>(cur, total);
+    else wait_step<0>(cur, total);
+  }
   static __device__ __forceinline__ void issue(const u32x4_t* stream, u32x4_t* ring0, int sub, int total, int64_t pitch,
                                                int lane, int wave) {
     if (sub < total) {
@@ -217,7 +240,8 @@ struct WeightPipe {
         const unsigned l = __builtin_amdgcn_readfirstlane(dst + (unsigned)((wave + 4 * i) * kWave * 16));
         // Issued as assembly so that the compiler's wait-count pass does not place a full vector-memory
         // wait in front of every later LDS read; completion is awaited explicitly when a step closes.
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory", "m0");
+        // M0 is reserved by the compiler and used by nothing else in these kernels.
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory");
       }
     }
   }
@@ -294,9 +318,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   using Pipe = WeightPipe<SUB>;
   const int64_t pitch = stream_pitch_u4(TOTAL_SUB);
   int cur = 0;  // sub-chunk being consumed; loads run at cur + 3
-  Pipe::issue(a.stream, ring[0], 0, TOTAL_SUB, pitch, lane, wave);
-  Pipe::issue(a.stream, ring[0], 1, TOTAL_SUB, pitch, lane, wave);
-  Pipe::issue(a.stream, ring[0], 2, TOTAL_SUB, pitch, lane, wave);
+#pragma unroll
+  for (int i = 0; i < NSLOT - 1; ++i) Pipe::issue(a.stream, ring[0], i, TOTAL_SUB, pitch, lane, wave);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): also the residual / attention rows loaded above
   __syncthreads();  // tables and the first three sub-chunks are in LDS
 
@@ -308,20 +331,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // One pipeline step around the MFMAs of sub-chunk `cur` (see WeightPipe).
 #define SI_STEP_OPEN()                                                           \
   __builtin_amdgcn_sched_barrier(0);                                             \
-  Pipe::issue(a.stream, ring[0], cur + 3, TOTAL_SUB, pitch, lane, wave);         \
+  Pipe::issue(a.stream, ring[0], cur + NSLOT - 1, TOTAL_SUB, pitch, lane, wave); \
   const u32x4_t* slot_c = ring[cur % NSLOT];                                     \
   const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                               \
   (void)slot_c; (void)slot_n
 #define SI_STEP_CLOSE()                                                          \
   __builtin_amdgcn_sched_barrier(0);                                             \
-  __builtin_amdgcn_s_waitcnt(Pipe::wait_imm(Pipe::PER_THREAD));                  \
+  Pipe::template wait_step<0>(cur, TOTAL_SUB);                                   \
   ++cur;                                                                         \
   __syncthreads()
   // as above when EXTRA (0 or 2) further loads were issued after this step's weight loads
 #define SI_STEP_CLOSE_EXTRA(EXTRA)                                               \
   __builtin_amdgcn_sched_barrier(0);                                             \
-  if ((EXTRA) == 2) __builtin_amdgcn_s_waitcnt(Pipe::wait_imm(Pipe::PER_THREAD + 2)); \
-  else __builtin_amdgcn_s_waitcnt(Pipe::wait_imm(Pipe::PER_THREAD));             \
+  if ((EXTRA) == 2) Pipe::template wait_step<2>(cur, TOTAL_SUB);                 \
+  else Pipe::template wait_step<0>(cur, TOTAL_SUB);                              \
   ++cur;                                                                         \
   __syncthreads()
   // fragment f of the current sub-chunk, and its replacement FIFO fragments further down the stream

@@ -35,7 +35,7 @@ struct AttnHalfArgs {
   Window win;           // temporal window: all F frames, positions [p0, p0 + Pw)
 };
 
-constexpr int kAttnMaxStats = 1024;  // F * G entries per batch entry held in LDS
+constexpr int kAttnMaxStats = 896;  // F * G entries per batch entry held in LDS
 
 // Cooperative slice-in of one workgroup tile (see attn_half_kernel).  NPOS consecutive sequences
 // (b, position) starting at seq_wg; xs row of (sequence j, frame f) = (j / TP) * 32 + (j % TP) * F + f.
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   (void)slot_c; (void)slot_n
 #define SI_STEP_CLOSE()                                                          \
   __builtin_amdgcn_sched_barrier(0);                                             \
-  __builtin_amdgcn_s_waitcnt(Pipe::wait_imm(Pipe::PER_THREAD));                  \
+  Pipe::template wait_step<0>(cur, TOTAL_SUB);                                   \
   ++cur;                                                                         \
   __syncthreads()
 #define SI_FRAG(f) fifo[(f) % FIFO]

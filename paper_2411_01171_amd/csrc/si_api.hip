@@ -14,6 +14,7 @@
 #include "k_cosine.h"
 #include "k_fused.h"
 #include "k_fused_attn.h"
+#include "k_fused_block.h"
 #include "k_gemm.h"
 #include "k_norm.h"
 #include "si_common.h"
@@ -139,14 +140,19 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     p->fused_nb = (int)(D / 32);
     const int tp = p->F <= 32 ? 32 / p->F : 0;
     const bool dh_ok = (D == 320 && (p->d == 40 || p->d == 64)) || (D == 64 && p->d == 32);
+    // a workgroup (up to 128 consecutive positions) keeps the statistics of two batch entries: every
+    // window, the shorter last one included, must be at least that long unless B <= 2
+    const int64_t last_len = p->extent % p->slice_len ? p->extent % p->slice_len : p->slice_len;
     p->fused_attn = p->kind == SI_BLOCK_TEMPORAL && tp >= 1 && dh_ok && (int64_t)p->F * p->G <= kAttnMaxStats &&
-                    (p->B <= 2 || p->slice_len >= 128);
+                    (p->B <= 2 || last_len >= 128);
   }
   // one slice's intermediates
   const size_t split = es == 2 ? 2 : 1;  // bf16 staged path: proj_in / proj_out operands travel as (high, low) pairs
-  if (p->fused_attn) {
-    p->off_a = take((size_t)p->Mmax * Dz * es);  // attention output o
-    p->off_h = take((size_t)p->Mmax * Dz * sizeof(float));
+  if (p->fused_attn) {  // one kernel per window: only the parked residual stream (128 rows per workgroup)
+    const int64_t npos = 4 * (32 / p->F);
+    const int64_t wgs = ((int64_t)p->B * p->slice_len + npos - 1) / npos;
+    p->off_a = take(0);
+    p->off_h = take((size_t)wgs * 128 * Dz * sizeof(float));
     p->off_big = take(0);
   } else {
     p->off_a = take((size_t)p->Mmax * (C > Dz ? C : Dz) * split * es);
@@ -165,8 +171,8 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_w1 = take(8 * Dz * Dz * es);
   p->off_w2 = take(4 * Dz * Dz * es);
   p->off_w_out = take(split * C * Dz * es);
-  p->off_ffn_stream = take(p->fused_nb ? (size_t)stream_bytes(14 * p->fused_nb, 2 * p->fused_nb) : 0);
-  p->off_attn_stream = take(p->fused_attn ? (size_t)stream_bytes(4 * p->fused_nb, 2 * p->fused_nb) : 0);
+  p->off_ffn_stream = take(p->fused_nb && !p->fused_attn ? (size_t)stream_bytes(14 * p->fused_nb, 2 * p->fused_nb) : 0);
+  p->off_attn_stream = take(p->fused_attn ? (size_t)stream_bytes(18 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->weights_bytes = off - act_end;
   p->total_bytes = off;
   return SI_OK;
@@ -242,22 +248,22 @@ static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, ch
   const int D = p.D;
   auto cB = [](const void* q) { return static_cast<const bf16*>(q); };
   const bool spatial = p.kind == SI_BLOCK_SPATIAL;
-  {  // FFN half: out-projection of the last attention, FFN, proj_out
-    u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + p.off_ffn_stream);
-    const int total = 14 * NB;
+  // FFN half (alone: sub-chunks 0..14NB; after the attention half: 4NB..18NB): out-projection of the
+  // last attention, FFN, proj_out
+  const int base = p.fused_attn ? 4 * NB : 0, total = base + 14 * NB;
+  u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + (p.fused_attn ? p.off_attn_stream : p.off_ffn_stream));
+  {
     BlockList list;
     for (int nb = 0; nb < NB; ++nb) list.b[nb] = BlockDesc{cB(spatial ? w->wo2 : w->wo), D, 32 * nb};
-    pack_blocks_kernel<NB><<<(NB * 2 * NB + 3) / 4, 256, 0, st>>>(list, NB, stream, 0, total);
+    pack_blocks_kernel<NB><<<(NB * 2 * NB + 3) / 4, 256, 0, st>>>(list, NB, stream, base, total);
     SI_CHECK_LAUNCH();
-    pack_ffn_stream_kernel<NB><<<(12 * NB * 2 * NB + 3) / 4, 256, 0, st>>>(cB(w->w1), cB(w->w2), stream, NB, total);
+    pack_ffn_stream_kernel<NB><<<(12 * NB * 2 * NB + 3) / 4, 256, 0, st>>>(cB(w->w1), cB(w->w2), stream, base + NB, total);
     SI_CHECK_LAUNCH();
     for (int nb = 0; nb < NB; ++nb) list.b[nb] = BlockDesc{cB(w->w_out), p.C, 32 * nb};
-    pack_blocks_kernel<NB><<<(NB * 2 * NB + 3) / 4, 256, 0, st>>>(list, NB, stream, 13 * NB, total);
+    pack_blocks_kernel<NB><<<(NB * 2 * NB + 3) / 4, 256, 0, st>>>(list, NB, stream, base + 13 * NB, total);
     SI_CHECK_LAUNCH();
   }
   if (p.fused_attn) {  // attention half: W_in blocks, then per head group q, k, v blocks
-    u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + p.off_attn_stream);
-    const int total = 4 * NB;
     const int gw = lcm_int(p.d, 32), nbg = gw / 32, ng = D / gw;
     BlockList list;
     int n = 0;
@@ -359,19 +365,22 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     const int64_t M = (int64_t)p.B * win.Fw * win.Pw;
 
     if constexpr (sizeof(T) == 2) {
-      if (fused_attn) {  // slice-in .. attention in one kernel: h0 -> h, attention output -> a
-        StageScope scope("attn_half_fused", st);
-        AttnHalfArgs aa;
-        aa.x = X; aa.stats = stats; aa.gn_g = cT(w->gn_g); aa.gn_b = cT(w->gn_b); aa.b_in = cT(w->b_in);
-        aa.ln_g = cT(w->ln1_g); aa.ln_b = cT(w->ln1_b); aa.pe = pe;
-        aa.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_attn_stream);
-        aa.h0 = h; aa.o = a; aa.ln_eps = w->ln_eps; aa.scale = scale; aa.win = win;
+      if (fused_attn) {  // the whole operator group of the window in one kernel
+        StageScope scope("temporal_block_fused", st);
+        TemporalBlockArgs ta;
+        ta.x = X; ta.out = OUT; ta.stats = stats;
+        ta.gn_g = cT(w->gn_g); ta.gn_b = cT(w->gn_b); ta.b_in = cT(w->b_in);
+        ta.ln1_g = cT(w->ln1_g); ta.ln1_b = cT(w->ln1_b); ta.b_o = cT(w->bo);
+        ta.ln3_g = cT(w->ln3_g); ta.ln3_b = cT(w->ln3_b); ta.b1 = cT(w->b1); ta.b2 = cT(w->b2); ta.b_out = cT(w->b_out);
+        ta.pe = pe; ta.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_attn_stream);
+        ta.hpark = h; ta.ln_eps = w->ln_eps; ta.scale = scale; ta.win = win;
         const int npos = 4 * (32 / p.F);
         const unsigned blocks = (unsigned)(((int64_t)p.B * win.Pw + npos - 1) / npos);
-        if (p.fused_nb == 2) attn_half_kernel<2, 32><<<blocks, 256, 0, st>>>(aa);
-        else if (p.d == 40) attn_half_kernel<10, 40><<<blocks, 256, 0, st>>>(aa);
-        else attn_half_kernel<10, 64><<<blocks, 256, 0, st>>>(aa);
+        if (p.fused_nb == 2) temporal_block_kernel<2, 32><<<blocks, 256, 0, st>>>(ta);
+        else if (p.d == 40) temporal_block_kernel<10, 40><<<blocks, 256, 0, st>>>(ta);
+        else temporal_block_kernel<10, 64><<<blocks, 256, 0, st>>>(ta);
         SI_CHECK_LAUNCH();
+        continue;
       }
     }
     if (!fused_attn) {
