@@ -208,13 +208,22 @@ def main():
         roof = {"bound": "hbm", "kernel": dominant, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS}
     roof["avg_launch_us"] = d_ms / d_cnt * 1e3
+    # HBM bytes per launch of that kernel from hardware counters (separate rocprofv3 --pmc runs of this
+    # command, summarised under profiles/); null for workloads that were not profiled
     roof["traffic"] = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "traffic_per_launch.txt")
     if os.path.exists(tpath):
         try:
-            roof["traffic"] = json.load(open(tpath)).get(args.workload, {}).get(dominant)
+            rec = json.load(open(tpath)).get(args.workload, {}).get(dominant)
+            if rec:
+                roof["traffic"] = rec["total_bytes"]
+                roof["traffic_detail"] = rec
         except Exception:
             pass
+    if d_kind == "flop":
+        roof["algorithmic_flop_per_launch"] = d_work
+    else:
+        roof["algorithmic_bytes_per_launch"] = d_work
 
     result = {
         "metric": "sliced block-forward TFLOP/s (% MFMA peak) + peak live activation bytes vs unsliced",

@@ -392,6 +392,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       const float4 v = park[(nb * 4 + q) * kWave];
       hacc[nb][4 * q + 0] = v.x; hacc[nb][4 * q + 1] = v.y; hacc[nb][4 * q + 2] = v.z; hacc[nb][4 * q + 3] = v.w;
     }
+  // all of it must be back before the steps: a wait for a late piece inside a step would also
+  // wait for the stream batches issued since
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 #define SI_WO_BLOCK(nb)                                                                             \
   {                                                                                                 \
     SI_STEP_OPEN();                                                                                 \
