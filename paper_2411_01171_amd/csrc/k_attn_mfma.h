@@ -1,0 +1,188 @@
+// Matrix-core attention for long sequences (spatial self-attention over H*W positions, cross-
+// attention over the context tokens): bf16, head dimension 64, online softmax in fp32.
+//
+// One workgroup = 128 queries of one (sequence, head); one wavefront = 32 queries, which stay the
+// *column* operand of every MFMA (v_mfma_f32_32x32x16_bf16: lane l supplies column l%32, k-slots
+// 8*(l/32) .. +7; a result lane holds column l%32 and, in register 4q + j, row 8q + 4*(l/32) + j):
+//   S^T[key, query] = K Q^T      row operand: 32 keys x 16 head channels, straight from k's rows
+//   O^T[chan, query] += V^T P^T  row operand: 32 head channels x 16 keys, from the transposed
+//                                copy vt[seq][channel][key]; column operand: the softmax result
+//                                registers of the lane, converted to bf16 -- no data movement.
+// The second product wants its 16 keys in the order of the result registers (rows 4g+j, then
+// 8+4g+j of each half), so the key rows of a 32-key tile are *loaded* in a permuted order (kappa
+// below) that makes that order the natural one: every fragment, K and V^T alike, is 16 contiguous
+// bytes per lane and goes to LDS with direct global->LDS loads, 64 keys (16 KiB) per stage through
+// a ring of kAttnStages stages.  A softmax is invariant under the permutation.
+#pragma once
+#include "k_fused.h"
+
+namespace si {
+
+struct AttnMfmaArgs {
+  const bf16* q;   // query i of sequence s: row s*Nq + i, head h at columns [64h, 64h+64)
+  int64_t ldq;
+  const bf16* k;   // key j of key sequence ks = s / kv_div: row ks*Nk + j
+  int64_t ldk;
+  const bf16* vt;  // values, transposed: [ks][heads*64][Nkp], keys contiguous, Nkp % 8 == 0, zero padded
+  bf16* o;         // output rows like q's
+  int64_t ldo;
+  int Nq, Nk, Nkp, heads, kv_div;
+  float scale_log2;  // softmax scale * log2(e)
+};
+
+constexpr int kAttnStages = 4;
+
+// key (within its 16-key group) whose score lands in MFMA row f of the group
+__host__ __device__ constexpr int kappa16(int f) { return f < 4 || f >= 12 ? f : (f < 8 ? f + 4 : f - 4); }
+
+// dst[(s*D + c)*Nkp + n] = src[(s*N + n)*ld + col0 + c]; zero for N <= n < Nkp.
+__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16* __restrict__ src, int64_t ld, int col0, bf16* __restrict__ dst,
+                                                          int N, int Nkp, int D) {
+  __shared__ unsigned short tile[32][33];
+  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
+  const int n0 = blockIdx.x * 32, c0 = blockIdx.y * 32, s = blockIdx.z;
+  for (int nn = ty; nn < 32; nn += 8) {
+    const int n = n0 + nn, c = c0 + tx;
+    tile[nn][tx] = (n < N && c < D) ? src[((int64_t)s * N + n) * ld + col0 + c].v : (unsigned short)0;
+  }
+  __syncthreads();
+  for (int cc = ty; cc < 32; cc += 8) {
+    const int n = n0 + tx, c = c0 + cc;
+    if (n < Nkp && c < D) dst[((int64_t)s * D + c) * Nkp + n].v = tile[tx][cc];
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnMfmaArgs a) {
+  constexpr int NS = kAttnStages, FR = 16;  // fragments per stage: 8 of K (2 tiles x 4 k-steps), 8 of V^T (2 tiles x 2 blocks x 2 k-steps)
+  __shared__ u32x4_t ring[NS][FR * kWave];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int r = lane % 32, g = lane / 32;
+  const int h = blockIdx.y, s = blockIdx.z, ks = s / a.kv_div;
+  const int qi = (blockIdx.x * 4 + wave) * 32 + r;
+  const bool qvalid = qi < a.Nq;
+  const int nst = (a.Nk + 63) / 64;
+
+  // ---- stage loads: lane's four fragments per stage.  i < 2: K tile u = i, k-step = wave;
+  // i >= 2: V^T tile u = i - 2, channel block = wave / 2, k-step = wave % 2.
+  const int kap = 16 * (r / 16) + kappa16(r % 16);
+  const bf16* kbase = a.k + (int64_t)ks * a.Nk * a.ldk + h * 64 + 16 * wave + 8 * g;
+  const bf16* vbase = a.vt + ((int64_t)ks * a.heads * 64 + h * 64 + 32 * (wave / 2) + r) * a.Nkp;
+  const int vk = 16 * (wave % 2) + 8 * g;  // first of this lane's 8 keys within a tile
+  auto issue = [&](int st) {
+    if (st < nst) {
+      const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(ring[st % NS]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bf16* src;
+        if (i < 2) {
+          int key = 64 * st + 32 * i + kap;
+          key = key < a.Nk ? key : a.Nk - 1;
+          src = kbase + (int64_t)key * a.ldk;
+        } else {
+          int k0 = 64 * st + 32 * (i - 2) + vk;  // groups of 8 keys past the row's end hold masked keys only
+          k0 = k0 < a.Nkp - 8 ? k0 : a.Nkp - 8;
+          src = vbase + k0;
+        }
+        const int id = i < 2 ? 4 * i + wave : 8 + 4 * (i - 2) + wave;
+        const unsigned l = __builtin_amdgcn_readfirstlane(dst + (unsigned)(id * kWave * 16));
+        // assembly for the same reason as in WeightPipe::issue: completion is awaited explicitly
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
+      }
+    }
+  };
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st) issue(st);
+
+  // ---- this lane's query as column operand (head channels in natural order, as K's fragments)
+  bf16x8_t qop[4];
+  {
+    const bf16* qrow = a.q + ((int64_t)s * a.Nq + (qvalid ? qi : a.Nq - 1)) * a.ldq + h * 64 + 8 * g;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) qop[s4] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(qrow + 16 * s4));
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the query loads; nothing the compiler tracks stays pending in the loop
+
+  f32x16_t oacc[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[b][e] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+  const float c = a.scale_log2;
+
+  for (int st = 0; st < nst; ++st) {
+    // own loads of stage st have landed: at most the batches of the next NS - 2 stages stay in flight
+    {
+      const int younger = nst - 1 - st;
+      if (younger >= 2) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(8));
+      else if (younger == 1) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(4));
+      else __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(0));
+    }
+    __syncthreads();  // stage st is visible to all; everybody has left stage st - 1, whose slot is loaded next
+    issue(st + NS - 1);
+    const u32x4_t* slot = ring[st % NS];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      f32x16_t sc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sc[e] = 0.f;
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4)
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, slot[(4 * u + s4) * kWave + lane]), qop[s4], sc, 0, 0, 0);
+      if (64 * st + 32 * u + 32 > a.Nk) {  // ragged tail: rows whose key does not exist
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int i = 8 * (e / 4) + 4 * g + (e % 4);
+          const int key = 64 * st + 32 * u + 16 * (i / 16) + kappa16(i % 16);
+          if (key >= a.Nk) sc[e] = -INFINITY;
+        }
+      }
+      float mx = sc[0];
+#pragma unroll
+      for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      const float mnew = fmaxf(m, mx);  // finite from the first tile on (it always holds a real key)
+      const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
+      const float mc = mnew * c;
+      float pr[16], rs = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        pr[e] = __builtin_amdgcn_exp2f(fmaf(sc[e], c, -mc));
+        rs += pr[e];
+      }
+      rs += __shfl_xor(rs, 32, kWave);
+      lsum = lsum * alpha + rs;
+      m = mnew;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[b][e] *= alpha;
+      bf16x8_t pop[2];
+      pop[0] = to_operand(&pr[0]);
+      pop[1] = to_operand(&pr[8]);
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8_t, slot[(8 + 4 * u + 2 * b + t) * kWave + lane]), pop[t], oacc[b], 0, 0, 0);
+    }
+  }
+
+  // ---- O^T / l: register 4q + j of block b is head channel 32b + 8q + 4g + j of this lane's query
+  if (qvalid) {
+    const float inv = 1.0f / lsum;
+    bf16* orow = a.o + ((int64_t)s * a.Nq + qi) * a.ldo + h * 64 + 4 * g;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint2 v;
+        v.x = pack_bf16x2(oacc[b][4 * q + 0] * inv, oacc[b][4 * q + 1] * inv);
+        v.y = pack_bf16x2(oacc[b][4 * q + 2] * inv, oacc[b][4 * q + 3] * inv);
+        *reinterpret_cast<uint2*>(orow + 32 * b + 8 * q) = v;
+      }
+  }
+}
+
+}  // namespace si

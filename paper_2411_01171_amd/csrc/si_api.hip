@@ -15,6 +15,7 @@
 #include "k_fused.h"
 #include "k_fused_attn.h"
 #include "k_fused_block.h"
+#include "k_attn_mfma.h"
 #include "k_gemm.h"
 #include "k_norm.h"
 #include "si_common.h"
@@ -74,8 +75,10 @@ struct Plan {
   bool pe;
   int fused_nb;     // > 0: register-resident FFN half with D = 32*fused_nb
   bool fused_attn;  // register-resident attention half as well (temporal blocks)
+  bool attn_mfma;   // matrix-core attention kernel for the staged spatial path (bf16, head dimension 64)
+  int Mcp;          // context tokens rounded up to a multiple of 8 (transposed value copy)
   // workspace offsets (bytes)
-  size_t off_stats, off_pe, off_ctxkv;
+  size_t off_stats, off_pe, off_ctxkv, off_ctxvt, off_vt;
   size_t off_w_in, off_wqkv, off_wo, off_wq2, off_wkv2, off_wo2, off_w1, off_w2, off_w_out;
   size_t off_a, off_h, off_big, off_ffn_stream, off_attn_stream;
   size_t weights_bytes, total_bytes;
@@ -133,6 +136,9 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_stats = take((size_t)p->B * p->F * p->G * 2 * sizeof(float));
   p->off_pe = take(p->pe ? (size_t)p->F * Dz * sizeof(float) : 0);
   p->off_ctxkv = take((size_t)p->B * p->Mc * 2 * Dz * es);
+  p->attn_mfma = p->dtype == SI_BF16 && p->kind == SI_BLOCK_SPATIAL && p->d == 64 && P % 8 == 0;
+  p->Mcp = (p->Mc + 7) / 8 * 8;
+  p->off_ctxvt = take(p->attn_mfma ? (size_t)p->B * Dz * p->Mcp * es : 0);
   // which path: register-resident kernels need bf16, C == D = 64 or 320 (instantiated widths)
   p->fused_nb = 0;
   p->fused_attn = false;
@@ -159,6 +165,7 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     p->off_h = take((size_t)p->Mmax * Dz * sizeof(float));
     p->off_big = take((size_t)p->Mmax * 4 * Dz * es);
   }
+  p->off_vt = take(p->attn_mfma ? (size_t)p->Mmax * Dz * es : 0);  // values of the window, keys contiguous
   const size_t act_end = off;
   // re-laid-out weights
   p->off_w_in = take(split * Dz * C * es);
@@ -222,6 +229,31 @@ static si_status launch_attention(const char* stage, const AttnArgs& a, hipStrea
   constexpr int QB = 4;
   dim3 grid((unsigned)((a.Nq + 4 * QB - 1) / (4 * QB)), (unsigned)a.heads, (unsigned)a.S);
   attn_valu_kernel<T, QB><<<grid, 256, 0, st>>>(a);
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+
+// Matrix-core attention (bf16, head dimension 64): v is first copied with keys contiguous.
+static si_status launch_attention_mfma(const char* stage, const bf16* q, int64_t ldq, const bf16* k, int64_t ldk,
+                                       const bf16* vt, bf16* o, int64_t ldo, int S, int Nq, int Nk, int Nkp, int heads,
+                                       int kv_div, float scale, hipStream_t st) {
+  if (S <= 0 || Nq <= 0) return SI_OK;
+  StageScope scope(stage, st);
+  AttnMfmaArgs a;
+  a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.o = o; a.ldo = ldo;
+  a.Nq = Nq; a.Nk = Nk; a.Nkp = Nkp; a.heads = heads; a.kv_div = kv_div;
+  a.scale_log2 = scale * 1.4426950408889634f;
+  dim3 grid((unsigned)((Nq + 127) / 128), (unsigned)heads, (unsigned)S);
+  attn_mfma_kernel<<<grid, 256, 0, st>>>(a);
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+static si_status launch_transpose_v(const char* stage, const bf16* src, int64_t ld, int col0, bf16* dst, int S, int N, int Nkp,
+                                    int D, hipStream_t st) {
+  if (S <= 0 || N <= 0) return SI_OK;
+  StageScope scope(stage, st);
+  dim3 grid((unsigned)((Nkp + 31) / 32), (unsigned)((D + 31) / 32), (unsigned)S);
+  transpose_v_kernel<<<grid, 256, 0, st>>>(src, ld, col0, dst, N, Nkp, D);
   SI_CHECK_LAUNCH();
   return SI_OK;
 }
@@ -349,6 +381,10 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   if (spatial) {
     EpiStore<T> epi{ctxkv, (int64_t)2 * D, nullptr};
     SI_TRY(launch_gemm<T>("ctx_kv", cT(ctx->ptr), (int64_t)p.Cc, wkv2, (int64_t)p.B * p.Mc, 2 * D, p.Cc, epi, st));
+    if constexpr (sizeof(T) == 2) {
+      if (p.attn_mfma)
+        SI_TRY(launch_transpose_v("ctx_vt", ctxkv, (int64_t)2 * D, D, reinterpret_cast<bf16*>(ws + p.off_ctxvt), p.B, p.Mc, p.Mcp, D, st));
+    }
   }
 
   // ---- Feature Slicer windows; one operator group per window (Eq. 1)
@@ -399,7 +435,17 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         EpiStore<T> epi{big, (int64_t)3 * D, nullptr};
         SI_TRY(launch_gemm<T>("qkv", a, (int64_t)D, wqkv, M, 3 * D, D, epi, st));
       }
-      {
+      bool self_done = false;
+      if constexpr (sizeof(T) == 2) {
+        if (p.attn_mfma) {  // spatial: sequence (b, f) = rows (b*Fw + f)*Pw + i
+          bf16* vt = reinterpret_cast<bf16*>(ws + p.off_vt);
+          SI_TRY(launch_transpose_v("v_transpose", big, (int64_t)3 * D, 2 * D, vt, p.B * win.Fw, win.Pw, win.Pw, D, st));
+          SI_TRY(launch_attention_mfma("self_attn", big, (int64_t)3 * D, big + D, (int64_t)3 * D, vt, a, (int64_t)D, p.B * win.Fw,
+                                       win.Pw, win.Pw, win.Pw, p.heads, 1, scale, st));
+          self_done = true;
+        }
+      }
+      if (!self_done) {
         AttnArgs at;
         at.q = big; at.k = big + D; at.v = big + 2 * D; at.o = a;
         at.ldq = at.ldk = at.ldv = (int64_t)3 * D; at.ldo = D;
@@ -424,7 +470,16 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
           EpiStore<T> epi{big, (int64_t)D, nullptr};
           SI_TRY(launch_gemm<T>("q2", a, (int64_t)D, wq2, M, D, D, epi, st));
         }
-        {
+        bool cross_done = false;
+        if constexpr (sizeof(T) == 2) {
+          if (p.attn_mfma) {  // keys / values: the context rows of the batch entry, shared by its frames
+            SI_TRY(launch_attention_mfma("cross_attn", big, (int64_t)D, ctxkv, (int64_t)2 * D,
+                                         reinterpret_cast<const bf16*>(ws + p.off_ctxvt), a, (int64_t)D, p.B * win.Fw, win.Pw,
+                                         p.Mc, p.Mcp, p.heads, win.Fw, scale, st));
+            cross_done = true;
+          }
+        }
+        if (!cross_done) {
           AttnArgs at;
           at.q = big; at.k = ctxkv; at.v = ctxkv + D; at.o = a;
           at.ldq = D; at.ldk = at.ldv = (int64_t)2 * D; at.ldo = D;

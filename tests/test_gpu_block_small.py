@@ -61,6 +61,27 @@ def test_small_spatial(dtype, slice_len):
     _check(spec, x, w, ctx, slice_len)
 
 
+@pytest.mark.parametrize("hw,M", [((8, 13), 5), ((10, 20), 77), ((4, 6), 1), ((16, 17), 12)])
+def test_spatial_head_dim_64_bf16(hw, M):
+    """Head dimension 64 takes the matrix-core attention kernel: query tiles of 128 and key stages of
+    64 with ragged tails (104, 200, 24, 272 positions), context lengths that are not multiples of 8."""
+    spec = tiny_spec(wl.SPATIAL, B=2, C=128, F=2, H=hw[0], W=hw[1], heads=2, dim_head=64, groups=8, M=M, Cc=16,
+                     dtype="bf16")
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, ctx, 1)
+
+
+def test_spatial_head_dim_64_peaky_bf16():
+    """Scaled-up queries and keys: the running maximum of the online softmax moves between key tiles."""
+    spec = tiny_spec(wl.SPATIAL, B=1, C=128, F=2, H=12, W=16, heads=2, dim_head=64, groups=8, M=9, Cc=16, dtype="bf16")
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, matrix_std=0.05)
+    for k in ("wq", "wk", "wq2", "wk2"):
+        w[k] = wl.round_to_storage(w[k] * 4.0, "bf16")
+    _check(spec, x, w, ctx, 2, branch_tol=4e-2)
+
+
 def test_head_dim_40_and_25_frames_bf16():
     spec = tiny_spec(wl.TEMPORAL, B=1, C=80, F=25, H=6, W=6, heads=2, dim_head=40, groups=4, pe=True, dtype="bf16")
     x = wl.make_x(spec)
