@@ -1,7 +1,8 @@
 // Matrix-core attention for long sequences (spatial self-attention over H*W positions, cross-
 // attention over the context tokens): bf16, head dimension 64, online softmax in fp32.
 //
-// One workgroup = 128 queries of one (sequence, head); one wavefront = 32 queries, which stay the
+// One workgroup = NW x 32 queries of one (sequence, head), NW = 4 or 8 wavefronts sharing the key /
+// value stages; one wavefront = 32 queries, which stay the
 // *column* operand of every MFMA (v_mfma_f32_32x32x16_bf16: lane l supplies column l%32, k-slots
 // 8*(l/32) .. +7; a result lane holds column l%32 and, in register 4q + j, row 8q + 4*(l/32) + j):
 //   S^T[key, query] = K Q^T      row operand: 32 keys x 16 head channels, straight from k's rows
@@ -30,7 +31,7 @@ struct AttnMfmaArgs {
   float scale_log2;  // softmax scale * log2(e)
 };
 
-constexpr int kAttnStages = 4;
+constexpr int kAttnStages = 3;  // 48 KiB of LDS: three 4-wavefront workgroups per CU
 
 // key (within its 16-key group) whose score lands in MFMA row f of the group
 __host__ __device__ constexpr int kappa16(int f) { return f < 4 || f >= 12 ? f : (f < 8 ? f + 4 : f - 4); }
@@ -52,38 +53,41 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16* __restrict
   }
 }
 
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnMfmaArgs a) {
+template <int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attn_mfma_kernel(AttnMfmaArgs a) {
   constexpr int NS = kAttnStages, FR = 16;  // fragments per stage: 8 of K (2 tiles x 4 k-steps), 8 of V^T (2 tiles x 2 blocks x 2 k-steps)
+  constexpr int PER = FR / NW;              // stage loads per lane
+  static_assert(NW == 4 || NW == 8, "wavefronts per workgroup");
   __shared__ u32x4_t ring[NS][FR * kWave];
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int r = lane % 32, g = lane / 32;
   const int h = blockIdx.y, s = blockIdx.z, ks = s / a.kv_div;
-  const int qi = (blockIdx.x * 4 + wave) * 32 + r;
+  const int qi = (blockIdx.x * NW + wave) * 32 + r;
   const bool qvalid = qi < a.Nq;
   const int nst = (a.Nk + 63) / 64;
 
-  // ---- stage loads: lane's four fragments per stage.  i < 2: K tile u = i, k-step = wave;
-  // i >= 2: V^T tile u = i - 2, channel block = wave / 2, k-step = wave % 2.
+  // ---- stage loads: fragment ids wave + NW*i, i < PER.  id < 8: K, tile u = id / 4, k-step id % 4;
+  // id >= 8: V^T, tile u = (id - 8) / 4, channel block ((id - 8) / 2) % 2, k-step id % 2.
   const int kap = 16 * (r / 16) + kappa16(r % 16);
-  const bf16* kbase = a.k + (int64_t)ks * a.Nk * a.ldk + h * 64 + 16 * wave + 8 * g;
-  const bf16* vbase = a.vt + ((int64_t)ks * a.heads * 64 + h * 64 + 32 * (wave / 2) + r) * a.Nkp;
+  const bf16* kbase = a.k + (int64_t)ks * a.Nk * a.ldk + h * 64 + 16 * (wave % 4) + 8 * g;
+  const bf16* vbase = a.vt + ((int64_t)ks * a.heads * 64 + h * 64 + 32 * ((wave / 2) % 2) + r) * a.Nkp;
   const int vk = 16 * (wave % 2) + 8 * g;  // first of this lane's 8 keys within a tile
   auto issue = [&](int st) {
     if (st < nst) {
       const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(ring[st % NS]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < PER; ++i) {
+        const int id = wave + NW * i;  // wave-uniform; K for i < PER / 2
         const bf16* src;
-        if (i < 2) {
-          int key = 64 * st + 32 * i + kap;
+        if (i < PER / 2) {
+          int key = 64 * st + 32 * (id / 4) + kap;
           key = key < a.Nk ? key : a.Nk - 1;
           src = kbase + (int64_t)key * a.ldk;
         } else {
-          int k0 = 64 * st + 32 * (i - 2) + vk;  // groups of 8 keys past the row's end hold masked keys only
+          int k0 = 64 * st + 32 * ((id - 8) / 4) + vk;  // groups of 8 keys past the row's end hold masked keys only
           k0 = k0 < a.Nkp - 8 ? k0 : a.Nkp - 8;
           src = vbase + k0;
         }
-        const int id = i < 2 ? 4 * i + wave : 8 + 4 * (i - 2) + wave;
         const unsigned l = __builtin_amdgcn_readfirstlane(dst + (unsigned)(id * kWave * 16));
         // assembly for the same reason as in WeightPipe::issue: completion is awaited explicitly
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
@@ -114,8 +118,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnMfmaArgs a) {
     // own loads of stage st have landed: at most the batches of the next NS - 2 stages stay in flight
     {
       const int younger = nst - 1 - st;
-      if (younger >= 2) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(8));
-      else if (younger == 1) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(4));
+      if (NS >= 4 && younger >= 2) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(2 * PER));
+      else if (younger >= 1) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(PER));
       else __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(0));
     }
     __syncthreads();  // stage st is visible to all; everybody has left stage st - 1, whose slot is loaded next
@@ -141,9 +145,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnMfmaArgs a) {
 #pragma unroll
       for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[e]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      const float mnew = fmaxf(m, mx);  // finite from the first tile on (it always holds a real key)
-      const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
-      const float mc = mnew * c;
+      // the running maximum moves in the first tiles and rarely afterwards: rescale only when some
+      // lane's maximum grew (finite from the first tile on, which always holds a real key)
+      if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {
+        const float mnew = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
+        lsum *= alpha;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[b][e] *= alpha;
+        m = mnew;
+      }
+      const float mc = m * c;
       float pr[16], rs = 0.f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
@@ -151,12 +165,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnMfmaArgs a) {
         rs += pr[e];
       }
       rs += __shfl_xor(rs, 32, kWave);
-      lsum = lsum * alpha + rs;
-      m = mnew;
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[b][e] *= alpha;
+      lsum += rs;
       bf16x8_t pop[2];
       pop[0] = to_operand(&pr[0]);
       pop[1] = to_operand(&pr[8]);

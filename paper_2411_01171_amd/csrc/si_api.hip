@@ -243,8 +243,15 @@ static si_status launch_attention_mfma(const char* stage, const bf16* q, int64_t
   a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.o = o; a.ldo = ldo;
   a.Nq = Nq; a.Nk = Nk; a.Nkp = Nkp; a.heads = heads; a.kv_div = kv_div;
   a.scale_log2 = scale * 1.4426950408889634f;
-  dim3 grid((unsigned)((Nq + 127) / 128), (unsigned)heads, (unsigned)S);
-  attn_mfma_kernel<<<grid, 256, 0, st>>>(a);
+  // 8 wavefronts share the key / value stages when that still leaves several workgroups for every CU
+  const int64_t wg8 = (int64_t)((Nq + 255) / 256) * heads * S;
+  if (wg8 >= 1024) {
+    dim3 grid((unsigned)((Nq + 255) / 256), (unsigned)heads, (unsigned)S);
+    attn_mfma_kernel<8><<<grid, 512, 0, st>>>(a);
+  } else {
+    dim3 grid((unsigned)((Nq + 127) / 128), (unsigned)heads, (unsigned)S);
+    attn_mfma_kernel<4><<<grid, 256, 0, st>>>(a);
+  }
   SI_CHECK_LAUNCH();
   return SI_OK;
 }
