@@ -117,36 +117,69 @@ __host__ __device__ inline int64_t stream_pitch_u4(int total_sub) {
 }
 __host__ __device__ inline int64_t stream_bytes(int total_sub, int sub) { return stream_pitch_u4(total_sub) * 16 * sub; }
 
-// Fragment stream of the FFN half, in consumption order.  A sub-chunk is 2*NB
-// fragments (fragment = 64 lanes x 8 bf16); with NC = 4*NB chunks of 32 inner columns:
+// Fragment stream, in consumption order.  A sub-chunk is 2*NB fragments (fragment = 64 lanes x
+// 8 bf16).  Block sub-chunks: one 32-column block of a row-major [D, ld] matrix, k-steps 0..2NB-1
+// over its D rows (proj_in, q/k/v, attention out-projection, proj_out).  FFN sub-chunks, with
+// NC = 4*NB chunks of 32 inner columns:
 //   V(c): W1 value rows 32c..32c+31, k-steps 0..2NB-1      G(c): the gate rows likewise
 //   W2(c): for nb in [0, NB): k-steps (inner 32c..32c+15), (32c+16..32c+31)
 // order: V0 G0 V1 G1 | for t in 1..NC-2: V(t+1) G(t+1) W2(t-1) | W2(NC-2) W2(NC-1)
-// written at sub-chunks [sub0, sub0 + 3*NC) of a stream of total_sub sub-chunks.
 // One thread per (fragment, lane).  Sources are row-major [in, out].
+struct BlockDesc {
+  const bf16* src;
+  int ld, col0;
+};
+
+// Whole fragment stream in one launch: n_pre block sub-chunks, the FFN's 12*NB sub-chunks, n_post
+// block sub-chunks, and -- in further workgroups -- the
+// sinusoidal frame table PE[f, 2i] = sin(f / 10000^(2i/D)), PE[f, 2i+1] = cos(same) when pe != NULL.
+struct StreamDesc {
+  BlockDesc b[64];  // pre blocks first, then post blocks
+  int n_pre, n_post;
+  const bf16 *w1, *w2;
+  float* pe;
+  int F;
+};
 template <int NB>
-__global__ __launch_bounds__(256) void pack_ffn_stream_kernel(const bf16* __restrict__ w1, const bf16* __restrict__ w2,
-                                                              u32x4_t* __restrict__ dst, int sub0, int total_sub) {
+__global__ __launch_bounds__(256) void pack_stream_kernel(StreamDesc sd, u32x4_t* __restrict__ dst) {
   constexpr int D = 32 * NB, SUB = 2 * NB, NC = 4 * NB;
+  const int total_sub = sd.n_pre + 3 * NC + sd.n_post;
+  const int frag_wgs = (total_sub * SUB + 3) / 4;
+  if ((int)blockIdx.x >= frag_wgs) {  // frame table
+    const int idx = ((int)blockIdx.x - frag_wgs) * 256 + threadIdx.x;
+    if (sd.pe && idx < sd.F * D) {
+      const int f = idx / D, i = idx % D;
+      const int even = i - (i & 1);
+      const double angle = (double)f / pow(10000.0, (double)even / (double)D);
+      sd.pe[idx] = (float)((i & 1) ? cos(angle) : sin(angle));
+    }
+    return;
+  }
   const int fidx = blockIdx.x * 4 + threadIdx.x / kWave;
-  if (fidx >= 3 * NC * SUB) return;
+  if (fidx >= total_sub * SUB) return;
   const int lane = threadIdx.x % kWave, r = lane % 32, g = lane / 32;
   const int sub = fidx / SUB, idx = fidx % SUB;
-  int kind, c;  // kind 0: V, 1: G, 2: W2
-  if (sub < 4) {
-    kind = sub % 2; c = sub / 2;
-  } else if (sub < 4 + 3 * (NC - 2)) {
-    const int rr = sub - 4, t = 1 + rr / 3, k = rr % 3;
-    kind = k; c = k == 2 ? t - 1 : t + 1;
-  } else {
-    kind = 2; c = NC - 2 + (sub - (4 + 3 * (NC - 2)));
-  }
   const bf16* src;
   int ld, n, k0;
-  if (kind < 2) {
-    src = w1; ld = 8 * D; n = (kind ? 4 * D : 0) + 32 * c + r; k0 = 16 * idx;
+  if (sub < sd.n_pre || sub >= sd.n_pre + 3 * NC) {
+    const BlockDesc d = sd.b[sub < sd.n_pre ? sub : sub - 3 * NC];
+    src = d.src; ld = d.ld; n = d.col0 + r; k0 = 16 * idx;
   } else {
-    src = w2; ld = D; n = 32 * (idx / 2) + r; k0 = 32 * c + 16 * (idx % 2);
+    const int fs = sub - sd.n_pre;
+    int kind, c;  // kind 0: V, 1: G, 2: W2
+    if (fs < 4) {
+      kind = fs % 2; c = fs / 2;
+    } else if (fs < 4 + 3 * (NC - 2)) {
+      const int rr = fs - 4, t = 1 + rr / 3, k = rr % 3;
+      kind = k; c = k == 2 ? t - 1 : t + 1;
+    } else {
+      kind = 2; c = NC - 2 + (fs - (4 + 3 * (NC - 2)));
+    }
+    if (kind < 2) {
+      src = sd.w1; ld = 8 * D; n = (kind ? 4 * D : 0) + 32 * c + r; k0 = 16 * idx;
+    } else {
+      src = sd.w2; ld = D; n = 32 * (idx / 2) + r; k0 = 32 * c + 16 * (idx % 2);
+    }
   }
   unsigned short e[8];
 #pragma unroll
@@ -156,37 +189,7 @@ __global__ __launch_bounds__(256) void pack_ffn_stream_kernel(const bf16* __rest
   o.y = e[2] | ((unsigned)e[3] << 16);
   o.z = e[4] | ((unsigned)e[5] << 16);
   o.w = e[6] | ((unsigned)e[7] << 16);
-  dst[idx * stream_pitch_u4(total_sub) + (int64_t)(sub0 + sub) * kWave + lane] = o;
-}
-
-// Sub-chunks that are one 32-column block of a [D, ld] row-major matrix, k-steps 0..2NB-1 over
-// its D rows (proj_in, q/k/v, attention out-projection, proj_out): block i of the list goes to
-// sub-chunk sub0 + i.
-struct BlockDesc {
-  const bf16* src;
-  int ld, col0;
-};
-struct BlockList {
-  BlockDesc b[48];
-};
-template <int NB>
-__global__ __launch_bounds__(256) void pack_blocks_kernel(BlockList list, int n_blocks, u32x4_t* __restrict__ dst, int sub0,
-                                                          int total_sub) {
-  constexpr int SUB = 2 * NB;
-  const int fidx = blockIdx.x * 4 + threadIdx.x / kWave;
-  if (fidx >= n_blocks * SUB) return;
-  const int lane = threadIdx.x % kWave, r = lane % 32, g = lane / 32;
-  const int blk = fidx / SUB, idx = fidx % SUB;
-  const BlockDesc d = list.b[blk];
-  unsigned short e[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) e[i] = d.src[(int64_t)(16 * idx + frag_k(g, i)) * d.ld + d.col0 + r].v;
-  u32x4_t o;
-  o.x = e[0] | ((unsigned)e[1] << 16);
-  o.y = e[2] | ((unsigned)e[3] << 16);
-  o.z = e[4] | ((unsigned)e[5] << 16);
-  o.w = e[6] | ((unsigned)e[7] << 16);
-  dst[idx * stream_pitch_u4(total_sub) + (int64_t)(sub0 + blk) * kWave + lane] = o;
+  dst[idx * stream_pitch_u4(total_sub) + (int64_t)sub * kWave + lane] = o;
 }
 
 // ----------------------------------------------------------------------------- weight stream pipeline
@@ -253,7 +256,7 @@ struct FfnHalfArgs {
   const float* h;         // [M, D] residual stream before the last attention output projection
   const bf16* o;          // [M, D] attention output (heads concatenated); h += o W_o + b_o comes first
   int64_t M;
-  const u32x4_t* stream;  // fragment stream: W_o blocks, FFN (pack_ffn_stream_kernel), W_out blocks
+  const u32x4_t* stream;  // fragment stream: W_o blocks, FFN, W_out blocks
   const bf16 *b_o, *ln_g, *ln_b, *b1, *b2, *b_out;
   float ln_eps;
   const bf16* x;

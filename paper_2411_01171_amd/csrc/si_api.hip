@@ -281,40 +281,35 @@ static si_status launch_layer_norm(const char* stage, const float* h, T* a, int6
     if (st__ != SI_OK) return st__;   \
   } while (0)
 
-// Fragment streams of the register-resident kernels (bf16 only).
+// Fragment stream of the register-resident kernels (bf16 only) and the frame table, one launch.
 template <int NB>
-static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, char* ws, hipStream_t st) {
+static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, char* ws, float* pe, hipStream_t st) {
   const int D = p.D;
   auto cB = [](const void* q) { return static_cast<const bf16*>(q); };
   const bool spatial = p.kind == SI_BLOCK_SPATIAL;
-  // FFN half (alone: sub-chunks 0..14NB; after the attention half: 4NB..18NB): out-projection of the
-  // last attention, FFN, proj_out
-  const int base = p.fused_attn ? 4 * NB : 0, total = base + 14 * NB;
-  u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + (p.fused_attn ? p.off_attn_stream : p.off_ffn_stream));
-  {
-    BlockList list;
-    for (int nb = 0; nb < NB; ++nb) list.b[nb] = BlockDesc{cB(spatial ? w->wo2 : w->wo), D, 32 * nb};
-    pack_blocks_kernel<NB><<<(NB * 2 * NB + 3) / 4, 256, 0, st>>>(list, NB, stream, base, total);
-    SI_CHECK_LAUNCH();
-    pack_ffn_stream_kernel<NB><<<(12 * NB * 2 * NB + 3) / 4, 256, 0, st>>>(cB(w->w1), cB(w->w2), stream, base + NB, total);
-    SI_CHECK_LAUNCH();
-    for (int nb = 0; nb < NB; ++nb) list.b[nb] = BlockDesc{cB(w->w_out), p.C, 32 * nb};
-    pack_blocks_kernel<NB><<<(NB * 2 * NB + 3) / 4, 256, 0, st>>>(list, NB, stream, base + 13 * NB, total);
-    SI_CHECK_LAUNCH();
-  }
+  StreamDesc sd;
+  int n = 0;
   if (p.fused_attn) {  // attention half: W_in blocks, then per head group q, k, v blocks
     const int gw = lcm_int(p.d, 32), nbg = gw / 32, ng = D / gw;
-    BlockList list;
-    int n = 0;
-    for (int nb = 0; nb < NB; ++nb) list.b[n++] = BlockDesc{cB(w->w_in), D, 32 * nb};
+    for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->w_in), D, 32 * nb};
     for (int gi = 0; gi < ng; ++gi) {
       const void* mats[3] = {w->wq, w->wk, w->wv};
       for (int kind = 0; kind < 3; ++kind)
-        for (int blk = 0; blk < nbg; ++blk) list.b[n++] = BlockDesc{cB(mats[kind]), D, gi * gw + 32 * blk};
+        for (int blk = 0; blk < nbg; ++blk) sd.b[n++] = BlockDesc{cB(mats[kind]), D, gi * gw + 32 * blk};
     }
-    pack_blocks_kernel<NB><<<(n * 2 * NB + 3) / 4, 256, 0, st>>>(list, n, stream, 0, total);
-    SI_CHECK_LAUNCH();
   }
+  // FFN half: out-projection of the last attention, FFN, proj_out
+  for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(spatial ? w->wo2 : w->wo), D, 32 * nb};
+  sd.n_pre = n;
+  for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->w_out), p.C, 32 * nb};
+  sd.n_post = NB;
+  sd.w1 = cB(w->w1); sd.w2 = cB(w->w2);
+  sd.pe = pe; sd.F = p.F;
+  const int total = sd.n_pre + 12 * NB + sd.n_post;
+  u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + (p.fused_attn ? p.off_attn_stream : p.off_ffn_stream));
+  const int frag_wgs = (total * 2 * NB + 3) / 4, pe_wgs = pe ? (p.F * D + 255) / 256 : 0;
+  pack_stream_kernel<NB><<<frag_wgs + pe_wgs, 256, 0, st>>>(sd, stream);
+  SI_CHECK_LAUNCH();
   return SI_OK;
 }
 
@@ -367,10 +362,10 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       SI_TRY(launch_pack<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 0, 4 * D, st));
       SI_TRY(launch_pack<T>(cT(w->w2), w2, 4 * D, D, D, 0, 0, st));
     } else if constexpr (sizeof(T) == 2) {
-      if (p.fused_nb == 2) SI_TRY(pack_fused_streams<2>(p, w, ws, st));
-      else SI_TRY(pack_fused_streams<10>(p, w, ws, st));
+      if (p.fused_nb == 2) SI_TRY(pack_fused_streams<2>(p, w, ws, pe, st));
+      else SI_TRY(pack_fused_streams<10>(p, w, ws, pe, st));
     }
-    if (pe) {
+    if (pe && !(fused_ffn && sizeof(T) == 2)) {
       pe_table_kernel<<<(p.F * D + 255) / 256, 256, 0, st>>>(pe, p.F, D);
       SI_CHECK_LAUNCH();
     }
