@@ -201,7 +201,12 @@ static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T
     dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 63) / 64));
     gemm_f32_kernel<Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
   } else {
-    if (N % 128 == 0) {
+    // small problems (a slice of a few thousand tokens times a D-wide matrix) get 64 x 64 tiles:
+    // four times the workgroups, so that every CU has work
+    if (((M + 127) / 128) * ((N + 127) / 128) < 256) {
+      dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 63) / 64));
+      gemm_bf16_kernel<64, 64, 2, 2, Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+    } else if (N % 128 == 0) {
       dim3 grid((unsigned)((M + 127) / 128), (unsigned)(N / 128));
       gemm_bf16_kernel<128, 128, 2, 2, Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
     } else {
