@@ -231,20 +231,28 @@ struct WeightPipe {
     else if (extra >= 4) wait_step<4>(cur, total);
     else wait_step<0>(cur, total);
   }
+  // Loads of sub-chunk `sub`.  voff = pipe_voff(lane, wave, pitch): the lane's byte offset inside a
+  // sub-chunk's first fragment row of its wavefront; wave_s: the wavefront index as a scalar.  The
+  // address is formed as scalar base + 32-bit lane offset, so a step's loads cost scalar
+  // instructions only.
+  static __device__ __forceinline__ unsigned pipe_voff(int lane, int wave, int64_t pitch) {
+    return (unsigned)((lane + (int64_t)wave * pitch) * 16);
+  }
   static __device__ __forceinline__ void issue(const u32x4_t* stream, u32x4_t* ring0, int sub, int total, int64_t pitch,
-                                               int lane, int wave) {
+                                               unsigned voff, int wave_s) {
     if (sub < total) {
-      const u32x4_t* src = stream + (int64_t)sub * kWave + lane;
-      // LDS byte address of the slot, wave-uniform (goes to M0)
-      const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(ring0 + (sub % kRingSlots) * (SUB * kWave));
+      const char* sbase = reinterpret_cast<const char*>(stream) + (int64_t)sub * (kWave * 16);
+      // LDS byte address of this wavefront's first fragment in the slot, wave-uniform (goes to M0)
+      const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)ring0 +
+                           (unsigned)((sub % kRingSlots) * (SUB * kWave * 16) + wave_s * (kWave * 16));
 #pragma unroll
       for (int i = 0; i < PER_THREAD; ++i) {
-        const u32x4_t* g = src + (wave + 4 * i) * pitch;
-        const unsigned l = __builtin_amdgcn_readfirstlane(dst + (unsigned)((wave + 4 * i) * kWave * 16));
+        const char* sb = sbase + (int64_t)(4 * i) * pitch * 16;
+        const unsigned l = dst + (unsigned)(4 * i * kWave * 16);
         // Issued as assembly so that the compiler's wait-count pass does not place a full vector-memory
         // wait in front of every later LDS read; completion is awaited explicitly when a step closes.
         // M0 is reserved by the compiler and used by nothing else in these kernels.
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory");
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sb), "s"(l) : "memory");
       }
     }
   }
@@ -320,9 +328,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // ---- weight stream: the first three sub-chunks go straight into the ring
   using Pipe = WeightPipe<SUB>;
   const int64_t pitch = stream_pitch_u4(TOTAL_SUB);
+  const unsigned pipe_voff = Pipe::pipe_voff(lane, wave, pitch);
+  const int pipe_wave = __builtin_amdgcn_readfirstlane(wave);
   int cur = 0;  // sub-chunk being consumed; loads run at cur + 3
 #pragma unroll
-  for (int i = 0; i < NSLOT - 1; ++i) Pipe::issue(a.stream, ring[0], i, TOTAL_SUB, pitch, lane, wave);
+  for (int i = 0; i < NSLOT - 1; ++i) Pipe::issue(a.stream, ring[0], i, TOTAL_SUB, pitch, pipe_voff, pipe_wave);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): also the residual / attention rows loaded above
   __syncthreads();  // tables and the first three sub-chunks are in LDS
 
@@ -334,7 +344,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // One pipeline step around the MFMAs of sub-chunk `cur` (see WeightPipe).
 #define SI_STEP_OPEN()                                                           \
   __builtin_amdgcn_sched_barrier(0);                                             \
-  Pipe::issue(a.stream, ring[0], cur + NSLOT - 1, TOTAL_SUB, pitch, lane, wave); \
+  Pipe::issue(a.stream, ring[0], cur + NSLOT - 1, TOTAL_SUB, pitch, pipe_voff, pipe_wave); \
   const u32x4_t* slot_c = ring[cur % NSLOT];                                     \
   const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                               \
   (void)slot_c; (void)slot_n

@@ -76,9 +76,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // ---- weight stream (see WeightPipe): sub-chunks 0 and 1 now, sub-chunk 2 once the x tile has left LDS
   using Pipe = WeightPipe<SUB>;
   const int64_t pitch = stream_pitch_u4(TOTAL_SUB);
+  const unsigned pipe_voff = Pipe::pipe_voff(lane, wave, pitch);
+  const int pipe_wave = __builtin_amdgcn_readfirstlane(wave);
   int cur = 0;
-  Pipe::issue(a.stream, ring[0], 0, TOTAL_SUB, pitch, lane, wave);
-  Pipe::issue(a.stream, ring[0], 1, TOTAL_SUB, pitch, lane, wave);
+  Pipe::issue(a.stream, ring[0], 0, TOTAL_SUB, pitch, pipe_voff, pipe_wave);
+  Pipe::issue(a.stream, ring[0], 1, TOTAL_SUB, pitch, pipe_voff, pipe_wave);
 
   // ---- tables; the staged tile starts as zeros (padding rows and columns stay zero)
   const int b_first = (int)(seq_wg / w.Pw);
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       if (idx < pe_n4) reinterpret_cast<float4*>(t_pe)[idx] = pev[i];
     }
   }
-  Pipe::issue(a.stream, ring[0], 2, TOTAL_SUB, pitch, lane, wave);
+  Pipe::issue(a.stream, ring[0], 2, TOTAL_SUB, pitch, pipe_voff, pipe_wave);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
 
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
 #define SI_STEP_OPEN()                                                           \
   __builtin_amdgcn_sched_barrier(0);                                             \
-  Pipe::issue(a.stream, ring[0], cur + 3, TOTAL_SUB, pitch, lane, wave);         \
+  Pipe::issue(a.stream, ring[0], cur + 3, TOTAL_SUB, pitch, pipe_voff, pipe_wave);         \
   const u32x4_t* slot_c = ring[cur % NSLOT];                                     \
   const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                               \
   (void)slot_c; (void)slot_n
