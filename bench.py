@@ -88,10 +88,13 @@ def cpu_baseline(spec, seconds_target=20.0):
         what = f"1 of {spec.F} frames (B={spec.B})"
     x, w, ctx = wl.make_x(sub), wl.make_weights(sub), wl.make_context(sub)
     t0 = time.perf_counter()
-    oracle.block_forward_ref(x, w, sub, ctx)
-    out = oracle.block_forward_ref(x, w, sub, ctx) if time.perf_counter() - t0 < seconds_target / 4 else None
-    dt = time.perf_counter() - t0
-    reps = 2 if out is not None else 1
+    reps = 0
+    while True:     # whole passes until about seconds_target / 2 of CPU work is behind us (at least one, at most 8)
+        oracle.block_forward_ref(x, w, sub, ctx)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if reps >= 8 or dt + dt / reps > seconds_target * 0.75:
+            break
     tflops = sub.flops() * reps / dt / 1e12
     return {"value": tflops, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{what}; fp64 NumPy; {reps} pass(es) in {dt:.1f} s",
