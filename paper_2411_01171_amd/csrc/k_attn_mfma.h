@@ -53,6 +53,64 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16* __restrict
   }
 }
 
+// One 64-key stage of the online softmax for this wavefront's 32 queries.  MASKED: keys >= Nk exist
+// in the stage (the last, ragged one) and get a score of -inf.
+template <bool MASKED>
+__device__ __forceinline__ void attn_stage(const u32x4_t* slot, int lane, int g, int key0, int Nk, float c, const bf16x8_t (&qop)[4],
+                                           f32x16_t (&oacc)[2], float& m, float& lsum) {
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    f32x16_t sc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sc[e] = 0.f;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, slot[(4 * u + s4) * kWave + lane]), qop[s4], sc, 0, 0, 0);
+    if (MASKED) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int i = 8 * (e / 4) + 4 * g + (e % 4);
+        const int key = key0 + 32 * u + 16 * (i / 16) + kappa16(i % 16);
+        if (key >= Nk) sc[e] = -INFINITY;
+      }
+    }
+    float mx = sc[0];
+#pragma unroll
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    // the running maximum moves in the first tiles and rarely afterwards: rescale only when some
+    // lane's maximum grew (finite from the first tile on, which always holds a real key)
+    if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {
+      const float mnew = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
+      lsum *= alpha;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[b][e] *= alpha;
+      m = mnew;
+    }
+    const float mc = m * c;
+    float pr[16], rs = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      pr[e] = __builtin_amdgcn_exp2f(fmaf(sc[e], c, -mc));
+      rs += pr[e];
+    }
+    rs += __shfl_xor(rs, 32, kWave);
+    lsum += rs;
+    bf16x8_t pop[2];
+    pop[0] = to_operand(&pr[0]);
+    pop[1] = to_operand(&pr[8]);
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, slot[(8 + 4 * u + 2 * b + t) * kWave + lane]),
+                                                          pop[t], oacc[b], 0, 0, 0);
+  }
+}
+
 template <int NW>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attn_mfma_kernel(AttnMfmaArgs a) {
   constexpr int NS = kAttnStages, FR = 16;  // fragments per stage: 8 of K (2 tiles x 4 k-steps), 8 of V^T (2 tiles x 2 blocks x 2 k-steps)
@@ -60,37 +118,49 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attn_mfma_kernel(Att
   static_assert(NW == 4 || NW == 8, "wavefronts per workgroup");
   __shared__ u32x4_t ring[NS][FR * kWave];
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int r = lane % 32, g = lane / 32;
   const int h = blockIdx.y, s = blockIdx.z, ks = s / a.kv_div;
   const int qi = (blockIdx.x * NW + wave) * 32 + r;
   const bool qvalid = qi < a.Nq;
   const int nst = (a.Nk + 63) / 64;
+  const int nfull = a.Nk / 64;  // stages without missing keys (Nkp >= Nk: their V^T groups are in-row too)
 
   // ---- stage loads: fragment ids wave + NW*i, i < PER.  id < 8: K, tile u = id / 4, k-step id % 4;
   // id >= 8: V^T, tile u = (id - 8) / 4, channel block ((id - 8) / 2) % 2, k-step id % 2.
+  // Address = scalar base (stage, fragment) + per-lane byte offset; the ragged last stage clamps
+  // per lane instead (keys past the end are masked, so what they load only has to be finite).
   const int kap = 16 * (r / 16) + kappa16(r % 16);
-  const bf16* kbase = a.k + (int64_t)ks * a.Nk * a.ldk + h * 64 + 16 * (wave % 4) + 8 * g;
-  const bf16* vbase = a.vt + ((int64_t)ks * a.heads * 64 + h * 64 + 32 * ((wave / 2) % 2) + r) * a.Nkp;
-  const int vk = 16 * (wave % 2) + 8 * g;  // first of this lane's 8 keys within a tile
+  const unsigned kvoff = (unsigned)(((int64_t)kap * a.ldk + 8 * g) * 2);
+  const unsigned vvoff = (unsigned)(((int64_t)r * a.Nkp + 8 * g) * 2);
+  const char* kb = reinterpret_cast<const char*>(a.k + (int64_t)ks * a.Nk * a.ldk + h * 64);
+  const char* vb = reinterpret_cast<const char*>(a.vt + ((int64_t)ks * a.heads * 64 + h * 64) * a.Nkp);
   auto issue = [&](int st) {
     if (st < nst) {
       const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(ring[st % NS]);
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
-        const int id = wave + NW * i;  // wave-uniform; K for i < PER / 2
-        const bf16* src;
-        if (i < PER / 2) {
-          int key = 64 * st + 32 * (id / 4) + kap;
-          key = key < a.Nk ? key : a.Nk - 1;
-          src = kbase + (int64_t)key * a.ldk;
+        const int id = wave_s + NW * i;  // scalar; K for i < PER / 2
+        const unsigned l = dst + (unsigned)(id * kWave * 16);
+        if (st < nfull) {
+          const char* sb = i < PER / 2
+                               ? kb + ((int64_t)(64 * st + 32 * (id / 4)) * a.ldk + 16 * (id % 4)) * 2
+                               : vb + ((int64_t)(32 * (((id - 8) / 2) % 2)) * a.Nkp + 64 * st + 32 * ((id - 8) / 4) + 16 * (id % 2)) * 2;
+          // assembly for the same reason as in WeightPipe::issue: completion is awaited explicitly
+          asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(i < PER / 2 ? kvoff : vvoff), "s"(sb), "s"(l) : "memory");
         } else {
-          int k0 = 64 * st + 32 * ((id - 8) / 4) + vk;  // groups of 8 keys past the row's end hold masked keys only
-          k0 = k0 < a.Nkp - 8 ? k0 : a.Nkp - 8;
-          src = vbase + k0;
+          const bf16* src;
+          if (i < PER / 2) {
+            int key = 64 * st + 32 * (id / 4) + kap;
+            key = key < a.Nk ? key : a.Nk - 1;
+            src = reinterpret_cast<const bf16*>(kb) + (int64_t)key * a.ldk + 16 * (id % 4) + 8 * g;
+          } else {
+            int k0 = 64 * st + 32 * ((id - 8) / 4) + 16 * (id % 2) + 8 * g;  // groups of 8 keys past the row's end hold masked keys only
+            k0 = k0 < a.Nkp - 8 ? k0 : a.Nkp - 8;
+            src = reinterpret_cast<const bf16*>(vb) + (int64_t)(32 * (((id - 8) / 2) % 2) + r) * a.Nkp + k0;
+          }
+          asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
         }
-        const unsigned l = __builtin_amdgcn_readfirstlane(dst + (unsigned)(id * kWave * 16));
-        // assembly for the same reason as in WeightPipe::issue: completion is awaited explicitly
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
       }
     }
   };
@@ -125,57 +195,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attn_mfma_kernel(Att
     __syncthreads();  // stage st is visible to all; everybody has left stage st - 1, whose slot is loaded next
     issue(st + NS - 1);
     const u32x4_t* slot = ring[st % NS];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      f32x16_t sc;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) sc[e] = 0.f;
-#pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4)
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, slot[(4 * u + s4) * kWave + lane]), qop[s4], sc, 0, 0, 0);
-      if (64 * st + 32 * u + 32 > a.Nk) {  // ragged tail: rows whose key does not exist
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int i = 8 * (e / 4) + 4 * g + (e % 4);
-          const int key = 64 * st + 32 * u + 16 * (i / 16) + kappa16(i % 16);
-          if (key >= a.Nk) sc[e] = -INFINITY;
-        }
-      }
-      float mx = sc[0];
-#pragma unroll
-      for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      // the running maximum moves in the first tiles and rarely afterwards: rescale only when some
-      // lane's maximum grew (finite from the first tile on, which always holds a real key)
-      if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {
-        const float mnew = fmaxf(m, mx);
-        const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
-        lsum *= alpha;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) oacc[b][e] *= alpha;
-        m = mnew;
-      }
-      const float mc = m * c;
-      float pr[16], rs = 0.f;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        pr[e] = __builtin_amdgcn_exp2f(fmaf(sc[e], c, -mc));
-        rs += pr[e];
-      }
-      rs += __shfl_xor(rs, 32, kWave);
-      lsum += rs;
-      bf16x8_t pop[2];
-      pop[0] = to_operand(&pr[0]);
-      pop[1] = to_operand(&pr[8]);
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-          oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8_t, slot[(8 + 4 * u + 2 * b + t) * kWave + lane]), pop[t], oacc[b], 0, 0, 0);
-    }
+    if (st < nfull) attn_stage<false>(slot, lane, g, 64 * st, a.Nk, c, qop, oacc, m, lsum);
+    else attn_stage<true>(slot, lane, g, 64 * st, a.Nk, c, qop, oacc, m, lsum);
   }
 
   // ---- O^T / l: register 4q + j of block b is head channel 32b + 8q + 4g + j of this lane's query

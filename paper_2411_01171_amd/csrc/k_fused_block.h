@@ -70,8 +70,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // this lane's token: sequence, frame, row of the window's token order m = (b*F + f)*Pw + pl
   const int my_pp = tcol / F, my_f = tcol % F;
   const int64_t my_seq = seq_wg + wave * TP + my_pp;
-  const bool live = tcol < TP * F && my_seq < nseq;
-  const int my_b = live ? (int)(my_seq / w.Pw) : 0, my_pl = live ? (int)(my_seq % w.Pw) : 0;
 
   // ---- weight stream (see WeightPipe): sub-chunks 0 and 1 now, sub-chunk 2 once the x tile has left LDS
   using Pipe = WeightPipe<SUB>;

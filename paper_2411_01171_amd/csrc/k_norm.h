@@ -21,14 +21,15 @@ __global__ __launch_bounds__(256) void gn_stats_kernel(const T* __restrict__ x, 
   const int b = blockIdx.x / (G * F);
   const int ng = C / G;
   const int pv = (int)(P / VEC);  // vectors per channel row (VEC divides P; ng*P < 2^31 is checked by the host)
-  const int total = ng * pv;
   const T* base = x + (((int64_t)b * C + (int64_t)g * ng) * F + f) * P;
   const int64_t cstride = (int64_t)F * P;
   const float shift = to_float(base[0]);
 
   float s1 = 0.f, s2 = 0.f;
-  for (int e = threadIdx.x; e < total; e += blockDim.x) {
-    const int c = e / pv, v = e - c * pv;
+  // a thread walks its vectors of every channel row; four rows' loads are in flight at a time
+  for (int v = threadIdx.x; v < pv; v += blockDim.x)
+#pragma unroll 4
+  for (int c = 0; c < ng; ++c) {
     const T* p = base + c * cstride + (int64_t)v * VEC;
     if constexpr (VEC == 1) {
       const float d = to_float(p[0]) - shift;
