@@ -69,7 +69,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   // this lane's token: sequence, frame, row of the window's token order m = (b*F + f)*Pw + pl
   const int my_pp = tcol / F, my_f = tcol % F;
-  const int64_t my_seq = seq_wg + wave * TP + my_pp;
 
   // ---- weight stream (see WeightPipe): sub-chunks 0 and 1 now, sub-chunk 2 once the x tile has left LDS
   using Pipe = WeightPipe<SUB>;

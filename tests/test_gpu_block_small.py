@@ -82,6 +82,23 @@ def test_spatial_head_dim_64_peaky_bf16():
     _check(spec, x, w, ctx, 2, branch_tol=4e-2)
 
 
+def test_temporal_three_batches_tiles_straddle_bf16():
+    """B = 3, F = 8 (16 positions per workgroup), 136 positions per batch entry: workgroup tiles
+    straddle batch entries and the last tile is ragged; one window, so the one-kernel path applies."""
+    spec = tiny_spec(wl.TEMPORAL, B=3, C=64, F=8, H=8, W=17, heads=2, dim_head=32, groups=8, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, None, 136)
+
+
+def test_temporal_32_frames_bf16():
+    """F = 32: one position per wavefront, all 32 MFMA columns are frames of one sequence."""
+    spec = tiny_spec(wl.TEMPORAL, B=1, C=64, F=32, H=5, W=8, heads=2, dim_head=32, groups=8, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, None, 24)
+
+
 def test_head_dim_40_and_25_frames_bf16():
     spec = tiny_spec(wl.TEMPORAL, B=1, C=80, F=25, H=6, W=6, heads=2, dim_head=40, groups=4, pe=True, dtype="bf16")
     x = wl.make_x(spec)
