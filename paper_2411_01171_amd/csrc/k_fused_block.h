@@ -198,6 +198,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // ---- proj_in; the residual stream is parked in scratch (register image, read back by the same lanes)
   f32x16_t hacc[NB];
   float4* park = reinterpret_cast<float4*>(a.hpark) + ((int64_t)blockIdx.x * 4 + wave) * (NB * 4 * kWave) + lane;
+  // The way back: block nb of the parked residual returns through LDS (two 16 KiB landing buffers in
+  // the patch area, [wavefront][quad][lane] float4) with the same direct loads as the weight stream,
+  // so that its waits are the steps' own closing waits.
+  const char* park_s = reinterpret_cast<const char*>(a.hpark) + ((int64_t)blockIdx.x * 4 + pipe_wave) * (NB * 4 * kWave * 16);
+  const unsigned park_lds = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(arena + 4 * SLOT_BYTES) + pipe_wave * (4 * kWave * 16);
+  const float4* park_back = reinterpret_cast<const float4*>(arena + 4 * SLOT_BYTES) + wave * (4 * kWave) + lane;
+#define SI_PARK_FETCH(nb)                                                                            \
+  _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                    \
+    const char* sb = park_s + ((nb) * 4 + q) * (kWave * 16);                                         \
+    const unsigned l = park_lds + (unsigned)((((nb) % 2) * 16 + q) * (kWave * 16));                  \
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"((unsigned)(lane * 16)), "s"(sb), "s"(l) : "memory"); \
+  }
 #define SI_PROJ_IN_BLOCK(nb)                                                                         \
   {                                                                                                  \
     SI_STEP_OPEN();                                                                                  \
@@ -313,6 +325,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           }
         }
       }
+      if (gi == NG - 1) {  // no more steps until the out-projection: its first two blocks' residual sets out now
+        SI_PARK_FETCH(0)
+        if (NB > 1) { SI_PARK_FETCH(1) }
+      }
 #pragma unroll
       for (int hh = 0; hh < HG; ++hh) {
         const int c0 = hh * DH, c1 = c0 + DH;  // head columns inside the group
@@ -381,34 +397,41 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #undef SI_BLOCK_WCOLS
 #undef SI_BLOCK_WROWS
 
-  // ---- h = h0 + o W_o + b_o: the parked residual comes back, NB steps add one 32-column block each
+  // ---- h = h0 + o W_o + b_o: NB steps form one 32-column block of o W_o each; the parked residual
+  // block (fetched two steps ahead) and the bias are added behind the step
 #pragma unroll
   for (int s = 0; s < SUB; ++s) aop[s] = __builtin_bit_cast(bf16x8_t, oop[s]);
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 v = park[(nb * 4 + q) * kWave];
-      hacc[nb][4 * q + 0] = v.x; hacc[nb][4 * q + 1] = v.y; hacc[nb][4 * q + 2] = v.z; hacc[nb][4 * q + 3] = v.w;
-    }
-  // all of it must be back before the steps: a wait for a late piece inside a step would also
-  // wait for the stream batches issued since
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 #define SI_WO_BLOCK(nb)                                                                             \
   {                                                                                                 \
     SI_STEP_OPEN();                                                                                 \
+    _Pragma("unroll") for (int e = 0; e < 16; ++e) hacc[nb][e] = 0.f;                               \
     _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                               \
       hacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), aop[s], hacc[nb], 0, 0, 0);    \
       SI_REFILL(s);                                                                                 \
       __builtin_amdgcn_sched_barrier(0);                                                            \
     }                                                                                               \
-    SI_STEP_CLOSE();                                                                                \
-    _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                   \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) hacc[nb][4 * q + j] += t_bo[32 * (nb) + 8 * q + 4 * g + j]; \
+    /* block nb's residual must have landed; the fetch of block nb + 1 and the batch of this step */ \
+    /* are younger and may stay in flight */                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                              \
+    Pipe::wait_step_n(cur, TOTAL_SUB, (nb) + 1 < NB ? 4 : 0);                                       \
+    ++cur;                                                                                          \
+    __syncthreads();                                                                                \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                 \
+      const float4 pk = park_back[(((nb) % 2) * 16 + q) * kWave];                                   \
+      hacc[nb][4 * q + 0] += pk.x + t_bo[32 * (nb) + 8 * q + 4 * g + 0];                            \
+      hacc[nb][4 * q + 1] += pk.y + t_bo[32 * (nb) + 8 * q + 4 * g + 1];                            \
+      hacc[nb][4 * q + 2] += pk.z + t_bo[32 * (nb) + 8 * q + 4 * g + 2];                            \
+      hacc[nb][4 * q + 3] += pk.w + t_bo[32 * (nb) + 8 * q + 4 * g + 3];                            \
+    }                                                                                               \
+    if ((nb) + 2 < NB) { /* this landing buffer is read out: block nb + 2 may overwrite it */       \
+      __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0) */                                          \
+      SI_PARK_FETCH((nb) + 2)                                                                       \
+    }                                                                                               \
   }
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) SI_WO_BLOCK(nb)
 #undef SI_WO_BLOCK
+#undef SI_PARK_FETCH
 
   // ---- LN3 over the row (this lane holds half of it, lane ^ 32 the other half); aop becomes its output
   {
