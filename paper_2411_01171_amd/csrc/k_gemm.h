@@ -137,14 +137,14 @@ struct EpiSliceOut {
 // loads for tile k+1 are issued before the MFMAs of tile k (register staging,
 // two LDS buffers, one barrier per tile).  Out-of-range rows / k are zero-filled.
 // Requires K % 8 == 0, lda % 8 == 0 and 16-byte aligned bases.
-template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
+template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi, int BK = 64>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16* __restrict__ A, int64_t lda,
                                                         const bf16* __restrict__ Wp, int64_t M, int N, int K, Epi epi) {
   static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per block");
-  constexpr int BK = 64, LDK = BK + 8;
+  constexpr int LDK = BK + 8, CPR = BK / 8;  // 16-byte chunks per tile row
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront tile
   constexpr int TM = WM / 32, TN = WN / 32;            // MFMA blocks per wavefront
-  constexpr int A_CHUNKS = BM * 8 / 256, W_CHUNKS = BN * 8 / 256;
+  constexpr int A_CHUNKS = BM * CPR / 256, W_CHUNKS = BN * CPR / 256;
   static_assert(WM % 32 == 0 && WN % 32 == 0 && A_CHUNKS >= 1 && W_CHUNKS >= 1, "tile shape");
 
   __shared__ __attribute__((aligned(16))) unsigned short As[2][BM][LDK];
@@ -159,13 +159,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16* __restrict__
   auto load_tile = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
-      const int id = tid + i * 256, row = id >> 3, kc = (id & 7) * 8;
+      const int id = tid + i * 256, row = id / CPR, kc = (id % CPR) * 8;
       const int64_t m = m0 + row;
       ra[i] = (m < M && k0 + kc < K) ? *reinterpret_cast<const uint4*>(A + m * lda + k0 + kc) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < W_CHUNKS; ++i) {
-      const int id = tid + i * 256, row = id >> 3, kc = (id & 7) * 8;
+      const int id = tid + i * 256, row = id / CPR, kc = (id % CPR) * 8;
       const int n = n0 + row;
       rw[i] = (n < N && k0 + kc < K) ? *reinterpret_cast<const uint4*>(Wp + (int64_t)n * K + k0 + kc) : make_uint4(0, 0, 0, 0);
     }
@@ -173,12 +173,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16* __restrict__
   auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < A_CHUNKS; ++i) {
-      const int id = tid + i * 256, row = id >> 3, kc = (id & 7) * 8;
+      const int id = tid + i * 256, row = id / CPR, kc = (id % CPR) * 8;
       *reinterpret_cast<uint4*>(&As[buf][row][kc]) = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < W_CHUNKS; ++i) {
-      const int id = tid + i * 256, row = id >> 3, kc = (id & 7) * 8;
+      const int id = tid + i * 256, row = id / CPR, kc = (id % CPR) * 8;
       *reinterpret_cast<uint4*>(&Ws[buf][row][kc]) = rw[i];
     }
   };

@@ -192,6 +192,22 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     if (hipGetLastError() != hipSuccess) return SI_ERR_HIP; \
   } while (0)
 
+template <typename T, class Epi, int BK>
+static void launch_gemm_bf16(const T* A, int64_t lda, const T* Wp, int64_t M, int N, int K, Epi epi, hipStream_t st) {
+  // small problems (a slice of a few thousand tokens times a D-wide matrix) get 64 x 64 tiles:
+  // four times the workgroups, so that every CU has work
+  if (((M + 127) / 128) * ((N + 127) / 128) < 256) {
+    dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 63) / 64));
+    gemm_bf16_kernel<64, 64, 2, 2, Epi, BK><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+  } else if (N % 128 == 0) {
+    dim3 grid((unsigned)((M + 127) / 128), (unsigned)(N / 128));
+    gemm_bf16_kernel<128, 128, 2, 2, Epi, BK><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+  } else {
+    dim3 grid((unsigned)((M + 127) / 128), (unsigned)((N + 63) / 64));
+    gemm_bf16_kernel<128, 64, 4, 1, Epi, BK><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+  }
+}
+
 template <typename T, class Epi>
 static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T* Wp, int64_t M, int N, int K, Epi epi,
                              hipStream_t st) {
@@ -201,18 +217,10 @@ static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T
     dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 63) / 64));
     gemm_f32_kernel<Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
   } else {
-    // small problems (a slice of a few thousand tokens times a D-wide matrix) get 64 x 64 tiles:
-    // four times the workgroups, so that every CU has work
-    if (((M + 127) / 128) * ((N + 127) / 128) < 256) {
-      dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 63) / 64));
-      gemm_bf16_kernel<64, 64, 2, 2, Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
-    } else if (N % 128 == 0) {
-      dim3 grid((unsigned)((M + 127) / 128), (unsigned)(N / 128));
-      gemm_bf16_kernel<128, 128, 2, 2, Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
-    } else {
-      dim3 grid((unsigned)((M + 127) / 128), (unsigned)((N + 63) / 64));
-      gemm_bf16_kernel<128, 64, 4, 1, Epi><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
-    }
+    // short contractions (K = 320: five 64-wide tiles) run better with 32-wide k tiles: half the LDS,
+    // twice the workgroups per CU to hide the pipeline's fill and drain
+    if (K <= 512) launch_gemm_bf16<T, Epi, 32>(A, lda, Wp, M, N, K, epi, st);
+    else launch_gemm_bf16<T, Epi, 64>(A, lda, Wp, M, N, K, epi, st);
   }
   SI_CHECK_LAUNCH();
   return SI_OK;
