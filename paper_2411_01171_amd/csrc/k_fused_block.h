@@ -168,9 +168,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   ++cur;                                                                         \
   __syncthreads()
 #define SI_FRAG(f) fifo[(f) % FIFO]
-#define SI_REFILL(f)                                                                                 \
+#define SI_REFILL1(f)                                                                                \
   fifo[(f) % FIFO] = __builtin_bit_cast(bf16x8_t, (f) < FIFO ? slot_c[((f) + FIFO) * kWave + lane]   \
                                                              : slot_n[((f)-FIFO) * kWave + lane])
+#define SI_REFILL(f)                                                                                 \
+  if constexpr (FIFO % 5 != 0) { SI_REFILL1(f); }                                                    \
+  else if ((f) % 5 == 4) { _Pragma("unroll") for (int rj = (f) - 4; rj <= (f); ++rj) { SI_REFILL1(rj); } }
   // one 32-column block: weights as rows (result: lane = token) or as columns (result: lane = column)
 #define SI_BLOCK_WROWS(ACC)                                                                 \
   {                                                                                         \
@@ -646,6 +649,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #undef SI_RUN_W1
 #undef SI_GEGLU_TAIL
 #undef SI_REFILL
+#undef SI_REFILL1
 #undef SI_FRAG
 #undef SI_STEP_CLOSE
 #undef SI_STEP_OPEN
