@@ -76,6 +76,8 @@ struct Plan {
   int fused_nb;     // > 0: register-resident FFN half with D = 32*fused_nb
   bool fused_attn;  // register-resident attention half as well (temporal blocks)
   bool attn_mfma;   // matrix-core attention kernel for the staged spatial path (bf16, head dimension 64)
+  int lanes;        // slices in flight (staged path with many small slices: 2, on two streams)
+  size_t lane_stride;  // bytes between the two lanes' slice intermediates
   int Mcp;          // context tokens rounded up to a multiple of 8 (transposed value copy)
   // workspace offsets (bytes)
   size_t off_stats, off_pe, off_ctxkv, off_ctxvt, off_vt;
@@ -166,6 +168,13 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     p->off_big = take((size_t)p->Mmax * 4 * Dz * es);
   }
   p->off_vt = take(p->attn_mfma ? (size_t)p->Mmax * Dz * es : 0);  // values of the window, keys contiguous
+  // Cross-slice pipelining (Sec. 4.2.2): with many small slices the staged kernels leave CUs idle, so
+  // two slices run at a time on two streams, each with its own intermediates.  Only with 8 or more
+  // slices: two slices' buffers then still stay within a quarter of the unsliced footprint.
+  const int64_t n_slices = (p->extent + p->slice_len - 1) / p->slice_len;
+  p->lanes = (!p->fused_attn && n_slices >= 8) ? 2 : 1;
+  p->lane_stride = off - p->off_a;
+  if (p->lanes == 2) take(p->lane_stride);
   const size_t act_end = off;
   // re-laid-out weights
   p->off_w_in = take(split * Dz * C * es);
@@ -326,6 +335,27 @@ static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, ch
   return SI_OK;
 }
 
+// Auxiliary stream and fork / join events for two slices in flight, one set per device, created on
+// first use (default priority) and kept for the life of the process.  Calls that overlap on one
+// device share them and must not run concurrently from several host threads.
+struct AuxStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+static si_status aux_stream(AuxStream** out) {
+  static AuxStream per_device[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SI_ERR_HIP;
+  AuxStream& a = per_device[dev];
+  if (!a.stream) {
+    if (hipStreamCreateWithFlags(&a.stream, hipStreamNonBlocking) != hipSuccess) return SI_ERR_HIP;
+    if (hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess) return SI_ERR_HIP;
+    if (hipEventCreateWithFlags(&a.join, hipEventDisableTiming) != hipSuccess) return SI_ERR_HIP;
+  }
+  *out = &a;
+  return SI_OK;
+}
+
 template <typename T>
 static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
                            si_tensor5* out, char* ws, hipStream_t st) {
@@ -404,8 +434,26 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
 
   // ---- Feature Slicer windows; one operator group per window (Eq. 1)
   const float scale = 1.0f / sqrtf((float)p.d);
+  hipStream_t const st_main = st;
+  T* const a_base = a;
+  float* const h_base = h;
+  T* const big_base = big;
+  AuxStream* aux = nullptr;
+  if (p.lanes == 2) {  // fork: the second lane starts after the once-per-call work above
+    SI_TRY(aux_stream(&aux));
+    if (hipEventRecord(aux->fork, st_main) != hipSuccess || hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess)
+      return SI_ERR_HIP;
+  }
   for (int64_t s0 = 0; s0 < p.extent; s0 += p.slice_len) {
     const int64_t s1 = s0 + p.slice_len < p.extent ? s0 + p.slice_len : p.extent;
+    // this slice's lane: stream and intermediates (the names below shadow the first lane's)
+    const size_t lane_off = (size_t)((s0 / p.slice_len) % p.lanes) * p.lane_stride;
+    hipStream_t st = lane_off ? aux->stream : st_main;
+    T* a = reinterpret_cast<T*>(reinterpret_cast<char*>(a_base) + lane_off);
+    float* h = reinterpret_cast<float*>(reinterpret_cast<char*>(h_base) + lane_off);
+    T* big = reinterpret_cast<T*>(reinterpret_cast<char*>(big_base) + lane_off);
+    char* const vt_lane = ws + p.off_vt + lane_off;
+    (void)vt_lane;
     Window win;
     win.B = p.B; win.C = C; win.F = p.F; win.P = p.P; win.G = p.G;
     if (p.axis == SI_AXIS_F) {
@@ -453,7 +501,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       bool self_done = false;
       if constexpr (sizeof(T) == 2) {
         if (p.attn_mfma) {  // spatial: sequence (b, f) = rows (b*Fw + f)*Pw + i
-          bf16* vt = reinterpret_cast<bf16*>(ws + p.off_vt);
+          bf16* vt = reinterpret_cast<bf16*>(vt_lane);
           SI_TRY(launch_transpose_v("v_transpose", big, (int64_t)3 * D, 2 * D, vt, p.B * win.Fw, win.Pw, win.Pw, D, st));
           SI_TRY(launch_attention_mfma("self_attn", big, (int64_t)3 * D, big + D, (int64_t)3 * D, vt, a, (int64_t)D, p.B * win.Fw,
                                        win.Pw, win.Pw, win.Pw, p.heads, 1, scale, st));
@@ -538,6 +586,10 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       EpiSliceOut<T> epi{X, OUT, cT(w->b_out), win};
       SI_TRY(launch_gemm<T>("proj_out", a, (int64_t)kSplit * D, w_out, M, C, kSplit * D, epi, st));
     }
+  }
+  if (p.lanes == 2) {  // join: the caller's stream continues after both lanes
+    if (hipEventRecord(aux->join, aux->stream) != hipSuccess || hipStreamWaitEvent(st_main, aux->join, 0) != hipSuccess)
+      return SI_ERR_HIP;
   }
   return SI_OK;
 }
