@@ -168,11 +168,12 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     p->off_big = take((size_t)p->Mmax * 4 * Dz * es);
   }
   p->off_vt = take(p->attn_mfma ? (size_t)p->Mmax * Dz * es : 0);  // values of the window, keys contiguous
-  // Cross-slice pipelining (Sec. 4.2.2): with many small slices the staged kernels leave CUs idle, so
-  // two slices run at a time on two streams, each with its own intermediates.  Only with 8 or more
+  // Cross-slice pipelining (Sec. 4.2.2): with many small slices the kernels of one slice leave CUs
+  // idle (under-filled grids, partial last rounds), so two slices run at a time on two streams, each
+  // with its own intermediates.  Only with 8 or more
   // slices: two slices' buffers then still stay within a quarter of the unsliced footprint.
   const int64_t n_slices = (p->extent + p->slice_len - 1) / p->slice_len;
-  p->lanes = (!p->fused_attn && n_slices >= 8) ? 2 : 1;
+  p->lanes = n_slices >= 8 ? 2 : 1;
   p->lane_stride = off - p->off_a;
   if (p->lanes == 2) take(p->lane_stride);
   const size_t act_end = off;
