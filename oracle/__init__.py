@@ -18,4 +18,5 @@ from .block_ref import (  # noqa: F401
 )
 from .rehash_ref import (  # noqa: F401
     cosine_terms_ref, cosine_ref, rehash_decision_ref, key_step_search_ref, rehash_replay_ref,
+    rehash_causal_ref,
 )

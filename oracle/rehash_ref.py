@@ -88,3 +88,25 @@ def rehash_replay_ref(compute: Callable[[int], np.ndarray], key_steps: Sequence[
             yield t, cache, True
         else:
             yield t, cache, False
+
+
+def rehash_causal_ref(inputs: Sequence[np.ndarray], compute: Callable[[np.ndarray], np.ndarray], gamma: float):
+    """One-pass (causal) variant of the Sec. 4.3.2 hand-back rule: the decision
+    for step t is taken from what is known when step t starts.  The block's
+    input x_t is compared with the input of the last recomputed step (the
+    anchor, as in Algorithm 1's walk: always the last key step, never simply
+    the previous step); similar (>= gamma) -> the anchor's output is handed
+    back, over as many consecutive steps as the test keeps passing; otherwise
+    the block is computed on x_t, which becomes the new anchor.  The first
+    step always computes.  Yields (t, feature, recomputed, cos) with cos = NaN
+    where no test was taken."""
+    anchor_x = None
+    anchor_y = None
+    for t, x in enumerate(inputs):
+        if anchor_x is not None and rehash_decision_ref(x, anchor_x, gamma) == 1:
+            yield t, anchor_y, False, cosine_ref(x, anchor_x)
+            continue
+        c = float("nan") if anchor_x is None else cosine_ref(x, anchor_x)
+        anchor_y = compute(x)
+        anchor_x = x
+        yield t, anchor_y, True, c

@@ -129,3 +129,70 @@ def test_replay_hands_back_cached_feature():
     assert calls == [0, 3, 5]
     assert [int(f[0]) for _, f, _ in got] == [0, 0, 0, 3, 3, 5]
     assert [r for _, _, r in got] == [True, False, False, True, False, True]
+
+
+def test_causal_walk_equals_algorithm1_on_the_input_map():
+    """The one-pass rule recomputes exactly at Algorithm 1's key steps of the INPUT similarity map
+    (its anchored walk), except that Algorithm 1 also forces the last step."""
+    rng = np.random.default_rng(11)
+    for trial in range(20):
+        K = int(rng.integers(2, 12))
+        n = 64
+        xs = [rng.standard_normal(n)]
+        for t in range(1, K):
+            xs.append(xs[-1] + float(rng.uniform(0.05, 0.6)) * rng.standard_normal(n))
+        gamma = float(rng.uniform(0.6, 0.99))
+        S = np.array([[oracle.cosine_ref(xs[i], xs[j]) for j in range(K)] for i in range(K)])
+        G = oracle.key_step_search_ref(S, float(np.float32(gamma)), K)
+        got = list(oracle.rehash_causal_ref(xs, lambda x: 2.0 * x, gamma))
+        rec = [t for t, _, r, _ in got if r]
+        assert sorted(set(rec + [K - 1])) == G and rec[0] == 0
+        # hand-back: a reused step returns the anchor's output, bit for bit
+        anchor = None
+        for t, y, r, c in got:
+            if r:
+                anchor = t
+                assert np.array_equal(y, 2.0 * xs[t])
+            else:
+                assert np.array_equal(y, 2.0 * xs[anchor])
+                assert c == oracle.cosine_ref(xs[t], xs[anchor]) and c >= np.float32(gamma) - 1e-15
+
+
+def test_causal_walk_extremes_and_chaining():
+    rng = np.random.default_rng(12)
+    xs = [rng.standard_normal(32) for _ in range(5)]            # unrelated inputs: |cos| small
+    calls = []
+
+    def compute(x):
+        calls.append(1)
+        return x + 1.0
+
+    assert [r for _, _, r, _ in oracle.rehash_causal_ref(xs, compute, 0.9)] == [True] * 5
+    assert [r for _, _, r, _ in oracle.rehash_causal_ref(xs, compute, -1.0)] == [True] + [False] * 4
+    same = [xs[0]] * 4                                           # identical inputs: cos = 1 >= gamma = 1 (tie reuses)
+    assert [r for _, _, r, _ in oracle.rehash_causal_ref(same, compute, 1.0)] == [True, False, False, False]
+    # chaining through a stack: a reused block hands its successor the anchor's output again, so the
+    # successor's input repeats exactly and it reuses too
+    drift = [xs[0], xs[0] + 0.01 * xs[1], xs[0] + 0.02 * xs[2], xs[3]]
+    first = list(oracle.rehash_causal_ref(drift, lambda x: np.tanh(x), 0.95))
+    second = list(oracle.rehash_causal_ref([y for _, y, _, _ in first], lambda x: x * x, 0.95))
+    assert [r for _, _, r, _ in first] == [True, False, False, True]
+    assert [r for _, _, r, _ in second] == [True, False, False, True]
+    assert all(c == 1.0 or math.isnan(c) or r for _, _, r, c in second)
+
+
+def test_causal_walk_cfg5_schedule_prediction():
+    """Gaussian drift of the cfg5 schedule: cos(x_t, x_anchor) = 1/sqrt(1 + sum sigma^2) in the limit,
+    which first falls below 0.95 four steps after an anchor at step 0 (0.981, 0.966, 0.956, 0.949)."""
+    acc, pred = 0.0, []
+    for t in range(1, 5):
+        acc += wl.cfg5_sigma(t) ** 2
+        pred.append(1 / math.sqrt(1 + acc))
+    assert pred[2] > 0.95 > pred[3]
+    rng = np.random.default_rng(13)
+    n = 2_000_000                                                # margin at t = 4 is ~1e-3; sampling noise ~ 1/sqrt(n)
+    xs = [rng.standard_normal(n)]
+    for t in range(1, wl.CFG5_STEPS):
+        xs.append(xs[-1] + wl.cfg5_sigma(t) * rng.standard_normal(n))
+    rec = [t for t, _, r, _ in oracle.rehash_causal_ref(xs, lambda x: x, wl.CFG5_GAMMA) if r]
+    assert rec[:2] == [0, 4]
