@@ -60,6 +60,12 @@ def stage_work(spec, stage, M, window_tokens_per_seq=None):
         return "flop", 2.0 * M * (C * D + 3 * D * D + D * D + 8 * D * D + 4 * D * D + D * C) + 4.0 * M * spec.F * D
     if stage == "gn_stats":
         return "byte", float(spec.tokens * C * es)
+    if stage == "gn_stats_cosine":      # statistics pass that also reduces x against the rehash anchor
+        return "byte", 2.0 * spec.tokens * C * es
+    if stage == "cache_handback":       # device copy of the cached output
+        return "byte", 2.0 * spec.tokens * C * es
+    if stage == "cache_update":         # device copies of x and out into the anchor
+        return "byte", 4.0 * spec.tokens * C * es
     if stage == "slice_in":
         return "byte", 2.0 * M * C * es
     if stage in ("ln1", "ln2", "ln3"):
@@ -109,6 +115,10 @@ def main():
     ap.add_argument("--workload", default="cfg2", help="cfg2 (default, the metric's configuration), cfg3, cfg4s, cfg4t, cfg5s, cfg5t")
     ap.add_argument("--slice-len", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rehash-probe", choices=["reuse", "compute"], default=None,
+                    help="time si_block_forward_rehash instead of forward + output check: the anchor is the input "
+                         "itself (reuse: the cached output is handed back) or a drifted input restored before every "
+                         "step (compute: test fails, full forward, anchor update)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of x (known bytes) so that hardware byte counters "
                          "collected around this command can be scaled")
@@ -155,6 +165,17 @@ def main():
     def step():
         si.si_block_forward(x, wts, ctx, out, axis, slice_len, ws)
         si.si_rehash_check(out, cached, gamma, cos, dec, scratch)
+
+    probe = {}
+    if args.rehash_probe:
+        cache = si.RehashCache(x)
+        far = to_dev(wl.round_to_storage(x_np + np.float32(0.5) * wl.make_x(spec, seed=spec.seed + 77), spec.dtype), spec.dtype)
+        si.si_block_forward_rehash(x, wts, ctx, out, axis, slice_len, ws, cache, gamma)     # fills the anchor with (x, out)
+
+        def step():                                                     # noqa: F811
+            if args.rehash_probe == "compute":
+                cache.x_key.copy_(far)
+            probe["reused"], probe["cos"] = si.si_block_forward_rehash(x, wts, ctx, out, axis, slice_len, ws, cache, gamma)
 
     if args.calibration_copy:
         torch.empty_like(x).copy_(x)       # reads and writes x.numel() * element_size bytes
@@ -236,13 +257,17 @@ def main():
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: {spec.kind} block x[B={spec.B},C={spec.C},F={spec.F},H={spec.H},W={spec.W}], "
                                f"{spec.heads} heads x {spec.dim_head}, sliced along {spec.slice_axis} in windows of {slice_len} "
-                               f"({n_slices} slices) + rehash check of the output (threshold {gamma})",
+                               f"({n_slices} slices) + " +
+                               (f"rehash check of the output (threshold {gamma})" if not args.rehash_probe else
+                                f"one-pass rehash on the input, probe '{args.rehash_probe}' (value counts the forward's "
+                                f"FLOPs whether computed or handed back)"),
                    "algorithmic_flop_per_step": flops, "tokens": spec.tokens},
         "frac_mfma_peak": value / PEAK_BF16_TFLOPS,
         "live_activation_bytes": {"sliced": live_sliced, "unsliced_same_kernels": live_unsliced,
                                   "ratio": live_sliced / live_unsliced, "workspace_bytes": ws_bytes,
                                   "x_bytes": x.numel() * x.element_size()},
-        "rehash": {"cos": float(cos.item()), "decision": int(dec.item())},
+        "rehash": ({"cos": float(cos.item()), "decision": int(dec.item())} if not args.rehash_probe else
+                   {"probe": args.rehash_probe, "reused": bool(probe["reused"]), "cos": probe["cos"]}),
         "roofline": roof,
         "stages": stage_report,
     }

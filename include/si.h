@@ -166,6 +166,40 @@ si_status si_rehash_check_sync(const void* feat_t, const void* feat_prev, int64_
                                float thresh, void* scratch, void* result_dev, void* stream,
                                double* cos_host, int32_t* decision_host);
 
+/* Anchor of the one-pass Step Rehash walk around one block: input and output
+ * of the last step at which the block was computed.  x_key and y_key are
+ * caller-owned device buffers of the feature's size and dtype, 16-byte
+ * aligned, disjoint from each other, from x, out and the workspace; the
+ * library writes them.  `valid` is host state: set it to 0 before the first
+ * step (nothing cached yet); the library sets it to 1. */
+typedef struct {
+  void* x_key;
+  void* y_key;
+  int32_t valid;
+} si_rehash_cache;
+
+/* Sliced block forward under Step Rehash, decided causally (Sec. 4.3: skip a
+ * block whose feature barely moved; Algorithm 1's anchoring: always compare
+ * with the last computed step, never just the previous one).  The test of
+ * si_rehash_check is applied to the block's INPUT: cos(x, cache->x_key) >=
+ * gamma -> out := cache->y_key (the cached output is handed back; over as many
+ * consecutive steps as the test keeps passing) and nothing else runs;
+ * otherwise out := si_block_forward(x) bit for bit, and x, out become the new
+ * anchor (two device-to-device copies).  With cache->valid == 0 the block is
+ * computed unconditionally.
+ *
+ * The similarity sums ride on the GroupNorm statistics pass (x is read once
+ * for both; the anchor input is the only extra read), then the call WAITS for
+ * `stream` to learn the decision -- it is not asynchronous when
+ * cache->valid != 0.  Arguments as si_block_forward (same workspace size);
+ * gamma NaN -> SI_ERR_ARG.
+ *   cos_host     host, may be NULL: the cosine, NaN when no test was taken
+ *   reused_host  host, required: 1 = cached output handed back, 0 = computed */
+si_status si_block_forward_rehash(const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
+                                  si_tensor5* out, int32_t axis, int64_t slice_len, void* workspace,
+                                  size_t workspace_bytes, si_rehash_cache* cache, float gamma, void* stream,
+                                  double* cos_host, int32_t* reused_host);
+
 /* Key-step search, Algorithm 1 (Appendix B).  Host only.
  *   S      host, row-major K x K similarity map; only S[i][anchor] entries are read
  *   gamma  threshold, must satisfy gamma <= 1 and gamma <= S[i][i] where visited

@@ -47,6 +47,10 @@ class _Weights(C.Structure):
                 + [(n, C.c_void_p) for n in WEIGHT_FIELDS])
 
 
+class _RehashCache(C.Structure):
+    _fields_ = [("x_key", C.c_void_p), ("y_key", C.c_void_p), ("valid", C.c_int32)]
+
+
 _lib = None
 
 
@@ -67,6 +71,9 @@ def lib() -> C.CDLL:
     L.si_block_forward.restype = i32
     L.si_block_forward.argtypes = [C.POINTER(_Tensor5), C.POINTER(_Weights), C.POINTER(_Context), C.POINTER(_Tensor5),
                                    i32, i64, vp, sz, vp]
+    L.si_block_forward_rehash.restype = i32
+    L.si_block_forward_rehash.argtypes = L.si_block_forward.argtypes[:8] + [
+        C.POINTER(_RehashCache), C.c_float, vp, C.POINTER(C.c_double), C.POINTER(i32)]
     L.si_rehash_scratch_bytes.restype = sz
     L.si_rehash_scratch_bytes.argtypes = [i64]
     L.si_rehash_check.restype = i32
@@ -173,6 +180,39 @@ def si_block_forward(x, weights: BlockWeights, ctx, out, axis: int, slice_len: i
                                 _stream_ptr(stream))
     if st != 0:
         raise SiError(st, "si_block_forward")
+
+
+class RehashCache:
+    """Anchor buffers of si_block_forward_rehash for one block (device tensors shaped like the feature)."""
+
+    def __init__(self, like):
+        import torch
+        self.x_key = torch.empty_like(like)
+        self.y_key = torch.empty_like(like)
+        self.struct = _RehashCache(self.x_key.data_ptr(), self.y_key.data_ptr(), 0)
+
+    @property
+    def valid(self) -> bool:
+        return bool(self.struct.valid)
+
+    def reset(self) -> None:
+        self.struct.valid = 0
+
+
+def si_block_forward_rehash(x, weights: BlockWeights, ctx, out, axis: int, slice_len: int, workspace,
+                            cache: RehashCache, gamma: float, stream=None) -> Tuple[bool, float]:
+    """Step Rehash around the block, decided on its input.  Returns (reused, cos); waits for the stream
+    when the cache holds an anchor."""
+    xd, od = _tensor5(x), _tensor5(out)
+    pc, _keep = _pctx(ctx)
+    cos, reused = C.c_double(), C.c_int32()
+    st = lib().si_block_forward_rehash(C.byref(xd), C.byref(weights.struct), pc, C.byref(od), axis, slice_len,
+                                       workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                       C.byref(cache.struct), gamma, _stream_ptr(stream),
+                                       C.byref(cos), C.byref(reused))
+    if st != 0:
+        raise SiError(st, "si_block_forward_rehash")
+    return bool(reused.value), cos.value
 
 
 def si_rehash_scratch_bytes(n: int) -> int:

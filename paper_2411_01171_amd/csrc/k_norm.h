@@ -13,9 +13,18 @@ namespace si {
 // Sums are taken relative to the group's first element so that a large common
 // offset does not cancel in fp32; per-thread fp32 partials are merged in fp64.
 // stats[((b*F + f)*G + g)*2 + {0,1}] = {mean, 1/sqrt(var + eps)}.
-template <typename T, int VEC>
+//
+// COS: the same pass also reduces x against a second tensor `key` of the same
+// shape (the input of the last recomputed step of the Step Rehash walk):
+// partial[block*3 + {0,1,2}] = {<x,key>, |x|^2, |key|^2} over the block's
+// elements, exact products and fp64 accumulation as in cosine_partial_kernel,
+// so the similarity test costs one extra read of `key` and no extra read of x.
+// The GroupNorm sums are the same instructions on the same values either way.
+template <typename T, int VEC, bool COS = false>
 __global__ __launch_bounds__(256) void gn_stats_kernel(const T* __restrict__ x, float* __restrict__ stats,
-                                                       int C, int F, int64_t P, int G, float eps) {
+                                                       int C, int F, int64_t P, int G, float eps,
+                                                       const T* __restrict__ key = nullptr,
+                                                       double* __restrict__ partial = nullptr) {
   const int g = blockIdx.x % G;
   const int f = (blockIdx.x / G) % F;
   const int b = blockIdx.x / (G * F);
@@ -26,15 +35,28 @@ __global__ __launch_bounds__(256) void gn_stats_kernel(const T* __restrict__ x, 
   const float shift = to_float(base[0]);
 
   float s1 = 0.f, s2 = 0.f;
-  // a thread walks its vectors of every channel row; four rows' loads are in flight at a time
-  for (int v = threadIdx.x; v < pv; v += blockDim.x)
+  double dot = 0.0, na = 0.0, nb = 0.0;
+  const T* kbase = COS ? key + (base - x) : nullptr;
+  // a thread walks its vectors of every channel row; four rows' loads are in flight at a time.  Short
+  // rows (fewer vectors than threads) are shared out so that 256 / vlanes rows are walked side by side.
+  int vlanes = 256;
+  while (vlanes / 2 >= pv && vlanes > 1) vlanes >>= 1;
+  const int v0 = threadIdx.x & (vlanes - 1), c0 = threadIdx.x / vlanes, cstep = 256 / vlanes;
+  for (int v = v0; v < pv; v += vlanes)
 #pragma unroll 4
-  for (int c = 0; c < ng; ++c) {
+  for (int c = c0; c < ng; c += cstep) {
     const T* p = base + c * cstride + (int64_t)v * VEC;
     if constexpr (VEC == 1) {
-      const float d = to_float(p[0]) - shift;
+      const float xv = to_float(p[0]);
+      const float d = xv - shift;
       s1 += d;
       s2 += d * d;
+      if constexpr (COS) {
+        const double da = xv, db = to_float(kbase[c * cstride + v]);
+        dot = fma(da, db, dot);
+        na = fma(da, da, na);
+        nb = fma(db, db, nb);
+      }
     } else if constexpr (sizeof(T) == 2) {  // 8 x bf16 = 16 bytes
       const uint4 raw = *reinterpret_cast<const uint4*>(p);
       const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -45,12 +67,54 @@ __global__ __launch_bounds__(256) void gn_stats_kernel(const T* __restrict__ x, 
         s1 += d0 + d1;
         s2 += d0 * d0 + d1 * d1;
       }
+      if constexpr (COS) {
+        const uint4 rk = *reinterpret_cast<const uint4*>(kbase + c * cstride + (int64_t)v * VEC);
+        const unsigned wk[4] = {rk.x, rk.y, rk.z, rk.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float a0 = __uint_as_float(w[i] << 16), a1 = __uint_as_float(w[i] & 0xffff0000u);
+          const float b0 = __uint_as_float(wk[i] << 16), b1 = __uint_as_float(wk[i] & 0xffff0000u);
+          // 8-bit significands: each product is exact in fp32
+          dot += (double)(a0 * b0);
+          dot += (double)(a1 * b1);
+          na += (double)(a0 * a0);
+          na += (double)(a1 * a1);
+          nb += (double)(b0 * b0);
+          nb += (double)(b1 * b1);
+        }
+      }
     } else {  // 4 x f32 = 16 bytes
       const float4 raw = *reinterpret_cast<const float4*>(p);
       const float d0 = raw.x - shift, d1 = raw.y - shift, d2 = raw.z - shift, d3 = raw.w - shift;
       s1 += (d0 + d1) + (d2 + d3);
       s2 += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+      if constexpr (COS) {
+        const float4 rk = *reinterpret_cast<const float4*>(kbase + c * cstride + (int64_t)v * VEC);
+        const float fa[4] = {raw.x, raw.y, raw.z, raw.w}, fb[4] = {rk.x, rk.y, rk.z, rk.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const double da = fa[i], db = fb[i];
+          dot = fma(da, db, dot);
+          na = fma(da, da, na);
+          nb = fma(db, db, nb);
+        }
+      }
     }
+  }
+  if constexpr (COS) {
+    dot = wave_sum(dot);
+    na = wave_sum(na);
+    nb = wave_sum(nb);
+    __shared__ double shc[3][4];
+    if (threadIdx.x % kWave == 0) {
+      shc[0][threadIdx.x / kWave] = dot;
+      shc[1][threadIdx.x / kWave] = na;
+      shc[2][threadIdx.x / kWave] = nb;
+    }
+    __syncthreads();
+    if (threadIdx.x < 3)
+      partial[(int64_t)blockIdx.x * 3 + threadIdx.x] =
+          (shc[threadIdx.x][0] + shc[threadIdx.x][1]) + (shc[threadIdx.x][2] + shc[threadIdx.x][3]);
   }
   double a1 = wave_sum((double)s1), a2 = wave_sum((double)s2);
   __shared__ double sh[2][4];

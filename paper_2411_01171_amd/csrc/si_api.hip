@@ -80,7 +80,7 @@ struct Plan {
   size_t lane_stride;  // bytes between the two lanes' slice intermediates
   int Mcp;          // context tokens rounded up to a multiple of 8 (transposed value copy)
   // workspace offsets (bytes)
-  size_t off_stats, off_pe, off_ctxkv, off_ctxvt, off_vt;
+  size_t off_stats, off_rehash, off_pe, off_ctxkv, off_ctxvt, off_vt;
   size_t off_w_in, off_wqkv, off_wo, off_wq2, off_wkv2, off_wo2, off_w1, off_w2, off_w_out;
   size_t off_a, off_h, off_big, off_ffn_stream, off_attn_stream;
   size_t weights_bytes, total_bytes;
@@ -136,6 +136,8 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   };
   // slice-independent activation-derived items
   p->off_stats = take((size_t)p->B * p->F * p->G * 2 * sizeof(float));
+  // similarity partials of the fused statistics + rehash pass (3 doubles per block), then {cos, decision}
+  p->off_rehash = take((size_t)p->B * p->F * p->G * 3 * sizeof(double) + 16);
   p->off_pe = take(p->pe ? (size_t)p->F * Dz * sizeof(float) : 0);
   p->off_ctxkv = take((size_t)p->B * p->Mc * 2 * Dz * es);
   p->attn_mfma = p->dtype == SI_BF16 && p->kind == SI_BLOCK_SPATIAL && p->d == 64 && P % 8 == 0;
@@ -357,9 +359,29 @@ static si_status aux_stream(AuxStream** out) {
   return SI_OK;
 }
 
+// GroupNorm statistics of the whole feature; with `key` the same pass also leaves the similarity
+// partials of x against key (one triple per block) at off_rehash.
+template <typename T>
+static si_status launch_gn_stats(const Plan& p, const T* X, const T* key, float eps, char* ws, hipStream_t st) {
+  StageScope scope(key ? "gn_stats_cosine" : "gn_stats", st);
+  constexpr int VEC = 16 / sizeof(T);
+  float* stats = reinterpret_cast<float*>(ws + p.off_stats);
+  double* partial = reinterpret_cast<double*>(ws + p.off_rehash);
+  const unsigned blocks = (unsigned)(p.B * p.F * p.G);
+  if (p.P % VEC == 0) {
+    if (key) gn_stats_kernel<T, VEC, true><<<blocks, 256, 0, st>>>(X, stats, p.C, p.F, p.P, p.G, eps, key, partial);
+    else gn_stats_kernel<T, VEC><<<blocks, 256, 0, st>>>(X, stats, p.C, p.F, p.P, p.G, eps);
+  } else {
+    if (key) gn_stats_kernel<T, 1, true><<<blocks, 256, 0, st>>>(X, stats, p.C, p.F, p.P, p.G, eps, key, partial);
+    else gn_stats_kernel<T, 1><<<blocks, 256, 0, st>>>(X, stats, p.C, p.F, p.P, p.G, eps);
+  }
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+
 template <typename T>
 static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
-                           si_tensor5* out, char* ws, hipStream_t st) {
+                           si_tensor5* out, char* ws, hipStream_t st, bool stats_done = false) {
   const T* X = static_cast<const T*>(x->ptr);
   T* OUT = static_cast<T*>(out->ptr);
   float* stats = reinterpret_cast<float*>(ws + p.off_stats);
@@ -414,16 +436,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       SI_CHECK_LAUNCH();
     }
   }
-  {
-    StageScope scope("gn_stats", st);
-    constexpr int VEC = 16 / sizeof(T);
-    const unsigned blocks = (unsigned)(p.B * p.F * p.G);
-    if (p.P % VEC == 0)
-      gn_stats_kernel<T, VEC><<<blocks, 256, 0, st>>>(X, stats, C, p.F, p.P, p.G, w->gn_eps);
-    else
-      gn_stats_kernel<T, 1><<<blocks, 256, 0, st>>>(X, stats, C, p.F, p.P, p.G, w->gn_eps);
-    SI_CHECK_LAUNCH();
-  }
+  if (!stats_done) SI_TRY(launch_gn_stats<T>(p, X, nullptr, w->gn_eps, ws, st));
   if (spatial) {
     EpiStore<T> epi{ctxkv, (int64_t)2 * D, nullptr};
     SI_TRY(launch_gemm<T>("ctx_kv", cT(ctx->ptr), (int64_t)p.Cc, wkv2, (int64_t)p.B * p.Mc, 2 * D, p.Cc, epi, st));
@@ -637,10 +650,10 @@ size_t si_live_activation_bytes(const si_tensor5* x, const si_block_weights* w, 
   return p.total_bytes - p.weights_bytes;
 }
 
-si_status si_block_forward(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, si_tensor5* out,
-                           int32_t axis, int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream) {
+// Argument checks shared by the forward entry points; fills the plan.
+static si_status check_forward(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, si_tensor5* out,
+                               int32_t axis, int64_t slice_len, void* workspace, size_t workspace_bytes, si::Plan& p) {
   if (!x || !w || !out) return SI_ERR_NULL;
-  si::Plan p;
   si_status s = si::make_plan(x, w, ctx, axis, slice_len, &p);
   if (s != SI_OK) return s;
   if (out->dtype != x->dtype) return SI_ERR_DTYPE;
@@ -669,11 +682,85 @@ si_status si_block_forward(const si_tensor5* x, const si_block_weights* w, const
   if (si::ranges_overlap(workspace, p.total_bytes, out->ptr, xbytes) ||
       si::ranges_overlap(workspace, p.total_bytes, x->ptr, xbytes))
     return SI_ERR_ARG;
+  return SI_OK;
+}
 
+si_status si_block_forward(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, si_tensor5* out,
+                           int32_t axis, int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream) {
+  si::Plan p;
+  si_status s = check_forward(x, w, ctx, out, axis, slice_len, workspace, workspace_bytes, p);
+  if (s != SI_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
   if (p.dtype == SI_F32) return si::run_block<float>(p, x, w, ctx, out, ws, st);
   return si::run_block<si::bf16>(p, x, w, ctx, out, ws, st);
+}
+
+si_status si_block_forward_rehash(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, si_tensor5* out,
+                                  int32_t axis, int64_t slice_len, void* workspace, size_t workspace_bytes,
+                                  si_rehash_cache* cache, float gamma, void* stream, double* cos_host,
+                                  int32_t* reused_host) {
+  si::Plan p;
+  si_status s = check_forward(x, w, ctx, out, axis, slice_len, workspace, workspace_bytes, p);
+  if (s != SI_OK) return s;
+  if (!cache || !reused_host) return SI_ERR_NULL;
+  if (!cache->x_key || !cache->y_key) return SI_ERR_NULL;
+  if (!si::aligned16(cache->x_key) || !si::aligned16(cache->y_key)) return SI_ERR_ALIGN;
+  if (std::isnan(gamma)) return SI_ERR_ARG;
+  const size_t xbytes = (size_t)p.B * p.C * p.F * (size_t)p.P * p.esize;
+  const void* held[] = {cache->x_key, cache->y_key};
+  for (const void* q : held)
+    if (si::ranges_overlap(q, xbytes, x->ptr, xbytes) || si::ranges_overlap(q, xbytes, out->ptr, xbytes) ||
+        si::ranges_overlap(q, xbytes, workspace, p.total_bytes))
+      return SI_ERR_ARG;
+  if (si::ranges_overlap(cache->x_key, xbytes, cache->y_key, xbytes)) return SI_ERR_ARG;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  double cosv = std::nan("");
+  bool stats_done = false;
+  if (cache->valid) {
+    // the statistics pass doubles as the similarity pass: x is read once for both
+    s = p.dtype == SI_F32
+            ? si::launch_gn_stats<float>(p, static_cast<const float*>(x->ptr), static_cast<const float*>(cache->x_key),
+                                         w->gn_eps, ws, st)
+            : si::launch_gn_stats<si::bf16>(p, static_cast<const si::bf16*>(x->ptr),
+                                            static_cast<const si::bf16*>(cache->x_key), w->gn_eps, ws, st);
+    if (s != SI_OK) return s;
+    const int blocks = p.B * p.F * p.G;
+    double* partial = reinterpret_cast<double*>(ws + p.off_rehash);
+    double* res = partial + (size_t)blocks * 3;
+    {
+      si::StageScope scope("cosine_finish", st);
+      si::cosine_finish_kernel<<<1, si::kCosBlock, 0, st>>>(partial, blocks, (double)gamma, res,
+                                                            reinterpret_cast<int*>(res + 1));
+      if (hipGetLastError() != hipSuccess) return SI_ERR_HIP;
+    }
+    struct { double c; int32_t d; int32_t pad; } host;
+    if (hipMemcpyAsync(&host, res, 16, hipMemcpyDeviceToHost, st) != hipSuccess) return SI_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return SI_ERR_HIP;
+    cosv = host.c;
+    stats_done = true;
+    if (host.d) {  // similar enough: hand the cached output back, nothing else runs
+      si::StageScope scope("cache_handback", st);
+      if (hipMemcpyAsync(out->ptr, cache->y_key, xbytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SI_ERR_HIP;
+      if (cos_host) *cos_host = cosv;
+      *reused_host = 1;
+      return SI_OK;
+    }
+  }
+  s = p.dtype == SI_F32 ? si::run_block<float>(p, x, w, ctx, out, ws, st, stats_done)
+                        : si::run_block<si::bf16>(p, x, w, ctx, out, ws, st, stats_done);
+  if (s != SI_OK) return s;
+  {
+    si::StageScope scope("cache_update", st);
+    if (hipMemcpyAsync(cache->x_key, x->ptr, xbytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SI_ERR_HIP;
+    if (hipMemcpyAsync(cache->y_key, out->ptr, xbytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SI_ERR_HIP;
+  }
+  cache->valid = 1;
+  if (cos_host) *cos_host = cosv;
+  *reused_host = 0;
+  return SI_OK;
 }
 
 static int rehash_blocks(int64_t n) {

@@ -83,12 +83,37 @@ def test_argument_validation_returns_codes_without_touching_the_gpu():
     assert si.lib().si_block_forward(None, None, None, None, 3, 1, None, 0, None) == 1
 
 
+def test_forward_rehash_validation():
+    x, w, _, out = _descs()
+    lib = si.lib()
+    fake = 0x10000
+    reused, cos = C.c_int32(-1), C.c_double()
+
+    def call(cache, gamma=0.95, xd=x, reused_p=C.byref(reused)):
+        return lib.si_block_forward_rehash(C.byref(xd), C.byref(w), None, C.byref(out), B.SI_AXIS_HW, 4,
+                                           0x7000000000, 1 << 40, cache, gamma, None, C.byref(cos), reused_p)
+
+    good = B._RehashCache(fake + (4 << 30), fake + (5 << 30), 0)
+    assert call(None) == 1                                             # no cache
+    assert call(C.byref(good), reused_p=None) == 1                     # no place for the decision
+    assert call(C.byref(B._RehashCache(None, fake + (5 << 30), 0))) == 1
+    assert call(C.byref(B._RehashCache(fake + (4 << 30) + 4, fake + (5 << 30), 0))) == 5
+    assert call(C.byref(good), gamma=float("nan")) == 7
+    assert call(C.byref(B._RehashCache(x.ptr, fake + (5 << 30), 0))) == 7              # anchor aliases x
+    assert call(C.byref(B._RehashCache(fake + (4 << 30), out.ptr + 256, 0))) == 7      # anchor aliases out
+    assert call(C.byref(B._RehashCache(fake + (4 << 30), fake + (4 << 30) + 1024, 0))) == 7  # anchors overlap
+    assert call(C.byref(B._RehashCache(0x7000000000 + 4096, fake + (5 << 30), 0))) == 7      # inside the workspace
+    bad = B._Tensor5(x.ptr, 5, 2, 64, 4, 8, 8)
+    assert call(C.byref(good), xd=bad) == 3                            # the forward's own checks come first
+    assert reused.value == -1 and good.valid == 0                      # nothing was decided or enqueued
+
+
 def test_workspace_scales_with_the_slice():
     x, w, _, _ = _descs(Cn=320, heads=8, dh=40, groups=32, F=16, H=64, W=64)
     lib = si.lib()
     full = lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 4096)
     quarter = lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 1024)
-    assert 0 < quarter < full and quarter / full < 0.2502
+    assert 0 < quarter < full and quarter / full < 0.2505
     assert lib.si_workspace_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 1024) > quarter
     # slice_len beyond the extent behaves as unsliced
     assert lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 10**9) == full
