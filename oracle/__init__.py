@@ -20,3 +20,6 @@ from .rehash_ref import (  # noqa: F401
     cosine_terms_ref, cosine_ref, rehash_decision_ref, key_step_search_ref, rehash_replay_ref,
     rehash_causal_ref,
 )
+from .resblock_ref import (  # noqa: F401
+    silu_ref, conv3x3_ref, resblock_forward_ref, sliced_resblock_forward_ref,
+)

@@ -195,3 +195,75 @@ def cfg5_step_input(prev: np.ndarray, t: int, dtype: str = "bf16") -> np.ndarray
 def scaled(spec: BlockSpec, **kw) -> BlockSpec:
     """A copy of `spec` with some fields replaced (small parity shapes)."""
     return dataclasses.replace(spec, **kw)
+
+
+# ----------------------------------------------------------------------------- Spatial ResBlock group
+
+@dataclasses.dataclass(frozen=True)
+class ResSpec:
+    """Shape of one Spatial ResBlock workload (GroupNorm, SiLU, 3x3 convolutions, identity skip)."""
+    name: str
+    dtype: str
+    B: int
+    C: int
+    F: int
+    H: int
+    W: int
+    temb_dim: int = 0        # 0: no timestep-embedding term
+    gn_groups: int = 32
+    gn_eps: float = 1e-6
+    slice_len: int = 1       # frames per slice
+    seed: int = 0
+
+    @property
+    def tokens(self) -> int:
+        return self.B * self.F * self.H * self.W
+
+    def flops(self) -> float:
+        """Two 3x3 convolutions as dense contractions (2 * positions * 9 * C * C each, padding taps
+        counted) plus the embedding projection; norms and SiLU are not counted."""
+        return 2.0 * 2.0 * self.tokens * 9 * self.C * self.C + 2.0 * self.B * self.temb_dim * self.C
+
+
+RES_CONFIGS: Dict[str, ResSpec] = {
+    # SVD-XT-shaped first-level ResBlock: the feature of cfg4, one frame per slice
+    "res4": ResSpec("res4", "bf16", 2, 320, 25, 72, 128, temb_dim=1280, slice_len=1, seed=7000),
+    # deeper level, smaller map: C = 640 at 36 x 64, two frames per slice
+    "res4b": ResSpec("res4b", "bf16", 2, 640, 25, 36, 64, temb_dim=1280, slice_len=2, seed=7100),
+    # small case the oracle finishes in seconds; map sizes that are no multiple of any tile
+    "res1": ResSpec("res1", "bf16", 2, 64, 3, 10, 12, temb_dim=32, slice_len=2, seed=7200),
+}
+
+
+def res_weight_shapes(spec: ResSpec) -> Dict[str, tuple]:
+    C = spec.C
+    shapes = {"gn1_g": (C,), "gn1_b": (C,), "w_conv1": (C, C, 3, 3), "b_conv1": (C,),
+              "gn2_g": (C,), "gn2_b": (C,), "w_conv2": (C, C, 3, 3), "b_conv2": (C,)}
+    if spec.temb_dim:
+        shapes.update({"w_temb": (spec.temb_dim, C), "b_temb": (C,)})
+    return shapes
+
+
+def make_res_weights(spec: ResSpec, seed: Optional[int] = None, *, randomize_affine: bool = False,
+                     kernel_std: float = 0.02) -> Dict[str, np.ndarray]:
+    """Kernels and W_t ~ N(0, kernel_std^2); biases 0, gains 1, shifts 0 unless `randomize_affine`
+    (gains ~ N(1, 0.1^2), shifts and biases ~ N(0, 0.1^2))."""
+    seed = spec.seed if seed is None else seed
+    out: Dict[str, np.ndarray] = {}
+    for k, (name, shape) in enumerate(res_weight_shapes(spec).items()):
+        s = seed + 2 + k
+        if len(shape) >= 2:
+            out[name] = _normal(s, shape, kernel_std, spec.dtype)
+        elif name.endswith("_g"):
+            out[name] = (round_to_storage(1.0 + _normal(s, shape, 0.1, "f32"), spec.dtype) if randomize_affine
+                         else np.ones(shape, np.float32))
+        else:
+            out[name] = _normal(s, shape, 0.1, spec.dtype) if randomize_affine else np.zeros(shape, np.float32)
+    return out
+
+
+def make_temb(spec: ResSpec, seed: Optional[int] = None) -> Optional[np.ndarray]:
+    if not spec.temb_dim:
+        return None
+    seed = spec.seed if seed is None else seed
+    return _normal(seed + 1, (spec.B, spec.temb_dim), 1.0, spec.dtype)

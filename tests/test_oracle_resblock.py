@@ -1,0 +1,152 @@
+"""Pins for the Spatial ResBlock oracle: the convolution against brute force, a library routine and
+closed-form kernels; SiLU identities; the block against an independent composition of library
+operators; exact slicing invariance along frames (Eq. 1)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import si_workloads as wl
+
+
+def _brute_conv(a, w, b):
+    N, C, H, W = a.shape
+    O = w.shape[0]
+    out = np.zeros((N, O, H, W))
+    for n in range(N):
+        for o in range(O):
+            for y in range(H):
+                for x in range(W):
+                    s = b[o]
+                    for c in range(C):
+                        for i in range(3):
+                            for j in range(3):
+                                yy, xx = y + i - 1, x + j - 1
+                                if 0 <= yy < H and 0 <= xx < W:
+                                    s += w[o, c, i, j] * a[n, c, yy, xx]
+                    out[n, o, y, x] = s
+    return out
+
+
+def test_conv_matches_brute_force():
+    rng = np.random.default_rng(0)
+    a = rng.standard_normal((2, 3, 5, 4)); w = rng.standard_normal((4, 3, 3, 3)); b = rng.standard_normal(4)
+    assert np.allclose(oracle.conv3x3_ref(a, w, b), _brute_conv(a, w, b), atol=1e-13)
+
+
+def test_conv_matches_library_correlation():
+    from scipy.signal import correlate2d
+    rng = np.random.default_rng(1)
+    a = rng.standard_normal((1, 2, 7, 9)); w = rng.standard_normal((3, 2, 3, 3))
+    got = oracle.conv3x3_ref(a, w)
+    for o in range(3):
+        want = sum(correlate2d(a[0, c], w[o, c], mode="same", boundary="fill", fillvalue=0.0) for c in range(2))
+        assert np.allclose(got[0, o], want, atol=1e-13)
+
+
+def test_conv_closed_form_kernels():
+    rng = np.random.default_rng(2)
+    a = rng.standard_normal((2, 4, 6, 5))
+    eye = np.zeros((4, 4, 3, 3))
+    eye[np.arange(4), np.arange(4), 1, 1] = 1.0                       # centre tap, identity channel map
+    assert np.array_equal(oracle.conv3x3_ref(a, eye), a)
+    for i in range(3):
+        for j in range(3):                                            # a single tap reads the pixel at (y+i-1, x+j-1)
+            k = np.zeros((4, 4, 3, 3)); k[np.arange(4), np.arange(4), i, j] = 1.0
+            want = np.zeros_like(a)
+            for y in range(6):
+                for x in range(5):
+                    yy, xx = y + i - 1, x + j - 1
+                    if 0 <= yy < 6 and 0 <= xx < 5:
+                        want[:, :, y, x] = a[:, :, yy, xx]
+            assert np.array_equal(oracle.conv3x3_ref(a, k), want), (i, j)
+    ones = np.ones((1, 1, 4, 4)); box = np.ones((1, 1, 3, 3))         # box filter counts the neighbours inside the image
+    cnt = oracle.conv3x3_ref(ones, box)[0, 0]
+    assert cnt[0, 0] == 4 and cnt[0, 1] == 6 and cnt[1, 1] == 9 and cnt[3, 3] == 4
+    # channel mixing is a matrix product at every pixel
+    mix = np.zeros((3, 4, 3, 3)); M = rng.standard_normal((3, 4)); mix[:, :, 1, 1] = M
+    assert np.allclose(oracle.conv3x3_ref(a, mix), np.einsum("oc,nchw->nohw", M, a), atol=1e-14)
+    # linear in input and kernel; bias is added once per output channel
+    w1, w2 = rng.standard_normal((2, 3, 4, 3, 3)); b = rng.standard_normal(3)
+    assert np.allclose(oracle.conv3x3_ref(a, w1 + 2 * w2, b),
+                       oracle.conv3x3_ref(a, w1) + 2 * oracle.conv3x3_ref(a, w2) + b.reshape(1, 3, 1, 1), atol=1e-12)
+
+
+def test_silu_identities():
+    v = np.linspace(-20, 20, 401)
+    s = oracle.silu_ref(v)
+    assert oracle.silu_ref(0.0) == 0.0
+    assert np.allclose(s - oracle.silu_ref(-v), v, atol=1e-13)        # silu(v) - silu(-v) = v
+    assert np.allclose(s, v * 0.5 * (1 + np.tanh(v / 2)), atol=1e-13)  # sigmoid(v) = (1 + tanh(v/2)) / 2
+    assert oracle.silu_ref(40.0) == pytest.approx(40.0, abs=1e-12) and abs(oracle.silu_ref(-40.0)) < 1e-12
+    assert oracle.silu_ref(1.0) == pytest.approx(1 / (1 + math.exp(-1.0)), abs=1e-15)
+    i = np.argmin(s)                                                  # minimum -0.27846 at v = -1.27846
+    assert v[i] == pytest.approx(-1.278, abs=0.06) and s[i] == pytest.approx(-0.27846, abs=1e-3)
+
+
+def _spec(**kw):
+    return wl.scaled(wl.RES_CONFIGS["res1"], **kw)
+
+
+def test_block_matches_library_composition():
+    """Same block from torch's CPU operators in float64 (group_norm, silu, conv2d, linear)."""
+    import torch
+    import torch.nn.functional as Fn
+    spec = _spec()
+    x = wl.make_x(spec).astype(np.float64)
+    w = {k: v.astype(np.float64) for k, v in wl.make_res_weights(spec, randomize_affine=True).items()}
+    temb = wl.make_temb(spec).astype(np.float64)
+    got = oracle.resblock_forward_ref(x, w, spec, temb)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
+    B, C, Fr, H, W = x.shape
+    xf = t(x).permute(0, 2, 1, 3, 4).reshape(B * Fr, C, H, W)
+    h = Fn.conv2d(Fn.silu(Fn.group_norm(xf, spec.gn_groups, t(w["gn1_g"]), t(w["gn1_b"]), spec.gn_eps)),
+                  t(w["w_conv1"]), t(w["b_conv1"]), padding=1)
+    e = Fn.linear(Fn.silu(t(temb)), t(w["w_temb"]).T, t(w["b_temb"]))           # [B, C]
+    h = h + e.repeat_interleave(Fr, dim=0)[:, :, None, None]
+    h = Fn.conv2d(Fn.silu(Fn.group_norm(h, spec.gn_groups, t(w["gn2_g"]), t(w["gn2_b"]), spec.gn_eps)),
+                  t(w["w_conv2"]), t(w["b_conv2"]), padding=1)
+    want = (xf + h).reshape(B, Fr, C, H, W).permute(0, 2, 1, 3, 4).numpy()
+    assert np.allclose(got, want, atol=1e-11)
+    # the embedding term matters and is per batch entry
+    assert not np.allclose(got, oracle.resblock_forward_ref(x, w, spec, None), atol=1e-3)
+
+
+def test_block_special_cases():
+    spec = _spec(temb_dim=0)
+    x = wl.make_x(spec).astype(np.float64)
+    w = wl.make_res_weights(spec, randomize_affine=True)
+    w0 = dict(w); w0["w_conv2"] = np.zeros_like(w["w_conv2"]); w0["b_conv2"] = np.zeros_like(w["b_conv2"])
+    assert np.array_equal(oracle.resblock_forward_ref(x, w0, spec), x)           # dead branch: identity skip only
+    wb = dict(w0); wb["b_conv2"] = np.arange(spec.C, dtype=np.float64)
+    d = oracle.resblock_forward_ref(x, wb, spec) - x
+    assert np.allclose(d, np.arange(spec.C).reshape(1, -1, 1, 1, 1), atol=1e-12)  # bias once per output channel
+    # GroupNorm makes the branch invariant to a positive rescale and a shift of the input
+    y1 = oracle.resblock_forward_ref(x, w, spec) - x
+    x2 = 3.0 * x + 5.0
+    y2 = oracle.resblock_forward_ref(x2, w, spec) - x2
+    assert np.allclose(y1, y2, atol=1e-6)
+
+
+@pytest.mark.parametrize("slice_len", [1, 2, 3, 5])
+def test_slicing_along_frames_is_exact(slice_len):
+    spec = _spec()
+    x = wl.make_x(spec)
+    w = wl.make_res_weights(spec, randomize_affine=True)
+    temb = wl.make_temb(spec)
+    full = oracle.resblock_forward_ref(x, w, spec, temb)
+    sliced = oracle.sliced_resblock_forward_ref(x, w, spec, temb, slice_len)
+    assert np.allclose(sliced, full, atol=1e-12) and not np.isnan(sliced).any()
+
+
+def test_frames_are_independent_and_flop_count():
+    spec = _spec(F=2)
+    x = wl.make_x(spec)
+    w = wl.make_res_weights(spec)
+    full = oracle.resblock_forward_ref(x, w, spec, wl.make_temb(spec))
+    x2 = x.copy(); x2[:, :, 1] += 1.0 + x2[:, :, 1] ** 2              # disturb frame 1 only
+    again = oracle.resblock_forward_ref(x2, w, spec, wl.make_temb(spec))
+    assert np.array_equal(full[:, :, 0], again[:, :, 0]) and not np.allclose(full[:, :, 1], again[:, :, 1])
+    r4 = wl.RES_CONFIGS["res4"]
+    assert r4.flops() == pytest.approx(2 * 2 * 2 * 25 * 9216 * 9 * 320 * 320 + 2 * 2 * 1280 * 320)
