@@ -107,12 +107,124 @@ def cpu_baseline(spec, seconds_target=20.0):
             "host_cpus": len(os.sched_getaffinity(0))}
 
 
+def res_stage_work(spec, stage, M):
+    """Algorithmic work of one launch of a ResBlock stage on a window of M tokens."""
+    C = spec.C
+    if stage in ("conv1", "conv2"):
+        return "flop", 2.0 * M * 9 * C * C
+    if stage == "gn_stats":
+        return "byte", float(spec.tokens * C * 2)
+    if stage == "slice_in":
+        return "byte", 2.0 * M * C * 2
+    if stage == "gn2_stats":
+        return "byte", 4.0 * M * C
+    if stage == "gn2_silu":
+        return "byte", 6.0 * M * C
+    return "none", 0.0
+
+
+def main_resblock(args):
+    """Spatial ResBlock operator group sliced along frames (the second spatial group workload)."""
+    import numpy as np
+    import torch
+    import paper_2411_01171_amd as si
+    import si_workloads as wl
+    from gpu_helpers import device_res_weights, to_dev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    spec = wl.RES_CONFIGS[args.workload]
+    slice_len = args.slice_len or spec.slice_len
+    x_np = wl.make_x(spec)
+    x = to_dev(x_np, spec.dtype)
+    temb_np = wl.make_temb(spec)
+    temb = None if temb_np is None else to_dev(temb_np, spec.dtype)
+    w_np = wl.make_res_weights(spec)
+    wts = device_res_weights(spec, w_np)
+    ws_bytes = si.si_resblock_workspace_bytes(x, wts, slice_len)
+    live_sliced = si.si_resblock_live_activation_bytes(x, wts, slice_len)
+    live_unsliced = si.si_resblock_live_activation_bytes(x, wts, spec.F)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(x)
+
+    def step():
+        si.si_resblock_forward(x, wts, temb, out, slice_len, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops = spec.flops()
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    si.si_stage_timing_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    stages = si.si_stage_timing_read()
+    si.si_stage_timing_enable(False)
+    n_slices = -(-spec.F // slice_len)
+    M_slice = spec.B * min(slice_len, spec.F) * spec.H * spec.W
+    stage_report = {}
+    for name, (ms, cnt) in stages.items():
+        avg_ms = ms / cnt
+        kind, work = res_stage_work(spec, name, M_slice)
+        rec = {"avg_us": round(avg_ms * 1e3, 2), "launches_per_step": cnt / args.steps, "ms_per_step": round(ms / args.steps, 4)}
+        if kind == "flop":
+            rec["TFLOP/s"] = round(work / (avg_ms * 1e-3) / 1e12, 2)
+        elif kind == "byte":
+            rec["GB/s"] = round(work / (avg_ms * 1e-3) / 1e9, 1)
+        stage_report[name] = rec
+    conv_ms = stages["conv1"][0] + stages["conv2"][0]
+    conv_cnt = stages["conv1"][1] + stages["conv2"][1]
+    d_work = res_stage_work(spec, "conv1", M_slice)[1]
+    ach = d_work / (conv_ms / conv_cnt * 1e-3) / 1e12
+    roof = {"bound": "mfma", "kernel": "conv3x3 (conv1 + conv2 launches)", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+            "avg_launch_us": conv_ms / conv_cnt * 1e3, "algorithmic_flop_per_launch": d_work}
+    result = {
+        "metric": "sliced block-forward TFLOP/s (% MFMA peak) + peak live activation bytes vs unsliced",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 operands from bf16 storage, f32 accumulation", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: Spatial ResBlock group x[B={spec.B},C={spec.C},F={spec.F},H={spec.H},W={spec.W}], "
+                               f"embedding width {spec.temb_dim}, sliced along frames in windows of {slice_len} ({n_slices} slices)",
+                   "algorithmic_flop_per_step": flops, "tokens": spec.tokens},
+        "frac_mfma_peak": value / PEAK_BF16_TFLOPS,
+        "live_activation_bytes": {"sliced": live_sliced, "unsliced_same_kernels": live_unsliced,
+                                  "ratio": live_sliced / live_unsliced, "workspace_bytes": ws_bytes,
+                                  "x_bytes": x.numel() * x.element_size()},
+        "roofline": roof,
+        "stages": stage_report,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sub = wl.scaled(spec, F=1)
+        xs = x_np[:, :, :1]
+        t0 = time.perf_counter()
+        oracle.resblock_forward_ref(xs, w_np, sub, temb_np)
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        except Exception:
+            threads = len(os.sched_getaffinity(0))
+        result["cpu_baseline"] = {"value": sub.flops() / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+                                  "sample": f"1 of {spec.F} frames (B={spec.B}); fp64 NumPy; 1 pass in {dt:.1f} s"}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", help="cfg2 (default, the metric's configuration), cfg3, cfg4s, cfg4t, cfg5s, cfg5t")
+    ap.add_argument("--workload", default="cfg2", help="cfg2 (default, the metric's configuration), cfg3, cfg4s, cfg4t, cfg5s, cfg5t; res4, res4b "
+                         "(Spatial ResBlock group)")
     ap.add_argument("--slice-len", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rehash-probe", choices=["reuse", "compute"], default=None,
@@ -127,6 +239,9 @@ def main():
         print("bench.py: this build measures one GPU only (the path shards without changing the kernel; "
               "see DESIGN.md); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload.startswith("res"):
+        return main_resblock(args)
 
     import numpy as np
     import torch

@@ -200,6 +200,44 @@ si_status si_block_forward_rehash(const si_tensor5* x, const si_block_weights* w
                                   size_t workspace_bytes, si_rehash_cache* cache, float gamma, void* stream,
                                   double* cos_host, int32_t* reused_host);
 
+/* Parameters of one Spatial ResBlock operator group (Sec. 4.2.1: the
+ * consecutive GroupNorm, Conv2D and SiLU operators of the Spatial ResBlock
+ * form one spatial group).  Device pointers, dtype of the feature, 16-byte
+ * aligned.  Convolution kernels in [C, C, 3, 3] order (output channel,
+ * input channel, row, column), applied as a cross-correlation with zero
+ * padding 1 and stride 1; w_temb row-major [temb_dim, C].  NULL biases mean
+ * zero, NULL gains / shifts mean one / zero.  w_temb is required iff
+ * temb_dim > 0. */
+typedef struct {
+  int32_t gn_groups;
+  float gn_eps;
+  int32_t temb_dim; /* width of the timestep embedding, 0 = none */
+  const void *gn1_g, *gn1_b, *w_conv1, *b_conv1;
+  const void *w_temb, *b_temb;
+  const void *gn2_g, *gn2_b, *w_conv2, *b_conv2;
+} si_resblock_weights;
+
+/* Workspace bytes of si_resblock_forward, and the activation-derived part of
+ * it (one slice's intermediates plus statistics; the rest is re-laid-out
+ * kernels).  0 if the arguments are invalid.  Host-only. */
+size_t si_resblock_workspace_bytes(const si_tensor5* x, const si_resblock_weights* w, int64_t slice_len);
+size_t si_resblock_live_activation_bytes(const si_tensor5* x, const si_resblock_weights* w, int64_t slice_len);
+
+/* Sliced Spatial ResBlock forward (Sec. 4.1 spatial layers slicer, Sec. 4.2.1, Eq. 1):
+ *   out = x + Conv3x3(SiLU(GN2( Conv3x3(SiLU(GN1(x))) + b1 + e ))) + b2,
+ *   e[b, :] = SiLU(temb[b, :]) w_temb + b_temb  broadcast over frames and positions,
+ * with GroupNorm statistics per (batch, frame, group).  The merged batch x
+ * frame axis is sliced: window i covers frames [i*slice_len, min((i+1)*
+ * slice_len, F)) of every batch entry, goes through the whole group on its
+ * own and is written to its window of `out` (every element of out is
+ * written; out must not overlap x).
+ *   x, out     [B,C,F,H,W] bf16 (SI_ERR_DTYPE otherwise), C a multiple of 32 and of gn_groups
+ *   temb       device [B, temb_dim] or NULL when temb_dim == 0
+ *   workspace  device, >= si_resblock_workspace_bytes(...), 256-byte aligned
+ * Returns SI_ERR_* on invalid arguments (nothing enqueued) or SI_ERR_HIP. */
+si_status si_resblock_forward(const si_tensor5* x, const si_resblock_weights* w, const void* temb, si_tensor5* out,
+                              int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Key-step search, Algorithm 1 (Appendix B).  Host only.
  *   S      host, row-major K x K similarity map; only S[i][anchor] entries are read
  *   gamma  threshold, must satisfy gamma <= 1 and gamma <= S[i][i] where visited

@@ -47,6 +47,14 @@ class _Weights(C.Structure):
                 + [(n, C.c_void_p) for n in WEIGHT_FIELDS])
 
 
+RES_WEIGHT_FIELDS = ("gn1_g", "gn1_b", "w_conv1", "b_conv1", "w_temb", "b_temb", "gn2_g", "gn2_b", "w_conv2", "b_conv2")
+
+
+class _ResWeights(C.Structure):
+    _fields_ = ([("gn_groups", C.c_int32), ("gn_eps", C.c_float), ("temb_dim", C.c_int32)]
+                + [(n, C.c_void_p) for n in RES_WEIGHT_FIELDS])
+
+
 class _RehashCache(C.Structure):
     _fields_ = [("x_key", C.c_void_p), ("y_key", C.c_void_p), ("valid", C.c_int32)]
 
@@ -74,6 +82,12 @@ def lib() -> C.CDLL:
     L.si_block_forward_rehash.restype = i32
     L.si_block_forward_rehash.argtypes = L.si_block_forward.argtypes[:8] + [
         C.POINTER(_RehashCache), C.c_float, vp, C.POINTER(C.c_double), C.POINTER(i32)]
+    L.si_resblock_workspace_bytes.restype = sz
+    L.si_resblock_workspace_bytes.argtypes = [C.POINTER(_Tensor5), C.POINTER(_ResWeights), i64]
+    L.si_resblock_live_activation_bytes.restype = sz
+    L.si_resblock_live_activation_bytes.argtypes = L.si_resblock_workspace_bytes.argtypes
+    L.si_resblock_forward.restype = i32
+    L.si_resblock_forward.argtypes = [C.POINTER(_Tensor5), C.POINTER(_ResWeights), vp, C.POINTER(_Tensor5), i64, vp, sz, vp]
     L.si_rehash_scratch_bytes.restype = sz
     L.si_rehash_scratch_bytes.argtypes = [i64]
     L.si_rehash_check.restype = i32
@@ -180,6 +194,43 @@ def si_block_forward(x, weights: BlockWeights, ctx, out, axis: int, slice_len: i
                                 _stream_ptr(stream))
     if st != 0:
         raise SiError(st, "si_block_forward")
+
+
+class ResBlockWeights:
+    """Device tensors of one Spatial ResBlock and the matching C struct (kept alive by this object)."""
+
+    def __init__(self, gn_groups: int, tensors: Dict[str, object], gn_eps: float = 1e-6, temb_dim: int = 0):
+        self.tensors = dict(tensors)
+        s = _ResWeights()
+        s.gn_groups, s.gn_eps, s.temb_dim = gn_groups, gn_eps, temb_dim
+        for name in RES_WEIGHT_FIELDS:
+            t = self.tensors.get(name)
+            if t is not None and not t.is_contiguous():
+                raise ValueError(f"{name} must be contiguous")
+            setattr(s, name, None if t is None else t.data_ptr())
+        self.struct = s
+
+
+def si_resblock_workspace_bytes(x, weights: ResBlockWeights, slice_len: int) -> int:
+    xd = _tensor5(x)
+    return int(lib().si_resblock_workspace_bytes(C.byref(xd), C.byref(weights.struct), slice_len))
+
+
+def si_resblock_live_activation_bytes(x, weights: ResBlockWeights, slice_len: int) -> int:
+    xd = _tensor5(x)
+    return int(lib().si_resblock_live_activation_bytes(C.byref(xd), C.byref(weights.struct), slice_len))
+
+
+def si_resblock_forward(x, weights: ResBlockWeights, temb, out, slice_len: int, workspace, stream=None) -> None:
+    """Enqueues the sliced Spatial ResBlock forward (frame windows of `slice_len`) on `stream`."""
+    xd, od = _tensor5(x), _tensor5(out)
+    if temb is not None and not temb.is_contiguous():
+        raise ValueError("temb must be contiguous")
+    st = lib().si_resblock_forward(C.byref(xd), C.byref(weights.struct), None if temb is None else temb.data_ptr(),
+                                   C.byref(od), slice_len, workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if st != 0:
+        raise SiError(st, "si_resblock_forward")
 
 
 class RehashCache:

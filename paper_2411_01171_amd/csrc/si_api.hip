@@ -615,6 +615,8 @@ static bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
 
 }  // namespace si
 
+#include "si_resblock_api.h"
+
 // ============================================================================= C ABI
 
 extern "C" {

@@ -1,0 +1,203 @@
+// Host side of the Spatial ResBlock operator group (see include/si.h): argument validation,
+// workspace layout, the slice loop over frame windows and the kernel launches.  Part of the
+// translation unit si_api.hip (uses its stage timing, alignment and overlap helpers).
+#pragma once
+#include "k_conv.h"
+
+namespace si {
+
+struct ResPlan {
+  int B, C, F, H, W, G, Kt;
+  int64_t P, slice_len, Mmax;
+  int lanes;           // frame windows in flight (two streams) when there are many small ones
+  size_t lane_stride;
+  size_t off_stats, off_emb, off_a, off_h, off_stats2, off_w1, off_w2;
+  size_t weights_bytes, total_bytes;
+};
+
+static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w, int64_t slice_len, ResPlan* p) {
+  if (!x || !w) return SI_ERR_NULL;
+  if (x->dtype != SI_BF16) return SI_ERR_DTYPE;
+  if (x->B < 1 || x->C < 1 || x->F < 1 || x->H < 1 || x->W < 1) return SI_ERR_SHAPE;
+  if (w->gn_groups < 1 || x->C % w->gn_groups || x->C % 32 || x->C > 8192) return SI_ERR_SHAPE;
+  const int64_t P = x->H * x->W;
+  if (x->B > 65535 || x->F > 65535 || x->H > 4096 || x->W > 4096) return SI_ERR_SHAPE;
+  if ((double)x->B * x->C * x->F * (double)P >= 1099511627776.0) return SI_ERR_SHAPE;
+  if ((int64_t)(x->C / w->gn_groups) * P >= (1LL << 31)) return SI_ERR_SHAPE;
+  if (!(w->gn_eps >= 0.f)) return SI_ERR_ARG;
+  if (w->temb_dim < 0 || w->temb_dim > 65536) return SI_ERR_SHAPE;
+  if (slice_len < 1) return SI_ERR_SLICE;
+  p->B = (int)x->B; p->C = (int)x->C; p->F = (int)x->F; p->H = (int)x->H; p->W = (int)x->W;
+  p->G = w->gn_groups; p->Kt = w->temb_dim; p->P = P;
+  p->slice_len = slice_len < x->F ? slice_len : x->F;
+  p->Mmax = (int64_t)x->B * p->slice_len * P;
+  if (p->Mmax >= (1LL << 31) / 16) return SI_ERR_SHAPE;
+  const size_t C = (size_t)p->C;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  p->off_stats = take((size_t)p->B * p->F * p->G * 2 * sizeof(float));
+  p->off_emb = take((size_t)p->B * C * sizeof(float));
+  // one window's intermediates: the fp16 operand of either convolution, the fp32 output of the first
+  // one, the second GroupNorm's statistics
+  p->off_a = take((size_t)p->Mmax * C * 2);
+  p->off_h = take((size_t)p->Mmax * C * sizeof(float));
+  p->off_stats2 = take((size_t)p->B * p->slice_len * p->G * 2 * sizeof(float));
+  const int64_t n_slices = (p->F + p->slice_len - 1) / p->slice_len;
+  p->lanes = n_slices >= 8 ? 2 : 1;  // two windows' buffers still stay within a quarter of the unsliced ones
+  p->lane_stride = off - p->off_a;
+  if (p->lanes == 2) take(p->lane_stride);
+  const size_t act_end = off;
+  p->off_w1 = take(9 * C * C * 2);
+  p->off_w2 = take(9 * C * C * 2);
+  p->weights_bytes = off - act_end;
+  p->total_bytes = off;
+  return SI_OK;
+}
+
+template <class Epi>
+static si_status launch_conv3x3(const char* stage, const _Float16* A, const _Float16* Wp, int64_t M, int C, int H, int W, Epi epi,
+                                hipStream_t st) {
+  StageScope scope(stage, st);
+  if (C % 64 == 0) {
+    dim3 grid((unsigned)((M + 127) / 128), (unsigned)((C + 127) / 128));
+    conv3x3_f16_kernel<128, 128, 2, 2, Epi, 64><<<grid, 256, 0, st>>>(A, Wp, M, C, C, H, W, epi);
+  } else {
+    dim3 grid((unsigned)((M + 127) / 128), (unsigned)((C + 127) / 128));
+    conv3x3_f16_kernel<128, 128, 2, 2, Epi, 32><<<grid, 256, 0, st>>>(A, Wp, M, C, C, H, W, epi);
+  }
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+
+static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_resblock_weights* w, const void* temb,
+                              si_tensor5* out, char* ws, hipStream_t st0) {
+  const bf16* X = static_cast<const bf16*>(x->ptr);
+  bf16* OUT = static_cast<bf16*>(out->ptr);
+  float* stats = reinterpret_cast<float*>(ws + p.off_stats);
+  float* emb = p.Kt ? reinterpret_cast<float*>(ws + p.off_emb) : nullptr;
+  _Float16* w1 = reinterpret_cast<_Float16*>(ws + p.off_w1);
+  _Float16* w2 = reinterpret_cast<_Float16*>(ws + p.off_w2);
+  const int C = p.C;
+  auto cB = [](const void* q) { return static_cast<const bf16*>(q); };
+
+  // ---- once per call: kernel re-layout, embedding projection, first GroupNorm's statistics
+  {
+    StageScope scope("pack_weights", st0);
+    const unsigned blocks = (unsigned)(((int64_t)9 * C * C + 255) / 256);
+    pack_conv_kernel<<<blocks, 256, 0, st0>>>(cB(w->w_conv1), w1, C, C);
+    SI_CHECK_LAUNCH();
+    pack_conv_kernel<<<blocks, 256, 0, st0>>>(cB(w->w_conv2), w2, C, C);
+    SI_CHECK_LAUNCH();
+    if (emb) {
+      temb_proj_kernel<<<dim3((unsigned)((C + 255) / 256), (unsigned)p.B), 256, 0, st0>>>(cB(temb), cB(w->w_temb),
+                                                                                          cB(w->b_temb), emb, p.Kt, C);
+      SI_CHECK_LAUNCH();
+    }
+  }
+  {
+    StageScope scope("gn_stats", st0);
+    const unsigned blocks = (unsigned)(p.B * p.F * p.G);
+    if (p.P % 8 == 0) gn_stats_kernel<bf16, 8><<<blocks, 256, 0, st0>>>(X, stats, C, p.F, p.P, p.G, w->gn_eps);
+    else gn_stats_kernel<bf16, 1><<<blocks, 256, 0, st0>>>(X, stats, C, p.F, p.P, p.G, w->gn_eps);
+    SI_CHECK_LAUNCH();
+  }
+
+  AuxStream* aux = nullptr;
+  if (p.lanes == 2) {
+    SI_TRY(aux_stream(&aux));
+    if (hipEventRecord(aux->fork, st0) != hipSuccess) return SI_ERR_HIP;
+    if (hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
+  }
+
+  // ---- the frame windows (Sec. 4.1): each goes through the whole group and lands in its window of out
+  int widx = 0;
+  for (int64_t f0 = 0; f0 < p.F; f0 += p.slice_len, ++widx) {
+    const int lane_id = p.lanes == 2 ? widx & 1 : 0;
+    hipStream_t st = lane_id ? aux->stream : st0;
+    char* lane_ws = ws + (size_t)lane_id * p.lane_stride;
+    _Float16* a = reinterpret_cast<_Float16*>(lane_ws + p.off_a);
+    float* h = reinterpret_cast<float*>(lane_ws + p.off_h);
+    float* stats2 = reinterpret_cast<float*>(lane_ws + p.off_stats2);
+    const int Fw = (int)((f0 + p.slice_len <= p.F) ? p.slice_len : p.F - f0);
+    const int64_t M = (int64_t)p.B * Fw * p.P;
+    Window win{p.B, C, p.F, p.P, (int)f0, Fw, 0, (int)p.P, p.G};
+    {
+      StageScope scope("slice_in", st);
+      dim3 grid((unsigned)((p.P + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * Fw));
+      window_to_tokens_kernel<bf16, true><<<grid, 256, 0, st>>>(X, stats, cB(w->gn1_g), cB(w->gn1_b),
+                                                                reinterpret_cast<bf16*>(a), win);
+      SI_CHECK_LAUNCH();
+    }
+    {
+      EpiConvEmb epi{h, (int64_t)C, cB(w->b_conv1), emb, (int64_t)Fw * p.P};
+      SI_TRY(launch_conv3x3("conv1", a, w1, M, C, p.H, p.W, epi, st));
+    }
+    {
+      StageScope scope("gn2_stats", st);
+      gn_stats_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(h, stats2, (int)p.P, C, p.G, w->gn_eps);
+      SI_CHECK_LAUNCH();
+    }
+    {
+      StageScope scope("gn2_silu", st);
+      const int64_t n = M * (C / 4);
+      gn_silu_tokens_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(h, stats2, cB(w->gn2_g), cB(w->gn2_b), a, M, (int)p.P,
+                                                                         C, p.G);
+      SI_CHECK_LAUNCH();
+    }
+    {
+      EpiSliceOut<bf16> epi{X, OUT, cB(w->b_conv2), win};
+      SI_TRY(launch_conv3x3("conv2", a, w2, M, C, p.H, p.W, epi, st));
+    }
+  }
+  if (p.lanes == 2) {
+    if (hipEventRecord(aux->join, aux->stream) != hipSuccess) return SI_ERR_HIP;
+    if (hipStreamWaitEvent(st0, aux->join, 0) != hipSuccess) return SI_ERR_HIP;
+  }
+  return SI_OK;
+}
+
+}  // namespace si
+
+extern "C" {
+
+size_t si_resblock_workspace_bytes(const si_tensor5* x, const si_resblock_weights* w, int64_t slice_len) {
+  si::ResPlan p;
+  if (si::make_res_plan(x, w, slice_len, &p) != SI_OK) return 0;
+  return p.total_bytes;
+}
+
+size_t si_resblock_live_activation_bytes(const si_tensor5* x, const si_resblock_weights* w, int64_t slice_len) {
+  si::ResPlan p;
+  if (si::make_res_plan(x, w, slice_len, &p) != SI_OK) return 0;
+  return p.total_bytes - p.weights_bytes;
+}
+
+si_status si_resblock_forward(const si_tensor5* x, const si_resblock_weights* w, const void* temb, si_tensor5* out,
+                              int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || !w || !out) return SI_ERR_NULL;
+  si::ResPlan p;
+  si_status s = si::make_res_plan(x, w, slice_len, &p);
+  if (s != SI_OK) return s;
+  if (out->dtype != x->dtype) return SI_ERR_DTYPE;
+  if (out->B != x->B || out->C != x->C || out->F != x->F || out->H != x->H || out->W != x->W) return SI_ERR_SHAPE;
+  if (!x->ptr || !out->ptr || !workspace || !w->w_conv1 || !w->w_conv2) return SI_ERR_NULL;
+  if (p.Kt > 0 && (!temb || !w->w_temb)) return SI_ERR_NULL;
+  const void* all[] = {x->ptr, out->ptr, temb, w->gn1_g, w->gn1_b, w->w_conv1, w->b_conv1, w->w_temb, w->b_temb,
+                       w->gn2_g, w->gn2_b, w->w_conv2, w->b_conv2};
+  for (const void* q : all)
+    if (q && !si::aligned16(q)) return SI_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SI_ERR_ALIGN;
+  if (workspace_bytes < p.total_bytes) return SI_ERR_WORKSPACE;
+  const size_t xbytes = (size_t)p.B * p.C * p.F * (size_t)p.P * 2;
+  if (si::ranges_overlap(x->ptr, xbytes, out->ptr, xbytes)) return SI_ERR_ARG;
+  if (si::ranges_overlap(workspace, p.total_bytes, out->ptr, xbytes) ||
+      si::ranges_overlap(workspace, p.total_bytes, x->ptr, xbytes))
+    return SI_ERR_ARG;
+  return si::run_resblock(p, x, w, temb, out, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -50,3 +50,22 @@ def errors(out: np.ndarray, ref: np.ndarray, x: np.ndarray):
         "rel_l2_branch": float(np.linalg.norm(d) / max(np.linalg.norm(branch), 1e-300)),
         "max_ref": float(np.max(np.abs(ref))),
     }
+
+
+def device_res_weights(spec: wl.ResSpec, w: dict) -> si.ResBlockWeights:
+    tensors = {k: to_dev(v, spec.dtype) for k, v in w.items()}
+    return si.ResBlockWeights(spec.gn_groups, tensors, gn_eps=spec.gn_eps, temb_dim=spec.temb_dim)
+
+
+def run_resblock(spec: wl.ResSpec, x: np.ndarray, w: dict, temb, slice_len=None) -> np.ndarray:
+    xd = to_dev(x, spec.dtype)
+    td = None if temb is None else to_dev(temb, spec.dtype)
+    wd = device_res_weights(spec, w)
+    sl = spec.slice_len if slice_len is None else slice_len
+    nbytes = si.si_resblock_workspace_bytes(xd, wd, sl)
+    assert nbytes > 0, "si_resblock_workspace_bytes rejected the arguments"
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    out = torch.full_like(xd, float("nan"))
+    si.si_resblock_forward(xd, wd, td, out, sl, ws)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64)

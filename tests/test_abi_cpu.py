@@ -108,6 +108,39 @@ def test_forward_rehash_validation():
     assert reused.value == -1 and good.valid == 0                      # nothing was decided or enqueued
 
 
+def test_resblock_validation_and_workspace():
+    lib = si.lib()
+    fake = 0x10000
+    x = B._Tensor5(fake, B.SI_BF16, 2, 64, 8, 6, 6)
+    out = B._Tensor5(fake + (1 << 30), B.SI_BF16, 2, 64, 8, 6, 6)
+    w = B._ResWeights()
+    w.gn_groups, w.gn_eps, w.temb_dim = 32, 1e-6, 16
+    for name in B.RES_WEIGHT_FIELDS:
+        setattr(w, name, fake + (2 << 30))
+
+    def call(xd=x, od=out, wd=w, temb=fake + (3 << 30), slice_len=1, ws=0x7000000000, ws_bytes=1 << 40):
+        return lib.si_resblock_forward(C.byref(xd), C.byref(wd), temb, C.byref(od), slice_len, ws, ws_bytes, None)
+
+    assert lib.si_resblock_workspace_bytes(C.byref(x), C.byref(w), 1) > 0
+    assert call(slice_len=0) == 4
+    assert call(temb=None) == 1                                         # embedding width > 0 needs temb
+    assert call(xd=B._Tensor5(fake, B.SI_F32, 2, 64, 8, 6, 6)) == 3     # bf16 features only
+    assert call(xd=B._Tensor5(fake, B.SI_BF16, 2, 48, 8, 6, 6), od=B._Tensor5(out.ptr, B.SI_BF16, 2, 48, 8, 6, 6)) == 2
+    assert call(od=B._Tensor5(out.ptr, B.SI_BF16, 2, 64, 8, 6, 7)) == 2
+    assert call(od=B._Tensor5(x.ptr + 1024, B.SI_BF16, 2, 64, 8, 6, 6)) == 7
+    assert call(xd=B._Tensor5(fake + 2, B.SI_BF16, 2, 64, 8, 6, 6)) == 5
+    assert call(ws_bytes=4096) == 6
+    w2 = B._ResWeights.from_buffer_copy(w); w2.w_conv2 = None
+    assert call(wd=w2) == 1
+    w3 = B._ResWeights.from_buffer_copy(w); w3.gn_groups = 5
+    assert call(wd=w3) == 2
+    # live bytes follow the window: 8 frames in windows of 1 run two at a time and still stay within a quarter
+    live1 = lib.si_resblock_live_activation_bytes(C.byref(x), C.byref(w), 1)
+    live8 = lib.si_resblock_live_activation_bytes(C.byref(x), C.byref(w), 8)
+    assert 0 < live1 < live8 and live1 / live8 < 0.27
+    assert lib.si_resblock_live_activation_bytes(C.byref(x), C.byref(w), 100) == live8
+
+
 def test_workspace_scales_with_the_slice():
     x, w, _, _ = _descs(Cn=320, heads=8, dh=40, groups=32, F=16, H=64, W=64)
     lib = si.lib()
