@@ -231,7 +231,7 @@ size_t si_resblock_live_activation_bytes(const si_tensor5* x, const si_resblock_
  * slice_len, F)) of every batch entry, goes through the whole group on its
  * own and is written to its window of `out` (every element of out is
  * written; out must not overlap x).
- *   x, out     [B,C,F,H,W] bf16 (SI_ERR_DTYPE otherwise), C a multiple of 32 and of gn_groups
+ *   x, out     [B,C,F,H,W] bf16 (SI_ERR_DTYPE otherwise), C a multiple of 32 and of gn_groups, C / gn_groups <= 64
  *   temb       device [B, temb_dim] or NULL when temb_dim == 0
  *   workspace  device, >= si_resblock_workspace_bytes(...), 256-byte aligned
  * Returns SI_ERR_* on invalid arguments (nothing enqueued) or SI_ERR_HIP. */
@@ -246,9 +246,11 @@ si_status si_resblock_forward(const si_tensor5* x, const si_resblock_weights* w,
  * a visited diagonal entry below gamma). */
 int32_t si_key_step_search(const float* S, int32_t K, float gamma, int32_t* G_out);
 
-/* Optional per-stage timing for measurement.  When enabled, si_block_forward
- * and si_rehash_check record a HIP event pair around every kernel launch on
- * the caller's stream (this serialises nothing but adds event overhead).
+/* Optional per-stage timing for measurement.  When enabled, the forward entry
+ * points and si_rehash_check record a HIP event pair around every kernel
+ * launch, and windows that would otherwise run two at a time on two streams
+ * run one after the other on the caller's stream, so that each pair brackets
+ * one kernel alone on the GPU (event overhead is added; results are the same).
  * si_stage_timing_read waits for the recorded events, adds each pair's
  * duration to its stage, writes up to `cap` entries (stage name, total
  * milliseconds, launches) and clears the record.  Returns the number of stages,

@@ -4,12 +4,15 @@
 // bits keep the operand rounding of two chained 9*C-term contractions well inside the error budget
 // that the final bf16 rounding of x + branch leaves.  bf16 kernels convert exactly unless a value
 // lies outside fp16's normal range (|w| < 6.1e-5 rounds to a multiple of 2^-24, |w| > 65504 overflows).
-//   conv3x3_f16_kernel     3x3 convolution (zero padding 1, stride 1) as an implicit GEMM on the
-//                           matrix cores over a token-major activation [M, C]               [MFMA bound]
-//   pack_conv_kernel        [O, C, 3, 3] bf16 kernel -> fp16 [O, 9*C] with k = tap*C + c (k contiguous)
+//   conv3x3_dma_kernel      3x3 convolution (zero padding 1, stride 1) as an implicit GEMM on the
+//                           matrix cores; both operands arrive in MFMA fragment order by direct
+//                           global->LDS loads through a multi-stage ring                     [MFMA bound]
+//   pack_conv_kernel        [O, C, 3, 3] bf16 kernel -> fp16 fragment stream in the order the kernel reads
 //   temb_proj_kernel        e[b, o] = b_t[o] + sum_k SiLU(temb[b, k]) * W_t[k, o]
-//   gn_stats_tokens_kernel  GroupNorm statistics of a token-major fp32 feature per (image, group)
-//   gn_silu_tokens_kernel   SiLU(GroupNorm(h)) -> fp16 operand, token-major                  [HBM bound]
+//   gn_partial_tokens_kernel + gn_finish_tokens_kernel
+//                           GroupNorm statistics of a token-major fp32 feature per (image, group)
+//   gn_silu_tokens_kernel   SiLU(GroupNorm(h)) -> fp16 operand in fragment order             [HBM bound]
+//   window_to_tokens_silu_kernel  slice window -> SiLU(GroupNorm1) -> fp16 operand in fragment order
 #pragma once
 #include "si_common.h"
 #include "k_gemm.h"
@@ -20,70 +23,107 @@ typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ float silu(float v) { return v / (1.f + __expf(-v)); }
 
-// acc[m, o] = sum_{tap, c} A[m + dy*W + dx, c] * Wp[o, tap*C + c] over the taps whose source pixel
-// lies inside the image (tap = 3*(dy+1) + (dx+1)); token m = img*H*W + y*W + x, A row stride C.
-// Same block structure as gemm_bf16_kernel (weights as the MFMA row operand, tokens as columns, so a
-// lane holds 4 consecutive output channels of one token); the activation loader shifts its rows by
-// the tap's offset and zero-fills rows that fall outside the image.  C % BK == 0.
-template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi, int BK>
-__global__ __launch_bounds__(256) void conv3x3_f16_kernel(const _Float16* __restrict__ A, const _Float16* __restrict__ Wp,
-                                                           int64_t M, int C, int O, int H, int W, Epi epi) {
-  static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per block");
-  constexpr int LDK = BK + 8, CPR = BK / 8;
-  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
-  constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int A_CHUNKS = BM * CPR / 256, W_CHUNKS = (BN * CPR + 255) / 256;
-  static_assert(WM % 32 == 0 && WN % 32 == 0 && A_CHUNKS >= 1, "tile shape");
+// Fragment order.  One fragment = 1 KiB = the 64 lanes' 16-byte operands of one
+// v_mfma_f32_32x32x16_f16: lane l holds row l % 32 and the eight k-values 8*(l/32) .. +7.
+//   activation  act_granule(t, c8): the 16 bytes (channels 8*c8 .. +7) of token t; fragments are
+//               (32-token block, 16-channel step) pairs, 16-channel steps fastest.  The buffer starts
+//               with a 256-byte block of zeros (what a tap outside the image reads).
+//   weights     per (column tile, k-tile of 32 input channels of one tap): 2 k-steps x TN fragments,
+//               rows = output channels; k-tiles ordered tap-major (tap = 3*(dy+1) + dx+1).
+constexpr int kActZeroBytes = 256;
+__host__ __device__ __forceinline__ int64_t act_granule(int64_t t, int c8, int C) {
+  return ((t >> 5) * (C / 16) + (c8 >> 1)) * 64 + (c8 & 1) * 32 + (t & 31);
+}
 
-  __shared__ __attribute__((aligned(16))) unsigned short As[2][BM][LDK];
-  __shared__ __attribute__((aligned(16))) unsigned short Ws[2][BN][LDK];
+struct ConvArgs {
+  const char* act;  // zero block + fragment-ordered fp16 activation of the window
+  const char* wf;   // fragment-ordered fp16 kernel
+  int64_t M;        // tokens of the window; token m = img*H*W + y*W + x
+  int C, O, H, W;
+  int ncol, ntiles;  // column tiles, row tiles * column tiles
+};
 
-  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-  const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
-  const int64_t m0 = (int64_t)blockIdx.x * BM;
-  const int n0 = blockIdx.y * BN;
-  const int K = 9 * C;
-  const int P = H * W;
+// acc[m, o] = sum_{tap, c} a[m + dy*W + dx, c] * w[o, c, tap] over the taps whose source pixel lies
+// inside the image.  Block = 4 wavefronts stacked along tokens; a wavefront owns TM*32 tokens x
+// TN*32 output channels (weights as the MFMA row operand, tokens as columns: a lane ends up with 4
+// consecutive output channels of one token, as in gemm_bf16_kernel).  A stage of the ring holds one
+// k-tile (32 input channels of one tap): the wavefronts' activation fragments, gathered with the
+// tap's shift by per-lane addresses, then the column tile's weight fragments.  Every wavefront
+// issues the same number of loads per stage (a padding load repeats the wavefront's first weight
+// fragment: same source, same destination) so that one s_waitcnt immediate closes a stage; stages
+// beyond the last k-tile read the zero block into a slot nobody reads any more.  The loads are inline assembly (the compiler would otherwise wait for all of them
+// before every LDS read); no compiler-visible vector-memory load sits inside the k loop.
+template <int TM, int TN, int STAGES, class Epi>
+__global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi) {
+  constexpr int AF = 4 * TM * 2, WFR = 2 * TN;           // fragments per stage
+  constexpr int NW = (WFR + 3) / 4;                      // weight loads per wavefront per stage
+  constexpr int PER = 2 * TM + NW;                       // loads per wavefront per stage
+  constexpr int SLOT = (AF + WFR) * 1024;
+  static_assert((STAGES - 2) * PER <= 63, "vmcnt range");
+  __shared__ __attribute__((aligned(1024))) char ring[STAGES * SLOT];
 
-  // pixel coordinates of the rows this thread stages (fixed over the k loop)
-  int py[A_CHUNKS], px[A_CHUNKS];
+  // XCD-aware order: consecutive logical tiles (the column tiles of one row tile, then the next
+  // row tile) stay on one XCD, whose L2 then serves the shared activation rows
+  const int chunk = (a.ntiles + 7) / 8;
+  const int tile = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  if (tile >= a.ntiles) return;
+  const int col = tile % a.ncol;
+  const int64_t m0 = (int64_t)(tile / a.ncol) * (128 * TM);
+
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int trow = lane % 32, half = lane / 32;
+  const int P = a.H * a.W;
+  const int per_tap = a.C / 32, nkt = 9 * per_tap;
+
+  int py[TM], px[TM];
+  int64_t tok[TM];
 #pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) {
-    const int row = (tid + i * 256) / CPR;
-    const int64_t m = m0 + row;
-    const int p = (int)(m % P);
-    py[i] = m < M ? p / W : -4;   // -4: no tap is ever inside
-    px[i] = p % W;
+  for (int j = 0; j < TM; ++j) {
+    tok[j] = m0 + (wave * TM + j) * 32 + trow;
+    const int p = (int)(tok[j] % P);
+    py[j] = tok[j] < a.M ? p / a.W : -4;  // -4: no tap is ever inside
+    px[j] = p % a.W;
   }
+  const unsigned ring_lds = (unsigned)(size_t)(__attribute__((address_space(3))) void*)ring;
+  const char* wtile = a.wf + (int64_t)col * nkt * (WFR * 1024);
 
-  uint4 ra[A_CHUNKS], rw[W_CHUNKS];
-  auto load_tile = [&](int tap, int c0) {
+  unsigned tapv[TM];  // byte offset of the lane's granule for the current tap at channel 0, 0 = outside
+  auto set_tap = [&](int tap) {
     const int dy = tap / 3 - 1, dx = tap % 3 - 1;
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) {
-      const int id = tid + i * 256, row = id / CPR, kc = (id % CPR) * 8;
-      const bool in = (unsigned)(py[i] + dy) < (unsigned)H && (unsigned)(px[i] + dx) < (unsigned)W;
-      const int64_t src = m0 + row + dy * W + dx;
-      ra[i] = in ? *reinterpret_cast<const uint4*>(A + src * C + c0 + kc) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < W_CHUNKS; ++i) {
-      const int id = tid + i * 256, row = id / CPR, kc = (id % CPR) * 8;
-      const int n = n0 + row;
-      rw[i] = (row < BN && n < O) ? *reinterpret_cast<const uint4*>(Wp + (int64_t)n * K + tap * C + c0 + kc)
-                                  : make_uint4(0, 0, 0, 0);
+    for (int j = 0; j < TM; ++j) {
+      const bool in = (unsigned)(py[j] + dy) < (unsigned)a.H && (unsigned)(px[j] + dx) < (unsigned)a.W;
+      const int64_t src = tok[j] + dy * a.W + dx;
+      tapv[j] = in ? (unsigned)(kActZeroBytes + 16 * (((src >> 5) * (a.C / 16)) * 64 + half * 32 + (src & 31))) : 0u;
     }
   };
-  auto store_tile = [&](int buf) {
+  int ld_tap = 0, ld_c = 0, ld_kt = 0;  // the k-tile the next issue() loads
+  set_tap(0);
+  auto issue = [&]() {
+    const unsigned slot = ring_lds + (unsigned)((ld_kt % STAGES) * SLOT);
+    const bool real = ld_kt < nkt;
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) {
-      const int id = tid + i * 256, row = id / CPR, kc = (id % CPR) * 8;
-      *reinterpret_cast<uint4*>(&As[buf][row][kc]) = ra[i];
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const unsigned voff = (real && tapv[j]) ? tapv[j] + (unsigned)((ld_c * 2 + ks) * 1024) : (unsigned)(lane * 16 % kActZeroBytes);
+        const unsigned dst = slot + (unsigned)((((wave * TM + j) * 2 + ks)) * 1024);
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(a.act), "s"(dst) : "memory");
+      }
+    const char* wk = wtile + (int64_t)(real ? ld_kt : 0) * (WFR * 1024);
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      const int fi = (wave + 4 * i) % WFR;  // beyond the stage's fragments: a repeat
+      const char* sb = real ? wk + fi * 1024 : a.act;
+      const unsigned voff = real ? (unsigned)(lane * 16) : (unsigned)(lane * 16 % kActZeroBytes);
+      const unsigned dst = slot + (unsigned)((AF + fi) * 1024);
+      asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sb), "s"(dst) : "memory");
     }
-#pragma unroll
-    for (int i = 0; i < W_CHUNKS; ++i) {
-      const int id = tid + i * 256, row = id / CPR, kc = (id % CPR) * 8;
-      if (row < BN) *reinterpret_cast<uint4*>(&Ws[buf][row][kc]) = rw[i];
+    ++ld_kt;
+    if (++ld_c == per_tap) {
+      ld_c = 0;
+      if (++ld_tap < 9) set_tap(ld_tap);
     }
   };
 
@@ -95,52 +135,40 @@ __global__ __launch_bounds__(256) void conv3x3_f16_kernel(const _Float16* __rest
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int per_tap = C / BK, nk = 9 * per_tap;
-  int tap = 0, c0 = 0;  // of the tile being loaded
-  auto advance = [&]() {
-    c0 += BK;
-    if (c0 == C) {
-      c0 = 0;
-      ++tap;
-    }
-  };
-  load_tile(tap, c0);
-  advance();
-  store_tile(0);
-  __syncthreads();
-  const int frow = lane % 32, fk = (lane / 32) * 8;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {
-      load_tile(tap, c0);
-      advance();
-    }
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
+  for (int s = 0; s < STAGES - 1; ++s) issue();
+  constexpr int kWaitImm = (((STAGES - 2) * PER) & 0xF) | 0x70 | 0xF00 | ((((STAGES - 2) * PER) >> 4) << 14);
+  for (int kt = 0; kt < nkt; ++kt) {
+    // k-tile kt has landed for this wavefront once at most the STAGES-2 younger stages are in flight
+    __builtin_amdgcn_s_waitcnt(kWaitImm);
+    __syncthreads();  // ... and for every wavefront; all have also finished reading k-tile kt-1's slot
+    issue();          // which the stage loaded now reuses
+    const char* slot = ring + (kt % STAGES) * SLOT;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
       f16x8_t wf[TN], af[TM];
 #pragma unroll
-      for (int i = 0; i < TN; ++i) wf[i] = *reinterpret_cast<const f16x8_t*>(&Ws[cur][wn0 + i * 32 + frow][kk + fk]);
+      for (int i = 0; i < TN; ++i) wf[i] = *reinterpret_cast<const f16x8_t*>(slot + (AF + ks * TN + i) * 1024 + lane * 16);
 #pragma unroll
-      for (int j = 0; j < TM; ++j) af[j] = *reinterpret_cast<const f16x8_t*>(&As[cur][wm0 + j * 32 + frow][kk + fk]);
+      for (int j = 0; j < TM; ++j) af[j] = *reinterpret_cast<const f16x8_t*>(slot + ((wave * TM + j) * 2 + ks) * 1024 + lane * 16);
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int j = 0; j < TM; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[i], af[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_tile(cur ^ 1);
-    __syncthreads();
   }
+  __builtin_amdgcn_s_waitcnt(0x0070 | 0xF00);  // vmcnt(0): the padding loads of the last stages
 
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
-    const int64_t m = m0 + wm0 + j * 32 + frow;
-    if (m >= M) continue;
+    const int64_t m = tok[j];
+    if (m >= a.M) continue;
 #pragma unroll
     for (int i = 0; i < TN; ++i) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn0 + i * 32 + q * 8 + (lane / 32) * 4;
-        if (n < O) {
+        const int n = (col * TN + i) * 32 + q * 8 + half * 4;
+        if (n < a.O) {
           const float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
           epi(m, n, v);
         }
@@ -167,65 +195,122 @@ struct EpiConvEmb {
   }
 };
 
-// dst[o, tap*C + c] = src[o, c, tap]  (src in [O, C, 3, 3] order)
-__global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__ src, _Float16* __restrict__ dst, int O, int C) {
+// Kernel [O, C, 3, 3] (bf16) -> fp16 fragment stream for column tiles of TN*32 output channels:
+// element e of lane l of fragment ((col*nkt + kt)*2 + ks)*TN + i is w[o, c, tap] with
+// o = (col*TN + i)*32 + l%32, tap = kt / (C/32), c = (kt % (C/32))*32 + ks*16 + (l/32)*8 + e; rows
+// beyond O are zero.  One thread per element.  Block 0 also clears the activation buffers' zero blocks.
+__global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__ src, _Float16* __restrict__ dst, int O, int C,
+                                                        int TN, int ncol, unsigned* __restrict__ zero0, unsigned* __restrict__ zero1) {
+  if (blockIdx.x == 0 && threadIdx.x < kActZeroBytes / 4) {
+    if (zero0) zero0[threadIdx.x] = 0u;
+    if (zero1) zero1[threadIdx.x] = 0u;
+  }
+  const int per_tap = C / 32, nkt = 9 * per_tap;
+  const int64_t total = (int64_t)ncol * nkt * 2 * TN * 512;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t total = (int64_t)O * 9 * C;
   if (idx >= total) return;
-  const int c = (int)(idx % C);
-  const int tap = (int)((idx / C) % 9);
-  const int64_t o = idx / ((int64_t)9 * C);
-  dst[idx] = (_Float16)to_float(src[(o * C + c) * 9 + tap]);
+  const int e = (int)(idx % 8), l = (int)((idx / 8) % 64);
+  int64_t f = idx / 512;
+  const int i = (int)(f % TN); f /= TN;
+  const int ks = (int)(f % 2); f /= 2;
+  const int kt = (int)(f % nkt);
+  const int col = (int)(f / nkt);
+  const int o = (col * TN + i) * 32 + l % 32;
+  const int tap = kt / per_tap, c = (kt % per_tap) * 32 + ks * 16 + (l / 32) * 8 + e;
+  dst[idx] = o < O ? (_Float16)to_float(src[((int64_t)o * C + c) * 9 + tap]) : (_Float16)0.f;
 }
 
-// e[b, o] = b_t[o] + sum_k SiLU(temb[b, k]) * W_t[k, o]; one thread per (b, o), fp32 accumulation in k order
+// e[b, o] = b_t[o] + sum_k SiLU(temb[b, k]) * W_t[k, o].  One block per (64 outputs, batch entry):
+// wavefront q sums k = q, q+4, ... for output o = lane, the four partial sums are added in a fixed order.
 __global__ __launch_bounds__(256) void temb_proj_kernel(const bf16* __restrict__ temb, const bf16* __restrict__ wt,
                                                         const bf16* __restrict__ bt, float* __restrict__ e, int Kt, int O) {
-  const int o = blockIdx.x * 256 + threadIdx.x;
+  const int lane = threadIdx.x % kWave, q = threadIdx.x / kWave;
+  const int o = blockIdx.x * kWave + lane;
   const int b = blockIdx.y;
-  if (o >= O) return;
   float s = 0.f;
-  for (int k = 0; k < Kt; ++k) s = fmaf(silu(to_float(temb[(int64_t)b * Kt + k])), to_float(wt[(int64_t)k * O + o]), s);
-  e[(int64_t)b * O + o] = s + param_or(bt, o, 0.f);
+  if (o < O) {
+#pragma unroll 8
+    for (int k = q; k < Kt; k += 4) s = fmaf(silu(to_float(temb[(int64_t)b * Kt + k])), to_float(wt[(int64_t)k * O + o]), s);
+  }
+  __shared__ float part[4][kWave];
+  part[q][lane] = s;
+  __syncthreads();
+  if (q == 0 && o < O) e[(int64_t)b * O + o] = ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])) + param_or(bt, o, 0.f);
 }
 
-// Statistics per (image, group) of h[img*P + p, g*ng .. (g+1)*ng): one block per (image, group);
-// sums relative to the first element, fp32 lanes merged in fp64.  stats[(img*G + g)*2 + {0,1}] =
-// {mean, 1/sqrt(var + eps)}.
-__global__ __launch_bounds__(256) void gn_stats_tokens_kernel(const float* __restrict__ h, float* __restrict__ stats, int P,
-                                                              int C, int G, float eps) {
+// Second GroupNorm's statistics of the token-major fp32 feature h[img*P + p, c], in two steps so
+// that every read is a full contiguous row:
+//   gn_partial_tokens_kernel  block (chunk, img): per channel, sum and sum of squares of
+//                             h - shift[c] over the chunk's kGnChunk tokens (shift[c] = the image's
+//                             first token, so a common offset does not cancel in fp32);
+//                             partial[((img*nchunk + chunk)*C + c)*2 + {0,1}]
+//   gn_finish_tokens_kernel   block (img, group): merges chunks and the group's channels in fp64 in
+//                             a fixed order; stats[(img*G + g)*2 + {0,1}] = {mean, 1/sqrt(var + eps)}
+constexpr int kGnChunk = 64;
+
+__global__ __launch_bounds__(256) void gn_partial_tokens_kernel(const float* __restrict__ h, float* __restrict__ partial,
+                                                                int P, int C) {
+  const int chunk = blockIdx.x, img = blockIdx.y, nchunk = gridDim.x;
+  const float* base = h + (int64_t)img * P * C;
+  const int p0 = chunk * kGnChunk;
+  const int p1 = p0 + kGnChunk < P ? p0 + kGnChunk : P;
+  for (int c = threadIdx.x; c < C; c += 256) {   // consecutive threads, consecutive channels: full rows
+    const float shift = base[c];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll 8
+    for (int p = p0; p < p1; ++p) {
+      const float d = base[(int64_t)p * C + c] - shift;
+      s1 += d;
+      s2 = fmaf(d, d, s2);
+    }
+    float* o = partial + (((int64_t)img * nchunk + chunk) * C + c) * 2;
+    o[0] = s1;
+    o[1] = s2;
+  }
+}
+
+__global__ __launch_bounds__(256) void gn_finish_tokens_kernel(const float* __restrict__ h, const float* __restrict__ partial,
+                                                               float* __restrict__ stats, int P, int C, int G, int nchunk,
+                                                               float eps) {
   const int g = blockIdx.x % G, img = blockIdx.x / G;
   const int ng = C / G;
-  const float* base = h + (int64_t)img * P * C + g * ng;
-  const float shift = base[0];
-  float s1 = 0.f, s2 = 0.f;
-  for (int p = threadIdx.x; p < P; p += 256) {
-    const float* r = base + (int64_t)p * C;
-    for (int c = 0; c < ng; ++c) {
-      const float d = r[c] - shift;
-      s1 += d;
-      s2 += d * d;
+  const int lane = threadIdx.x % kWave, q = threadIdx.x / kWave;
+  // lane < ng: one channel of the group (ng <= 64 is checked by the host); wavefront q takes chunks q, q+4, ...
+  __shared__ double sh[2][4][kWave];
+  double s1 = 0.0, s2 = 0.0;
+  if (lane < ng) {
+    const float2* src = reinterpret_cast<const float2*>(partial) + (int64_t)img * nchunk * C + g * ng + lane;
+#pragma unroll 8
+    for (int k = q; k < nchunk; k += 4) {
+      const float2 v = src[(int64_t)k * C];
+      s1 += (double)v.x;
+      s2 += (double)v.y;
     }
   }
-  const double a1 = wave_sum((double)s1), a2 = wave_sum((double)s2);
-  __shared__ double sh[2][4];
-  if (threadIdx.x % kWave == 0) {
-    sh[0][threadIdx.x / kWave] = a1;
-    sh[1][threadIdx.x / kWave] = a2;
-  }
+  sh[0][q][lane] = s1;
+  sh[1][q][lane] = s2;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    const double n = (double)ng * (double)P;
-    const double m1 = (sh[0][0] + sh[0][1] + sh[0][2] + sh[0][3]) / n;
-    const double m2 = (sh[1][0] + sh[1][1] + sh[1][2] + sh[1][3]) / n;
-    double var = m2 - m1 * m1;
+  if (q != 0) return;
+  double mean_c = 0.0, m2_c = 0.0;
+  if (lane < ng) {
+    s1 = (sh[0][0][lane] + sh[0][1][lane]) + (sh[0][2][lane] + sh[0][3][lane]);
+    s2 = (sh[1][0][lane] + sh[1][1][lane]) + (sh[1][2][lane] + sh[1][3][lane]);
+    const double n = (double)P;
+    mean_c = (double)h[(int64_t)img * P * C + g * ng + lane] + s1 / n;
+    m2_c = s2 - s1 * s1 / n;   // sum of squared deviations from the channel's own mean
+  }
+  const double mean_g = wave_sum(lane < ng ? mean_c : 0.0) / (double)ng;
+  const double dev = mean_c - mean_g;
+  const double m2 = wave_sum(lane < ng ? m2_c + (double)P * dev * dev : 0.0);
+  if (lane == 0) {
+    double var = m2 / ((double)ng * (double)P);
     if (var < 0.0) var = 0.0;
-    stats[(int64_t)blockIdx.x * 2 + 0] = (float)((double)shift + m1);
+    stats[(int64_t)blockIdx.x * 2 + 0] = (float)mean_g;
     stats[(int64_t)blockIdx.x * 2 + 1] = (float)(1.0 / sqrt(var + (double)eps));
   }
 }
 
-// a[m, c] = fp16(SiLU((h[m, c] - mean) * rstd * gamma[c] + beta[c])), four channels per thread (C % 4 == 0)
+// a(m, c) = fp16(SiLU((h[m, c] - mean) * rstd * gamma[c] + beta[c])) in fragment order, four channels per thread
 __global__ __launch_bounds__(256) void gn_silu_tokens_kernel(const float* __restrict__ h, const float* __restrict__ stats,
                                                              const bf16* __restrict__ gamma, const bf16* __restrict__ beta,
                                                              _Float16* __restrict__ a, int64_t M, int P, int C, int G) {
@@ -247,7 +332,62 @@ __global__ __launch_bounds__(256) void gn_silu_tokens_kernel(const float* __rest
   }
   typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
   f16x4_t pk = {(_Float16)o[0], (_Float16)o[1], (_Float16)o[2], (_Float16)o[3]};
-  *reinterpret_cast<f16x4_t*>(a + m * C + c) = pk;
+  *reinterpret_cast<f16x4_t*>(a + kActZeroBytes / 2 + act_granule(m, c / 8, C) * 8 + (c % 8)) = pk;
+}
+
+// Slice-in of the ResBlock: a(m, c) = fp16(SiLU(GroupNorm1(x)[b, c, f, p])) in fragment order for the
+// window's tokens m = (b*Fw + f - f0)*P + p.  64 x 64 (position x channel) tiles are transposed through LDS: 8-byte
+// reads along positions, 16-byte writes along channels.  C % 8 == 0.
+__global__ __launch_bounds__(256) void window_to_tokens_silu_kernel(const bf16* __restrict__ x, const float* __restrict__ stats,
+                                                                    const bf16* __restrict__ gamma, const bf16* __restrict__ beta,
+                                                                    _Float16* __restrict__ a, Window w) {
+  __shared__ float tile[64][65];
+  const int bf = blockIdx.z;
+  const int b = bf / w.Fw, fl = bf % w.Fw, f = w.f0 + fl;
+  const int pt = blockIdx.x * 64, ct = blockIdx.y * 64;
+  const int ng = w.C / w.G;
+  const bool vec_ok = (w.P % 4 == 0) && (w.p0 % 4 == 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int id = threadIdx.x + i * 256, cl = id / 16, pq = (id % 16) * 4;
+    const int c = ct + cl, pl = pt + pq;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (c < w.C && pl < w.Pw) {
+      const int g = c / ng;
+      const float mean = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 0];
+      const float rstd = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 1];
+      const float ga = param_or(gamma, c, 1.f) * rstd, be = param_or(beta, c, 0.f);
+      const bf16* src = x + (((int64_t)b * w.C + c) * w.F + f) * w.P + w.p0 + pl;
+      float xv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (vec_ok && pl + 3 < w.Pw) {
+        const uint2 raw = *reinterpret_cast<const uint2*>(src);
+        xv[0] = __uint_as_float(raw.x << 16);
+        xv[1] = __uint_as_float(raw.x & 0xffff0000u);
+        xv[2] = __uint_as_float(raw.y << 16);
+        xv[3] = __uint_as_float(raw.y & 0xffff0000u);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (pl + j < w.Pw) xv[j] = to_float(src[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = silu((xv[j] - mean) * ga + be);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tile[cl][pq + j] = v[j];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int id = threadIdx.x + i * 256, pl = id / 8, co = (id % 8) * 8;
+    const int p = pt + pl, c = ct + co;
+    if (p < w.Pw && c < w.C) {
+      f16x8_t o;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[j] = (_Float16)tile[co + j][pl];
+      *reinterpret_cast<f16x8_t*>(a + kActZeroBytes / 2 + act_granule((int64_t)bf * w.Pw + p, c / 8, w.C) * 8) = o;
+    }
+  }
 }
 
 }  // namespace si

@@ -453,7 +453,9 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   float* const h_base = h;
   T* const big_base = big;
   AuxStream* aux = nullptr;
-  if (p.lanes == 2) {  // fork: the second lane starts after the once-per-call work above
+  // per-stage timing wants each kernel alone on the GPU: one window at a time while it is enabled
+  const int lanes = g_timing ? 1 : p.lanes;
+  if (lanes == 2) {  // fork: the second lane starts after the once-per-call work above
     SI_TRY(aux_stream(&aux));
     if (hipEventRecord(aux->fork, st_main) != hipSuccess || hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess)
       return SI_ERR_HIP;
@@ -461,7 +463,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   for (int64_t s0 = 0; s0 < p.extent; s0 += p.slice_len) {
     const int64_t s1 = s0 + p.slice_len < p.extent ? s0 + p.slice_len : p.extent;
     // this slice's lane: stream and intermediates (the names below shadow the first lane's)
-    const size_t lane_off = (size_t)((s0 / p.slice_len) % p.lanes) * p.lane_stride;
+    const size_t lane_off = (size_t)((s0 / p.slice_len) % lanes) * p.lane_stride;
     hipStream_t st = lane_off ? aux->stream : st_main;
     T* a = reinterpret_cast<T*>(reinterpret_cast<char*>(a_base) + lane_off);
     float* h = reinterpret_cast<float*>(reinterpret_cast<char*>(h_base) + lane_off);
@@ -601,7 +603,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       SI_TRY(launch_gemm<T>("proj_out", a, (int64_t)kSplit * D, w_out, M, C, kSplit * D, epi, st));
     }
   }
-  if (p.lanes == 2) {  // join: the caller's stream continues after both lanes
+  if (lanes == 2) {  // join: the caller's stream continues after both lanes
     if (hipEventRecord(aux->join, aux->stream) != hipSuccess || hipStreamWaitEvent(st_main, aux->join, 0) != hipSuccess)
       return SI_ERR_HIP;
   }

@@ -4,14 +4,19 @@
 #pragma once
 #include "k_conv.h"
 
+#ifndef SI_CONV_BIG_MIN
+#define SI_CONV_BIG_MIN 512
+#endif
+
 namespace si {
 
 struct ResPlan {
   int B, C, F, H, W, G, Kt;
+  int TN, ncol;        // column tiles of the convolution kernel: ncol tiles of TN*32 output channels
   int64_t P, slice_len, Mmax;
   int lanes;           // frame windows in flight (two streams) when there are many small ones
   size_t lane_stride;
-  size_t off_stats, off_emb, off_a, off_h, off_stats2, off_w1, off_w2;
+  size_t off_stats, off_emb, off_a, off_h, off_stats2, off_part, off_w1, off_w2;
   size_t weights_bytes, total_bytes;
 };
 
@@ -20,6 +25,7 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
   if (x->dtype != SI_BF16) return SI_ERR_DTYPE;
   if (x->B < 1 || x->C < 1 || x->F < 1 || x->H < 1 || x->W < 1) return SI_ERR_SHAPE;
   if (w->gn_groups < 1 || x->C % w->gn_groups || x->C % 32 || x->C > 8192) return SI_ERR_SHAPE;
+  if (x->C / w->gn_groups > 64) return SI_ERR_SHAPE;  // a group's channels are merged by one wavefront
   const int64_t P = x->H * x->W;
   if (x->B > 65535 || x->F > 65535 || x->H > 4096 || x->W > 4096) return SI_ERR_SHAPE;
   if ((double)x->B * x->C * x->F * (double)P >= 1099511627776.0) return SI_ERR_SHAPE;
@@ -43,31 +49,59 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
   p->off_emb = take((size_t)p->B * C * sizeof(float));
   // one window's intermediates: the fp16 operand of either convolution, the fp32 output of the first
   // one, the second GroupNorm's statistics
-  p->off_a = take((size_t)p->Mmax * C * 2);
+  if ((double)p->Mmax * (double)C * 2.0 + 4096.0 >= 4294967296.0) return SI_ERR_SHAPE;  // 32-bit operand offsets
+  p->off_a = take(kActZeroBytes + (size_t)((p->Mmax + 31) / 32 * 32) * C * 2);
   p->off_h = take((size_t)p->Mmax * C * sizeof(float));
   p->off_stats2 = take((size_t)p->B * p->slice_len * p->G * 2 * sizeof(float));
+  p->off_part = take((size_t)p->B * p->slice_len * (size_t)((P + kGnChunk - 1) / kGnChunk) * C * 2 * sizeof(float));
   const int64_t n_slices = (p->F + p->slice_len - 1) / p->slice_len;
   p->lanes = n_slices >= 8 ? 2 : 1;  // two windows' buffers still stay within a quarter of the unsliced ones
   p->lane_stride = off - p->off_a;
   if (p->lanes == 2) take(p->lane_stride);
   const size_t act_end = off;
-  p->off_w1 = take(9 * C * C * 2);
-  p->off_w2 = take(9 * C * C * 2);
+  // column tile width: the candidate that pads the output channels least, the wider one on a tie
+  p->TN = 1;
+  p->ncol = p->C / 32;
+  for (int tn : {2, 4, 5}) {
+    const int nc = (p->C + 32 * tn - 1) / (32 * tn);
+    if (nc * tn <= p->ncol * p->TN) {
+      p->TN = tn;
+      p->ncol = nc;
+    }
+  }
+  const size_t wbytes = (size_t)p->ncol * 9 * (C / 32) * 2 * p->TN * 1024;
+  p->off_w1 = take(wbytes);
+  p->off_w2 = take(wbytes);
   p->weights_bytes = off - act_end;
   p->total_bytes = off;
   return SI_OK;
 }
 
+template <int TM, int TN, int STAGES, class Epi>
+static void launch_conv_tile(const ConvArgs& a, Epi epi, hipStream_t st) {
+  const int grid = (a.ntiles + 7) / 8 * 8;
+  conv3x3_dma_kernel<TM, TN, STAGES, Epi><<<grid, 256, 0, st>>>(a, epi);
+}
+
+// Row tiles of 256 tokens when that still gives every CU two blocks, else 128 tokens.
 template <class Epi>
-static si_status launch_conv3x3(const char* stage, const _Float16* A, const _Float16* Wp, int64_t M, int C, int H, int W, Epi epi,
+static si_status launch_conv3x3(const char* stage, const ResPlan& p, const _Float16* act, const _Float16* wf, int64_t M, Epi epi,
                                 hipStream_t st) {
   StageScope scope(stage, st);
-  if (C % 64 == 0) {
-    dim3 grid((unsigned)((M + 127) / 128), (unsigned)((C + 127) / 128));
-    conv3x3_f16_kernel<128, 128, 2, 2, Epi, 64><<<grid, 256, 0, st>>>(A, Wp, M, C, C, H, W, epi);
-  } else {
-    dim3 grid((unsigned)((M + 127) / 128), (unsigned)((C + 127) / 128));
-    conv3x3_f16_kernel<128, 128, 2, 2, Epi, 32><<<grid, 256, 0, st>>>(A, Wp, M, C, C, H, W, epi);
+  ConvArgs a{reinterpret_cast<const char*>(act), reinterpret_cast<const char*>(wf), M, p.C, p.C, p.H, p.W, p.ncol, 0};
+  const int64_t rows2 = (M + 255) / 256;
+  const bool big = rows2 * p.ncol >= SI_CONV_BIG_MIN;
+  a.ntiles = (int)((big ? rows2 : (M + 127) / 128) * p.ncol);
+  switch (p.TN * 2 + (big ? 1 : 0)) {
+    case 11: launch_conv_tile<2, 5, 3>(a, epi, st); break;
+    case 10: launch_conv_tile<1, 5, 4>(a, epi, st); break;
+    case 9: launch_conv_tile<2, 4, 3>(a, epi, st); break;
+    case 8: launch_conv_tile<1, 4, 4>(a, epi, st); break;
+    case 5: launch_conv_tile<2, 2, 4>(a, epi, st); break;
+    case 4: launch_conv_tile<1, 2, 4>(a, epi, st); break;
+    case 3: launch_conv_tile<2, 1, 4>(a, epi, st); break;
+    case 2: launch_conv_tile<1, 1, 4>(a, epi, st); break;
+    default: return SI_ERR_SHAPE;
   }
   SI_CHECK_LAUNCH();
   return SI_OK;
@@ -87,13 +121,16 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
   // ---- once per call: kernel re-layout, embedding projection, first GroupNorm's statistics
   {
     StageScope scope("pack_weights", st0);
-    const unsigned blocks = (unsigned)(((int64_t)9 * C * C + 255) / 256);
-    pack_conv_kernel<<<blocks, 256, 0, st0>>>(cB(w->w_conv1), w1, C, C);
+    const int64_t elems = (int64_t)p.ncol * 9 * (C / 32) * 2 * p.TN * 512;
+    const unsigned blocks = (unsigned)((elems + 255) / 256);
+    unsigned* z0 = reinterpret_cast<unsigned*>(ws + p.off_a);
+    unsigned* z1 = p.lanes == 2 ? reinterpret_cast<unsigned*>(ws + p.off_a + p.lane_stride) : nullptr;
+    pack_conv_kernel<<<blocks, 256, 0, st0>>>(cB(w->w_conv1), w1, C, C, p.TN, p.ncol, z0, z1);
     SI_CHECK_LAUNCH();
-    pack_conv_kernel<<<blocks, 256, 0, st0>>>(cB(w->w_conv2), w2, C, C);
+    pack_conv_kernel<<<blocks, 256, 0, st0>>>(cB(w->w_conv2), w2, C, C, p.TN, p.ncol, nullptr, nullptr);
     SI_CHECK_LAUNCH();
     if (emb) {
-      temb_proj_kernel<<<dim3((unsigned)((C + 255) / 256), (unsigned)p.B), 256, 0, st0>>>(cB(temb), cB(w->w_temb),
+      temb_proj_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)p.B), 256, 0, st0>>>(cB(temb), cB(w->w_temb),
                                                                                           cB(w->b_temb), emb, p.Kt, C);
       SI_CHECK_LAUNCH();
     }
@@ -107,7 +144,8 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
   }
 
   AuxStream* aux = nullptr;
-  if (p.lanes == 2) {
+  const int lanes = g_timing ? 1 : p.lanes;  // per-stage timing: one window at a time
+  if (lanes == 2) {
     SI_TRY(aux_stream(&aux));
     if (hipEventRecord(aux->fork, st0) != hipSuccess) return SI_ERR_HIP;
     if (hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
@@ -116,29 +154,32 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
   // ---- the frame windows (Sec. 4.1): each goes through the whole group and lands in its window of out
   int widx = 0;
   for (int64_t f0 = 0; f0 < p.F; f0 += p.slice_len, ++widx) {
-    const int lane_id = p.lanes == 2 ? widx & 1 : 0;
+    const int lane_id = lanes == 2 ? widx & 1 : 0;
     hipStream_t st = lane_id ? aux->stream : st0;
     char* lane_ws = ws + (size_t)lane_id * p.lane_stride;
     _Float16* a = reinterpret_cast<_Float16*>(lane_ws + p.off_a);
     float* h = reinterpret_cast<float*>(lane_ws + p.off_h);
     float* stats2 = reinterpret_cast<float*>(lane_ws + p.off_stats2);
+    float* part = reinterpret_cast<float*>(lane_ws + p.off_part);
     const int Fw = (int)((f0 + p.slice_len <= p.F) ? p.slice_len : p.F - f0);
     const int64_t M = (int64_t)p.B * Fw * p.P;
     Window win{p.B, C, p.F, p.P, (int)f0, Fw, 0, (int)p.P, p.G};
     {
       StageScope scope("slice_in", st);
       dim3 grid((unsigned)((p.P + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * Fw));
-      window_to_tokens_kernel<bf16, true><<<grid, 256, 0, st>>>(X, stats, cB(w->gn1_g), cB(w->gn1_b),
-                                                                reinterpret_cast<bf16*>(a), win);
+      window_to_tokens_silu_kernel<<<grid, 256, 0, st>>>(X, stats, cB(w->gn1_g), cB(w->gn1_b), a, win);
       SI_CHECK_LAUNCH();
     }
     {
       EpiConvEmb epi{h, (int64_t)C, cB(w->b_conv1), emb, (int64_t)Fw * p.P};
-      SI_TRY(launch_conv3x3("conv1", a, w1, M, C, p.H, p.W, epi, st));
+      SI_TRY(launch_conv3x3("conv1", p, a, w1, M, epi, st));
     }
     {
       StageScope scope("gn2_stats", st);
-      gn_stats_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(h, stats2, (int)p.P, C, p.G, w->gn_eps);
+      const int nchunk = (int)((p.P + kGnChunk - 1) / kGnChunk);
+      gn_partial_tokens_kernel<<<dim3((unsigned)nchunk, (unsigned)(p.B * Fw)), 256, 0, st>>>(h, part, (int)p.P, C);
+      SI_CHECK_LAUNCH();
+      gn_finish_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(h, part, stats2, (int)p.P, C, p.G, nchunk, w->gn_eps);
       SI_CHECK_LAUNCH();
     }
     {
@@ -150,10 +191,10 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
     }
     {
       EpiSliceOut<bf16> epi{X, OUT, cB(w->b_conv2), win};
-      SI_TRY(launch_conv3x3("conv2", a, w2, M, C, p.H, p.W, epi, st));
+      SI_TRY(launch_conv3x3("conv2", p, a, w2, M, epi, st));
     }
   }
-  if (p.lanes == 2) {
+  if (lanes == 2) {
     if (hipEventRecord(aux->join, aux->stream) != hipSuccess) return SI_ERR_HIP;
     if (hipStreamWaitEvent(st0, aux->join, 0) != hipSuccess) return SI_ERR_HIP;
   }
