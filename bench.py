@@ -116,10 +116,10 @@ def res_stage_work(spec, stage, M):
         return "byte", float(spec.tokens * C * 2)
     if stage == "slice_in":
         return "byte", 2.0 * M * C * 2
-    if stage == "gn2_stats":
+    if stage == "gn2_stats":            # one read of the fp16 intermediate
+        return "byte", 2.0 * M * C
+    if stage == "gn2_silu":             # fp16 in, fp16 out
         return "byte", 4.0 * M * C
-    if stage == "gn2_silu":
-        return "byte", 6.0 * M * C
     return "none", 0.0
 
 

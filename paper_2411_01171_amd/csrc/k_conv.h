@@ -10,7 +10,7 @@
 //   pack_conv_kernel        [O, C, 3, 3] bf16 kernel -> fp16 fragment stream in the order the kernel reads
 //   temb_proj_kernel        e[b, o] = b_t[o] + sum_k SiLU(temb[b, k]) * W_t[k, o]
 //   gn_partial_tokens_kernel + gn_finish_tokens_kernel
-//                           GroupNorm statistics of a token-major fp32 feature per (image, group)
+//                           GroupNorm statistics of a token-major fp16 feature per (image, group)
 //   gn_silu_tokens_kernel   SiLU(GroupNorm(h)) -> fp16 operand in fragment order             [HBM bound]
 //   window_to_tokens_silu_kernel  slice window -> SiLU(GroupNorm1) -> fp16 operand in fragment order
 #pragma once
@@ -159,6 +159,39 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi
   }
   __builtin_amdgcn_s_waitcnt(0x0070 | 0xF00);  // vmcnt(0): the padding loads of the last stages
 
+  if constexpr (Epi::kRows8) {
+    // Output channels are far apart in the feature, tokens adjacent: hand the epilogue 8 consecutive
+    // tokens of one channel.  One 32-channel block at a time is transposed through the (now idle)
+    // ring: patch[channel][token], rows padded by 4 floats.
+    constexpr int TOK = 128 * TM, LDP = TOK + 4;
+    static_assert(32 * LDP * 4 <= STAGES * SLOT, "patch fits the ring");
+    float* patch = reinterpret_cast<float*>(ring);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+      __syncthreads();  // the ring (first pass) or the previous block's patch is no longer read
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) patch[(q * 8 + half * 4 + r) * LDP + (wave * TM + j) * 32 + trow] = acc[i][j][q * 4 + r];
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < 2 * TM; ++u) {
+        const int id = tid + u * 256, ch = id / (TOK / 8), t8 = (id % (TOK / 8)) * 8;
+        const int n = (col * TN + i) * 32 + ch;
+        const int64_t m = m0 + t8;
+        if (n < a.O && m < a.M) {
+          const float4 lo = *reinterpret_cast<const float4*>(patch + ch * LDP + t8);
+          const float4 hi = *reinterpret_cast<const float4*>(patch + ch * LDP + t8 + 4);
+          const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+          epi.rows8(m, n, v, a.M);
+        }
+      }
+    }
+    return;
+  }
+
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
     const int64_t m = tok[j];
@@ -177,21 +210,61 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi
   }
 }
 
-// h[m, n] = acc + bias[n] + e[b(m), n]   (fp32, token-major; e may be NULL); b(m) = m / tokens_per_batch
+// h[m, n] = fp16(acc + bias[n] + e[b(m), n])   (token-major; e may be NULL); b(m) = m / tokens_per_batch
 struct EpiConvEmb {
-  float* h;
+  static constexpr bool kRows8 = false;
+  _Float16* h;
   int64_t ld;
   const bf16* bias;
   const float* e;
   int64_t tokens_per_batch;
   __device__ __forceinline__ void operator()(int64_t m, int n0, const float (&v)[4]) const {
     const float* er = e ? e + (m / tokens_per_batch) * ld + n0 : nullptr;
-    float4 o;
-    o.x = v[0] + param_or(bias, n0 + 0, 0.f) + (er ? er[0] : 0.f);
-    o.y = v[1] + param_or(bias, n0 + 1, 0.f) + (er ? er[1] : 0.f);
-    o.z = v[2] + param_or(bias, n0 + 2, 0.f) + (er ? er[2] : 0.f);
-    o.w = v[3] + param_or(bias, n0 + 3, 0.f) + (er ? er[3] : 0.f);
-    *reinterpret_cast<float4*>(h + m * ld + n0) = o;
+    typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+    f16x4_t o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (_Float16)(v[i] + param_or(bias, n0 + i, 0.f) + (er ? er[i] : 0.f));
+    *reinterpret_cast<f16x4_t*>(h + m * ld + n0) = o;
+  }
+};
+
+// Slice-out of the ResBlock: out[b, n, f, p] = x[b, n, f, p] + acc + bias[n] for 8 consecutive tokens
+// m .. m+7 of the window (token = (b*Fw + f - f0)*Pw + p); the sum is formed in fp32 and rounded once.
+// 16-byte accesses when the eight tokens are eight aligned positions of one image.
+struct EpiSliceOutRows {
+  static constexpr bool kRows8 = true;
+  const bf16* x;
+  bf16* out;
+  const bf16* bias;
+  Window w;
+  __device__ __forceinline__ void operator()(int64_t, int, const float (&)[4]) const {}
+  __device__ __forceinline__ void rows8(int64_t m, int n, const float (&v)[8], int64_t M) const {
+    const float bn = param_or(bias, n, 0.f);
+    const int pl = (int)(m % w.Pw);
+    const int64_t bf = m / w.Pw;
+    const int64_t off = (((bf / w.Fw) * w.C + n) * w.F + (w.f0 + (int)(bf % w.Fw))) * w.P + w.p0 + pl;
+    if (pl + 7 < w.Pw && m + 7 < M && ((w.P | w.p0 | pl) & 7) == 0) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(x + off);
+      const unsigned xw[4] = {raw.x, raw.y, raw.z, raw.w};
+      unsigned ow[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float r0 = __uint_as_float(xw[i] << 16) + (v[2 * i] + bn);
+        const float r1 = __uint_as_float(xw[i] & 0xffff0000u) + (v[2 * i + 1] + bn);
+        ow[i] = (unsigned)float_to_bf16_bits(r0) | ((unsigned)float_to_bf16_bits(r1) << 16);
+      }
+      *reinterpret_cast<uint4*>(out + off) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    } else {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int64_t mt = m + t;
+        if (mt >= M) break;
+        const int plt = (int)(mt % w.Pw);
+        const int64_t bft = mt / w.Pw;
+        const int64_t o2 = (((bft / w.Fw) * w.C + n) * w.F + (w.f0 + (int)(bft % w.Fw))) * w.P + w.p0 + plt;
+        out[o2] = from_float<bf16>(to_float(x[o2]) + (v[t] + bn));
+      }
+    }
   }
 };
 
@@ -220,25 +293,31 @@ __global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__
   dst[idx] = o < O ? (_Float16)to_float(src[((int64_t)o * C + c) * 9 + tap]) : (_Float16)0.f;
 }
 
-// e[b, o] = b_t[o] + sum_k SiLU(temb[b, k]) * W_t[k, o].  One block per (64 outputs, batch entry):
-// wavefront q sums k = q, q+4, ... for output o = lane, the four partial sums are added in a fixed order.
-__global__ __launch_bounds__(256) void temb_proj_kernel(const bf16* __restrict__ temb, const bf16* __restrict__ wt,
-                                                        const bf16* __restrict__ bt, float* __restrict__ e, int Kt, int O) {
+// e[b, o] = b_t[o] + sum_k SiLU(temb[b, k]) * W_t[k, o].  One block (16 wavefronts) per (64 outputs,
+// batch entry): wavefront q sums k = q, q+16, ... for output o = lane; the 16 partial sums are added
+// in a fixed order.
+__global__ __launch_bounds__(1024) void temb_proj_kernel(const bf16* __restrict__ temb, const bf16* __restrict__ wt,
+                                                         const bf16* __restrict__ bt, float* __restrict__ e, int Kt, int O) {
   const int lane = threadIdx.x % kWave, q = threadIdx.x / kWave;
   const int o = blockIdx.x * kWave + lane;
   const int b = blockIdx.y;
   float s = 0.f;
   if (o < O) {
 #pragma unroll 8
-    for (int k = q; k < Kt; k += 4) s = fmaf(silu(to_float(temb[(int64_t)b * Kt + k])), to_float(wt[(int64_t)k * O + o]), s);
+    for (int k = q; k < Kt; k += 16) s = fmaf(silu(to_float(temb[(int64_t)b * Kt + k])), to_float(wt[(int64_t)k * O + o]), s);
   }
-  __shared__ float part[4][kWave];
+  __shared__ float part[16][kWave];
   part[q][lane] = s;
   __syncthreads();
-  if (q == 0 && o < O) e[(int64_t)b * O + o] = ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])) + param_or(bt, o, 0.f);
+  if (q == 0 && o < O) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += part[i][lane];
+    e[(int64_t)b * O + o] = t + param_or(bt, o, 0.f);
+  }
 }
 
-// Second GroupNorm's statistics of the token-major fp32 feature h[img*P + p, c], in two steps so
+// Second GroupNorm's statistics of the token-major fp16 feature h[img*P + p, c], in two steps so
 // that every read is a full contiguous row:
 //   gn_partial_tokens_kernel  block (chunk, img): per channel, sum and sum of squares of
 //                             h - shift[c] over the chunk's kGnChunk tokens (shift[c] = the image's
@@ -248,18 +327,18 @@ __global__ __launch_bounds__(256) void temb_proj_kernel(const bf16* __restrict__
 //                             a fixed order; stats[(img*G + g)*2 + {0,1}] = {mean, 1/sqrt(var + eps)}
 constexpr int kGnChunk = 64;
 
-__global__ __launch_bounds__(256) void gn_partial_tokens_kernel(const float* __restrict__ h, float* __restrict__ partial,
+__global__ __launch_bounds__(256) void gn_partial_tokens_kernel(const _Float16* __restrict__ h, float* __restrict__ partial,
                                                                 int P, int C) {
   const int chunk = blockIdx.x, img = blockIdx.y, nchunk = gridDim.x;
-  const float* base = h + (int64_t)img * P * C;
+  const _Float16* base = h + (int64_t)img * P * C;
   const int p0 = chunk * kGnChunk;
   const int p1 = p0 + kGnChunk < P ? p0 + kGnChunk : P;
   for (int c = threadIdx.x; c < C; c += 256) {   // consecutive threads, consecutive channels: full rows
-    const float shift = base[c];
+    const float shift = (float)base[c];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll 8
     for (int p = p0; p < p1; ++p) {
-      const float d = base[(int64_t)p * C + c] - shift;
+      const float d = (float)base[(int64_t)p * C + c] - shift;
       s1 += d;
       s2 = fmaf(d, d, s2);
     }
@@ -269,7 +348,7 @@ __global__ __launch_bounds__(256) void gn_partial_tokens_kernel(const float* __r
   }
 }
 
-__global__ __launch_bounds__(256) void gn_finish_tokens_kernel(const float* __restrict__ h, const float* __restrict__ partial,
+__global__ __launch_bounds__(256) void gn_finish_tokens_kernel(const _Float16* __restrict__ h, const float* __restrict__ partial,
                                                                float* __restrict__ stats, int P, int C, int G, int nchunk,
                                                                float eps) {
   const int g = blockIdx.x % G, img = blockIdx.x / G;
@@ -311,7 +390,7 @@ __global__ __launch_bounds__(256) void gn_finish_tokens_kernel(const float* __re
 }
 
 // a(m, c) = fp16(SiLU((h[m, c] - mean) * rstd * gamma[c] + beta[c])) in fragment order, four channels per thread
-__global__ __launch_bounds__(256) void gn_silu_tokens_kernel(const float* __restrict__ h, const float* __restrict__ stats,
+__global__ __launch_bounds__(256) void gn_silu_tokens_kernel(const _Float16* __restrict__ h, const float* __restrict__ stats,
                                                              const bf16* __restrict__ gamma, const bf16* __restrict__ beta,
                                                              _Float16* __restrict__ a, int64_t M, int P, int C, int G) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -321,8 +400,9 @@ __global__ __launch_bounds__(256) void gn_silu_tokens_kernel(const float* __rest
   const int c = (int)(idx % cv) * 4;
   const int64_t img = m / P;
   const int ng = C / G;
-  const float4 v = *reinterpret_cast<const float4*>(h + m * C + c);
-  const float in[4] = {v.x, v.y, v.z, v.w};
+  typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+  const f16x4_t v = *reinterpret_cast<const f16x4_t*>(h + m * C + c);
+  const float in[4] = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
   float o[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -330,7 +410,6 @@ __global__ __launch_bounds__(256) void gn_silu_tokens_kernel(const float* __rest
     const float mean = stats[(img * G + g) * 2 + 0], rstd = stats[(img * G + g) * 2 + 1];
     o[i] = silu((in[i] - mean) * rstd * param_or(gamma, c + i, 1.f) + param_or(beta, c + i, 0.f));
   }
-  typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
   f16x4_t pk = {(_Float16)o[0], (_Float16)o[1], (_Float16)o[2], (_Float16)o[3]};
   *reinterpret_cast<f16x4_t*>(a + kActZeroBytes / 2 + act_granule(m, c / 8, C) * 8 + (c % 8)) = pk;
 }

@@ -47,11 +47,11 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
   };
   p->off_stats = take((size_t)p->B * p->F * p->G * 2 * sizeof(float));
   p->off_emb = take((size_t)p->B * C * sizeof(float));
-  // one window's intermediates: the fp16 operand of either convolution, the fp32 output of the first
+  // one window's intermediates: the fp16 operand of either convolution, the fp16 output of the first
   // one, the second GroupNorm's statistics
   if ((double)p->Mmax * (double)C * 2.0 + 4096.0 >= 4294967296.0) return SI_ERR_SHAPE;  // 32-bit operand offsets
   p->off_a = take(kActZeroBytes + (size_t)((p->Mmax + 31) / 32 * 32) * C * 2);
-  p->off_h = take((size_t)p->Mmax * C * sizeof(float));
+  p->off_h = take((size_t)p->Mmax * C * 2);
   p->off_stats2 = take((size_t)p->B * p->slice_len * p->G * 2 * sizeof(float));
   p->off_part = take((size_t)p->B * p->slice_len * (size_t)((P + kGnChunk - 1) / kGnChunk) * C * 2 * sizeof(float));
   const int64_t n_slices = (p->F + p->slice_len - 1) / p->slice_len;
@@ -130,7 +130,7 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
     pack_conv_kernel<<<blocks, 256, 0, st0>>>(cB(w->w_conv2), w2, C, C, p.TN, p.ncol, nullptr, nullptr);
     SI_CHECK_LAUNCH();
     if (emb) {
-      temb_proj_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)p.B), 256, 0, st0>>>(cB(temb), cB(w->w_temb),
+      temb_proj_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)p.B), 1024, 0, st0>>>(cB(temb), cB(w->w_temb),
                                                                                           cB(w->b_temb), emb, p.Kt, C);
       SI_CHECK_LAUNCH();
     }
@@ -158,7 +158,7 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
     hipStream_t st = lane_id ? aux->stream : st0;
     char* lane_ws = ws + (size_t)lane_id * p.lane_stride;
     _Float16* a = reinterpret_cast<_Float16*>(lane_ws + p.off_a);
-    float* h = reinterpret_cast<float*>(lane_ws + p.off_h);
+    _Float16* h = reinterpret_cast<_Float16*>(lane_ws + p.off_h);
     float* stats2 = reinterpret_cast<float*>(lane_ws + p.off_stats2);
     float* part = reinterpret_cast<float*>(lane_ws + p.off_part);
     const int Fw = (int)((f0 + p.slice_len <= p.F) ? p.slice_len : p.F - f0);
@@ -190,7 +190,7 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
       SI_CHECK_LAUNCH();
     }
     {
-      EpiSliceOut<bf16> epi{X, OUT, cB(w->b_conv2), win};
+      EpiSliceOutRows epi{X, OUT, cB(w->b_conv2), win};
       SI_TRY(launch_conv3x3("conv2", p, a, w2, M, epi, st));
     }
   }
