@@ -22,4 +22,5 @@ from .rehash_ref import (  # noqa: F401
 )
 from .resblock_ref import (  # noqa: F401
     silu_ref, conv3x3_ref, resblock_forward_ref, sliced_resblock_forward_ref,
+    downsample_ref, upsample_ref, sliced_resample_ref,
 )

@@ -90,3 +90,32 @@ def sliced_resblock_forward_ref(x, w: dict, hp, temb, slice_len: int):
     for f0, f1 in slice_windows_ref(x.shape[2], slice_len):
         out[:, :, f0:f1] = resblock_forward_ref(x[:, :, f0:f1], w, hp, temb)
     return out
+
+
+def downsample_ref(x, weight, bias=None):
+    """Spatial DownSample of the group (Sec. 4.2.1 names the operator only; reading: the strided
+    convolution of the latent-diffusion U-Nets): 3x3 convolution with zero padding 1 and stride 2,
+    out[n, o, y, x] = bias[o] + sum weight[o, c, i, j] * a[n, c, 2y + i - 1, 2x + j - 1], i.e. the
+    stride-1 convolution sampled at even pixels.  x: [B,C,F,H,W] -> [B,O,F,ceil(H/2),ceil(W/2)]."""
+    x = np.asarray(x, F64)
+    B, C, Fr, H, W = x.shape
+    full = conv3x3_ref(_frames_first(x), weight, bias)
+    return _frames_back(full[:, :, ::2, ::2], B, Fr)
+
+
+def upsample_ref(x, weight, bias=None):
+    """Spatial UpSample (reading: nearest-neighbour doubling followed by a 3x3 convolution, zero
+    padding 1): u[n, c, Y, X] = a[n, c, Y // 2, X // 2]; out = Conv3x3(u) + bias.
+    x: [B,C,F,H,W] -> [B,O,F,2H,2W]."""
+    x = np.asarray(x, F64)
+    B, C, Fr, H, W = x.shape
+    u = np.repeat(np.repeat(_frames_first(x), 2, axis=2), 2, axis=3)
+    return _frames_back(conv3x3_ref(u, weight, bias), B, Fr)
+
+
+def sliced_resample_ref(x, weight, bias, kind: str, slice_len: int):
+    """Eq. 1 along frames for the resampling operators (each frame is independent)."""
+    x = np.asarray(x, F64)
+    fn = downsample_ref if kind == "down" else upsample_ref
+    parts = [fn(x[:, :, f0:f1], weight, bias) for f0, f1 in slice_windows_ref(x.shape[2], slice_len)]
+    return np.concatenate(parts, axis=2)

@@ -150,3 +150,41 @@ def test_frames_are_independent_and_flop_count():
     assert np.array_equal(full[:, :, 0], again[:, :, 0]) and not np.allclose(full[:, :, 1], again[:, :, 1])
     r4 = wl.RES_CONFIGS["res4"]
     assert r4.flops() == pytest.approx(2 * 2 * 2 * 25 * 9216 * 9 * 320 * 320 + 2 * 2 * 1280 * 320)
+
+
+def test_resample_matches_library_operators():
+    import torch
+    import torch.nn.functional as Fn
+    rng = np.random.default_rng(5)
+    for (H, W) in [(6, 8), (7, 5), (1, 1), (2, 3)]:
+        x = rng.standard_normal((2, 3, 2, H, W)); w = rng.standard_normal((4, 3, 3, 3)); b = rng.standard_normal(4)
+        xf = torch.from_numpy(x).permute(0, 2, 1, 3, 4).reshape(4, 3, H, W)
+        down = Fn.conv2d(xf, torch.from_numpy(w), torch.from_numpy(b), stride=2, padding=1)
+        got = oracle.downsample_ref(x, w, b)
+        assert got.shape == (2, 4, 2, (H + 1) // 2, (W + 1) // 2)
+        assert np.allclose(got, down.reshape(2, 2, 4, *down.shape[2:]).permute(0, 2, 1, 3, 4).numpy(), atol=1e-12)
+        up = Fn.conv2d(Fn.interpolate(xf, scale_factor=2, mode="nearest"), torch.from_numpy(w), torch.from_numpy(b), padding=1)
+        got = oracle.upsample_ref(x, w, b)
+        assert got.shape == (2, 4, 2, 2 * H, 2 * W)
+        assert np.allclose(got, up.reshape(2, 2, 4, 2 * H, 2 * W).permute(0, 2, 1, 3, 4).numpy(), atol=1e-12)
+
+
+def test_resample_closed_forms_and_slicing():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((1, 2, 3, 4, 6))
+    eye = np.zeros((2, 2, 3, 3)); eye[np.arange(2), np.arange(2), 1, 1] = 1.0
+    assert np.array_equal(oracle.downsample_ref(x, eye), x[:, :, :, ::2, ::2])             # centre tap: even pixels
+    up = oracle.upsample_ref(x, eye)
+    assert np.array_equal(up[:, :, :, 1::2, 0::2], x) and np.array_equal(up[:, :, :, 0::2, 1::2], x)   # each pixel four times
+    right = np.zeros((2, 2, 3, 3)); right[np.arange(2), np.arange(2), 1, 2] = 1.0           # tap (0, +1)
+    d = oracle.downsample_ref(x, right)
+    assert np.array_equal(d, x[:, :, :, ::2, 1::2])                                         # reads pixel (2y, 2x+1)
+    u = oracle.upsample_ref(x, right)
+    assert np.array_equal(u[:, :, :, :, :-1], np.repeat(np.repeat(x, 2, 3), 2, 4)[:, :, :, :, 1:]) and not u[:, :, :, :, -1].any()
+    box = np.ones((1, 2, 3, 3)); ones = np.ones((1, 2, 1, 4, 4))
+    assert oracle.downsample_ref(ones, box)[0, 0, 0].tolist() == [[8.0, 12.0], [12.0, 18.0]]   # neighbours inside, 2 channels
+    assert oracle.upsample_ref(ones, box)[0, 0, 0, 0, 0] == 8.0 and oracle.upsample_ref(ones, box)[0, 0, 0, 3, 3] == 18.0
+    w = rng.standard_normal((3, 2, 3, 3)); b = rng.standard_normal(3)
+    for kind, fn in (("down", oracle.downsample_ref), ("up", oracle.upsample_ref)):
+        for sl in (1, 2, 3):
+            assert np.array_equal(oracle.sliced_resample_ref(x, w, b, kind, sl), fn(x, w, b))
