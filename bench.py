@@ -218,13 +218,79 @@ def main_resblock(args):
     print(json.dumps(result))
 
 
+def main_resample(args):
+    """Spatial Down/UpSample of the ResBlock group on the ResBlock workloads' features (down4, up4b)."""
+    import numpy as np
+    import torch
+    import paper_2411_01171_amd as si
+    import si_workloads as wl
+    from gpu_helpers import to_dev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    kind = "down" if args.workload.startswith("down") else "up"
+    spec = wl.RES_CONFIGS["res4" if kind == "down" else "res4b"]
+    slice_len = args.slice_len or spec.slice_len
+    x_np = wl.make_x(spec)
+    x = to_dev(x_np, "bf16")
+    rng = np.random.default_rng(spec.seed + 50)
+    w_np = wl.round_to_storage(0.02 * rng.standard_normal((spec.C, spec.C, 3, 3), dtype=np.float32), "bf16")
+    w = to_dev(w_np, "bf16")
+    k = si.SI_RESAMPLE_DOWN if kind == "down" else si.SI_RESAMPLE_UP
+    Ho, Wo = ((spec.H + 1) // 2, (spec.W + 1) // 2) if kind == "down" else (2 * spec.H, 2 * spec.W)
+    out = torch.empty((spec.B, spec.C, spec.F, Ho, Wo), dtype=torch.bfloat16, device="cuda")
+    ws_bytes = si.si_resample_workspace_bytes(x, k, slice_len)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+    def step():
+        si.si_resample_forward(x, k, w, None, out, slice_len, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    M_out = spec.B * spec.F * Ho * Wo
+    flops = 2.0 * M_out * 9 * spec.C * spec.C
+    si.si_stage_timing_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    stages = si.si_stage_timing_read()
+    si.si_stage_timing_enable(False)
+    conv = "conv_down" if kind == "down" else "conv_up"
+    n_slices = -(-spec.F // slice_len)
+    w_flops = 2.0 * (M_out // spec.F) * min(slice_len, spec.F) * 9 * spec.C * spec.C
+    stage_report = {n: {"avg_us": round(ms / c * 1e3, 2), "launches_per_step": c / args.steps, "ms_per_step": round(ms / args.steps, 4)}
+                    for n, (ms, c) in stages.items()}
+    c_ms, c_cnt = stages[conv]
+    ach = w_flops / (c_ms / c_cnt * 1e-3) / 1e12
+    stage_report[conv]["TFLOP/s"] = round(ach, 2)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "sliced block-forward TFLOP/s (% MFMA peak) + peak live activation bytes vs unsliced",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: Spatial {kind}-sample (3x3 convolution) of x[B={spec.B},C={spec.C},F={spec.F},H={spec.H},"
+                               f"W={spec.W}] -> {Ho}x{Wo}, sliced along frames in windows of {slice_len} ({n_slices} slices)",
+                   "algorithmic_flop_per_step": flops},
+        "frac_mfma_peak": value / PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": conv, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "avg_launch_us": c_ms / c_cnt * 1e3,
+                     "algorithmic_flop_per_launch": w_flops},
+        "stages": stage_report}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", help="cfg2 (default, the metric's configuration), cfg3, cfg4s, cfg4t, cfg5s, cfg5t; res4, res4b "
-                         "(Spatial ResBlock group)")
+                         "(Spatial ResBlock group); down4, up4b (its Down/UpSample)")
     ap.add_argument("--slice-len", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rehash-probe", choices=["reuse", "compute"], default=None,
@@ -242,6 +308,8 @@ def main():
 
     if args.workload.startswith("res"):
         return main_resblock(args)
+    if args.workload in ("down4", "up4b"):
+        return main_resample(args)
 
     import numpy as np
     import torch

@@ -238,6 +238,22 @@ size_t si_resblock_live_activation_bytes(const si_tensor5* x, const si_resblock_
 si_status si_resblock_forward(const si_tensor5* x, const si_resblock_weights* w, const void* temb, si_tensor5* out,
                               int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Spatial Up/DownSample of the ResBlock group (Sec. 4.2.1 names the operators;
+ * the definitions taken are those of the latent-diffusion U-Nets), sliced along
+ * frames like si_resblock_forward:
+ *   SI_RESAMPLE_DOWN  out = Conv3x3(x), zero padding 1, stride 2:
+ *                     out[.., y, x] = b + sum w[o,c,i,j] * x[.., 2y+i-1, 2x+j-1];
+ *                     out is [B,C,F,ceil(H/2),ceil(W/2)]
+ *   SI_RESAMPLE_UP    out = Conv3x3(u) + b, zero padding 1, u[.., Y, X] = x[.., Y/2, X/2]
+ *                     (nearest-neighbour doubling); out is [B,C,F,2H,2W]
+ * x, out bf16, C a multiple of 32; w_conv [C, C, 3, 3] and b_conv (may be NULL)
+ * device bf16.  Operands stay bf16 (exact), accumulation is fp32, one rounding
+ * of the result.  Workspace and error behaviour as si_resblock_forward. */
+typedef enum { SI_RESAMPLE_DOWN = 0, SI_RESAMPLE_UP = 1 } si_resample_kind;
+size_t si_resample_workspace_bytes(const si_tensor5* x, int32_t kind, int64_t slice_len);
+si_status si_resample_forward(const si_tensor5* x, int32_t kind, const void* w_conv, const void* b_conv, si_tensor5* out,
+                              int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Key-step search, Algorithm 1 (Appendix B).  Host only.
  *   S      host, row-major K x K similarity map; only S[i][anchor] entries are read
  *   gamma  threshold, must satisfy gamma <= 1 and gamma <= S[i][i] where visited

@@ -88,6 +88,10 @@ def lib() -> C.CDLL:
     L.si_resblock_live_activation_bytes.argtypes = L.si_resblock_workspace_bytes.argtypes
     L.si_resblock_forward.restype = i32
     L.si_resblock_forward.argtypes = [C.POINTER(_Tensor5), C.POINTER(_ResWeights), vp, C.POINTER(_Tensor5), i64, vp, sz, vp]
+    L.si_resample_workspace_bytes.restype = sz
+    L.si_resample_workspace_bytes.argtypes = [C.POINTER(_Tensor5), i32, i64]
+    L.si_resample_forward.restype = i32
+    L.si_resample_forward.argtypes = [C.POINTER(_Tensor5), i32, vp, vp, C.POINTER(_Tensor5), i64, vp, sz, vp]
     L.si_rehash_scratch_bytes.restype = sz
     L.si_rehash_scratch_bytes.argtypes = [i64]
     L.si_rehash_check.restype = i32
@@ -231,6 +235,26 @@ def si_resblock_forward(x, weights: ResBlockWeights, temb, out, slice_len: int, 
                                    workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if st != 0:
         raise SiError(st, "si_resblock_forward")
+
+
+SI_RESAMPLE_DOWN, SI_RESAMPLE_UP = 0, 1
+
+
+def si_resample_workspace_bytes(x, kind: int, slice_len: int) -> int:
+    xd = _tensor5(x)
+    return int(lib().si_resample_workspace_bytes(C.byref(xd), kind, slice_len))
+
+
+def si_resample_forward(x, kind: int, w_conv, b_conv, out, slice_len: int, workspace, stream=None) -> None:
+    """Enqueues the sliced Spatial Down/UpSample (3x3 convolution, stride 2 / after nearest doubling)."""
+    xd, od = _tensor5(x), _tensor5(out)
+    if not w_conv.is_contiguous() or (b_conv is not None and not b_conv.is_contiguous()):
+        raise ValueError("parameters must be contiguous")
+    st = lib().si_resample_forward(C.byref(xd), kind, w_conv.data_ptr(), None if b_conv is None else b_conv.data_ptr(),
+                                   C.byref(od), slice_len, workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if st != 0:
+        raise SiError(st, "si_resample_forward")
 
 
 class RehashCache:

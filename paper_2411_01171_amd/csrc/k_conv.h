@@ -35,12 +35,18 @@ __host__ __device__ __forceinline__ int64_t act_granule(int64_t t, int c8, int C
   return ((t >> 5) * (C / 16) + (c8 >> 1)) * 64 + (c8 & 1) * 32 + (t & 31);
 }
 
+enum ConvMode { kConvSame = 0, kConvStride2 = 1, kConvNearestUp = 2 };
+
 struct ConvArgs {
-  const char* act;  // zero block + fragment-ordered fp16 activation of the window
-  const char* wf;   // fragment-ordered fp16 kernel
-  int64_t M;        // tokens of the window; token m = img*H*W + y*W + x
-  int C, O, H, W;
+  const char* act;  // zero block + fragment-ordered 16-bit activation of the window (source map)
+  const char* wf;   // fragment-ordered 16-bit kernel
+  int64_t M;        // output tokens of the window; token m = img*H*W + y*W + x
+  int C, O, H, W;   // input / output channels, output map
   int ncol, ntiles;  // column tiles, row tiles * column tiles
+  int Hi, Wi;       // source map: (H, W) for kConvSame; the larger map for kConvStride2 (output pixel (y, x),
+                    // tap (dy, dx) reads source (2y+dy, 2x+dx)); the smaller one for kConvNearestUp (reads
+                    // source ((y+dy)/2, (x+dx)/2) when (y+dy, x+dx) lies inside the output map)
+  int mode;
 };
 
 // acc[m, o] = sum_{tap, c} a[m + dy*W + dx, c] * w[o, c, tap] over the taps whose source pixel lies
@@ -53,7 +59,8 @@ struct ConvArgs {
 // fragment: same source, same destination) so that one s_waitcnt immediate closes a stage; stages
 // beyond the last k-tile read the zero block into a slot nobody reads any more.  The loads are inline assembly (the compiler would otherwise wait for all of them
 // before every LDS read); no compiler-visible vector-memory load sits inside the k loop.
-template <int TM, int TN, int STAGES, class Epi>
+// F16: operands are fp16 (v_mfma_f32_32x32x16_f16), else bf16 (v_mfma_f32_32x32x16_bf16).
+template <int TM, int TN, int STAGES, bool F16, class Epi>
 __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi) {
   constexpr int AF = 4 * TM * 2, WFR = 2 * TN;           // fragments per stage
   constexpr int NW = (WFR + 3) / 4;                      // weight loads per wavefront per stage
@@ -77,12 +84,13 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi
   const int per_tap = a.C / 32, nkt = 9 * per_tap;
 
   int py[TM], px[TM];
-  int64_t tok[TM];
+  int64_t tok[TM], img0[TM];  // img0: first source token of the token's image
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
     tok[j] = m0 + (wave * TM + j) * 32 + trow;
     const int p = (int)(tok[j] % P);
-    py[j] = tok[j] < a.M ? p / a.W : -4;  // -4: no tap is ever inside
+    img0[j] = (tok[j] / P) * ((int64_t)a.Hi * a.Wi);
+    py[j] = tok[j] < a.M ? p / a.W : -100000;  // far outside: no tap is ever inside
     px[j] = p % a.W;
   }
   const unsigned ring_lds = (unsigned)(size_t)(__attribute__((address_space(3))) void*)ring;
@@ -93,8 +101,22 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi
     const int dy = tap / 3 - 1, dx = tap % 3 - 1;
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
-      const bool in = (unsigned)(py[j] + dy) < (unsigned)a.H && (unsigned)(px[j] + dx) < (unsigned)a.W;
-      const int64_t src = tok[j] + dy * a.W + dx;
+      int sy, sx;
+      bool in;
+      if (a.mode == kConvStride2) {
+        sy = 2 * py[j] + dy;
+        sx = 2 * px[j] + dx;
+        in = (unsigned)sy < (unsigned)a.Hi && (unsigned)sx < (unsigned)a.Wi;
+      } else if (a.mode == kConvNearestUp) {
+        in = (unsigned)(py[j] + dy) < (unsigned)a.H && (unsigned)(px[j] + dx) < (unsigned)a.W;
+        sy = (py[j] + dy) >> 1;
+        sx = (px[j] + dx) >> 1;
+      } else {
+        sy = py[j] + dy;
+        sx = px[j] + dx;
+        in = (unsigned)sy < (unsigned)a.Hi && (unsigned)sx < (unsigned)a.Wi;
+      }
+      const int64_t src = img0[j] + (int64_t)sy * a.Wi + sx;
       tapv[j] = in ? (unsigned)(kActZeroBytes + 16 * (((src >> 5) * (a.C / 16)) * 64 + half * 32 + (src & 31))) : 0u;
     }
   };
@@ -146,15 +168,22 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi
     const char* slot = ring + (kt % STAGES) * SLOT;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      f16x8_t wf[TN], af[TM];
+      u32x4_t wf[TN], af[TM];
 #pragma unroll
-      for (int i = 0; i < TN; ++i) wf[i] = *reinterpret_cast<const f16x8_t*>(slot + (AF + ks * TN + i) * 1024 + lane * 16);
+      for (int i = 0; i < TN; ++i) wf[i] = *reinterpret_cast<const u32x4_t*>(slot + (AF + ks * TN + i) * 1024 + lane * 16);
 #pragma unroll
-      for (int j = 0; j < TM; ++j) af[j] = *reinterpret_cast<const f16x8_t*>(slot + ((wave * TM + j) * 2 + ks) * 1024 + lane * 16);
+      for (int j = 0; j < TM; ++j) af[j] = *reinterpret_cast<const u32x4_t*>(slot + ((wave * TM + j) * 2 + ks) * 1024 + lane * 16);
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int j = 0; j < TM; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[i], af[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TM; ++j) {
+          if constexpr (F16)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, wf[i]), __builtin_bit_cast(f16x8_t, af[j]),
+                                                               acc[i][j], 0, 0, 0);
+          else
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[i]), __builtin_bit_cast(bf16x8_t, af[j]),
+                                                                acc[i][j], 0, 0, 0);
+        }
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0070 | 0xF00);  // vmcnt(0): the padding loads of the last stages
@@ -268,11 +297,44 @@ struct EpiSliceOutRows {
   }
 };
 
-// Kernel [O, C, 3, 3] (bf16) -> fp16 fragment stream for column tiles of TN*32 output channels:
+// out[b, n, f, p] = acc + bias[n] for 8 consecutive tokens of the window (no residual): the
+// resampling operators' output.  Same addressing as EpiSliceOutRows, w describes the OUTPUT tensor.
+struct EpiStoreRows {
+  static constexpr bool kRows8 = true;
+  bf16* out;
+  const bf16* bias;
+  Window w;
+  __device__ __forceinline__ void operator()(int64_t, int, const float (&)[4]) const {}
+  __device__ __forceinline__ void rows8(int64_t m, int n, const float (&v)[8], int64_t M) const {
+    const float bn = param_or(bias, n, 0.f);
+    const int pl = (int)(m % w.Pw);
+    const int64_t bf = m / w.Pw;
+    const int64_t off = (((bf / w.Fw) * w.C + n) * w.F + (w.f0 + (int)(bf % w.Fw))) * w.P + w.p0 + pl;
+    if (pl + 7 < w.Pw && m + 7 < M && ((w.P | w.p0 | pl) & 7) == 0) {
+      unsigned ow[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        ow[i] = (unsigned)float_to_bf16_bits(v[2 * i] + bn) | ((unsigned)float_to_bf16_bits(v[2 * i + 1] + bn) << 16);
+      *reinterpret_cast<uint4*>(out + off) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    } else {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int64_t mt = m + t;
+        if (mt >= M) break;
+        const int plt = (int)(mt % w.Pw);
+        const int64_t bft = mt / w.Pw;
+        out[(((bft / w.Fw) * w.C + n) * w.F + (w.f0 + (int)(bft % w.Fw))) * w.P + w.p0 + plt] = from_float<bf16>(v[t] + bn);
+      }
+    }
+  }
+};
+
+// Kernel [O, C, 3, 3] (bf16) -> fp16 (F16) or bf16 fragment stream for column tiles of TN*32 output channels:
 // element e of lane l of fragment ((col*nkt + kt)*2 + ks)*TN + i is w[o, c, tap] with
 // o = (col*TN + i)*32 + l%32, tap = kt / (C/32), c = (kt % (C/32))*32 + ks*16 + (l/32)*8 + e; rows
 // beyond O are zero.  One thread per element.  Block 0 also clears the activation buffers' zero blocks.
-__global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__ src, _Float16* __restrict__ dst, int O, int C,
+template <bool F16>
+__global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__ src, unsigned short* __restrict__ dst, int O, int C,
                                                         int TN, int ncol, unsigned* __restrict__ zero0, unsigned* __restrict__ zero1) {
   if (blockIdx.x == 0 && threadIdx.x < kActZeroBytes / 4) {
     if (zero0) zero0[threadIdx.x] = 0u;
@@ -290,7 +352,13 @@ __global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__
   const int col = (int)(f / nkt);
   const int o = (col * TN + i) * 32 + l % 32;
   const int tap = kt / per_tap, c = (kt % per_tap) * 32 + ks * 16 + (l / 32) * 8 + e;
-  dst[idx] = o < O ? (_Float16)to_float(src[((int64_t)o * C + c) * 9 + tap]) : (_Float16)0.f;
+  unsigned short bits = 0;
+  if (o < O) {
+    const bf16 v = src[((int64_t)o * C + c) * 9 + tap];
+    if constexpr (F16) bits = __builtin_bit_cast(unsigned short, (_Float16)to_float(v));
+    else bits = v.v;
+  }
+  dst[idx] = bits;
 }
 
 // e[b, o] = b_t[o] + sum_k SiLU(temb[b, k]) * W_t[k, o].  One block (16 wavefronts) per (64 outputs,
@@ -417,9 +485,11 @@ __global__ __launch_bounds__(256) void gn_silu_tokens_kernel(const _Float16* __r
 // Slice-in of the ResBlock: a(m, c) = fp16(SiLU(GroupNorm1(x)[b, c, f, p])) in fragment order for the
 // window's tokens m = (b*Fw + f - f0)*P + p.  64 x 64 (position x channel) tiles are transposed through LDS: 8-byte
 // reads along positions, 16-byte writes along channels.  C % 8 == 0.
+// RAW: no normalisation and no activation, the bf16 values are copied (operand of the resampling convolutions).
+template <bool RAW>
 __global__ __launch_bounds__(256) void window_to_tokens_silu_kernel(const bf16* __restrict__ x, const float* __restrict__ stats,
                                                                     const bf16* __restrict__ gamma, const bf16* __restrict__ beta,
-                                                                    _Float16* __restrict__ a, Window w) {
+                                                                    unsigned short* __restrict__ a, Window w) {
   __shared__ float tile[64][65];
   const int bf = blockIdx.z;
   const int b = bf / w.Fw, fl = bf % w.Fw, f = w.f0 + fl;
@@ -432,10 +502,13 @@ __global__ __launch_bounds__(256) void window_to_tokens_silu_kernel(const bf16* 
     const int c = ct + cl, pl = pt + pq;
     float v[4] = {0.f, 0.f, 0.f, 0.f};
     if (c < w.C && pl < w.Pw) {
-      const int g = c / ng;
-      const float mean = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 0];
-      const float rstd = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 1];
-      const float ga = param_or(gamma, c, 1.f) * rstd, be = param_or(beta, c, 0.f);
+      float mean = 0.f, ga = 1.f, be = 0.f;
+      if constexpr (!RAW) {
+        const int g = c / ng;
+        mean = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 0];
+        ga = param_or(gamma, c, 1.f) * stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 1];
+        be = param_or(beta, c, 0.f);
+      }
       const bf16* src = x + (((int64_t)b * w.C + c) * w.F + f) * w.P + w.p0 + pl;
       float xv[4] = {0.f, 0.f, 0.f, 0.f};
       if (vec_ok && pl + 3 < w.Pw) {
@@ -450,7 +523,7 @@ __global__ __launch_bounds__(256) void window_to_tokens_silu_kernel(const bf16* 
           if (pl + j < w.Pw) xv[j] = to_float(src[j]);
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = silu((xv[j] - mean) * ga + be);
+      for (int j = 0; j < 4; ++j) v[j] = RAW ? xv[j] : silu((xv[j] - mean) * ga + be);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) tile[cl][pq + j] = v[j];
@@ -461,10 +534,14 @@ __global__ __launch_bounds__(256) void window_to_tokens_silu_kernel(const bf16* 
     const int id = threadIdx.x + i * 256, pl = id / 8, co = (id % 8) * 8;
     const int p = pt + pl, c = ct + co;
     if (p < w.Pw && c < w.C) {
-      f16x8_t o;
+      typedef unsigned short u16x8_t __attribute__((ext_vector_type(8)));
+      u16x8_t o;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) o[j] = (_Float16)tile[co + j][pl];
-      *reinterpret_cast<f16x8_t*>(a + kActZeroBytes / 2 + act_granule((int64_t)bf * w.Pw + p, c / 8, w.C) * 8) = o;
+      for (int j = 0; j < 8; ++j) {
+        if constexpr (RAW) o[j] = float_to_bf16_bits(tile[co + j][pl]);
+        else o[j] = __builtin_bit_cast(unsigned short, (_Float16)tile[co + j][pl]);
+      }
+      *reinterpret_cast<u16x8_t*>(a + kActZeroBytes / 2 + act_granule((int64_t)bf * w.Pw + p, c / 8, w.C) * 8) = o;
     }
   }
 }

@@ -20,6 +20,8 @@ struct ResPlan {
   size_t weights_bytes, total_bytes;
 };
 
+static void conv_column_tiles(int O, int* TN, int* ncol);
+
 static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w, int64_t slice_len, ResPlan* p) {
   if (!x || !w) return SI_ERR_NULL;
   if (x->dtype != SI_BF16) return SI_ERR_DTYPE;
@@ -59,16 +61,7 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
   p->lane_stride = off - p->off_a;
   if (p->lanes == 2) take(p->lane_stride);
   const size_t act_end = off;
-  // column tile width: the candidate that pads the output channels least, the wider one on a tie
-  p->TN = 1;
-  p->ncol = p->C / 32;
-  for (int tn : {2, 4, 5}) {
-    const int nc = (p->C + 32 * tn - 1) / (32 * tn);
-    if (nc * tn <= p->ncol * p->TN) {
-      p->TN = tn;
-      p->ncol = nc;
-    }
-  }
+  conv_column_tiles(p->C, &p->TN, &p->ncol);
   const size_t wbytes = (size_t)p->ncol * 9 * (C / 32) * 2 * p->TN * 1024;
   p->off_w1 = take(wbytes);
   p->off_w2 = take(wbytes);
@@ -77,30 +70,45 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
   return SI_OK;
 }
 
-template <int TM, int TN, int STAGES, class Epi>
+template <int TM, int TN, int STAGES, bool F16, class Epi>
 static void launch_conv_tile(const ConvArgs& a, Epi epi, hipStream_t st) {
   const int grid = (a.ntiles + 7) / 8 * 8;
-  conv3x3_dma_kernel<TM, TN, STAGES, Epi><<<grid, 256, 0, st>>>(a, epi);
+  conv3x3_dma_kernel<TM, TN, STAGES, F16, Epi><<<grid, 256, 0, st>>>(a, epi);
 }
 
-// Row tiles of 256 tokens when that still gives every CU two blocks, else 128 tokens.
-template <class Epi>
-static si_status launch_conv3x3(const char* stage, const ResPlan& p, const _Float16* act, const _Float16* wf, int64_t M, Epi epi,
-                                hipStream_t st) {
+// Column tiles of the convolution kernel: the candidate width that pads the output channels least,
+// the wider one on a tie.
+static void conv_column_tiles(int O, int* TN, int* ncol) {
+  *TN = 1;
+  *ncol = (O + 31) / 32;
+  for (int tn : {2, 4, 5}) {
+    const int nc = (O + 32 * tn - 1) / (32 * tn);
+    if (nc * tn <= *ncol * *TN) {
+      *TN = tn;
+      *ncol = nc;
+    }
+  }
+}
+
+// Row tiles of 256 tokens when that still gives every CU two blocks, else 128 tokens.  M output
+// tokens on an H x W map; (Hi, Wi, mode) describe the source map (see ConvArgs).
+template <bool F16, class Epi>
+static si_status launch_conv3x3(const char* stage, const void* act, const void* wf, int64_t M, int C, int TN, int ncol, int H,
+                                int W, int Hi, int Wi, int mode, Epi epi, hipStream_t st) {
   StageScope scope(stage, st);
-  ConvArgs a{reinterpret_cast<const char*>(act), reinterpret_cast<const char*>(wf), M, p.C, p.C, p.H, p.W, p.ncol, 0};
+  ConvArgs a{static_cast<const char*>(act), static_cast<const char*>(wf), M, C, C, H, W, ncol, 0, Hi, Wi, mode};
   const int64_t rows2 = (M + 255) / 256;
-  const bool big = rows2 * p.ncol >= SI_CONV_BIG_MIN;
-  a.ntiles = (int)((big ? rows2 : (M + 127) / 128) * p.ncol);
-  switch (p.TN * 2 + (big ? 1 : 0)) {
-    case 11: launch_conv_tile<2, 5, 3>(a, epi, st); break;
-    case 10: launch_conv_tile<1, 5, 4>(a, epi, st); break;
-    case 9: launch_conv_tile<2, 4, 3>(a, epi, st); break;
-    case 8: launch_conv_tile<1, 4, 4>(a, epi, st); break;
-    case 5: launch_conv_tile<2, 2, 4>(a, epi, st); break;
-    case 4: launch_conv_tile<1, 2, 4>(a, epi, st); break;
-    case 3: launch_conv_tile<2, 1, 4>(a, epi, st); break;
-    case 2: launch_conv_tile<1, 1, 4>(a, epi, st); break;
+  const bool big = rows2 * ncol >= SI_CONV_BIG_MIN;
+  a.ntiles = (int)((big ? rows2 : (M + 127) / 128) * ncol);
+  switch (TN * 2 + (big ? 1 : 0)) {
+    case 11: launch_conv_tile<2, 5, 3, F16>(a, epi, st); break;
+    case 10: launch_conv_tile<1, 5, 4, F16>(a, epi, st); break;
+    case 9: launch_conv_tile<2, 4, 3, F16>(a, epi, st); break;
+    case 8: launch_conv_tile<1, 4, 4, F16>(a, epi, st); break;
+    case 5: launch_conv_tile<2, 2, 4, F16>(a, epi, st); break;
+    case 4: launch_conv_tile<1, 2, 4, F16>(a, epi, st); break;
+    case 3: launch_conv_tile<2, 1, 4, F16>(a, epi, st); break;
+    case 2: launch_conv_tile<1, 1, 4, F16>(a, epi, st); break;
     default: return SI_ERR_SHAPE;
   }
   SI_CHECK_LAUNCH();
@@ -125,9 +133,10 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
     const unsigned blocks = (unsigned)((elems + 255) / 256);
     unsigned* z0 = reinterpret_cast<unsigned*>(ws + p.off_a);
     unsigned* z1 = p.lanes == 2 ? reinterpret_cast<unsigned*>(ws + p.off_a + p.lane_stride) : nullptr;
-    pack_conv_kernel<<<blocks, 256, 0, st0>>>(cB(w->w_conv1), w1, C, C, p.TN, p.ncol, z0, z1);
+    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv1), reinterpret_cast<unsigned short*>(w1), C, C, p.TN, p.ncol, z0, z1);
     SI_CHECK_LAUNCH();
-    pack_conv_kernel<<<blocks, 256, 0, st0>>>(cB(w->w_conv2), w2, C, C, p.TN, p.ncol, nullptr, nullptr);
+    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv2), reinterpret_cast<unsigned short*>(w2), C, C, p.TN, p.ncol, nullptr,
+                                                    nullptr);
     SI_CHECK_LAUNCH();
     if (emb) {
       temb_proj_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)p.B), 1024, 0, st0>>>(cB(temb), cB(w->w_temb),
@@ -167,12 +176,13 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
     {
       StageScope scope("slice_in", st);
       dim3 grid((unsigned)((p.P + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * Fw));
-      window_to_tokens_silu_kernel<<<grid, 256, 0, st>>>(X, stats, cB(w->gn1_g), cB(w->gn1_b), a, win);
+      window_to_tokens_silu_kernel<false><<<grid, 256, 0, st>>>(X, stats, cB(w->gn1_g), cB(w->gn1_b),
+                                                                reinterpret_cast<unsigned short*>(a), win);
       SI_CHECK_LAUNCH();
     }
     {
       EpiConvEmb epi{h, (int64_t)C, cB(w->b_conv1), emb, (int64_t)Fw * p.P};
-      SI_TRY(launch_conv3x3("conv1", p, a, w1, M, epi, st));
+      SI_TRY(launch_conv3x3<true>("conv1", a, w1, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
     }
     {
       StageScope scope("gn2_stats", st);
@@ -191,8 +201,101 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
     }
     {
       EpiSliceOutRows epi{X, OUT, cB(w->b_conv2), win};
-      SI_TRY(launch_conv3x3("conv2", p, a, w2, M, epi, st));
+      SI_TRY(launch_conv3x3<true>("conv2", a, w2, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
     }
+  }
+  if (lanes == 2) {
+    if (hipEventRecord(aux->join, aux->stream) != hipSuccess) return SI_ERR_HIP;
+    if (hipStreamWaitEvent(st0, aux->join, 0) != hipSuccess) return SI_ERR_HIP;
+  }
+  return SI_OK;
+}
+
+// ----------------------------------------------------------------------------- Up/DownSample
+
+struct ResamplePlan {
+  int B, C, F, Hi, Wi, Ho, Wo, mode, TN, ncol;
+  int64_t Pi, Po, slice_len, Mi_max;
+  int lanes;
+  size_t lane_stride, off_a, off_w, weights_bytes, total_bytes;
+};
+
+static si_status make_resample_plan(const si_tensor5* x, int32_t kind, int64_t slice_len, ResamplePlan* p) {
+  if (!x) return SI_ERR_NULL;
+  if (x->dtype != SI_BF16) return SI_ERR_DTYPE;
+  if (kind != SI_RESAMPLE_DOWN && kind != SI_RESAMPLE_UP) return SI_ERR_ARG;
+  if (x->B < 1 || x->C < 1 || x->F < 1 || x->H < 1 || x->W < 1) return SI_ERR_SHAPE;
+  if (x->C % 32 || x->C > 8192 || x->B > 65535 || x->F > 65535 || x->H > 4096 || x->W > 4096) return SI_ERR_SHAPE;
+  if (slice_len < 1) return SI_ERR_SLICE;
+  p->B = (int)x->B; p->C = (int)x->C; p->F = (int)x->F; p->Hi = (int)x->H; p->Wi = (int)x->W;
+  p->mode = kind == SI_RESAMPLE_DOWN ? kConvStride2 : kConvNearestUp;
+  p->Ho = kind == SI_RESAMPLE_DOWN ? (p->Hi + 1) / 2 : 2 * p->Hi;
+  p->Wo = kind == SI_RESAMPLE_DOWN ? (p->Wi + 1) / 2 : 2 * p->Wi;
+  p->Pi = (int64_t)p->Hi * p->Wi;
+  p->Po = (int64_t)p->Ho * p->Wo;
+  if ((double)p->B * p->C * p->F * (double)(p->Pi > p->Po ? p->Pi : p->Po) >= 1099511627776.0) return SI_ERR_SHAPE;
+  p->slice_len = slice_len < x->F ? slice_len : x->F;
+  p->Mi_max = (int64_t)p->B * p->slice_len * p->Pi;
+  if ((double)p->Mi_max * p->C * 2.0 + 4096.0 >= 4294967296.0) return SI_ERR_SHAPE;  // 32-bit operand offsets
+  if ((int64_t)p->B * p->slice_len * p->Po >= (1LL << 31) / 16) return SI_ERR_SHAPE;
+  conv_column_tiles(p->C, &p->TN, &p->ncol);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  p->off_a = take(kActZeroBytes + (size_t)((p->Mi_max + 31) / 32 * 32) * p->C * 2);
+  const int64_t n_slices = (p->F + p->slice_len - 1) / p->slice_len;
+  p->lanes = n_slices >= 8 ? 2 : 1;
+  p->lane_stride = off - p->off_a;
+  if (p->lanes == 2) take(p->lane_stride);
+  const size_t act_end = off;
+  p->off_w = take((size_t)p->ncol * 9 * (p->C / 32) * 2 * p->TN * 1024);
+  p->weights_bytes = off - act_end;
+  p->total_bytes = off;
+  return SI_OK;
+}
+
+static si_status run_resample(const ResamplePlan& p, const si_tensor5* x, const void* w_conv, const void* b_conv, si_tensor5* out,
+                              char* ws, hipStream_t st0) {
+  const bf16* X = static_cast<const bf16*>(x->ptr);
+  bf16* OUT = static_cast<bf16*>(out->ptr);
+  unsigned short* wf = reinterpret_cast<unsigned short*>(ws + p.off_w);
+  const int C = p.C;
+  {
+    StageScope scope("pack_weights", st0);
+    const int64_t elems = (int64_t)p.ncol * 9 * (C / 32) * 2 * p.TN * 512;
+    unsigned* z0 = reinterpret_cast<unsigned*>(ws + p.off_a);
+    unsigned* z1 = p.lanes == 2 ? reinterpret_cast<unsigned*>(ws + p.off_a + p.lane_stride) : nullptr;
+    pack_conv_kernel<false><<<(unsigned)((elems + 255) / 256), 256, 0, st0>>>(static_cast<const bf16*>(w_conv), wf, C, C, p.TN,
+                                                                             p.ncol, z0, z1);
+    SI_CHECK_LAUNCH();
+  }
+  AuxStream* aux = nullptr;
+  const int lanes = g_timing ? 1 : p.lanes;
+  if (lanes == 2) {
+    SI_TRY(aux_stream(&aux));
+    if (hipEventRecord(aux->fork, st0) != hipSuccess) return SI_ERR_HIP;
+    if (hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
+  }
+  int widx = 0;
+  for (int64_t f0 = 0; f0 < p.F; f0 += p.slice_len, ++widx) {
+    const int lane_id = lanes == 2 ? widx & 1 : 0;
+    hipStream_t st = lane_id ? aux->stream : st0;
+    unsigned short* a = reinterpret_cast<unsigned short*>(ws + p.off_a + (size_t)lane_id * p.lane_stride);
+    const int Fw = (int)((f0 + p.slice_len <= p.F) ? p.slice_len : p.F - f0);
+    Window win_in{p.B, C, p.F, p.Pi, (int)f0, Fw, 0, (int)p.Pi, 1};
+    Window win_out{p.B, C, p.F, p.Po, (int)f0, Fw, 0, (int)p.Po, 1};
+    {
+      StageScope scope("slice_in", st);
+      dim3 grid((unsigned)((p.Pi + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * Fw));
+      window_to_tokens_silu_kernel<true><<<grid, 256, 0, st>>>(X, nullptr, nullptr, nullptr, a, win_in);
+      SI_CHECK_LAUNCH();
+    }
+    EpiStoreRows epi{OUT, static_cast<const bf16*>(b_conv), win_out};
+    SI_TRY(launch_conv3x3<false>(p.mode == kConvStride2 ? "conv_down" : "conv_up", a, wf, (int64_t)p.B * Fw * p.Po, C, p.TN,
+                                 p.ncol, p.Ho, p.Wo, p.Hi, p.Wi, p.mode, epi, st));
   }
   if (lanes == 2) {
     if (hipEventRecord(aux->join, aux->stream) != hipSuccess) return SI_ERR_HIP;
@@ -204,6 +307,34 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
 }  // namespace si
 
 extern "C" {
+
+size_t si_resample_workspace_bytes(const si_tensor5* x, int32_t kind, int64_t slice_len) {
+  si::ResamplePlan p;
+  if (si::make_resample_plan(x, kind, slice_len, &p) != SI_OK) return 0;
+  return p.total_bytes;
+}
+
+si_status si_resample_forward(const si_tensor5* x, int32_t kind, const void* w_conv, const void* b_conv, si_tensor5* out,
+                              int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || !out) return SI_ERR_NULL;
+  si::ResamplePlan p;
+  si_status s = si::make_resample_plan(x, kind, slice_len, &p);
+  if (s != SI_OK) return s;
+  if (out->dtype != x->dtype) return SI_ERR_DTYPE;
+  if (out->B != x->B || out->C != x->C || out->F != x->F || out->H != p.Ho || out->W != p.Wo) return SI_ERR_SHAPE;
+  if (!x->ptr || !out->ptr || !workspace || !w_conv) return SI_ERR_NULL;
+  const void* all[] = {x->ptr, out->ptr, w_conv, b_conv};
+  for (const void* q : all)
+    if (q && !si::aligned16(q)) return SI_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SI_ERR_ALIGN;
+  if (workspace_bytes < p.total_bytes) return SI_ERR_WORKSPACE;
+  const size_t xbytes = (size_t)p.B * p.C * p.F * (size_t)p.Pi * 2, obytes = (size_t)p.B * p.C * p.F * (size_t)p.Po * 2;
+  if (si::ranges_overlap(x->ptr, xbytes, out->ptr, obytes)) return SI_ERR_ARG;
+  if (si::ranges_overlap(workspace, p.total_bytes, out->ptr, obytes) ||
+      si::ranges_overlap(workspace, p.total_bytes, x->ptr, xbytes))
+    return SI_ERR_ARG;
+  return si::run_resample(p, x, w_conv, b_conv, out, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
 
 size_t si_resblock_workspace_bytes(const si_tensor5* x, const si_resblock_weights* w, int64_t slice_len) {
   si::ResPlan p;

@@ -142,6 +142,28 @@ def test_resblock_validation_and_workspace():
     assert lib.si_resblock_live_activation_bytes(C.byref(x), C.byref(w), 100) == live8
 
 
+def test_resample_validation():
+    lib = si.lib()
+    fake = 0x10000
+    x = B._Tensor5(fake, B.SI_BF16, 2, 64, 4, 7, 10)
+    down = B._Tensor5(fake + (1 << 30), B.SI_BF16, 2, 64, 4, 4, 5)
+    up = B._Tensor5(fake + (1 << 30), B.SI_BF16, 2, 64, 4, 14, 20)
+
+    def call(kind, od, xd=x, w=fake + (2 << 30), slice_len=1, ws_bytes=1 << 40):
+        return lib.si_resample_forward(C.byref(xd), kind, w, None, C.byref(od), slice_len, 0x7000000000, ws_bytes, None)
+
+    assert lib.si_resample_workspace_bytes(C.byref(x), B.SI_RESAMPLE_DOWN, 1) > 0
+    assert lib.si_resample_workspace_bytes(C.byref(x), 5, 1) == 0
+    assert call(B.SI_RESAMPLE_DOWN, up) == 2 and call(B.SI_RESAMPLE_UP, down) == 2      # output map must match the kind
+    assert call(7, down) == 7
+    assert call(B.SI_RESAMPLE_DOWN, down, w=None) == 1
+    assert call(B.SI_RESAMPLE_DOWN, down, slice_len=0) == 4
+    assert call(B.SI_RESAMPLE_UP, up, ws_bytes=1024) == 6
+    assert call(B.SI_RESAMPLE_UP, up, xd=B._Tensor5(fake, B.SI_F32, 2, 64, 4, 7, 10)) == 3
+    assert call(B.SI_RESAMPLE_UP, up, xd=B._Tensor5(fake, B.SI_BF16, 2, 48, 4, 7, 10)) == 2
+    assert call(B.SI_RESAMPLE_DOWN, B._Tensor5(x.ptr + 256, B.SI_BF16, 2, 64, 4, 4, 5)) == 7   # out overlaps x
+
+
 def test_workspace_scales_with_the_slice():
     x, w, _, _ = _descs(Cn=320, heads=8, dh=40, groups=32, F=16, H=64, W=64)
     lib = si.lib()
