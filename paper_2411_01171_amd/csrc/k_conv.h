@@ -257,6 +257,26 @@ struct EpiConvEmb {
   }
 };
 
+// Same values, stored in the convolutions' fragment order (h points at the buffer's zero block):
+// the lanes l and l+32 of a store fill the two halves of one 16-byte granule, a wavefront's store
+// covers 32 consecutive granules.
+struct EpiConvEmbFrag {
+  static constexpr bool kRows8 = false;
+  _Float16* h;
+  int C;
+  const bf16* bias;
+  const float* e;
+  int64_t tokens_per_batch;
+  __device__ __forceinline__ void operator()(int64_t m, int n0, const float (&v)[4]) const {
+    const float* er = e ? e + (m / tokens_per_batch) * C + n0 : nullptr;
+    typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+    f16x4_t o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (_Float16)(v[i] + param_or(bias, n0 + i, 0.f) + (er ? er[i] : 0.f));
+    *reinterpret_cast<f16x4_t*>(h + kActZeroBytes / 2 + act_granule(m, n0 / 8, C) * 8 + (n0 % 8)) = o;
+  }
+};
+
 // Slice-out of the ResBlock: out[b, n, f, p] = x[b, n, f, p] + acc + bias[n] for 8 consecutive tokens
 // m .. m+7 of the window (token = (b*Fw + f - f0)*Pw + p); the sum is formed in fp32 and rounded once.
 // 16-byte accesses when the eight tokens are eight aligned positions of one image.
@@ -335,10 +355,13 @@ struct EpiStoreRows {
 // beyond O are zero.  One thread per element.  Block 0 also clears the activation buffers' zero blocks.
 template <bool F16>
 __global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__ src, unsigned short* __restrict__ dst, int O, int C,
-                                                        int TN, int ncol, unsigned* __restrict__ zero0, unsigned* __restrict__ zero1) {
-  if (blockIdx.x == 0 && threadIdx.x < kActZeroBytes / 4) {
+                                                        int TN, int ncol, unsigned* __restrict__ zero0, unsigned* __restrict__ zero1,
+                                                        int64_t zero_pair = 0) {
+  if (blockIdx.x == 0 && threadIdx.x < kActZeroBytes / 4) {  // zero_pair: a second buffer that many bytes further on
     if (zero0) zero0[threadIdx.x] = 0u;
     if (zero1) zero1[threadIdx.x] = 0u;
+    if (zero0 && zero_pair) zero0[zero_pair / 4 + threadIdx.x] = 0u;
+    if (zero1 && zero_pair) zero1[zero_pair / 4 + threadIdx.x] = 0u;
   }
   const int per_tap = C / 32, nkt = 9 * per_tap;
   const int64_t total = (int64_t)ncol * nkt * 2 * TN * 512;
@@ -443,7 +466,7 @@ __global__ __launch_bounds__(256) void gn_finish_tokens_kernel(const _Float16* _
     s1 = (sh[0][0][lane] + sh[0][1][lane]) + (sh[0][2][lane] + sh[0][3][lane]);
     s2 = (sh[1][0][lane] + sh[1][1][lane]) + (sh[1][2][lane] + sh[1][3][lane]);
     const double n = (double)P;
-    mean_c = (double)h[(int64_t)img * P * C + g * ng + lane] + s1 / n;
+    mean_c = (h ? (double)h[(int64_t)img * P * C + g * ng + lane] : 0.0) + s1 / n;  // h == NULL: sums were taken unshifted
     m2_c = s2 - s1 * s1 / n;   // sum of squared deviations from the channel's own mean
   }
   const double mean_g = wave_sum(lane < ng ? mean_c : 0.0) / (double)ng;
@@ -480,6 +503,112 @@ __global__ __launch_bounds__(256) void gn_silu_tokens_kernel(const _Float16* __r
   }
   f16x4_t pk = {(_Float16)o[0], (_Float16)o[1], (_Float16)o[2], (_Float16)o[3]};
   *reinterpret_cast<f16x4_t*>(a + kActZeroBytes / 2 + act_granule(m, c / 8, C) * 8 + (c % 8)) = pk;
+}
+
+// The same two steps for an intermediate held in fragment order (P % 32 == 0: a 32-token block never
+// straddles two images).  gn_partial_frag_kernel: block (chunk of kGnFragChunk token blocks, image,
+// 64 channels); wavefront w owns the 16-channel step 4*blockIdx.z + w, a lane accumulates its 8
+// channels over the chunk's token blocks (unshifted fp32 sums over at most 8 values per lane), the
+// 32 lanes of each half are then summed by shuffles.  Output layout as gn_partial_tokens_kernel.
+constexpr int kGnFragChunk = 8;
+
+__global__ __launch_bounds__(256) void gn_partial_frag_kernel(const _Float16* __restrict__ h, float* __restrict__ partial, int P,
+                                                              int C) {
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int chunk = blockIdx.x, img = blockIdx.y, nchunk = gridDim.x;
+  const int cs = blockIdx.z * 4 + wave;
+  if (cs >= C / 16) return;
+  const int tb_img = P / 32;
+  const int tb0 = chunk * kGnFragChunk;
+  const int tb1 = tb0 + kGnFragChunk < tb_img ? tb0 + kGnFragChunk : tb_img;
+  const f16x8_t* src = reinterpret_cast<const f16x8_t*>(h + kActZeroBytes / 2) + ((int64_t)img * tb_img * (C / 16) + cs) * 64 + lane;
+  float s1[8], s2[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s1[e] = s2[e] = 0.f;
+#pragma unroll
+  for (int t = 0; t < kGnFragChunk; ++t) {
+    if (tb0 + t < tb1) {
+      const f16x8_t v = src[(int64_t)(tb0 + t) * (C / 16) * 64];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float d = (float)v[e];
+        s1[e] += d;
+        s2[e] = fmaf(d, d, s2[e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int off = 1; off < 32; off <<= 1) {
+      s1[e] += __shfl_xor(s1[e], off);
+      s2[e] += __shfl_xor(s2[e], off);
+    }
+  if (lane % 32 == 0) {
+    float* o = partial + (((int64_t)img * nchunk + chunk) * C + cs * 16 + (lane / 32) * 8) * 2;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      o[2 * e] = s1[e];
+      o[2 * e + 1] = s2[e];
+    }
+  }
+}
+
+// In place: granule (token, 8 channels) -> fp16(SiLU((h - mean) * rstd * gamma + beta)); one thread per granule.
+__global__ __launch_bounds__(256) void gn_silu_frag_kernel(_Float16* __restrict__ h, const float* __restrict__ stats,
+                                                           const bf16* __restrict__ gamma, const bf16* __restrict__ beta, int64_t M,
+                                                           int P, int C, int G) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int lane = (int)(idx % 64);
+  const int64_t frag = idx / 64;
+  const int cs = (int)(frag % (C / 16));
+  const int64_t token = (frag / (C / 16)) * 32 + lane % 32;
+  if (token >= M) return;
+  const int c0 = cs * 16 + (lane / 32) * 8;
+  const int img = (int)(token / P);
+  const int ng = C / G;
+  f16x8_t* p = reinterpret_cast<f16x8_t*>(h + kActZeroBytes / 2) + idx;
+  const f16x8_t v = *p;
+  // the 8 channels lie in at most 8 consecutive groups; walk (group, position in group) instead of dividing per channel
+  int g = c0 / ng, r = c0 - g * ng;
+  const float2* st = reinterpret_cast<const float2*>(stats) + (int64_t)img * G;
+  float2 mr = st[g];
+  float ga[8], be[8];
+  if (gamma) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(gamma + c0);
+    const unsigned wv[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      ga[2 * i] = __uint_as_float(wv[i] << 16);
+      ga[2 * i + 1] = __uint_as_float(wv[i] & 0xffff0000u);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ga[e] = 1.f;
+  }
+  if (beta) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(beta + c0);
+    const unsigned wv[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      be[2 * i] = __uint_as_float(wv[i] << 16);
+      be[2 * i + 1] = __uint_as_float(wv[i] & 0xffff0000u);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) be[e] = 0.f;
+  }
+  f16x8_t o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    o[e] = (_Float16)silu(((float)v[e] - mr.x) * mr.y * ga[e] + be[e]);
+    if (++r == ng) {
+      r = 0;
+      ++g;
+      if (e < 7) mr = st[g];
+    }
+  }
+  *p = o;
 }
 
 // Slice-in of the ResBlock: a(m, c) = fp16(SiLU(GroupNorm1(x)[b, c, f, p])) in fragment order for the

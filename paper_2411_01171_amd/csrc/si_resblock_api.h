@@ -53,9 +53,9 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
   // one, the second GroupNorm's statistics
   if ((double)p->Mmax * (double)C * 2.0 + 4096.0 >= 4294967296.0) return SI_ERR_SHAPE;  // 32-bit operand offsets
   p->off_a = take(kActZeroBytes + (size_t)((p->Mmax + 31) / 32 * 32) * C * 2);
-  p->off_h = take((size_t)p->Mmax * C * 2);
+  p->off_h = take(kActZeroBytes + (size_t)((p->Mmax + 31) / 32 * 32) * C * 2);  // token-major or fragment order
   p->off_stats2 = take((size_t)p->B * p->slice_len * p->G * 2 * sizeof(float));
-  p->off_part = take((size_t)p->B * p->slice_len * (size_t)((P + kGnChunk - 1) / kGnChunk) * C * 2 * sizeof(float));
+  p->off_part = take((size_t)p->B * p->slice_len * (size_t)((P + 31) / 32) * C * 2 * sizeof(float));  // >= either chunking
   const int64_t n_slices = (p->F + p->slice_len - 1) / p->slice_len;
   p->lanes = n_slices >= 8 ? 2 : 1;  // two windows' buffers still stay within a quarter of the unsliced ones
   p->lane_stride = off - p->off_a;
@@ -133,7 +133,8 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
     const unsigned blocks = (unsigned)((elems + 255) / 256);
     unsigned* z0 = reinterpret_cast<unsigned*>(ws + p.off_a);
     unsigned* z1 = p.lanes == 2 ? reinterpret_cast<unsigned*>(ws + p.off_a + p.lane_stride) : nullptr;
-    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv1), reinterpret_cast<unsigned short*>(w1), C, C, p.TN, p.ncol, z0, z1);
+    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv1), reinterpret_cast<unsigned short*>(w1), C, C, p.TN, p.ncol, z0, z1,
+                                                    (int64_t)(p.off_h - p.off_a));
     SI_CHECK_LAUNCH();
     pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv2), reinterpret_cast<unsigned short*>(w2), C, C, p.TN, p.ncol, nullptr,
                                                     nullptr);
@@ -180,28 +181,48 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
                                                                 reinterpret_cast<unsigned short*>(a), win);
       SI_CHECK_LAUNCH();
     }
-    {
+    // The intermediate between the convolutions stays in fragment order when no 32-token block
+    // straddles two images: GroupNorm2 + SiLU then run in place on it and conv2 reads it as it is.
+    const bool frag_h = p.P % 32 == 0;
+    if (frag_h) {
+      EpiConvEmbFrag epi{h, C, cB(w->b_conv1), emb, (int64_t)Fw * p.P};
+      SI_TRY(launch_conv3x3<true>("conv1", a, w1, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
+    } else {
       EpiConvEmb epi{h, (int64_t)C, cB(w->b_conv1), emb, (int64_t)Fw * p.P};
       SI_TRY(launch_conv3x3<true>("conv1", a, w1, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
     }
     {
       StageScope scope("gn2_stats", st);
-      const int nchunk = (int)((p.P + kGnChunk - 1) / kGnChunk);
-      gn_partial_tokens_kernel<<<dim3((unsigned)nchunk, (unsigned)(p.B * Fw)), 256, 0, st>>>(h, part, (int)p.P, C);
-      SI_CHECK_LAUNCH();
-      gn_finish_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(h, part, stats2, (int)p.P, C, p.G, nchunk, w->gn_eps);
+      if (frag_h) {
+        const int nchunk = (int)((p.P / 32 + kGnFragChunk - 1) / kGnFragChunk);
+        gn_partial_frag_kernel<<<dim3((unsigned)nchunk, (unsigned)(p.B * Fw), (unsigned)((C / 16 + 3) / 4)), 256, 0, st>>>(
+            h, part, (int)p.P, C);
+        SI_CHECK_LAUNCH();
+        gn_finish_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(nullptr, part, stats2, (int)p.P, C, p.G, nchunk,
+                                                                            w->gn_eps);
+      } else {
+        const int nchunk = (int)((p.P + kGnChunk - 1) / kGnChunk);
+        gn_partial_tokens_kernel<<<dim3((unsigned)nchunk, (unsigned)(p.B * Fw)), 256, 0, st>>>(h, part, (int)p.P, C);
+        SI_CHECK_LAUNCH();
+        gn_finish_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(h, part, stats2, (int)p.P, C, p.G, nchunk, w->gn_eps);
+      }
       SI_CHECK_LAUNCH();
     }
     {
       StageScope scope("gn2_silu", st);
-      const int64_t n = M * (C / 4);
-      gn_silu_tokens_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(h, stats2, cB(w->gn2_g), cB(w->gn2_b), a, M, (int)p.P,
-                                                                         C, p.G);
+      if (frag_h) {
+        const int64_t n = (M + 31) / 32 * (C / 16) * 64;
+        gn_silu_frag_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(h, stats2, cB(w->gn2_g), cB(w->gn2_b), M, (int)p.P, C, p.G);
+      } else {
+        const int64_t n = M * (C / 4);
+        gn_silu_tokens_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(h, stats2, cB(w->gn2_g), cB(w->gn2_b), a, M, (int)p.P,
+                                                                           C, p.G);
+      }
       SI_CHECK_LAUNCH();
     }
     {
       EpiSliceOutRows epi{X, OUT, cB(w->b_conv2), win};
-      SI_TRY(launch_conv3x3<true>("conv2", a, w2, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
+      SI_TRY(launch_conv3x3<true>("conv2", frag_h ? h : a, w2, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
     }
   }
   if (lanes == 2) {

@@ -31,6 +31,8 @@ def _check(name, got, ref, x):
     (dict(C=64, F=2, H=33, W=5), 1),                    # narrow map: every row of pixels touches both side borders
     (dict(B=1, C=32, F=1, H=1, W=1, temb_dim=8), 1),    # a single pixel: only the centre tap is inside
     (dict(B=3, C=64, F=4, H=3, W=40), 3),
+    (dict(C=96, F=2, H=8, W=8), 1),                     # 64 pixels: the intermediate stays in fragment order
+    (dict(C=160, F=3, H=4, W=16, temb_dim=0), 2),
 ])
 def test_small_shapes_elementwise(kw, slice_len):
     from gpu_helpers import run_resblock
