@@ -1,4 +1,5 @@
-"""CPU oracle for the sliced transformer-block forward and the Step Rehash test.
+"""CPU oracle for the sliced transformer-block forward, the Step Rehash test and walks, and the
+Spatial ResBlock operator group with its Up/DownSample.
 
 TEST INFRASTRUCTURE ONLY.  Plain NumPy in float64, full tensors, one operator
 after the other, no blocking or fusion.  Nothing here is imported by the HIP

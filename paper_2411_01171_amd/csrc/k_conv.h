@@ -4,15 +4,21 @@
 // bits keep the operand rounding of two chained 9*C-term contractions well inside the error budget
 // that the final bf16 rounding of x + branch leaves.  bf16 kernels convert exactly unless a value
 // lies outside fp16's normal range (|w| < 6.1e-5 rounds to a multiple of 2^-24, |w| > 65504 overflows).
-//   conv3x3_dma_kernel      3x3 convolution (zero padding 1, stride 1) as an implicit GEMM on the
-//                           matrix cores; both operands arrive in MFMA fragment order by direct
-//                           global->LDS loads through a multi-stage ring                     [MFMA bound]
-//   pack_conv_kernel        [O, C, 3, 3] bf16 kernel -> fp16 fragment stream in the order the kernel reads
+// The resampling operators of the same group (stride-2 convolution, nearest doubling + convolution)
+// run on the raw bf16 feature with bf16 operands (exact).
+//   conv3x3_dma_kernel      3x3 convolution, zero padding 1 -- same map, stride 2, or after nearest
+//                           doubling -- as an implicit GEMM on the matrix cores; both operands arrive
+//                           in MFMA fragment order by direct global->LDS loads through a multi-stage
+//                           ring                                                             [MFMA bound]
+//   pack_conv_kernel        [O, C, 3, 3] bf16 kernel -> fragment stream in the order the kernel reads
 //   temb_proj_kernel        e[b, o] = b_t[o] + sum_k SiLU(temb[b, k]) * W_t[k, o]
-//   gn_partial_tokens_kernel + gn_finish_tokens_kernel
-//                           GroupNorm statistics of a token-major fp16 feature per (image, group)
-//   gn_silu_tokens_kernel   SiLU(GroupNorm(h)) -> fp16 operand in fragment order             [HBM bound]
-//   window_to_tokens_silu_kernel  slice window -> SiLU(GroupNorm1) -> fp16 operand in fragment order
+//   window_to_tokens_silu_kernel  slice window -> SiLU(GroupNorm1) (or a plain copy) -> operand in
+//                           fragment order                                                   [HBM bound]
+//   gn_partial_{tokens,frag}_kernel + gn_finish_tokens_kernel
+//                           GroupNorm2 statistics per (image, group) of the fp16 intermediate,
+//                           token-major or in fragment order
+//   gn_silu_{tokens,frag}_kernel  SiLU(GroupNorm2(h)) -> fp16 operand in fragment order (in place
+//                           when h already is)                                               [HBM bound]
 #pragma once
 #include "si_common.h"
 #include "k_gemm.h"

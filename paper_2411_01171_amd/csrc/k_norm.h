@@ -151,9 +151,7 @@ struct Window {
 // (along positions) and the write (along channels) are contiguous.  For bf16
 // storage the normalised value is kept as a (high, low) bf16 pair -- row m holds
 // C high parts followed by C low parts -- so that proj_in sees it to ~16 bits.
-// SILU: the ResBlock variant -- SiLU follows the normalisation and the result is stored as one fp16
-// value per element (row m holds C values; a0 is then an fp16 buffer).
-template <typename T, bool SILU = false>
+template <typename T>
 __global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restrict__ x, const float* __restrict__ stats,
                                                                const T* __restrict__ gamma, const T* __restrict__ beta,
                                                                T* __restrict__ a0, Window w) {
@@ -173,7 +171,6 @@ __global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restri
       const float rstd = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 1];
       const float xv = to_float(x[(((int64_t)b * w.C + c) * w.F + f) * w.P + w.p0 + pl]);
       v = (xv - mean) * rstd * param_or(gamma, c, 1.f) + param_or(beta, c, 0.f);
-      if constexpr (SILU) v = v / (1.f + __expf(-v));
     }
     tile[cl][tx] = v;
   }
@@ -183,9 +180,7 @@ __global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restri
     const int c = ct + tx, p = pt + pl;
     if (c < w.C && p < w.Pw) {
       const int64_t m = (int64_t)bf * w.Pw + p;
-      if constexpr (SILU) {
-        reinterpret_cast<_Float16*>(a0)[m * w.C + c] = (_Float16)tile[tx][pl];
-      } else if constexpr (sizeof(T) == 2) {
+      if constexpr (sizeof(T) == 2) {
         const T hi = from_float<T>(tile[tx][pl]);
         a0[m * (2 * w.C) + c] = hi;
         a0[m * (2 * w.C) + w.C + c] = from_float<T>(tile[tx][pl] - to_float(hi));
