@@ -358,16 +358,19 @@ struct EpiStoreRows {
 // Kernel [O, C, 3, 3] (bf16) -> fp16 (F16) or bf16 fragment stream for column tiles of TN*32 output channels:
 // element e of lane l of fragment ((col*nkt + kt)*2 + ks)*TN + i is w[o, c, tap] with
 // o = (col*TN + i)*32 + l%32, tap = kt / (C/32), c = (kt % (C/32))*32 + ks*16 + (l/32)*8 + e; rows
-// beyond O are zero.  One thread per element.  Block 0 also clears the activation buffers' zero blocks.
+// beyond O are zero.  One thread per element.  Block 0 also clears the operand buffers' zero blocks.
 template <bool F16>
 __global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__ src, unsigned short* __restrict__ dst, int O, int C,
-                                                        int TN, int ncol, unsigned* __restrict__ zero0, unsigned* __restrict__ zero1,
-                                                        int64_t zero_pair = 0) {
-  if (blockIdx.x == 0 && threadIdx.x < kActZeroBytes / 4) {  // zero_pair: a second buffer that many bytes further on
-    if (zero0) zero0[threadIdx.x] = 0u;
-    if (zero1) zero1[threadIdx.x] = 0u;
-    if (zero0 && zero_pair) zero0[zero_pair / 4 + threadIdx.x] = 0u;
-    if (zero1 && zero_pair) zero1[zero_pair / 4 + threadIdx.x] = 0u;
+                                                        int TN, int ncol, unsigned* __restrict__ zero0, int zero_lanes = 0,
+                                                        int64_t zero_lane_stride = 0, int64_t zero_pair = 0) {
+  // zero blocks of the operand buffers: one per lane (zero_lane_stride bytes apart), and, with
+  // zero_pair, of a second buffer that many bytes further on in every lane
+  if (blockIdx.x == 0 && threadIdx.x < kActZeroBytes / 4) {
+    for (int l = 0; l < zero_lanes; ++l) {
+      unsigned* z = zero0 + l * (zero_lane_stride / 4);
+      z[threadIdx.x] = 0u;
+      if (zero_pair) z[zero_pair / 4 + threadIdx.x] = 0u;
+    }
   }
   const int per_tap = C / 32, nkt = 9 * per_tap;
   const int64_t total = (int64_t)ncol * nkt * 2 * TN * 512;

@@ -64,6 +64,10 @@ struct StageScope {
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+#ifndef SI_LANES3_MIN
+#define SI_LANES3_MIN 12
+#endif
+
 struct Plan {
   int kind, dtype, esize;
   int B, C, F, H, W, G, heads, d, D;
@@ -76,8 +80,8 @@ struct Plan {
   int fused_nb;     // > 0: register-resident FFN half with D = 32*fused_nb
   bool fused_attn;  // register-resident attention half as well (temporal blocks)
   bool attn_mfma;   // matrix-core attention kernel for the staged spatial path (bf16, head dimension 64)
-  int lanes;        // slices in flight (staged path with many small slices: 2, on two streams)
-  size_t lane_stride;  // bytes between the two lanes' slice intermediates
+  int lanes;        // slices in flight (many small slices: 2 or 3, each on a stream of its own)
+  size_t lane_stride;  // bytes between two lanes' slice intermediates
   int Mcp;          // context tokens rounded up to a multiple of 8 (transposed value copy)
   // workspace offsets (bytes)
   size_t off_stats, off_rehash, off_pe, off_ctxkv, off_ctxvt, off_vt;
@@ -171,13 +175,13 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   }
   p->off_vt = take(p->attn_mfma ? (size_t)p->Mmax * Dz * es : 0);  // values of the window, keys contiguous
   // Cross-slice pipelining (Sec. 4.2.2): with many small slices the kernels of one slice leave CUs
-  // idle (under-filled grids, partial last rounds), so two slices run at a time on two streams, each
-  // with its own intermediates.  Only with 8 or more
-  // slices: two slices' buffers then still stay within a quarter of the unsliced footprint.
+  // idle (under-filled grids, partial last rounds), so two slices (from 8 slices on) or three (from
+  // 12 on) run at a time, each on a stream and with intermediates of its own: their buffers together
+  // still stay within a quarter of the unsliced footprint.
   const int64_t n_slices = (p->extent + p->slice_len - 1) / p->slice_len;
-  p->lanes = n_slices >= 8 ? 2 : 1;
+  p->lanes = n_slices >= SI_LANES3_MIN ? 3 : n_slices >= 8 ? 2 : 1;
   p->lane_stride = off - p->off_a;
-  if (p->lanes == 2) take(p->lane_stride);
+  for (int l = 1; l < p->lanes; ++l) take(p->lane_stride);
   const size_t act_end = off;
   // re-laid-out weights
   p->off_w_in = take(split * Dz * C * es);
@@ -342,8 +346,8 @@ static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, ch
 // first use (default priority) and kept for the life of the process.  Calls that overlap on one
 // device share them and must not run concurrently from several host threads.
 struct AuxStream {
-  hipStream_t stream = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
+  hipStream_t stream = nullptr, stream2 = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr, join2 = nullptr;
 };
 static si_status aux_stream(AuxStream** out) {
   static AuxStream per_device[64];
@@ -354,6 +358,8 @@ static si_status aux_stream(AuxStream** out) {
     if (hipStreamCreateWithFlags(&a.stream, hipStreamNonBlocking) != hipSuccess) return SI_ERR_HIP;
     if (hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess) return SI_ERR_HIP;
     if (hipEventCreateWithFlags(&a.join, hipEventDisableTiming) != hipSuccess) return SI_ERR_HIP;
+    if (hipStreamCreateWithFlags(&a.stream2, hipStreamNonBlocking) != hipSuccess) return SI_ERR_HIP;
+    if (hipEventCreateWithFlags(&a.join2, hipEventDisableTiming) != hipSuccess) return SI_ERR_HIP;
   }
   *out = &a;
   return SI_OK;
@@ -455,16 +461,18 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   AuxStream* aux = nullptr;
   // per-stage timing wants each kernel alone on the GPU: one window at a time while it is enabled
   const int lanes = g_timing ? 1 : p.lanes;
-  if (lanes == 2) {  // fork: the second lane starts after the once-per-call work above
+  if (lanes >= 2) {  // fork: the other lanes start after the once-per-call work above
     SI_TRY(aux_stream(&aux));
     if (hipEventRecord(aux->fork, st_main) != hipSuccess || hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess)
       return SI_ERR_HIP;
+    if (lanes == 3 && hipStreamWaitEvent(aux->stream2, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
   }
   for (int64_t s0 = 0; s0 < p.extent; s0 += p.slice_len) {
     const int64_t s1 = s0 + p.slice_len < p.extent ? s0 + p.slice_len : p.extent;
     // this slice's lane: stream and intermediates (the names below shadow the first lane's)
-    const size_t lane_off = (size_t)((s0 / p.slice_len) % lanes) * p.lane_stride;
-    hipStream_t st = lane_off ? aux->stream : st_main;
+    const int lane_id = (int)((s0 / p.slice_len) % lanes);
+    const size_t lane_off = (size_t)lane_id * p.lane_stride;
+    hipStream_t st = lane_id == 0 ? st_main : lane_id == 1 ? aux->stream : aux->stream2;
     T* a = reinterpret_cast<T*>(reinterpret_cast<char*>(a_base) + lane_off);
     float* h = reinterpret_cast<float*>(reinterpret_cast<char*>(h_base) + lane_off);
     T* big = reinterpret_cast<T*>(reinterpret_cast<char*>(big_base) + lane_off);
@@ -603,8 +611,11 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       SI_TRY(launch_gemm<T>("proj_out", a, (int64_t)kSplit * D, w_out, M, C, kSplit * D, epi, st));
     }
   }
-  if (lanes == 2) {  // join: the caller's stream continues after both lanes
+  if (lanes >= 2) {  // join: the caller's stream continues after all lanes
     if (hipEventRecord(aux->join, aux->stream) != hipSuccess || hipStreamWaitEvent(st_main, aux->join, 0) != hipSuccess)
+      return SI_ERR_HIP;
+    if (lanes == 3 &&
+        (hipEventRecord(aux->join2, aux->stream2) != hipSuccess || hipStreamWaitEvent(st_main, aux->join2, 0) != hipSuccess))
       return SI_ERR_HIP;
   }
   return SI_OK;

@@ -4,6 +4,9 @@
 #pragma once
 #include "k_conv.h"
 
+#ifndef SI_RES_LANES3_MIN
+#define SI_RES_LANES3_MIN 12
+#endif
 #ifndef SI_CONV_BIG_MIN
 #define SI_CONV_BIG_MIN 512
 #endif
@@ -57,9 +60,10 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
   p->off_stats2 = take((size_t)p->B * p->slice_len * p->G * 2 * sizeof(float));
   p->off_part = take((size_t)p->B * p->slice_len * (size_t)((P + 31) / 32) * C * 2 * sizeof(float));  // >= either chunking
   const int64_t n_slices = (p->F + p->slice_len - 1) / p->slice_len;
-  p->lanes = n_slices >= 8 ? 2 : 1;  // two windows' buffers still stay within a quarter of the unsliced ones
+  // windows in flight: their buffers together stay within a quarter of the unsliced ones
+  p->lanes = n_slices >= SI_RES_LANES3_MIN ? 3 : n_slices >= 8 ? 2 : 1;
   p->lane_stride = off - p->off_a;
-  if (p->lanes == 2) take(p->lane_stride);
+  for (int l = 1; l < p->lanes; ++l) take(p->lane_stride);
   const size_t act_end = off;
   conv_column_tiles(p->C, &p->TN, &p->ncol);
   const size_t wbytes = (size_t)p->ncol * 9 * (C / 32) * 2 * p->TN * 1024;
@@ -132,12 +136,10 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
     const int64_t elems = (int64_t)p.ncol * 9 * (C / 32) * 2 * p.TN * 512;
     const unsigned blocks = (unsigned)((elems + 255) / 256);
     unsigned* z0 = reinterpret_cast<unsigned*>(ws + p.off_a);
-    unsigned* z1 = p.lanes == 2 ? reinterpret_cast<unsigned*>(ws + p.off_a + p.lane_stride) : nullptr;
-    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv1), reinterpret_cast<unsigned short*>(w1), C, C, p.TN, p.ncol, z0, z1,
-                                                    (int64_t)(p.off_h - p.off_a));
+    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv1), reinterpret_cast<unsigned short*>(w1), C, C, p.TN, p.ncol, z0,
+                                                    p.lanes, (int64_t)p.lane_stride, (int64_t)(p.off_h - p.off_a));
     SI_CHECK_LAUNCH();
-    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv2), reinterpret_cast<unsigned short*>(w2), C, C, p.TN, p.ncol, nullptr,
-                                                    nullptr);
+    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv2), reinterpret_cast<unsigned short*>(w2), C, C, p.TN, p.ncol, nullptr);
     SI_CHECK_LAUNCH();
     if (emb) {
       temb_proj_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)p.B), 1024, 0, st0>>>(cB(temb), cB(w->w_temb),
@@ -155,17 +157,18 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
 
   AuxStream* aux = nullptr;
   const int lanes = g_timing ? 1 : p.lanes;  // per-stage timing: one window at a time
-  if (lanes == 2) {
+  if (lanes >= 2) {
     SI_TRY(aux_stream(&aux));
     if (hipEventRecord(aux->fork, st0) != hipSuccess) return SI_ERR_HIP;
     if (hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
+    if (lanes == 3 && hipStreamWaitEvent(aux->stream2, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
   }
 
   // ---- the frame windows (Sec. 4.1): each goes through the whole group and lands in its window of out
   int widx = 0;
   for (int64_t f0 = 0; f0 < p.F; f0 += p.slice_len, ++widx) {
-    const int lane_id = lanes == 2 ? widx & 1 : 0;
-    hipStream_t st = lane_id ? aux->stream : st0;
+    const int lane_id = widx % lanes;
+    hipStream_t st = lane_id == 0 ? st0 : lane_id == 1 ? aux->stream : aux->stream2;
     char* lane_ws = ws + (size_t)lane_id * p.lane_stride;
     _Float16* a = reinterpret_cast<_Float16*>(lane_ws + p.off_a);
     _Float16* h = reinterpret_cast<_Float16*>(lane_ws + p.off_h);
@@ -225,9 +228,13 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
       SI_TRY(launch_conv3x3<true>("conv2", frag_h ? h : a, w2, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
     }
   }
-  if (lanes == 2) {
+  if (lanes >= 2) {
     if (hipEventRecord(aux->join, aux->stream) != hipSuccess) return SI_ERR_HIP;
     if (hipStreamWaitEvent(st0, aux->join, 0) != hipSuccess) return SI_ERR_HIP;
+    if (lanes == 3) {
+      if (hipEventRecord(aux->join2, aux->stream2) != hipSuccess) return SI_ERR_HIP;
+      if (hipStreamWaitEvent(st0, aux->join2, 0) != hipSuccess) return SI_ERR_HIP;
+    }
   }
   return SI_OK;
 }
@@ -288,9 +295,8 @@ static si_status run_resample(const ResamplePlan& p, const si_tensor5* x, const 
     StageScope scope("pack_weights", st0);
     const int64_t elems = (int64_t)p.ncol * 9 * (C / 32) * 2 * p.TN * 512;
     unsigned* z0 = reinterpret_cast<unsigned*>(ws + p.off_a);
-    unsigned* z1 = p.lanes == 2 ? reinterpret_cast<unsigned*>(ws + p.off_a + p.lane_stride) : nullptr;
     pack_conv_kernel<false><<<(unsigned)((elems + 255) / 256), 256, 0, st0>>>(static_cast<const bf16*>(w_conv), wf, C, C, p.TN,
-                                                                             p.ncol, z0, z1);
+                                                                             p.ncol, z0, p.lanes, (int64_t)p.lane_stride);
     SI_CHECK_LAUNCH();
   }
   AuxStream* aux = nullptr;
