@@ -13,12 +13,14 @@ pre-activation residual block of the latent-diffusion U-Net family:
      deep-learning sense: a cross-correlation, no kernel flip).
   3. optional: h[b, :, f] += (SiLU(temb[b]) W_t + b_t) broadcast over frames and positions.
   4. h = Conv3x3(SiLU(GroupNorm2(h))) + b2.
-  5. out = x + h          (identity skip; C_out = C_in).
+  5. out = skip(x) + h    skip = identity when C_out = C_in, else the 1x1 convolution
+     skip(x)[b, o, f, p] = sum_c w_skip[o, c] * x[b, c, f, p] + b_skip[o]  (used whenever the
+     parameter dict holds "w_skip").
 
 Every frame is independent, so slicing along frames reproduces the unsliced
 result exactly.  Parameters: dict of arrays named like the fields of the C-ABI
-weight struct; convolution kernels in [C_out, C_in, 3, 3] order, W_t row-major
-[temb_dim, C_out].
+weight struct; convolution kernels in [C_out, C_in, 3, 3] order (conv1 maps C_in to C_out,
+conv2 C_out to C_out), w_skip [C_out, C_in], W_t row-major [temb_dim, C_out].
 """
 from __future__ import annotations
 
@@ -76,9 +78,14 @@ def resblock_forward_ref(x, w: dict, hp, temb: Optional[np.ndarray] = None):
     h = _frames_back(conv3x3_ref(_frames_first(a), w["w_conv1"], w["b_conv1"]), B, Fr)
     if temb is not None:
         e = silu_ref(np.asarray(temb, F64)) @ np.asarray(w["w_temb"], F64) + np.asarray(w["b_temb"], F64)
-        h = h + e.reshape(B, C, 1, 1, 1)
+        h = h + e.reshape(B, -1, 1, 1, 1)
     a2 = silu_ref(group_norm_ref(h, hp.gn_groups, hp.gn_eps, w["gn2_g"], w["gn2_b"]))
     h2 = _frames_back(conv3x3_ref(_frames_first(a2), w["w_conv2"], w["b_conv2"]), B, Fr)
+    if w.get("w_skip") is not None:
+        skip = np.einsum("oc,bcfhw->bofhw", np.asarray(w["w_skip"], F64), x)
+        if w.get("b_skip") is not None:
+            skip = skip + np.asarray(w["b_skip"], F64).reshape(1, -1, 1, 1, 1)
+        return skip + h2
     return x + h2
 
 
@@ -86,10 +93,8 @@ def sliced_resblock_forward_ref(x, w: dict, hp, temb, slice_len: int):
     """Eq. 1 along frames: every window of frames goes through the whole group on its own and lands
     in its window of the preallocated output."""
     x = np.asarray(x, F64)
-    out = np.full_like(x, np.nan)
-    for f0, f1 in slice_windows_ref(x.shape[2], slice_len):
-        out[:, :, f0:f1] = resblock_forward_ref(x[:, :, f0:f1], w, hp, temb)
-    return out
+    parts = [resblock_forward_ref(x[:, :, f0:f1], w, hp, temb) for f0, f1 in slice_windows_ref(x.shape[2], slice_len)]
+    return np.concatenate(parts, axis=2)
 
 
 def downsample_ref(x, weight, bias=None):

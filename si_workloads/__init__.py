@@ -210,6 +210,7 @@ class ResSpec:
     H: int
     W: int
     temb_dim: int = 0        # 0: no timestep-embedding term
+    C_out: int = 0           # 0: same as C (identity skip); else the 1x1 skip convolution maps C -> C_out
     gn_groups: int = 32
     gn_eps: float = 1e-6
     slice_len: int = 1       # frames per slice
@@ -222,7 +223,9 @@ class ResSpec:
     def flops(self) -> float:
         """Two 3x3 convolutions as dense contractions (2 * positions * 9 * C * C each, padding taps
         counted) plus the embedding projection; norms and SiLU are not counted."""
-        return 2.0 * 2.0 * self.tokens * 9 * self.C * self.C + 2.0 * self.B * self.temb_dim * self.C
+        Co = self.C_out or self.C
+        skip = 2.0 * self.tokens * self.C * Co if Co != self.C else 0.0
+        return 2.0 * self.tokens * 9 * (self.C * Co + Co * Co) + skip + 2.0 * self.B * self.temb_dim * Co
 
 
 RES_CONFIGS: Dict[str, ResSpec] = {
@@ -230,17 +233,21 @@ RES_CONFIGS: Dict[str, ResSpec] = {
     "res4": ResSpec("res4", "bf16", 2, 320, 25, 72, 128, temb_dim=1280, slice_len=1, seed=7000),
     # deeper level, smaller map: C = 640 at 36 x 64, two frames per slice
     "res4b": ResSpec("res4b", "bf16", 2, 640, 25, 36, 64, temb_dim=1280, slice_len=2, seed=7100),
+    # level transition: 320 -> 640 channels with the 1x1 skip, at the deeper level's map
+    "res4c": ResSpec("res4c", "bf16", 2, 320, 25, 36, 64, temb_dim=1280, C_out=640, slice_len=2, seed=7300),
     # small case the oracle finishes in seconds; map sizes that are no multiple of any tile
     "res1": ResSpec("res1", "bf16", 2, 64, 3, 10, 12, temb_dim=32, slice_len=2, seed=7200),
 }
 
 
 def res_weight_shapes(spec: ResSpec) -> Dict[str, tuple]:
-    C = spec.C
-    shapes = {"gn1_g": (C,), "gn1_b": (C,), "w_conv1": (C, C, 3, 3), "b_conv1": (C,),
-              "gn2_g": (C,), "gn2_b": (C,), "w_conv2": (C, C, 3, 3), "b_conv2": (C,)}
+    C, Co = spec.C, spec.C_out or spec.C
+    shapes = {"gn1_g": (C,), "gn1_b": (C,), "w_conv1": (Co, C, 3, 3), "b_conv1": (Co,),
+              "gn2_g": (Co,), "gn2_b": (Co,), "w_conv2": (Co, Co, 3, 3), "b_conv2": (Co,)}
     if spec.temb_dim:
-        shapes.update({"w_temb": (spec.temb_dim, C), "b_temb": (C,)})
+        shapes.update({"w_temb": (spec.temb_dim, Co), "b_temb": (Co,)})
+    if Co != C:
+        shapes.update({"w_skip": (Co, C), "b_skip": (Co,)})
     return shapes
 
 

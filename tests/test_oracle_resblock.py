@@ -188,3 +188,34 @@ def test_resample_closed_forms_and_slicing():
     for kind, fn in (("down", oracle.downsample_ref), ("up", oracle.upsample_ref)):
         for sl in (1, 2, 3):
             assert np.array_equal(oracle.sliced_resample_ref(x, w, b, kind, sl), fn(x, w, b))
+
+
+def test_block_with_channel_change_and_1x1_skip():
+    import torch
+    import torch.nn.functional as Fn
+    spec = _spec(C_out=96)
+    x = wl.make_x(spec).astype(np.float64)
+    w = {k: v.astype(np.float64) for k, v in wl.make_res_weights(spec, randomize_affine=True).items()}
+    assert w["w_conv1"].shape == (96, 64, 3, 3) and w["w_conv2"].shape == (96, 96, 3, 3) and w["w_skip"].shape == (96, 64)
+    temb = wl.make_temb(spec).astype(np.float64)
+    got = oracle.resblock_forward_ref(x, w, spec, temb)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
+    B, C, Fr, H, W = x.shape
+    xf = t(x).permute(0, 2, 1, 3, 4).reshape(B * Fr, C, H, W)
+    h = Fn.conv2d(Fn.silu(Fn.group_norm(xf, spec.gn_groups, t(w["gn1_g"]), t(w["gn1_b"]), spec.gn_eps)),
+                  t(w["w_conv1"]), t(w["b_conv1"]), padding=1)
+    h = h + Fn.linear(Fn.silu(t(temb)), t(w["w_temb"]).T, t(w["b_temb"])).repeat_interleave(Fr, dim=0)[:, :, None, None]
+    h = Fn.conv2d(Fn.silu(Fn.group_norm(h, spec.gn_groups, t(w["gn2_g"]), t(w["gn2_b"]), spec.gn_eps)),
+                  t(w["w_conv2"]), t(w["b_conv2"]), padding=1)
+    skip = Fn.conv2d(xf, t(w["w_skip"])[:, :, None, None], t(w["b_skip"]))
+    want = (skip + h).reshape(B, Fr, 96, H, W).permute(0, 2, 1, 3, 4).numpy()
+    assert got.shape == (B, 96, Fr, H, W) and np.allclose(got, want, atol=1e-11)
+    # an identity 1x1 skip is the identity skip
+    s2 = _spec()
+    w2 = wl.make_res_weights(s2)
+    a = oracle.resblock_forward_ref(x, w2, s2, None)
+    w3 = dict(w2); w3["w_skip"] = np.eye(64); w3["b_skip"] = np.zeros(64)
+    assert np.allclose(a, oracle.resblock_forward_ref(x, w3, s2, None), atol=1e-13)
+    # slicing stays exact with the channel change
+    full = oracle.resblock_forward_ref(x, w, spec, temb)
+    assert np.allclose(oracle.sliced_resblock_forward_ref(x, w, spec, temb, 2), full, atol=1e-12)
