@@ -109,13 +109,18 @@ def cpu_baseline(spec, seconds_target=20.0):
 
 def res_stage_work(spec, stage, M):
     """Algorithmic work of one launch of a ResBlock stage on a window of M tokens."""
-    C = spec.C
-    if stage in ("conv1", "conv2"):
-        return "flop", 2.0 * M * 9 * C * C
+    C, Co = spec.C, spec.C_out or spec.C
+    if stage == "conv1":
+        return "flop", 2.0 * M * 9 * C * Co
+    if stage == "conv2":
+        return "flop", 2.0 * M * 9 * Co * Co
+    if stage == "conv_skip":
+        return "flop", 2.0 * M * C * Co
     if stage == "gn_stats":
         return "byte", float(spec.tokens * C * 2)
-    if stage == "slice_in":
+    if stage in ("slice_in", "slice_in_raw"):
         return "byte", 2.0 * M * C * 2
+    C = Co                              # the stages after conv1 work on the output width
     if stage == "gn2_stats":            # one read of the fp16 intermediate
         return "byte", 2.0 * M * C
     if stage == "gn2_silu":             # fp16 in, fp16 out
@@ -145,7 +150,7 @@ def main_resblock(args):
     live_sliced = si.si_resblock_live_activation_bytes(x, wts, slice_len)
     live_unsliced = si.si_resblock_live_activation_bytes(x, wts, spec.F)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    out = torch.empty_like(x)
+    out = torch.empty((spec.B, spec.C_out or spec.C, spec.F, spec.H, spec.W), dtype=x.dtype, device="cuda")
 
     def step():
         si.si_resblock_forward(x, wts, temb, out, slice_len, ws)
@@ -181,7 +186,7 @@ def main_resblock(args):
         stage_report[name] = rec
     conv_ms = stages["conv1"][0] + stages["conv2"][0]
     conv_cnt = stages["conv1"][1] + stages["conv2"][1]
-    d_work = res_stage_work(spec, "conv1", M_slice)[1]
+    d_work = 0.5 * (res_stage_work(spec, "conv1", M_slice)[1] + res_stage_work(spec, "conv2", M_slice)[1])
     ach = d_work / (conv_ms / conv_cnt * 1e-3) / 1e12
     roof = {"bound": "mfma", "kernel": "conv3x3 (conv1 + conv2 launches)", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
@@ -191,7 +196,7 @@ def main_resblock(args):
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 operands from bf16 storage, f32 accumulation", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: Spatial ResBlock group x[B={spec.B},C={spec.C},F={spec.F},H={spec.H},W={spec.W}], "
+        "config": {"workload": f"{args.workload}: Spatial ResBlock group x[B={spec.B},C={spec.C}->{spec.C_out or spec.C},F={spec.F},H={spec.H},W={spec.W}], "
                                f"embedding width {spec.temb_dim}, sliced along frames in windows of {slice_len} ({n_slices} slices)",
                    "algorithmic_flop_per_step": flops, "tokens": spec.tokens},
         "frac_mfma_peak": value / PEAK_BF16_TFLOPS,
@@ -289,7 +294,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", help="cfg2 (default, the metric's configuration), cfg3, cfg4s, cfg4t, cfg5s, cfg5t; res4, res4b "
+    ap.add_argument("--workload", default="cfg2", help="cfg2 (default, the metric's configuration), cfg3, cfg4s, cfg4t, cfg5s, cfg5t; res4, res4b, res4c "
                          "(Spatial ResBlock group); down4, up4b (its Down/UpSample)")
     ap.add_argument("--slice-len", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -203,9 +203,10 @@ si_status si_block_forward_rehash(const si_tensor5* x, const si_block_weights* w
 /* Parameters of one Spatial ResBlock operator group (Sec. 4.2.1: the
  * consecutive GroupNorm, Conv2D and SiLU operators of the Spatial ResBlock
  * form one spatial group).  Device pointers, dtype of the feature, 16-byte
- * aligned.  Convolution kernels in [C, C, 3, 3] order (output channel,
- * input channel, row, column), applied as a cross-correlation with zero
- * padding 1 and stride 1; w_temb row-major [temb_dim, C].  NULL biases mean
+ * aligned.  Convolution kernels in (output channel, input channel, row,
+ * column) order -- w_conv1 [c_out, C, 3, 3], w_conv2 [c_out, c_out, 3, 3] --
+ * applied as a cross-correlation with zero padding 1 and stride 1; w_temb
+ * row-major [temb_dim, c_out]; gn2 and the biases have c_out entries.  NULL biases mean
  * zero, NULL gains / shifts mean one / zero.  w_temb is required iff
  * temb_dim > 0. */
 typedef struct {
@@ -215,6 +216,8 @@ typedef struct {
   const void *gn1_g, *gn1_b, *w_conv1, *b_conv1;
   const void *w_temb, *b_temb;
   const void *gn2_g, *gn2_b, *w_conv2, *b_conv2;
+  int32_t c_out;                 /* output channels; 0 or x->C: no channel change, identity skip */
+  const void *w_skip, *b_skip;   /* 1x1 skip convolution [c_out, C], required iff c_out != C */
 } si_resblock_weights;
 
 /* Workspace bytes of si_resblock_forward, and the activation-derived part of
@@ -224,14 +227,16 @@ size_t si_resblock_workspace_bytes(const si_tensor5* x, const si_resblock_weight
 size_t si_resblock_live_activation_bytes(const si_tensor5* x, const si_resblock_weights* w, int64_t slice_len);
 
 /* Sliced Spatial ResBlock forward (Sec. 4.1 spatial layers slicer, Sec. 4.2.1, Eq. 1):
- *   out = x + Conv3x3(SiLU(GN2( Conv3x3(SiLU(GN1(x))) + b1 + e ))) + b2,
+ *   out = skip(x) + Conv3x3(SiLU(GN2( Conv3x3(SiLU(GN1(x))) + b1 + e ))) + b2,
  *   e[b, :] = SiLU(temb[b, :]) w_temb + b_temb  broadcast over frames and positions,
+ *   skip(x) = x, or w_skip x + b_skip per pixel when the block changes the channel count,
  * with GroupNorm statistics per (batch, frame, group).  The merged batch x
  * frame axis is sliced: window i covers frames [i*slice_len, min((i+1)*
  * slice_len, F)) of every batch entry, goes through the whole group on its
  * own and is written to its window of `out` (every element of out is
  * written; out must not overlap x).
- *   x, out     [B,C,F,H,W] bf16 (SI_ERR_DTYPE otherwise), C a multiple of 32 and of gn_groups, C / gn_groups <= 64
+ *   x          [B,C,F,H,W] bf16 (SI_ERR_DTYPE otherwise); out [B,c_out,F,H,W]; C and c_out multiples
+ *              of 32 and of gn_groups, at most 64 channels per group
  *   temb       device [B, temb_dim] or NULL when temb_dim == 0
  *   workspace  device, >= si_resblock_workspace_bytes(...), 256-byte aligned
  * Returns SI_ERR_* on invalid arguments (nothing enqueued) or SI_ERR_HIP. */

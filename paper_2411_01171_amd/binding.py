@@ -52,7 +52,8 @@ RES_WEIGHT_FIELDS = ("gn1_g", "gn1_b", "w_conv1", "b_conv1", "w_temb", "b_temb",
 
 class _ResWeights(C.Structure):
     _fields_ = ([("gn_groups", C.c_int32), ("gn_eps", C.c_float), ("temb_dim", C.c_int32)]
-                + [(n, C.c_void_p) for n in RES_WEIGHT_FIELDS])
+                + [(n, C.c_void_p) for n in RES_WEIGHT_FIELDS]
+                + [("c_out", C.c_int32), ("w_skip", C.c_void_p), ("b_skip", C.c_void_p)])
 
 
 class _RehashCache(C.Structure):
@@ -203,11 +204,11 @@ def si_block_forward(x, weights: BlockWeights, ctx, out, axis: int, slice_len: i
 class ResBlockWeights:
     """Device tensors of one Spatial ResBlock and the matching C struct (kept alive by this object)."""
 
-    def __init__(self, gn_groups: int, tensors: Dict[str, object], gn_eps: float = 1e-6, temb_dim: int = 0):
+    def __init__(self, gn_groups: int, tensors: Dict[str, object], gn_eps: float = 1e-6, temb_dim: int = 0, c_out: int = 0):
         self.tensors = dict(tensors)
         s = _ResWeights()
-        s.gn_groups, s.gn_eps, s.temb_dim = gn_groups, gn_eps, temb_dim
-        for name in RES_WEIGHT_FIELDS:
+        s.gn_groups, s.gn_eps, s.temb_dim, s.c_out = gn_groups, gn_eps, temb_dim, c_out
+        for name in RES_WEIGHT_FIELDS + ("w_skip", "b_skip"):
             t = self.tensors.get(name)
             if t is not None and not t.is_contiguous():
                 raise ValueError(f"{name} must be contiguous")

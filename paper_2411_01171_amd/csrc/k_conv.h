@@ -53,6 +53,7 @@ struct ConvArgs {
                     // tap (dy, dx) reads source (2y+dy, 2x+dx)); the smaller one for kConvNearestUp (reads
                     // source ((y+dy)/2, (x+dx)/2) when (y+dy, x+dx) lies inside the output map)
   int mode;
+  int ntaps;        // 9, or 1: the centre tap only (a 1x1 convolution; the kernel stream then holds one tap)
 };
 
 // acc[m, o] = sum_{tap, c} a[m + dy*W + dx, c] * w[o, c, tap] over the taps whose source pixel lies
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int trow = lane % 32, half = lane / 32;
   const int P = a.H * a.W;
-  const int per_tap = a.C / 32, nkt = 9 * per_tap;
+  const int per_tap = a.C / 32, nkt = a.ntaps * per_tap;
 
   int py[TM], px[TM];
   int64_t tok[TM], img0[TM];  // img0: first source token of the token's image
@@ -104,7 +105,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi
 
   unsigned tapv[TM];  // byte offset of the lane's granule for the current tap at channel 0, 0 = outside
   auto set_tap = [&](int tap) {
-    const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+    const int t9 = a.ntaps == 1 ? 4 : tap;
+    const int dy = t9 / 3 - 1, dx = t9 % 3 - 1;
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
       int sy, sx;
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi
     ++ld_kt;
     if (++ld_c == per_tap) {
       ld_c = 0;
-      if (++ld_tap < 9) set_tap(ld_tap);
+      if (++ld_tap < a.ntaps) set_tap(ld_tap);
     }
   };
 
@@ -362,7 +364,7 @@ struct EpiStoreRows {
 template <bool F16>
 __global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__ src, unsigned short* __restrict__ dst, int O, int C,
                                                         int TN, int ncol, unsigned* __restrict__ zero0, int zero_lanes = 0,
-                                                        int64_t zero_lane_stride = 0, int64_t zero_pair = 0) {
+                                                        int64_t zero_lane_stride = 0, int64_t zero_pair = 0, int ntaps = 9) {
   // zero blocks of the operand buffers: one per lane (zero_lane_stride bytes apart), and, with
   // zero_pair, of a second buffer that many bytes further on in every lane
   if (blockIdx.x == 0 && threadIdx.x < kActZeroBytes / 4) {
@@ -372,7 +374,7 @@ __global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__
       if (zero_pair) z[zero_pair / 4 + threadIdx.x] = 0u;
     }
   }
-  const int per_tap = C / 32, nkt = 9 * per_tap;
+  const int per_tap = C / 32, nkt = ntaps * per_tap;  // ntaps == 1: src is [O, C]
   const int64_t total = (int64_t)ncol * nkt * 2 * TN * 512;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(256) void pack_conv_kernel(const bf16* __restrict__
   const int tap = kt / per_tap, c = (kt % per_tap) * 32 + ks * 16 + (l / 32) * 8 + e;
   unsigned short bits = 0;
   if (o < O) {
-    const bf16 v = src[((int64_t)o * C + c) * 9 + tap];
+    const bf16 v = src[((int64_t)o * C + c) * ntaps + tap];
     if constexpr (F16) bits = __builtin_bit_cast(unsigned short, (_Float16)to_float(v));
     else bits = v.v;
   }

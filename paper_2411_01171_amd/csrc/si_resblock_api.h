@@ -15,11 +15,12 @@ namespace si {
 
 struct ResPlan {
   int B, C, F, H, W, G, Kt;
+  int Co;              // output channels (== C: identity skip, else the 1x1 skip convolution runs)
   int TN, ncol;        // column tiles of the convolution kernel: ncol tiles of TN*32 output channels
   int64_t P, slice_len, Mmax;
   int lanes;           // frame windows in flight (two streams) when there are many small ones
   size_t lane_stride;
-  size_t off_stats, off_emb, off_a, off_h, off_stats2, off_part, off_w1, off_w2;
+  size_t off_stats, off_emb, off_a, off_xr, off_h, off_stats2, off_part, off_w1, off_w2, off_wskip;
   size_t weights_bytes, total_bytes;
 };
 
@@ -40,10 +41,14 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
   if (slice_len < 1) return SI_ERR_SLICE;
   p->B = (int)x->B; p->C = (int)x->C; p->F = (int)x->F; p->H = (int)x->H; p->W = (int)x->W;
   p->G = w->gn_groups; p->Kt = w->temb_dim; p->P = P;
+  p->Co = w->c_out > 0 ? w->c_out : p->C;
+  if (p->Co % w->gn_groups || p->Co % 32 || p->Co > 8192 || p->Co / w->gn_groups > 64) return SI_ERR_SHAPE;
+  if ((double)x->B * p->Co * x->F * (double)P >= 1099511627776.0) return SI_ERR_SHAPE;
   p->slice_len = slice_len < x->F ? slice_len : x->F;
   p->Mmax = (int64_t)x->B * p->slice_len * P;
   if (p->Mmax >= (1LL << 31) / 16) return SI_ERR_SHAPE;
-  const size_t C = (size_t)p->C;
+  const size_t C = (size_t)p->C, Co = (size_t)p->Co;
+  const bool skip_conv = p->Co != p->C;
   size_t off = 0;
   auto take = [&](size_t bytes) {
     const size_t o = off;
@@ -51,24 +56,27 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
     return o;
   };
   p->off_stats = take((size_t)p->B * p->F * p->G * 2 * sizeof(float));
-  p->off_emb = take((size_t)p->B * C * sizeof(float));
+  p->off_emb = take((size_t)p->B * Co * sizeof(float));
   // one window's intermediates: the fp16 operand of either convolution, the fp16 output of the first
   // one, the second GroupNorm's statistics
-  if ((double)p->Mmax * (double)C * 2.0 + 4096.0 >= 4294967296.0) return SI_ERR_SHAPE;  // 32-bit operand offsets
-  p->off_a = take(kActZeroBytes + (size_t)((p->Mmax + 31) / 32 * 32) * C * 2);
-  p->off_h = take(kActZeroBytes + (size_t)((p->Mmax + 31) / 32 * 32) * C * 2);  // token-major or fragment order
+  if ((double)p->Mmax * (double)(C > Co ? C : Co) * 2.0 + 4096.0 >= 4294967296.0) return SI_ERR_SHAPE;  // 32-bit operand offsets
+  const size_t Mpad = (size_t)((p->Mmax + 31) / 32 * 32);
+  p->off_a = take(kActZeroBytes + Mpad * (C > Co ? C : Co) * 2);   // conv1's operand; conv2's when h is token-major
+  p->off_xr = take(skip_conv ? kActZeroBytes + Mpad * C * 2 : 0);  // the raw window, operand of the 1x1 skip
+  p->off_h = take(kActZeroBytes + Mpad * Co * 2);                   // token-major or fragment order
   p->off_stats2 = take((size_t)p->B * p->slice_len * p->G * 2 * sizeof(float));
-  p->off_part = take((size_t)p->B * p->slice_len * (size_t)((P + 31) / 32) * C * 2 * sizeof(float));  // >= either chunking
+  p->off_part = take((size_t)p->B * p->slice_len * (size_t)((P + 31) / 32) * Co * 2 * sizeof(float));  // >= either chunking
   const int64_t n_slices = (p->F + p->slice_len - 1) / p->slice_len;
   // windows in flight: their buffers together stay within a quarter of the unsliced ones
   p->lanes = n_slices >= SI_RES_LANES3_MIN ? 3 : n_slices >= 8 ? 2 : 1;
   p->lane_stride = off - p->off_a;
   for (int l = 1; l < p->lanes; ++l) take(p->lane_stride);
   const size_t act_end = off;
-  conv_column_tiles(p->C, &p->TN, &p->ncol);
-  const size_t wbytes = (size_t)p->ncol * 9 * (C / 32) * 2 * p->TN * 1024;
-  p->off_w1 = take(wbytes);
-  p->off_w2 = take(wbytes);
+  conv_column_tiles(p->Co, &p->TN, &p->ncol);
+  const size_t per_ktile = (size_t)p->ncol * 2 * p->TN * 1024;  // bytes of one 32-channel k-tile over all column tiles
+  p->off_w1 = take(per_ktile * 9 * (C / 32));
+  p->off_w2 = take(per_ktile * 9 * (Co / 32));
+  p->off_wskip = take(skip_conv ? per_ktile * (C / 32) : 0);
   p->weights_bytes = off - act_end;
   p->total_bytes = off;
   return SI_OK;
@@ -98,9 +106,9 @@ static void conv_column_tiles(int O, int* TN, int* ncol) {
 // tokens on an H x W map; (Hi, Wi, mode) describe the source map (see ConvArgs).
 template <bool F16, class Epi>
 static si_status launch_conv3x3(const char* stage, const void* act, const void* wf, int64_t M, int C, int TN, int ncol, int H,
-                                int W, int Hi, int Wi, int mode, Epi epi, hipStream_t st) {
+                                int W, int Hi, int Wi, int mode, Epi epi, hipStream_t st, int O = 0, int ntaps = 9) {
   StageScope scope(stage, st);
-  ConvArgs a{static_cast<const char*>(act), static_cast<const char*>(wf), M, C, C, H, W, ncol, 0, Hi, Wi, mode};
+  ConvArgs a{static_cast<const char*>(act), static_cast<const char*>(wf), M, C, O ? O : C, H, W, ncol, 0, Hi, Wi, mode, ntaps};
   const int64_t rows2 = (M + 255) / 256;
   const bool big = rows2 * ncol >= SI_CONV_BIG_MIN;
   a.ntiles = (int)((big ? rows2 : (M + 127) / 128) * ncol);
@@ -127,23 +135,33 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
   float* emb = p.Kt ? reinterpret_cast<float*>(ws + p.off_emb) : nullptr;
   _Float16* w1 = reinterpret_cast<_Float16*>(ws + p.off_w1);
   _Float16* w2 = reinterpret_cast<_Float16*>(ws + p.off_w2);
-  const int C = p.C;
+  unsigned short* wskip = reinterpret_cast<unsigned short*>(ws + p.off_wskip);
+  const int C = p.C, Co = p.Co;
+  const bool skip_conv = Co != C;
   auto cB = [](const void* q) { return static_cast<const bf16*>(q); };
 
   // ---- once per call: kernel re-layout, embedding projection, first GroupNorm's statistics
   {
     StageScope scope("pack_weights", st0);
-    const int64_t elems = (int64_t)p.ncol * 9 * (C / 32) * 2 * p.TN * 512;
-    const unsigned blocks = (unsigned)((elems + 255) / 256);
+    const int64_t per_ktile = (int64_t)p.ncol * 2 * p.TN * 512;  // elements of one k-tile over all column tiles
+    auto blocks = [&](int64_t elems) { return (unsigned)((elems + 255) / 256); };
     unsigned* z0 = reinterpret_cast<unsigned*>(ws + p.off_a);
-    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv1), reinterpret_cast<unsigned short*>(w1), C, C, p.TN, p.ncol, z0,
-                                                    p.lanes, (int64_t)p.lane_stride, (int64_t)(p.off_h - p.off_a));
+    pack_conv_kernel<true><<<blocks(per_ktile * 9 * (C / 32)), 256, 0, st0>>>(cB(w->w_conv1), reinterpret_cast<unsigned short*>(w1),
+                                                                             Co, C, p.TN, p.ncol, z0, p.lanes,
+                                                                             (int64_t)p.lane_stride, (int64_t)(p.off_h - p.off_a));
     SI_CHECK_LAUNCH();
-    pack_conv_kernel<true><<<blocks, 256, 0, st0>>>(cB(w->w_conv2), reinterpret_cast<unsigned short*>(w2), C, C, p.TN, p.ncol, nullptr);
+    pack_conv_kernel<true><<<blocks(per_ktile * 9 * (Co / 32)), 256, 0, st0>>>(cB(w->w_conv2), reinterpret_cast<unsigned short*>(w2),
+                                                                              Co, Co, p.TN, p.ncol, nullptr);
     SI_CHECK_LAUNCH();
+    if (skip_conv) {
+      pack_conv_kernel<false><<<blocks(per_ktile * (C / 32)), 256, 0, st0>>>(cB(w->w_skip), wskip, Co, C, p.TN, p.ncol,
+                                                                            reinterpret_cast<unsigned*>(ws + p.off_xr), p.lanes,
+                                                                            (int64_t)p.lane_stride, 0, 1);
+      SI_CHECK_LAUNCH();
+    }
     if (emb) {
-      temb_proj_kernel<<<dim3((unsigned)((C + 63) / 64), (unsigned)p.B), 1024, 0, st0>>>(cB(temb), cB(w->w_temb),
-                                                                                          cB(w->b_temb), emb, p.Kt, C);
+      temb_proj_kernel<<<dim3((unsigned)((Co + 63) / 64), (unsigned)p.B), 1024, 0, st0>>>(cB(temb), cB(w->w_temb),
+                                                                                           cB(w->b_temb), emb, p.Kt, Co);
       SI_CHECK_LAUNCH();
     }
   }
@@ -184,48 +202,61 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
                                                                 reinterpret_cast<unsigned short*>(a), win);
       SI_CHECK_LAUNCH();
     }
+    Window win_out{p.B, Co, p.F, p.P, (int)f0, Fw, 0, (int)p.P, p.G};
+    if (skip_conv) {  // out window := w_skip x + b_skip; conv2's epilogue then adds the branch in place
+      unsigned short* xr = reinterpret_cast<unsigned short*>(lane_ws + p.off_xr);
+      {
+        StageScope scope("slice_in_raw", st);
+        dim3 grid((unsigned)((p.P + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * Fw));
+        window_to_tokens_silu_kernel<true><<<grid, 256, 0, st>>>(X, nullptr, nullptr, nullptr, xr, win);
+        SI_CHECK_LAUNCH();
+      }
+      EpiStoreRows epi{OUT, cB(w->b_skip), win_out};
+      SI_TRY(launch_conv3x3<false>("conv_skip", xr, wskip, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st, Co, 1));
+    }
     // The intermediate between the convolutions stays in fragment order when no 32-token block
     // straddles two images: GroupNorm2 + SiLU then run in place on it and conv2 reads it as it is.
     const bool frag_h = p.P % 32 == 0;
     if (frag_h) {
-      EpiConvEmbFrag epi{h, C, cB(w->b_conv1), emb, (int64_t)Fw * p.P};
-      SI_TRY(launch_conv3x3<true>("conv1", a, w1, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
+      EpiConvEmbFrag epi{h, Co, cB(w->b_conv1), emb, (int64_t)Fw * p.P};
+      SI_TRY(launch_conv3x3<true>("conv1", a, w1, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st, Co));
     } else {
-      EpiConvEmb epi{h, (int64_t)C, cB(w->b_conv1), emb, (int64_t)Fw * p.P};
-      SI_TRY(launch_conv3x3<true>("conv1", a, w1, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
+      EpiConvEmb epi{h, (int64_t)Co, cB(w->b_conv1), emb, (int64_t)Fw * p.P};
+      SI_TRY(launch_conv3x3<true>("conv1", a, w1, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st, Co));
     }
     {
       StageScope scope("gn2_stats", st);
       if (frag_h) {
         const int nchunk = (int)((p.P / 32 + kGnFragChunk - 1) / kGnFragChunk);
-        gn_partial_frag_kernel<<<dim3((unsigned)nchunk, (unsigned)(p.B * Fw), (unsigned)((C / 16 + 3) / 4)), 256, 0, st>>>(
-            h, part, (int)p.P, C);
+        gn_partial_frag_kernel<<<dim3((unsigned)nchunk, (unsigned)(p.B * Fw), (unsigned)((Co / 16 + 3) / 4)), 256, 0, st>>>(
+            h, part, (int)p.P, Co);
         SI_CHECK_LAUNCH();
-        gn_finish_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(nullptr, part, stats2, (int)p.P, C, p.G, nchunk,
+        gn_finish_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(nullptr, part, stats2, (int)p.P, Co, p.G, nchunk,
                                                                             w->gn_eps);
       } else {
         const int nchunk = (int)((p.P + kGnChunk - 1) / kGnChunk);
-        gn_partial_tokens_kernel<<<dim3((unsigned)nchunk, (unsigned)(p.B * Fw)), 256, 0, st>>>(h, part, (int)p.P, C);
+        gn_partial_tokens_kernel<<<dim3((unsigned)nchunk, (unsigned)(p.B * Fw)), 256, 0, st>>>(h, part, (int)p.P, Co);
         SI_CHECK_LAUNCH();
-        gn_finish_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(h, part, stats2, (int)p.P, C, p.G, nchunk, w->gn_eps);
+        gn_finish_tokens_kernel<<<(unsigned)(p.B * Fw * p.G), 256, 0, st>>>(h, part, stats2, (int)p.P, Co, p.G, nchunk, w->gn_eps);
       }
       SI_CHECK_LAUNCH();
     }
     {
       StageScope scope("gn2_silu", st);
       if (frag_h) {
-        const int64_t n = (M + 31) / 32 * (C / 16) * 64;
-        gn_silu_frag_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(h, stats2, cB(w->gn2_g), cB(w->gn2_b), M, (int)p.P, C, p.G);
+        const int64_t n = (M + 31) / 32 * (Co / 16) * 64;
+        gn_silu_frag_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(h, stats2, cB(w->gn2_g), cB(w->gn2_b), M, (int)p.P, Co, p.G);
       } else {
-        const int64_t n = M * (C / 4);
+        const int64_t n = M * (Co / 4);
         gn_silu_tokens_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(h, stats2, cB(w->gn2_g), cB(w->gn2_b), a, M, (int)p.P,
-                                                                           C, p.G);
+                                                                           Co, p.G);
       }
       SI_CHECK_LAUNCH();
     }
     {
-      EpiSliceOutRows epi{X, OUT, cB(w->b_conv2), win};
-      SI_TRY(launch_conv3x3<true>("conv2", frag_h ? h : a, w2, M, C, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
+      // residual source: x itself, or the skip convolution's result already sitting in the out window
+      EpiSliceOutRows epi{skip_conv ? OUT : X, OUT, cB(w->b_conv2), win_out};
+      SI_TRY(launch_conv3x3<true>("conv2", frag_h ? h : a, w2, M, Co, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
     }
   }
   if (lanes >= 2) {
@@ -382,18 +413,19 @@ si_status si_resblock_forward(const si_tensor5* x, const si_resblock_weights* w,
   si_status s = si::make_res_plan(x, w, slice_len, &p);
   if (s != SI_OK) return s;
   if (out->dtype != x->dtype) return SI_ERR_DTYPE;
-  if (out->B != x->B || out->C != x->C || out->F != x->F || out->H != x->H || out->W != x->W) return SI_ERR_SHAPE;
+  if (out->B != x->B || out->C != p.Co || out->F != x->F || out->H != x->H || out->W != x->W) return SI_ERR_SHAPE;
   if (!x->ptr || !out->ptr || !workspace || !w->w_conv1 || !w->w_conv2) return SI_ERR_NULL;
   if (p.Kt > 0 && (!temb || !w->w_temb)) return SI_ERR_NULL;
+  if (p.Co != p.C && !w->w_skip) return SI_ERR_NULL;
   const void* all[] = {x->ptr, out->ptr, temb, w->gn1_g, w->gn1_b, w->w_conv1, w->b_conv1, w->w_temb, w->b_temb,
-                       w->gn2_g, w->gn2_b, w->w_conv2, w->b_conv2};
+                       w->gn2_g, w->gn2_b, w->w_conv2, w->b_conv2, w->w_skip, w->b_skip};
   for (const void* q : all)
     if (q && !si::aligned16(q)) return SI_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SI_ERR_ALIGN;
   if (workspace_bytes < p.total_bytes) return SI_ERR_WORKSPACE;
-  const size_t xbytes = (size_t)p.B * p.C * p.F * (size_t)p.P * 2;
-  if (si::ranges_overlap(x->ptr, xbytes, out->ptr, xbytes)) return SI_ERR_ARG;
-  if (si::ranges_overlap(workspace, p.total_bytes, out->ptr, xbytes) ||
+  const size_t xbytes = (size_t)p.B * p.C * p.F * (size_t)p.P * 2, obytes = (size_t)p.B * p.Co * p.F * (size_t)p.P * 2;
+  if (si::ranges_overlap(x->ptr, xbytes, out->ptr, obytes)) return SI_ERR_ARG;
+  if (si::ranges_overlap(workspace, p.total_bytes, out->ptr, obytes) ||
       si::ranges_overlap(workspace, p.total_bytes, x->ptr, xbytes))
     return SI_ERR_ARG;
   return si::run_resblock(p, x, w, temb, out, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));

@@ -54,7 +54,7 @@ def errors(out: np.ndarray, ref: np.ndarray, x: np.ndarray):
 
 def device_res_weights(spec: wl.ResSpec, w: dict) -> si.ResBlockWeights:
     tensors = {k: to_dev(v, spec.dtype) for k, v in w.items()}
-    return si.ResBlockWeights(spec.gn_groups, tensors, gn_eps=spec.gn_eps, temb_dim=spec.temb_dim)
+    return si.ResBlockWeights(spec.gn_groups, tensors, gn_eps=spec.gn_eps, temb_dim=spec.temb_dim, c_out=spec.C_out)
 
 
 def run_resblock(spec: wl.ResSpec, x: np.ndarray, w: dict, temb, slice_len=None) -> np.ndarray:
@@ -65,7 +65,8 @@ def run_resblock(spec: wl.ResSpec, x: np.ndarray, w: dict, temb, slice_len=None)
     nbytes = si.si_resblock_workspace_bytes(xd, wd, sl)
     assert nbytes > 0, "si_resblock_workspace_bytes rejected the arguments"
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    out = torch.full_like(xd, float("nan"))
+    B, C, F, H, W = xd.shape
+    out = torch.full((B, spec.C_out or C, F, H, W), float("nan"), dtype=xd.dtype, device="cuda")
     si.si_resblock_forward(xd, wd, td, out, sl, ws)
     torch.cuda.synchronize()
     return out.float().cpu().numpy().astype(np.float64)

@@ -134,6 +134,14 @@ def test_resblock_validation_and_workspace():
     assert call(wd=w2) == 1
     w3 = B._ResWeights.from_buffer_copy(w); w3.gn_groups = 5
     assert call(wd=w3) == 2
+    w4 = B._ResWeights.from_buffer_copy(w); w4.c_out = 96                  # channel change
+    o96 = B._Tensor5(out.ptr, B.SI_BF16, 2, 96, 8, 6, 6)
+    assert call(wd=w4) == 2                                               # out must have c_out channels
+    assert call(wd=w4, od=o96) == 1                                       # ... and the 1x1 skip kernel is required
+    w4.w_skip = fake + (2 << 30)
+    w5 = B._ResWeights.from_buffer_copy(w4); w5.c_out = 80
+    assert call(wd=w5, od=B._Tensor5(out.ptr, B.SI_BF16, 2, 80, 8, 6, 6)) == 2   # c_out not a multiple of 32
+    assert lib.si_resblock_workspace_bytes(C.byref(x), C.byref(w4), 1) > lib.si_resblock_workspace_bytes(C.byref(x), C.byref(w), 1)
     # live bytes follow the window: 8 frames in windows of 1 run two at a time and still stay within a quarter
     x = B._Tensor5(fake, B.SI_BF16, 2, 64, 8, 48, 48)     # large enough that the fixed few KB do not matter
     live1 = lib.si_resblock_live_activation_bytes(C.byref(x), C.byref(w), 1)

@@ -14,6 +14,8 @@ BF16_MAX_ABS, BF16_REL_L2 = 2e-2, 5e-3
 
 def _check(name, got, ref, x):
     from gpu_helpers import errors
+    if x.shape != ref.shape:        # channel change: no identity residual to take out, the whole output is "branch"
+        x = np.zeros_like(ref)
     e = errors(got, ref, x)
     print(name, e)
     assert np.all(np.isfinite(got))
@@ -33,6 +35,9 @@ def _check(name, got, ref, x):
     (dict(B=3, C=64, F=4, H=3, W=40), 3),
     (dict(C=96, F=2, H=8, W=8), 1),                     # 64 pixels: the intermediate stays in fragment order
     (dict(C=160, F=3, H=4, W=16, temb_dim=0), 2),
+    (dict(C=64, C_out=96, F=3), 2),                     # channel change: 1x1 skip convolution, token-major intermediate
+    (dict(C=96, C_out=32, F=2, H=8, W=8), 1),           # fewer output channels, fragment-order intermediate
+    (dict(C=64, C_out=160, F=9, H=4, W=8, temb_dim=0), 1),
 ])
 def test_small_shapes_elementwise(kw, slice_len):
     from gpu_helpers import run_resblock
@@ -84,6 +89,10 @@ def _sampled_frames(spec, frames):
 
 def test_res4_svdxt_shape_sampled_frames():
     _check("res4", *_sampled_frames(wl.RES_CONFIGS["res4"], frames=[0, 24]))
+
+
+def test_res4c_level_transition_sampled_frame():
+    _check("res4c", *_sampled_frames(wl.RES_CONFIGS["res4c"], frames=[24]))     # 320 -> 640 channels, ragged last window
 
 
 def test_res4b_deeper_level_sampled_frames():
