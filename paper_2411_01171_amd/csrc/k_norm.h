@@ -191,6 +191,68 @@ __global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restri
   }
 }
 
+// The same slice-in for bf16 storage with wide accesses: 8-byte reads along positions (when the
+// frame size and the window start are multiples of 4 positions), 16-byte writes of 8 channels'
+// high parts and of their low parts.  C % 8 == 0.
+__global__ __launch_bounds__(256) void window_to_tokens_split_kernel(const bf16* __restrict__ x, const float* __restrict__ stats,
+                                                                     const bf16* __restrict__ gamma, const bf16* __restrict__ beta,
+                                                                     bf16* __restrict__ a0, Window w) {
+  __shared__ float tile[64][65];
+  const int bf = blockIdx.z;
+  const int b = bf / w.Fw, fl = bf % w.Fw, f = w.f0 + fl;
+  const int pt = blockIdx.x * 64, ct = blockIdx.y * 64;
+  const int ng = w.C / w.G;
+  const bool vec_ok = (w.P % 4 == 0) && (w.p0 % 4 == 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int id = threadIdx.x + i * 256, cl = id / 16, pq = (id % 16) * 4;
+    const int c = ct + cl, pl = pt + pq;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (c < w.C && pl < w.Pw) {
+      const int g = c / ng;
+      const float mean = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 0];
+      const float rstd = stats[(((int64_t)b * w.F + f) * w.G + g) * 2 + 1];
+      const float ga = param_or(gamma, c, 1.f), be = param_or(beta, c, 0.f);
+      const bf16* src = x + (((int64_t)b * w.C + c) * w.F + f) * w.P + w.p0 + pl;
+      float xv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (vec_ok && pl + 3 < w.Pw) {
+        const uint2 raw = *reinterpret_cast<const uint2*>(src);
+        xv[0] = __uint_as_float(raw.x << 16);
+        xv[1] = __uint_as_float(raw.x & 0xffff0000u);
+        xv[2] = __uint_as_float(raw.y << 16);
+        xv[3] = __uint_as_float(raw.y & 0xffff0000u);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (pl + j < w.Pw) xv[j] = to_float(src[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = (xv[j] - mean) * rstd * ga + be;  // same expression as window_to_tokens_kernel
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tile[cl][pq + j] = v[j];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int id = threadIdx.x + i * 256, pl = id / 8, co = (id % 8) * 8;
+    const int p = pt + pl, c = ct + co;
+    if (p < w.Pw && c < w.C) {
+      typedef unsigned short u16x8_t __attribute__((ext_vector_type(8)));
+      u16x8_t hi, lo;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float t = tile[co + j][pl];
+        hi[j] = float_to_bf16_bits(t);
+        lo[j] = float_to_bf16_bits(t - bf16_bits_to_float(hi[j]));
+      }
+      bf16* row = a0 + ((int64_t)bf * w.Pw + p) * (2 * w.C);
+      *reinterpret_cast<u16x8_t*>(row + c) = hi;
+      *reinterpret_cast<u16x8_t*>(row + w.C + c) = lo;
+    }
+  }
+}
+
 // PE[f, 2i] = sin(f / 10000^(2i/D)), PE[f, 2i+1] = cos(same), evaluated in fp64.
 __global__ void pe_table_kernel(float* __restrict__ pe, int F, int D) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
@@ -241,12 +303,21 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float* __restrict
     const int v = lane + i * kWave;
     if (v < nv) {
       const float in[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+      float y[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int c = v * 4 + e;
-        float y = (in[e] - mean) * rstd * param_or(gamma, c, 1.f) + param_or(beta, c, 0.f);
-        if (perow) y += perow[c];
-        a[m * D + c] = from_float<T>(y);
+        y[e] = (in[e] - mean) * rstd * param_or(gamma, c, 1.f) + param_or(beta, c, 0.f);
+        if (perow) y[e] += perow[c];
+      }
+      // four consecutive channels per store (rows start 8- / 16-byte aligned: D % 4 == 0)
+      if constexpr (sizeof(T) == 2) {
+        uint2 pk;
+        pk.x = (unsigned)float_to_bf16_bits(y[0]) | ((unsigned)float_to_bf16_bits(y[1]) << 16);
+        pk.y = (unsigned)float_to_bf16_bits(y[2]) | ((unsigned)float_to_bf16_bits(y[3]) << 16);
+        *reinterpret_cast<uint2*>(a + m * D + v * 4) = pk;
+      } else {
+        *reinterpret_cast<float4*>(a + m * D + v * 4) = make_float4(y[0], y[1], y[2], y[3]);
       }
     }
   }

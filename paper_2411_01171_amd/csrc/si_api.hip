@@ -510,7 +510,10 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       {  // slice-in: window -> GroupNorm -> token rows
         StageScope scope("slice_in", st);
         dim3 grid((unsigned)((win.Pw + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * win.Fw));
-        window_to_tokens_kernel<T><<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
+        if constexpr (sizeof(T) == 2)
+          window_to_tokens_split_kernel<<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
+        else
+          window_to_tokens_kernel<T><<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
         SI_CHECK_LAUNCH();
       }
       {
