@@ -298,6 +298,9 @@ def main():
                          "(Spatial ResBlock group); down4, up4b (its Down/UpSample)")
     ap.add_argument("--slice-len", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--weights-packed", action="store_true",
+                    help="steady-state serving: the timed steps promise unchanged weights (SI_FWD_WEIGHTS_PACKED), so "
+                         "the per-call weight re-layout is skipped; the default re-lays-out the weights in every step")
     ap.add_argument("--rehash-probe", choices=["reuse", "compute"], default=None,
                     help="time si_block_forward_rehash instead of forward + output check: the anchor is the input "
                          "itself (reuse: the cached output is handed back) or a drifted input restored before every "
@@ -350,8 +353,10 @@ def main():
     si.si_block_forward(x_prev, wts, ctx, cached, axis, slice_len, ws)
     torch.cuda.synchronize()
 
+    fwd_flags = si.SI_FWD_WEIGHTS_PACKED if args.weights_packed else 0   # ws holds these weights since the call above
+
     def step():
-        si.si_block_forward(x, wts, ctx, out, axis, slice_len, ws)
+        si.si_block_forward_ex(x, wts, ctx, out, axis, slice_len, ws, fwd_flags)
         si.si_rehash_check(out, cached, gamma, cos, dec, scratch)
 
     probe = {}
@@ -446,6 +451,7 @@ def main():
         "config": {"workload": f"{args.workload}: {spec.kind} block x[B={spec.B},C={spec.C},F={spec.F},H={spec.H},W={spec.W}], "
                                f"{spec.heads} heads x {spec.dim_head}, sliced along {spec.slice_axis} in windows of {slice_len} "
                                f"({n_slices} slices) + " +
+                               ("weights re-laid-out once, not per step; " if args.weights_packed else "") +
                                (f"rehash check of the output (threshold {gamma})" if not args.rehash_probe else
                                 f"one-pass rehash on the input, probe '{args.rehash_probe}' (value counts the forward's "
                                 f"FLOPs whether computed or handed back)"),

@@ -140,6 +140,21 @@ si_status si_block_forward(const si_tensor5* x, const si_block_weights* w, const
                            si_tensor5* out, int32_t axis, int64_t slice_len,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* si_block_forward with options.  flags:
+ *   SI_FWD_WEIGHTS_PACKED  the caller vouches that `workspace` was last used by a forward call
+ *                          (any entry point) with the SAME weight values, tensor shapes, context
+ *                          shape, axis and slice_len, and has not been written since: the
+ *                          re-laid-out weights and the frame table it still holds are used as
+ *                          they are and the re-layout pass is skipped (weights are constant
+ *                          across diffusion steps).  Everything activation-derived (statistics,
+ *                          context keys / values) is recomputed.  A wrong promise gives wrong
+ *                          results, not an error.
+ * Unknown flag bits -> SI_ERR_ARG.  flags == 0 is si_block_forward. */
+#define SI_FWD_WEIGHTS_PACKED 1u
+si_status si_block_forward_ex(const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
+                              si_tensor5* out, int32_t axis, int64_t slice_len, void* workspace,
+                              size_t workspace_bytes, uint32_t flags, void* stream);
+
 /* Scratch bytes si_rehash_check needs for n elements (partial sums). */
 size_t si_rehash_scratch_bytes(int64_t n);
 

@@ -80,6 +80,8 @@ def lib() -> C.CDLL:
     L.si_block_forward.restype = i32
     L.si_block_forward.argtypes = [C.POINTER(_Tensor5), C.POINTER(_Weights), C.POINTER(_Context), C.POINTER(_Tensor5),
                                    i32, i64, vp, sz, vp]
+    L.si_block_forward_ex.restype = i32
+    L.si_block_forward_ex.argtypes = L.si_block_forward.argtypes[:8] + [C.c_uint32, vp]
     L.si_block_forward_rehash.restype = i32
     L.si_block_forward_rehash.argtypes = L.si_block_forward.argtypes[:8] + [
         C.POINTER(_RehashCache), C.c_float, vp, C.POINTER(C.c_double), C.POINTER(i32)]
@@ -190,6 +192,9 @@ def si_live_activation_bytes(x, weights: BlockWeights, ctx, axis: int, slice_len
     return int(lib().si_live_activation_bytes(C.byref(xd), C.byref(weights.struct), pc, axis, slice_len))
 
 
+SI_FWD_WEIGHTS_PACKED = 1
+
+
 def si_block_forward(x, weights: BlockWeights, ctx, out, axis: int, slice_len: int, workspace, stream=None) -> None:
     """Enqueues the sliced block forward on `stream` (default: torch's current stream)."""
     xd, od = _tensor5(x), _tensor5(out)
@@ -199,6 +204,18 @@ def si_block_forward(x, weights: BlockWeights, ctx, out, axis: int, slice_len: i
                                 _stream_ptr(stream))
     if st != 0:
         raise SiError(st, "si_block_forward")
+
+
+def si_block_forward_ex(x, weights: BlockWeights, ctx, out, axis: int, slice_len: int, workspace, flags: int = 0,
+                        stream=None) -> None:
+    """si_block_forward with flags (SI_FWD_WEIGHTS_PACKED: the workspace still holds these weights re-laid-out)."""
+    xd, od = _tensor5(x), _tensor5(out)
+    pc, _keep = _pctx(ctx)
+    st = lib().si_block_forward_ex(C.byref(xd), C.byref(weights.struct), pc, C.byref(od), axis, slice_len,
+                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(), flags,
+                                   _stream_ptr(stream))
+    if st != 0:
+        raise SiError(st, "si_block_forward_ex")
 
 
 class ResBlockWeights:

@@ -387,7 +387,7 @@ static si_status launch_gn_stats(const Plan& p, const T* X, const T* key, float 
 
 template <typename T>
 static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
-                           si_tensor5* out, char* ws, hipStream_t st, bool stats_done = false) {
+                           si_tensor5* out, char* ws, hipStream_t st, bool stats_done = false, bool packed = false) {
   const T* X = static_cast<const T*>(x->ptr);
   T* OUT = static_cast<T*>(out->ptr);
   float* stats = reinterpret_cast<float*>(ws + p.off_stats);
@@ -411,8 +411,9 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   constexpr int kSplit = sizeof(T) == 2 ? 2 : 1;
   auto cT = [](const void* q) { return static_cast<const T*>(q); };
 
-  // ---- once per call: weight re-layout, frame embedding table, GroupNorm statistics, context K/V
-  {
+  // ---- once per call: weight re-layout, frame embedding table (skipped when the caller vouches that
+  // the workspace still holds them), GroupNorm statistics, context K/V
+  if (!packed) {
     StageScope scope("pack_weights", st);
     if (!fused_attn) {
       for (int h2 = 0; h2 < kSplit; ++h2)
@@ -703,15 +704,23 @@ static si_status check_forward(const si_tensor5* x, const si_block_weights* w, c
   return SI_OK;
 }
 
-si_status si_block_forward(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, si_tensor5* out,
-                           int32_t axis, int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream) {
+si_status si_block_forward_ex(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, si_tensor5* out,
+                              int32_t axis, int64_t slice_len, void* workspace, size_t workspace_bytes, uint32_t flags,
+                              void* stream) {
+  if (flags & ~(uint32_t)SI_FWD_WEIGHTS_PACKED) return SI_ERR_ARG;
   si::Plan p;
   si_status s = check_forward(x, w, ctx, out, axis, slice_len, workspace, workspace_bytes, p);
   if (s != SI_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  if (p.dtype == SI_F32) return si::run_block<float>(p, x, w, ctx, out, ws, st);
-  return si::run_block<si::bf16>(p, x, w, ctx, out, ws, st);
+  const bool packed = (flags & SI_FWD_WEIGHTS_PACKED) != 0;
+  if (p.dtype == SI_F32) return si::run_block<float>(p, x, w, ctx, out, ws, st, false, packed);
+  return si::run_block<si::bf16>(p, x, w, ctx, out, ws, st, false, packed);
+}
+
+si_status si_block_forward(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, si_tensor5* out,
+                           int32_t axis, int64_t slice_len, void* workspace, size_t workspace_bytes, void* stream) {
+  return si_block_forward_ex(x, w, ctx, out, axis, slice_len, workspace, workspace_bytes, 0u, stream);
 }
 
 si_status si_block_forward_rehash(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, si_tensor5* out,

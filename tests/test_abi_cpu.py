@@ -172,6 +172,14 @@ def test_resample_validation():
     assert call(B.SI_RESAMPLE_DOWN, B._Tensor5(x.ptr + 256, B.SI_BF16, 2, 64, 4, 4, 5)) == 7   # out overlaps x
 
 
+def test_forward_ex_flags():
+    x, w, _, out = _descs()
+    lib = si.lib()
+    args = (C.byref(x), C.byref(w), None, C.byref(out), B.SI_AXIS_HW, 4, 0x7000000000, 1 << 40)
+    assert lib.si_block_forward_ex(*args, 2, None) == 7                    # unknown flag bit
+    assert lib.si_block_forward_ex(*args[:5], 0, *args[6:], B.SI_FWD_WEIGHTS_PACKED, None) == 4   # the forward's checks still apply
+
+
 def test_workspace_scales_with_the_slice():
     x, w, _, _ = _descs(Cn=320, heads=8, dh=40, groups=32, F=16, H=64, W=64)
     lib = si.lib()

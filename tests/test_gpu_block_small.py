@@ -155,3 +155,32 @@ def test_deterministic():
     a = run_block(spec, x, w, ctx, 1)
     b = run_block(spec, x, w, ctx, 1)
     assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("cfg,kw", [("cfg2", dict(H=8, W=8, slice_len=24)), ("cfg3", dict(C=64, F=3, H=8, W=8, heads=1, dim_head=64, ctx_tokens=5, ctx_dim=16)),
+                                    ("cfg1", dict())])
+def test_packed_weights_flag_reuses_the_workspace(cfg, kw):
+    """A second call that promises unchanged weights skips the re-layout and must give the same bits, also for another input."""
+    import torch
+    import paper_2411_01171_amd as si
+    from gpu_helpers import AXIS, device_weights, to_dev
+    spec = wl.scaled(wl.CONFIGS[cfg], **kw)
+    x1, x2 = wl.make_x(spec), wl.make_x(spec, seed=spec.seed + 9)
+    ctx_np = wl.make_context(spec)
+    ctx = None if ctx_np is None else to_dev(ctx_np, spec.dtype)
+    wd = device_weights(spec, wl.make_weights(spec, randomize_affine=True))
+    xa, xb = to_dev(x1, spec.dtype), to_dev(x2, spec.dtype)
+    axis = AXIS[spec.slice_axis]
+    ws = torch.empty(si.si_workspace_bytes(xa, wd, ctx, axis, spec.slice_len), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty_like(ws)
+    ref_a, ref_b, out = torch.empty_like(xa), torch.empty_like(xa), torch.empty_like(xa)
+    si.si_block_forward(xa, wd, ctx, ref_a, axis, spec.slice_len, ws2)
+    si.si_block_forward(xb, wd, ctx, ref_b, axis, spec.slice_len, ws2)
+    si.si_block_forward(xa, wd, ctx, out, axis, spec.slice_len, ws)                       # packs
+    for x, ref in ((xb, ref_b), (xa, ref_a)):
+        out.fill_(float("nan"))
+        si.si_block_forward_ex(x, wd, ctx, out, axis, spec.slice_len, ws, si.SI_FWD_WEIGHTS_PACKED)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
+    with pytest.raises(si.SiError):
+        si.si_block_forward_ex(xa, wd, ctx, out, axis, spec.slice_len, ws, 8)             # unknown flag
