@@ -47,9 +47,8 @@ struct EpiStore {
 };
 
 // Residual stream (fp32): h[m, n] = (accumulate ? h[m, n] : 0) + acc + bias[n];
-// optionally the new value is also stored as T in copy (operand of the next GEMM):
-// fp32 storage as is; bf16 storage as a (high, low) pair, high parts in columns
-// [0, ld), low parts in [ld, 2*ld) of a row of 2*ld elements.
+// optionally the new value is also stored in copy (operand of proj_out): fp32 storage
+// as is; 16-bit storage as fp16 (11 significand bits, saturated at +-65504), row stride ld.
 template <typename T>
 struct EpiResidual {
   float* h;
@@ -68,13 +67,11 @@ struct EpiResidual {
     if (copy) {
       const float ov[4] = {o.x, o.y, o.z, o.w};
       if constexpr (sizeof(T) == 2) {
-        T* c = copy + m * (2 * ld) + n0;
+        typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+        f16x4_t c4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const T hi = from_float<T>(ov[i]);
-          c[i] = hi;
-          c[ld + i] = from_float<T>(ov[i] - to_float(hi));
-        }
+        for (int i = 0; i < 4; ++i) c4[i] = (_Float16)__builtin_amdgcn_fmed3f(ov[i], -65504.f, 65504.f);
+        *reinterpret_cast<f16x4_t*>(copy + m * ld + n0) = c4;
       } else {
         T* c = copy + m * ld + n0;
 #pragma unroll
@@ -137,7 +134,8 @@ struct EpiSliceOut {
 // loads for tile k+1 are issued before the MFMAs of tile k (register staging,
 // two LDS buffers, one barrier per tile).  Out-of-range rows / k are zero-filled.
 // Requires K % 8 == 0, lda % 8 == 0 and 16-byte aligned bases.
-template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi, int BK = 64>
+// F16: the 16-bit operands are fp16 (v_mfma_f32_32x32x16_f16) instead of bf16.
+template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi, int BK = 64, bool F16 = false>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16* __restrict__ A, int64_t lda,
                                                         const bf16* __restrict__ Wp, int64_t M, int N, int K, Epi epi) {
   static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per block");
@@ -201,15 +199,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16* __restrict__
     if (kt + 1 < nk) load_tile((kt + 1) * BK);
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8_t wf[TN], af[TM];
+      u32x4_t wf[TN], af[TM];
 #pragma unroll
-      for (int i = 0; i < TN; ++i) wf[i] = *reinterpret_cast<const bf16x8_t*>(&Ws[cur][wn0 + i * 32 + frow][kk + fk]);
+      for (int i = 0; i < TN; ++i) wf[i] = *reinterpret_cast<const u32x4_t*>(&Ws[cur][wn0 + i * 32 + frow][kk + fk]);
 #pragma unroll
-      for (int j = 0; j < TM; ++j) af[j] = *reinterpret_cast<const bf16x8_t*>(&As[cur][wm0 + j * 32 + frow][kk + fk]);
+      for (int j = 0; j < TM; ++j) af[j] = *reinterpret_cast<const u32x4_t*>(&As[cur][wm0 + j * 32 + frow][kk + fk]);
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int j = 0; j < TM; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], af[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TM; ++j) {
+          if constexpr (F16) {
+            typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, wf[i]), __builtin_bit_cast(f16x8_t, af[j]),
+                                                               acc[i][j], 0, 0, 0);
+          } else {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[i]), __builtin_bit_cast(bf16x8_t, af[j]),
+                                                                acc[i][j], 0, 0, 0);
+          }
+        }
     }
     if (kt + 1 < nk) store_tile(cur ^ 1);
     __syncthreads();

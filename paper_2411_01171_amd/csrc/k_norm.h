@@ -148,9 +148,8 @@ struct Window {
 
 // Slice-in: a0[m, c] = GN(x)[b, c, f, p] for the window's tokens.  64 x 64
 // (position x channel) tiles are transposed through LDS so that both the read
-// (along positions) and the write (along channels) are contiguous.  For bf16
-// storage the normalised value is kept as a (high, low) bf16 pair -- row m holds
-// C high parts followed by C low parts -- so that proj_in sees it to ~16 bits.
+// (along positions) and the write (along channels) are contiguous.  Used for fp32
+// storage; 16-bit storage takes window_to_tokens_f16_kernel.
 template <typename T>
 __global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restrict__ x, const float* __restrict__ stats,
                                                                const T* __restrict__ gamma, const T* __restrict__ beta,
@@ -180,21 +179,16 @@ __global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restri
     const int c = ct + tx, p = pt + pl;
     if (c < w.C && p < w.Pw) {
       const int64_t m = (int64_t)bf * w.Pw + p;
-      if constexpr (sizeof(T) == 2) {
-        const T hi = from_float<T>(tile[tx][pl]);
-        a0[m * (2 * w.C) + c] = hi;
-        a0[m * (2 * w.C) + w.C + c] = from_float<T>(tile[tx][pl] - to_float(hi));
-      } else {
-        a0[m * w.C + c] = from_float<T>(tile[tx][pl]);
-      }
+      a0[m * w.C + c] = from_float<T>(tile[tx][pl]);
     }
   }
 }
 
-// The same slice-in for bf16 storage with wide accesses: 8-byte reads along positions (when the
-// frame size and the window start are multiples of 4 positions), 16-byte writes of 8 channels'
-// high parts and of their low parts.  C % 8 == 0.
-__global__ __launch_bounds__(256) void window_to_tokens_split_kernel(const bf16* __restrict__ x, const float* __restrict__ stats,
+// Slice-in for bf16 storage: the normalised value (bounded by construction) is kept as fp16, the
+// operand type of proj_in on this path -- three more significand bits than bf16 for the same bytes.
+// 8-byte reads along positions (when the frame size and the window start are multiples of 4
+// positions), 16-byte writes of 8 channels.  C % 8 == 0; row m holds C values.
+__global__ __launch_bounds__(256) void window_to_tokens_f16_kernel(const bf16* __restrict__ x, const float* __restrict__ stats,
                                                                      const bf16* __restrict__ gamma, const bf16* __restrict__ beta,
                                                                      bf16* __restrict__ a0, Window w) {
   __shared__ float tile[64][65];
@@ -238,17 +232,11 @@ __global__ __launch_bounds__(256) void window_to_tokens_split_kernel(const bf16*
     const int id = threadIdx.x + i * 256, pl = id / 8, co = (id % 8) * 8;
     const int p = pt + pl, c = ct + co;
     if (p < w.Pw && c < w.C) {
-      typedef unsigned short u16x8_t __attribute__((ext_vector_type(8)));
-      u16x8_t hi, lo;
+      typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+      f16x8_t o;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float t = tile[co + j][pl];
-        hi[j] = float_to_bf16_bits(t);
-        lo[j] = float_to_bf16_bits(t - bf16_bits_to_float(hi[j]));
-      }
-      bf16* row = a0 + ((int64_t)bf * w.Pw + p) * (2 * w.C);
-      *reinterpret_cast<u16x8_t*>(row + c) = hi;
-      *reinterpret_cast<u16x8_t*>(row + w.C + c) = lo;
+      for (int j = 0; j < 8; ++j) o[j] = (_Float16)__builtin_amdgcn_fmed3f(tile[co + j][pl], -65504.f, 65504.f);
+      *reinterpret_cast<f16x8_t*>(a0 + ((int64_t)bf * w.Pw + p) * w.C + c) = o;
     }
   }
 }
@@ -327,9 +315,11 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float* __restrict
 // layout the GEMM kernels read (ld_dst > K lets two copies sit side by side for
 // operands that arrive as high/low pairs).  col(r) = col0 + r, or, with `interleave` > 0
 // (GEGLU projection), even r -> value column r/2, odd r -> gate column interleave + r/2.
+// to_f16 (16-bit T only): the bf16 values are stored as fp16 (weights of the GEMMs whose activation
+// operand is fp16; exact for normal fp16 magnitudes, saturated at +-65504).
 template <typename T>
 __global__ __launch_bounds__(256) void pack_transpose_kernel(const T* __restrict__ src, T* __restrict__ dst, int K, int ld_src,
-                                                             int rows, int col0, int interleave, int ld_dst) {
+                                                             int rows, int col0, int interleave, int ld_dst, int to_f16 = 0) {
   __shared__ T tile[32][33];
   const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
   const int r0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
@@ -343,7 +333,13 @@ __global__ __launch_bounds__(256) void pack_transpose_kernel(const T* __restrict
   __syncthreads();
   for (int rr = ty; rr < 32; rr += 8) {
     const int r = r0 + rr, k = k0 + tx;
-    if (r < rows && k < K) dst[(int64_t)r * ld_dst + k] = tile[tx][rr];
+    if (r < rows && k < K) {
+      T v = tile[tx][rr];
+      if constexpr (sizeof(T) == 2) {
+        if (to_f16) v.v = __builtin_bit_cast(unsigned short, (_Float16)__builtin_amdgcn_fmed3f(to_float(v), -65504.f, 65504.f));
+      }
+      dst[(int64_t)r * ld_dst + k] = v;
+    }
   }
 }
 

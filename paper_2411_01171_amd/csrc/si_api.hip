@@ -161,7 +161,7 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
                     (p->B <= 2 || last_len >= 128);
   }
   // one slice's intermediates
-  const size_t split = es == 2 ? 2 : 1;  // bf16 staged path: proj_in / proj_out operands travel as (high, low) pairs
+  const size_t split = 1;  // proj_in / proj_out operands of the bf16 staged path travel as fp16, same bytes as bf16
   if (p->fused_attn) {  // one kernel per window: only the parked residual stream (128 rows per workgroup)
     const int64_t npos = 4 * (32 / p->F);
     const int64_t wgs = ((int64_t)p->B * p->slice_len + npos - 1) / npos;
@@ -208,23 +208,24 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     if (hipGetLastError() != hipSuccess) return SI_ERR_HIP; \
   } while (0)
 
-template <typename T, class Epi, int BK>
+template <typename T, class Epi, int BK, bool F16>
 static void launch_gemm_bf16(const T* A, int64_t lda, const T* Wp, int64_t M, int N, int K, Epi epi, hipStream_t st) {
   // small problems (a slice of a few thousand tokens times a D-wide matrix) get 64 x 64 tiles:
   // four times the workgroups, so that every CU has work
   if (((M + 127) / 128) * ((N + 127) / 128) < 256) {
     dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 63) / 64));
-    gemm_bf16_kernel<64, 64, 2, 2, Epi, BK><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+    gemm_bf16_kernel<64, 64, 2, 2, Epi, BK, F16><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
   } else if (N % 128 == 0) {
     dim3 grid((unsigned)((M + 127) / 128), (unsigned)(N / 128));
-    gemm_bf16_kernel<128, 128, 2, 2, Epi, BK><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+    gemm_bf16_kernel<128, 128, 2, 2, Epi, BK, F16><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
   } else {
     dim3 grid((unsigned)((M + 127) / 128), (unsigned)((N + 63) / 64));
-    gemm_bf16_kernel<128, 64, 4, 1, Epi, BK><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
+    gemm_bf16_kernel<128, 64, 4, 1, Epi, BK, F16><<<grid, 256, 0, st>>>(A, lda, Wp, M, N, K, epi);
   }
 }
 
-template <typename T, class Epi>
+// F16: both 16-bit operands hold fp16 values (proj_in / proj_out of the bf16 staged path).
+template <typename T, bool F16 = false, class Epi>
 static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T* Wp, int64_t M, int N, int K, Epi epi,
                              hipStream_t st) {
   if (M <= 0) return SI_OK;
@@ -235,8 +236,8 @@ static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T
   } else {
     // short contractions (K = 320: five 64-wide tiles) run better with 32-wide k tiles: half the LDS,
     // twice the workgroups per CU to hide the pipeline's fill and drain
-    if (K <= 512) launch_gemm_bf16<T, Epi, 32>(A, lda, Wp, M, N, K, epi, st);
-    else launch_gemm_bf16<T, Epi, 64>(A, lda, Wp, M, N, K, epi, st);
+    if (K <= 512) launch_gemm_bf16<T, Epi, 32, F16>(A, lda, Wp, M, N, K, epi, st);
+    else launch_gemm_bf16<T, Epi, 64, F16>(A, lda, Wp, M, N, K, epi, st);
   }
   SI_CHECK_LAUNCH();
   return SI_OK;
@@ -244,9 +245,9 @@ static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T
 
 template <typename T>
 static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, int col0, int interleave, hipStream_t st,
-                             int ld_dst = 0) {
+                             int ld_dst = 0, bool to_f16 = false) {
   dim3 grid((unsigned)((rows + 31) / 32), (unsigned)((K + 31) / 32));
-  pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, dst, K, ld_src, rows, col0, interleave, ld_dst ? ld_dst : K);
+  pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, dst, K, ld_src, rows, col0, interleave, ld_dst ? ld_dst : K, to_f16 ? 1 : 0);
   SI_CHECK_LAUNCH();
   return SI_OK;
 }
@@ -408,7 +409,8 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   const int C = p.C, D = p.D;
   const bool spatial = p.kind == SI_BLOCK_SPATIAL;
   const bool fused_ffn = p.fused_nb > 0, fused_attn = p.fused_attn;
-  constexpr int kSplit = sizeof(T) == 2 ? 2 : 1;
+  constexpr int kSplit = 1;
+  constexpr bool kF16 = sizeof(T) == 2;  // proj_in / proj_out run on fp16 operands for 16-bit storage
   auto cT = [](const void* q) { return static_cast<const T*>(q); };
 
   // ---- once per call: weight re-layout, frame embedding table (skipped when the caller vouches that
@@ -417,7 +419,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     StageScope scope("pack_weights", st);
     if (!fused_attn) {
       for (int h2 = 0; h2 < kSplit; ++h2)
-        SI_TRY(launch_pack<T>(cT(w->w_in), w_in + (size_t)h2 * C, C, D, D, 0, 0, st, kSplit * C));
+        SI_TRY(launch_pack<T>(cT(w->w_in), w_in + (size_t)h2 * C, C, D, D, 0, 0, st, kSplit * C, kF16));
       SI_TRY(launch_pack<T>(cT(w->wq), wqkv, D, D, D, 0, 0, st));
       SI_TRY(launch_pack<T>(cT(w->wk), wqkv + (size_t)D * D, D, D, D, 0, 0, st));
       SI_TRY(launch_pack<T>(cT(w->wv), wqkv + (size_t)2 * D * D, D, D, D, 0, 0, st));
@@ -431,7 +433,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     }
     if (!fused_ffn) {
       for (int h2 = 0; h2 < kSplit; ++h2)
-        SI_TRY(launch_pack<T>(cT(w->w_out), w_out + (size_t)h2 * D, D, C, C, 0, 0, st, kSplit * D));
+        SI_TRY(launch_pack<T>(cT(w->w_out), w_out + (size_t)h2 * D, D, C, C, 0, 0, st, kSplit * D, kF16));
       SI_TRY(launch_pack<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 0, 4 * D, st));
       SI_TRY(launch_pack<T>(cT(w->w2), w2, 4 * D, D, D, 0, 0, st));
     } else if constexpr (sizeof(T) == 2) {
@@ -512,14 +514,14 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         StageScope scope("slice_in", st);
         dim3 grid((unsigned)((win.Pw + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * win.Fw));
         if constexpr (sizeof(T) == 2)
-          window_to_tokens_split_kernel<<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
+          window_to_tokens_f16_kernel<<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
         else
           window_to_tokens_kernel<T><<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
         SI_CHECK_LAUNCH();
       }
       {
         EpiResidual<T> epi{h, (int64_t)D, cT(w->b_in), 0, nullptr};
-        SI_TRY(launch_gemm<T>("proj_in", a, (int64_t)kSplit * C, w_in, M, D, kSplit * C, epi, st));
+        SI_TRY((launch_gemm<T, kF16>("proj_in", a, (int64_t)kSplit * C, w_in, M, D, kSplit * C, epi, st)));
       }
       SI_TRY(launch_layer_norm<T>("ln1", h, a, M, D, w->ln1_g, w->ln1_b, w->ln_eps, pe, win.Pw, win.Fw, win.f0, st));
       {
@@ -612,7 +614,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     }
     {
       EpiSliceOut<T> epi{X, OUT, cT(w->b_out), win};
-      SI_TRY(launch_gemm<T>("proj_out", a, (int64_t)kSplit * D, w_out, M, C, kSplit * D, epi, st));
+      SI_TRY((launch_gemm<T, kF16>("proj_out", a, (int64_t)kSplit * D, w_out, M, C, kSplit * D, epi, st)));
     }
   }
   if (lanes >= 2) {  // join: the caller's stream continues after all lanes
