@@ -46,6 +46,29 @@ struct EpiStore {
   }
 };
 
+// q/k/v projection for the matrix-core attention kernel: columns [0, 2D) (queries, keys) are stored
+// row-major as EpiStore does; the value columns go straight to the transposed copy the kernel reads,
+// vt[(s*D + c)*Pw + key] for token m = s*Pw + key (keys contiguous), and are not stored row-major.
+struct EpiStoreQKVt {
+  bf16* out;
+  int64_t ld;
+  bf16* vt;
+  int D, Pw;
+  __device__ __forceinline__ void operator()(int64_t m, int n0, const float (&v)[4]) const {
+    if (n0 < 2 * D) {
+      uint2 pk;
+      pk.x = (unsigned)float_to_bf16_bits(v[0]) | ((unsigned)float_to_bf16_bits(v[1]) << 16);
+      pk.y = (unsigned)float_to_bf16_bits(v[2]) | ((unsigned)float_to_bf16_bits(v[3]) << 16);
+      *reinterpret_cast<uint2*>(out + m * ld + n0) = pk;
+    } else {
+      const int mi = (int)m, s = mi / Pw, key = mi - s * Pw;
+      bf16* p = vt + ((int64_t)s * D + (n0 - 2 * D)) * Pw + key;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) p[(int64_t)i * Pw] = from_float<bf16>(v[i]);
+    }
+  }
+};
+
 // Residual stream (fp32): h[m, n] = (accumulate ? h[m, n] : 0) + acc + bias[n];
 // optionally the new value is also stored in copy (operand of proj_out): fp32 storage
 // as is; 16-bit storage as fp16 (11 significand bits, saturated at +-65504), row stride ld.

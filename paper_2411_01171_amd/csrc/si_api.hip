@@ -524,21 +524,22 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         SI_TRY((launch_gemm<T, kF16>("proj_in", a, (int64_t)kSplit * C, w_in, M, D, kSplit * C, epi, st)));
       }
       SI_TRY(launch_layer_norm<T>("ln1", h, a, M, D, w->ln1_g, w->ln1_b, w->ln_eps, pe, win.Pw, win.Fw, win.f0, st));
-      {
-        EpiStore<T> epi{big, (int64_t)3 * D, nullptr};
-        SI_TRY(launch_gemm<T>("qkv", a, (int64_t)D, wqkv, M, 3 * D, D, epi, st));
-      }
       bool self_done = false;
       if constexpr (sizeof(T) == 2) {
-        if (p.attn_mfma) {  // spatial: sequence (b, f) = rows (b*Fw + f)*Pw + i
+        if (p.attn_mfma) {  // spatial: sequence (b, f) = rows (b*Fw + f)*Pw + i; the projection writes V transposed
           bf16* vt = reinterpret_cast<bf16*>(vt_lane);
-          SI_TRY(launch_transpose_v("v_transpose", big, (int64_t)3 * D, 2 * D, vt, p.B * win.Fw, win.Pw, win.Pw, D, st));
+          EpiStoreQKVt epi{big, (int64_t)3 * D, vt, D, win.Pw};
+          SI_TRY(launch_gemm<T>("qkv", a, (int64_t)D, wqkv, M, 3 * D, D, epi, st));
           SI_TRY(launch_attention_mfma("self_attn", big, (int64_t)3 * D, big + D, (int64_t)3 * D, vt, a, (int64_t)D, p.B * win.Fw,
                                        win.Pw, win.Pw, win.Pw, p.heads, 1, scale, st));
           self_done = true;
         }
       }
       if (!self_done) {
+        {
+          EpiStore<T> epi{big, (int64_t)3 * D, nullptr};
+          SI_TRY(launch_gemm<T>("qkv", a, (int64_t)D, wqkv, M, 3 * D, D, epi, st));
+        }
         AttnArgs at;
         at.q = big; at.k = big + D; at.v = big + 2 * D; at.o = a;
         at.ldq = at.ldk = at.ldv = (int64_t)3 * D; at.ldo = D;
