@@ -457,9 +457,15 @@ def main():
                                 f"FLOPs whether computed or handed back)"),
                    "algorithmic_flop_per_step": flops, "tokens": spec.tokens},
         "frac_mfma_peak": value / PEAK_BF16_TFLOPS,
+        # unsliced_same_kernels: this library run with slice_len = whole axis (its fused kernels keep most
+        # intermediates on chip even then); unsliced_op_by_op: the operator-by-operator forward the method
+        # is defined against (Sec. 4.2.1), whose live set at the FFN is the residual stream plus the GEGLU
+        # projection and its gated product, (1 + 8 + 4) * tokens * C elements
         "live_activation_bytes": {"sliced": live_sliced, "unsliced_same_kernels": live_unsliced,
-                                  "ratio": live_sliced / live_unsliced, "workspace_bytes": ws_bytes,
-                                  "x_bytes": x.numel() * x.element_size()},
+                                  "ratio": live_sliced / live_unsliced,
+                                  "unsliced_op_by_op": 13 * spec.tokens * spec.C * x.element_size(),
+                                  "ratio_op_by_op": live_sliced / (13 * spec.tokens * spec.C * x.element_size()),
+                                  "workspace_bytes": ws_bytes, "x_bytes": x.numel() * x.element_size()},
         "rehash": ({"cos": float(cos.item()), "decision": int(dec.item())} if not args.rehash_probe else
                    {"probe": args.rehash_probe, "reused": bool(probe["reused"]), "cos": probe["cos"]}),
         "roofline": roof,
