@@ -201,7 +201,10 @@ typedef struct {
  * consecutive steps as the test keeps passing) and nothing else runs;
  * otherwise out := si_block_forward(x) bit for bit, and x, out become the new
  * anchor (two device-to-device copies).  With cache->valid == 0 the block is
- * computed unconditionally.
+ * computed unconditionally.  out->ptr may equal cache->y_key (the one overlap
+ * that is allowed): the result then lives in the anchor's output buffer, a
+ * reused step copies nothing and a computed step copies only x; the caller
+ * must be done with it before the next call on this cache.
  *
  * The similarity sums ride on the GroupNorm statistics pass (x is read once
  * for both; the anchor input is the only extra read), then the call WAITS for

@@ -738,9 +738,12 @@ si_status si_block_forward_rehash(const si_tensor5* x, const si_block_weights* w
   if (!si::aligned16(cache->x_key) || !si::aligned16(cache->y_key)) return SI_ERR_ALIGN;
   if (std::isnan(gamma)) return SI_ERR_ARG;
   const size_t xbytes = (size_t)p.B * p.C * p.F * (size_t)p.P * p.esize;
+  // out may BE the anchor's output buffer: the result then lives there and nothing is copied back and forth
+  const bool in_place = out->ptr == cache->y_key;
   const void* held[] = {cache->x_key, cache->y_key};
   for (const void* q : held)
-    if (si::ranges_overlap(q, xbytes, x->ptr, xbytes) || si::ranges_overlap(q, xbytes, out->ptr, xbytes) ||
+    if (si::ranges_overlap(q, xbytes, x->ptr, xbytes) ||
+        (!(in_place && q == cache->y_key) && si::ranges_overlap(q, xbytes, out->ptr, xbytes)) ||
         si::ranges_overlap(q, xbytes, workspace, p.total_bytes))
       return SI_ERR_ARG;
   if (si::ranges_overlap(cache->x_key, xbytes, cache->y_key, xbytes)) return SI_ERR_ARG;
@@ -772,8 +775,10 @@ si_status si_block_forward_rehash(const si_tensor5* x, const si_block_weights* w
     cosv = host.c;
     stats_done = true;
     if (host.d) {  // similar enough: hand the cached output back, nothing else runs
-      si::StageScope scope("cache_handback", st);
-      if (hipMemcpyAsync(out->ptr, cache->y_key, xbytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SI_ERR_HIP;
+      if (!in_place) {
+        si::StageScope scope("cache_handback", st);
+        if (hipMemcpyAsync(out->ptr, cache->y_key, xbytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SI_ERR_HIP;
+      }
       if (cos_host) *cos_host = cosv;
       *reused_host = 1;
       return SI_OK;
@@ -785,7 +790,8 @@ si_status si_block_forward_rehash(const si_tensor5* x, const si_block_weights* w
   {
     si::StageScope scope("cache_update", st);
     if (hipMemcpyAsync(cache->x_key, x->ptr, xbytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SI_ERR_HIP;
-    if (hipMemcpyAsync(cache->y_key, out->ptr, xbytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SI_ERR_HIP;
+    if (!in_place && hipMemcpyAsync(cache->y_key, out->ptr, xbytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+      return SI_ERR_HIP;
   }
   cache->valid = 1;
   if (cos_host) *cos_host = cosv;

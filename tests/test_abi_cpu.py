@@ -100,7 +100,7 @@ def test_forward_rehash_validation():
     assert call(C.byref(B._RehashCache(fake + (4 << 30) + 4, fake + (5 << 30), 0))) == 5
     assert call(C.byref(good), gamma=float("nan")) == 7
     assert call(C.byref(B._RehashCache(x.ptr, fake + (5 << 30), 0))) == 7              # anchor aliases x
-    assert call(C.byref(B._RehashCache(fake + (4 << 30), out.ptr + 256, 0))) == 7      # anchor aliases out
+    assert call(C.byref(B._RehashCache(fake + (4 << 30), out.ptr + 256, 0))) == 7      # anchor overlaps out partially
     assert call(C.byref(B._RehashCache(fake + (4 << 30), fake + (4 << 30) + 1024, 0))) == 7  # anchors overlap
     assert call(C.byref(B._RehashCache(0x7000000000 + 4096, fake + (5 << 30), 0))) == 7      # inside the workspace
     bad = B._Tensor5(x.ptr, 5, 2, 64, 4, 8, 8)

@@ -43,6 +43,30 @@ def _walk(spec, xs_np, gamma, ctx_np=None):
     return got
 
 
+def test_result_in_the_anchor_buffer_copies_nothing_back():
+    """out == cache.y_key: same decisions and the same bits as the copying mode, the result read from the anchor buffer."""
+    import torch
+    import paper_2411_01171_amd as si
+    from gpu_helpers import AXIS, device_weights, to_dev
+    spec = wl.scaled(wl.CONFIGS["cfg2"], H=8, W=8, slice_len=24)
+    rng = np.random.default_rng(31)
+    xs_np = [wl.make_x(spec)]
+    for s in (0.05, 0.4, 0.0, 0.05):
+        xs_np.append(wl.round_to_storage(xs_np[-1] + np.float32(s) * rng.standard_normal(xs_np[-1].shape, dtype=np.float32), "bf16"))
+    wd = device_weights(spec, wl.make_weights(spec))
+    xs = [to_dev(x, "bf16") for x in xs_np]
+    axis = AXIS[spec.slice_axis]
+    ws = torch.empty(si.si_workspace_bytes(xs[0], wd, None, axis, spec.slice_len), dtype=torch.uint8, device="cuda")
+    ref = _walk(spec, xs_np, 0.95)
+    cache = si.RehashCache(xs[0])
+    for x, (reused_ref, cos_ref, out_ref) in zip(xs, ref):
+        reused, cos = si.si_block_forward_rehash(x, wd, None, cache.y_key, axis, spec.slice_len, ws, cache, 0.95)
+        torch.cuda.synchronize()
+        assert reused == reused_ref and (cos == cos_ref or (math.isnan(cos) and math.isnan(cos_ref)))
+        assert torch.equal(cache.y_key, out_ref)
+    assert [r for r, _, _ in ref] == [False, True, False, True, True]
+
+
 def _check_against_oracle(xs_np, got, gamma):
     ref = list(oracle.rehash_causal_ref(xs_np, lambda x: x, gamma))      # identity "block": only the walk matters
     anchor = None
