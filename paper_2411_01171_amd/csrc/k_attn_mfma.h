@@ -29,6 +29,7 @@ struct AttnMfmaArgs {
   int64_t ldo;
   int Nq, Nk, Nkp, heads, kv_div;
   float scale_log2;  // softmax scale * log2(e)
+  int o_frag;        // 0: o rows of ldo elements; else o is a fragment-order buffer of that many channels per token
 };
 
 constexpr int kAttnStages = 3;  // 48 KiB of LDS: three 4-wavefront workgroups per CU
@@ -202,7 +203,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attn_mfma_kernel(Att
   // ---- O^T / l: register 4q + j of block b is head channel 32b + 8q + 4g + j of this lane's query
   if (qvalid) {
     const float inv = 1.0f / lsum;
-    bf16* orow = a.o + ((int64_t)s * a.Nq + qi) * a.ldo + h * 64 + 4 * g;
+    const int64_t m = (int64_t)s * a.Nq + qi;
+    bf16* orow = a.o + m * a.ldo + h * 64 + 4 * g;
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -210,7 +212,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attn_mfma_kernel(Att
         uint2 v;
         v.x = pack_bf16x2(oacc[b][4 * q + 0] * inv, oacc[b][4 * q + 1] * inv);
         v.y = pack_bf16x2(oacc[b][4 * q + 2] * inv, oacc[b][4 * q + 3] * inv);
-        *reinterpret_cast<uint2*>(orow + 32 * b + 8 * q) = v;
+        bf16* dst = a.o_frag ? a.o + act_offset(m, h * 64 + 32 * b + 8 * q + 4 * g, a.o_frag) : orow + 32 * b + 8 * q;
+        *reinterpret_cast<uint2*>(dst) = v;
       }
   }
 }

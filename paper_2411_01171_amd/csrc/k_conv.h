@@ -31,15 +31,11 @@ __device__ __forceinline__ float silu(float v) { return v / (1.f + __expf(-v)); 
 
 // Fragment order.  One fragment = 1 KiB = the 64 lanes' 16-byte operands of one
 // v_mfma_f32_32x32x16_f16: lane l holds row l % 32 and the eight k-values 8*(l/32) .. +7.
-//   activation  act_granule(t, c8): the 16 bytes (channels 8*c8 .. +7) of token t; fragments are
-//               (32-token block, 16-channel step) pairs, 16-channel steps fastest.  The buffer starts
+//   activation  act_granule(t, c8) (k_norm.h): the 16 bytes (channels 8*c8 .. +7) of token t; fragments
+//               are (32-token block, 16-channel step) pairs, 16-channel steps fastest.  The buffer starts
 //               with a 256-byte block of zeros (what a tap outside the image reads).
 //   weights     per (column tile, k-tile of 32 input channels of one tap): 2 k-steps x TN fragments,
 //               rows = output channels; k-tiles ordered tap-major (tap = 3*(dy+1) + dx+1).
-constexpr int kActZeroBytes = 256;
-__host__ __device__ __forceinline__ int64_t act_granule(int64_t t, int c8, int C) {
-  return ((t >> 5) * (C / 16) + (c8 >> 1)) * 64 + (c8 & 1) * 32 + (t & 31);
-}
 
 enum ConvMode { kConvSame = 0, kConvStride2 = 1, kConvNearestUp = 2 };
 

@@ -23,6 +23,7 @@ namespace si {
 // out[m, n] = T(acc + bias[n])
 template <typename T>
 struct EpiStore {
+  static constexpr bool kRows8 = false;
   T* out;
   int64_t ld;
   const T* bias;
@@ -50,6 +51,7 @@ struct EpiStore {
 // row-major as EpiStore does; the value columns go straight to the transposed copy the kernel reads,
 // vt[(s*D + c)*Pw + key] for token m = s*Pw + key (keys contiguous), and are not stored row-major.
 struct EpiStoreQKVt {
+  static constexpr bool kRows8 = false;
   bf16* out;
   int64_t ld;
   bf16* vt;
@@ -72,8 +74,10 @@ struct EpiStoreQKVt {
 // Residual stream (fp32): h[m, n] = (accumulate ? h[m, n] : 0) + acc + bias[n];
 // optionally the new value is also stored in copy (operand of proj_out): fp32 storage
 // as is; 16-bit storage as fp16 (11 significand bits, saturated at +-65504), row stride ld.
-template <typename T>
+// FRAG: the copy goes to a buffer in the ring kernels' fragment order.
+template <typename T, bool FRAG = false>
 struct EpiResidual {
+  static constexpr bool kRows8 = false;
   float* h;
   int64_t ld;
   const T* bias;
@@ -94,7 +98,7 @@ struct EpiResidual {
         f16x4_t c4;
 #pragma unroll
         for (int i = 0; i < 4; ++i) c4[i] = (_Float16)__builtin_amdgcn_fmed3f(ov[i], -65504.f, 65504.f);
-        *reinterpret_cast<f16x4_t*>(copy + m * ld + n0) = c4;
+        *reinterpret_cast<f16x4_t*>(copy + (FRAG ? act_offset(m, n0, (int)ld) : m * ld + n0)) = c4;
       } else {
         T* c = copy + m * ld + n0;
 #pragma unroll
@@ -107,8 +111,10 @@ struct EpiResidual {
 // GEGLU: the packed weight interleaves value column j (row 2j) with gate column
 // j (row 2j+1), so columns (n0, n0+1) and (n0+2, n0+3) are (value, gate) pairs.
 // g[m, n0/2 + i] = (value + b1[j]) * gelu_erf(gate + b1[inner + j])
-template <typename T>
+// FRAG: g is a buffer in the ring kernels' fragment order (row width ld).
+template <typename T, bool FRAG = false>
 struct EpiGeglu {
+  static constexpr bool kRows8 = false;
   T* g;
   int64_t ld;
   const T* b1;
@@ -117,7 +123,7 @@ struct EpiGeglu {
     const int j = n0 >> 1;
     const float a0 = (v[0] + param_or(b1, j, 0.f)) * gelu_erf(v[1] + param_or(b1, inner + j, 0.f));
     const float a1 = (v[2] + param_or(b1, j + 1, 0.f)) * gelu_erf(v[3] + param_or(b1, inner + j + 1, 0.f));
-    T* p = g + m * ld + j;
+    T* p = g + (FRAG ? act_offset(m, j, (int)ld) : m * ld + j);
     if constexpr (sizeof(T) == 2) {
       *reinterpret_cast<unsigned*>(p) = (unsigned)float_to_bf16_bits(a0) | ((unsigned)float_to_bf16_bits(a1) << 16);
     } else {
@@ -130,6 +136,7 @@ struct EpiGeglu {
 // of the window; the sum is formed in fp32 and rounded once.
 template <typename T>
 struct EpiSliceOut {
+  static constexpr bool kRows8 = false;
   const T* x;
   T* out;
   const T* bias;

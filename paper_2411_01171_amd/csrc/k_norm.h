@@ -9,6 +9,19 @@
 
 namespace si {
 
+// Fragment order of a 16-bit activation operand of the ring kernels (k_conv.h): granule
+// act_granule(t, c8) holds the 16 bytes (channels 8*c8 .. +7) of token t; a 1 KiB fragment is the
+// 64 granules of (32-token block, 16-channel step), 16-channel steps fastest; the buffer starts with
+// a 256-byte block of zeros.
+constexpr int kActZeroBytes = 256;
+__host__ __device__ __forceinline__ int64_t act_granule(int64_t t, int c8, int C) {
+  return ((t >> 5) * (C / 16) + (c8 >> 1)) * 64 + (c8 & 1) * 32 + (t & 31);
+}
+// element offset (16-bit elements) of channel c of token t in such a buffer
+__host__ __device__ __forceinline__ int64_t act_offset(int64_t t, int c, int C) {
+  return kActZeroBytes / 2 + act_granule(t, c >> 3, C) * 8 + (c & 7);
+}
+
 // One block per (b, f, g).  Reduces the n_g * P values x[b, g*n_g:(g+1)*n_g, f, :].
 // Sums are taken relative to the group's first element so that a large common
 // offset does not cancel in fp32; per-thread fp32 partials are merged in fp64.
@@ -187,7 +200,9 @@ __global__ __launch_bounds__(256) void window_to_tokens_kernel(const T* __restri
 // Slice-in for bf16 storage: the normalised value (bounded by construction) is kept as fp16, the
 // operand type of proj_in on this path -- three more significand bits than bf16 for the same bytes.
 // 8-byte reads along positions (when the frame size and the window start are multiples of 4
-// positions), 16-byte writes of 8 channels.  C % 8 == 0; row m holds C values.
+// positions), 16-byte writes of 8 channels.  C % 8 == 0; row m holds C values, or (FRAG) the
+// buffer is in the ring kernels' fragment order.
+template <bool FRAG>
 __global__ __launch_bounds__(256) void window_to_tokens_f16_kernel(const bf16* __restrict__ x, const float* __restrict__ stats,
                                                                      const bf16* __restrict__ gamma, const bf16* __restrict__ beta,
                                                                      bf16* __restrict__ a0, Window w) {
@@ -236,7 +251,8 @@ __global__ __launch_bounds__(256) void window_to_tokens_f16_kernel(const bf16* _
       f16x8_t o;
 #pragma unroll
       for (int j = 0; j < 8; ++j) o[j] = (_Float16)__builtin_amdgcn_fmed3f(tile[co + j][pl], -65504.f, 65504.f);
-      *reinterpret_cast<f16x8_t*>(a0 + ((int64_t)bf * w.Pw + p) * w.C + c) = o;
+      const int64_t m = (int64_t)bf * w.Pw + p;
+      *reinterpret_cast<f16x8_t*>(a0 + (FRAG ? act_offset(m, c, w.C) : m * w.C + c)) = o;
     }
   }
 }
@@ -254,7 +270,8 @@ __global__ void pe_table_kernel(float* __restrict__ pe, int F, int D) {
 // Row LayerNorm of the fp32 residual stream; one wavefront per row, the row is
 // held in registers (D <= 2048, D % 4 == 0).  Optional frame embedding: row m
 // belongs to frame f0 + (m / Pw) % Fw.
-template <typename T>
+// FRAG (16-bit T): the output is written in the ring kernels' fragment order instead of rows of D.
+template <typename T, bool FRAG = false>
 __global__ __launch_bounds__(256) void layer_norm_kernel(const float* __restrict__ h, T* __restrict__ a, int64_t M, int D,
                                                          const T* __restrict__ gamma, const T* __restrict__ beta, float eps,
                                                          const float* __restrict__ pe, int Pw, int Fw, int f0) {
@@ -303,7 +320,7 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float* __restrict
         uint2 pk;
         pk.x = (unsigned)float_to_bf16_bits(y[0]) | ((unsigned)float_to_bf16_bits(y[1]) << 16);
         pk.y = (unsigned)float_to_bf16_bits(y[2]) | ((unsigned)float_to_bf16_bits(y[3]) << 16);
-        *reinterpret_cast<uint2*>(a + m * D + v * 4) = pk;
+        *reinterpret_cast<uint2*>(a + (FRAG ? act_offset(m, v * 4, D) : m * D + v * 4)) = pk;
       } else {
         *reinterpret_cast<float4*>(a + m * D + v * 4) = make_float4(y[0], y[1], y[2], y[3]);
       }
@@ -317,9 +334,19 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float* __restrict
 // (GEGLU projection), even r -> value column r/2, odd r -> gate column interleave + r/2.
 // to_f16 (16-bit T only): the bf16 values are stored as fp16 (weights of the GEMMs whose activation
 // operand is fp16; exact for normal fp16 magnitudes, saturated at +-65504).
+// frag_tn > 0: the destination is the ring kernels' weight fragment stream for column tiles of
+// frag_tn*32 rows of the whole [N, frag_K] matrix; this call fills rows frag_row0 .. of it: element
+// (n, k) sits at weight_fragment_index(n, k, frag_K, frag_tn).
+__host__ __device__ __forceinline__ int64_t weight_fragment_index(int n, int k, int K, int TN) {
+  const int col = n / (32 * TN), i = (n / 32) % TN, lrow = n % 32;
+  const int kt = k / 32, ks = (k % 32) / 16, half = (k % 16) / 8, e = k % 8;
+  return ((((int64_t)col * (K / 32) + kt) * 2 + ks) * TN + i) * 512 + (half * 32 + lrow) * 8 + e;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void pack_transpose_kernel(const T* __restrict__ src, T* __restrict__ dst, int K, int ld_src,
-                                                             int rows, int col0, int interleave, int ld_dst, int to_f16 = 0) {
+                                                             int rows, int col0, int interleave, int ld_dst, int to_f16 = 0,
+                                                             int frag_tn = 0, int frag_row0 = 0, int frag_K = 0) {
   __shared__ T tile[32][33];
   const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
   const int r0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
@@ -338,7 +365,8 @@ __global__ __launch_bounds__(256) void pack_transpose_kernel(const T* __restrict
       if constexpr (sizeof(T) == 2) {
         if (to_f16) v.v = __builtin_bit_cast(unsigned short, (_Float16)__builtin_amdgcn_fmed3f(to_float(v), -65504.f, 65504.f));
       }
-      dst[(int64_t)r * ld_dst + k] = v;
+      if (frag_tn > 0) dst[weight_fragment_index(frag_row0 + r, k, frag_K, frag_tn)] = v;
+      else dst[(int64_t)r * ld_dst + k] = v;
     }
   }
 }

@@ -16,6 +16,7 @@
 #include "k_fused_attn.h"
 #include "k_fused_block.h"
 #include "k_attn_mfma.h"
+#include "k_conv.h"
 #include "k_gemm.h"
 #include "k_norm.h"
 #include "si_common.h"
@@ -68,6 +69,28 @@ static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t
 #define SI_LANES3_MIN 12
 #endif
 
+// Column tiles of the ring kernel used as a GEMM on up to Mmax tokens x N columns over K: the widest
+// tile (5, 4, 2 or 1 blocks of 32 columns) that pads N by at most a tenth and still gives enough
+// workgroups of 128 tokens, else the narrowest such tile.  Enough (measured): one per CU when the
+// k loop is long (K > 512: the tile's reuse of the activation rows then outweighs the idle tail of
+// the last round of workgroups), 400 for short k loops.  Weight packing and launch use the same
+// (Mmax, N, K).
+struct RingShape {
+  int tn, ncol;
+};
+static RingShape ring_shape(int64_t Mmax, int N, int K) {
+  const int64_t rows = (Mmax + 127) / 128;
+  const int min_wg = K > 512 ? 256 : 400;
+  RingShape best{1, (N + 31) / 32};
+  for (int tn : {5, 4, 2, 1}) {
+    const int nc = (N + 32 * tn - 1) / (32 * tn);
+    if ((int64_t)nc * tn * 32 * 10 > (int64_t)N * 11) continue;  // too much padding
+    best = RingShape{tn, nc};
+    if (rows * nc >= min_wg) break;
+  }
+  return best;
+}
+
 struct Plan {
   int kind, dtype, esize;
   int B, C, F, H, W, G, heads, d, D;
@@ -80,6 +103,7 @@ struct Plan {
   int fused_nb;     // > 0: register-resident FFN half with D = 32*fused_nb
   bool fused_attn;  // register-resident attention half as well (temporal blocks)
   bool attn_mfma;   // matrix-core attention kernel for the staged spatial path (bf16, head dimension 64)
+  bool ring;        // staged bf16 GEMMs run on the fragment-order ring kernel (operands in fragment order)
   int lanes;        // slices in flight (many small slices: 2 or 3, each on a stream of its own)
   size_t lane_stride;  // bytes between two lanes' slice intermediates
   int Mcp;          // context tokens rounded up to a multiple of 8 (transposed value copy)
@@ -160,6 +184,10 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     p->fused_attn = p->kind == SI_BLOCK_TEMPORAL && tp >= 1 && dh_ok && (int64_t)p->F * p->G <= kAttnMaxStats &&
                     (p->B <= 2 || last_len >= 128);
   }
+  // Ring GEMMs: 16-bit storage, every contraction length a multiple of the 32-wide k-tile, operand
+  // buffers addressable with 32-bit byte offsets.
+  p->ring = p->dtype == SI_BF16 && p->C % 32 == 0 && D % 32 == 0 &&
+            (double)p->Mmax * (double)(4 * D > p->C ? 4 * D : p->C) * 2.0 + 4096.0 < 4294967296.0;
   // one slice's intermediates
   const size_t split = 1;  // proj_in / proj_out operands of the bf16 staged path travel as fp16, same bytes as bf16
   if (p->fused_attn) {  // one kernel per window: only the parked residual stream (128 rows per workgroup)
@@ -169,9 +197,11 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     p->off_h = take((size_t)wgs * 128 * Dz * sizeof(float));
     p->off_big = take(0);
   } else {
-    p->off_a = take((size_t)p->Mmax * (C > Dz ? C : Dz) * split * es);
+    // fragment-order operand buffers carry a 256-byte head and whole 32-token blocks
+    const size_t pad = p->ring ? kActZeroBytes : 0, Mp = p->ring ? (size_t)((p->Mmax + 31) / 32 * 32) : (size_t)p->Mmax;
+    p->off_a = take(pad + Mp * (C > Dz ? C : Dz) * split * es);
     p->off_h = take((size_t)p->Mmax * Dz * sizeof(float));
-    p->off_big = take((size_t)p->Mmax * 4 * Dz * es);
+    p->off_big = take(pad + Mp * 4 * Dz * es);
   }
   p->off_vt = take(p->attn_mfma ? (size_t)p->Mmax * Dz * es : 0);  // values of the window, keys contiguous
   // Cross-slice pipelining (Sec. 4.2.2): with many small slices the kernels of one slice leave CUs
@@ -183,17 +213,22 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->lane_stride = off - p->off_a;
   for (int l = 1; l < p->lanes; ++l) take(p->lane_stride);
   const size_t act_end = off;
-  // re-laid-out weights
-  p->off_w_in = take(split * Dz * C * es);
-  p->off_wqkv = take(3 * Dz * Dz * es);
-  p->off_wo = take(Dz * Dz * es);
+  // re-laid-out weights ([N, K]; fragment streams pad N to whole column tiles)
+  auto wbytes = [&](size_t N, size_t K) {
+    if (!p->ring) return N * K * es;
+    const RingShape rs = ring_shape(p->Mmax, (int)N, (int)K);
+    return (size_t)rs.ncol * rs.tn * 32 * K * es;
+  };
+  p->off_w_in = take(wbytes(Dz, split * C));
+  p->off_wqkv = take(wbytes(3 * Dz, Dz));
+  p->off_wo = take(wbytes(Dz, Dz));
   const bool sp = p->kind == SI_BLOCK_SPATIAL;
-  p->off_wq2 = take(sp ? Dz * Dz * es : 0);
+  p->off_wq2 = take(sp ? wbytes(Dz, Dz) : 0);
   p->off_wkv2 = take(sp ? 2 * Dz * (size_t)p->Cc * es : 0);
-  p->off_wo2 = take(sp ? Dz * Dz * es : 0);
-  p->off_w1 = take(8 * Dz * Dz * es);
-  p->off_w2 = take(4 * Dz * Dz * es);
-  p->off_w_out = take(split * C * Dz * es);
+  p->off_wo2 = take(sp ? wbytes(Dz, Dz) : 0);
+  p->off_w1 = take(wbytes(8 * Dz, Dz));
+  p->off_w2 = take(wbytes(Dz, 4 * Dz));
+  p->off_w_out = take(wbytes(C, split * Dz));
   p->off_ffn_stream = take(p->fused_nb && !p->fused_attn ? (size_t)stream_bytes(14 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->off_attn_stream = take(p->fused_attn ? (size_t)stream_bytes(18 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->weights_bytes = off - act_end;
@@ -243,6 +278,11 @@ static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T
   return SI_OK;
 }
 
+// as_ring: A is a fragment-order buffer and Wp a fragment stream -> ring kernel; else rows of lda.
+template <typename T, bool F16, class Epi>
+static si_status launch_gemm_sel(const char* stage, bool as_ring, const T* A, int64_t lda, const T* Wp, int64_t M, int64_t Mmax,
+                                 int N, int K, Epi epi, hipStream_t st);
+
 template <typename T>
 static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, int col0, int interleave, hipStream_t st,
                              int ld_dst = 0, bool to_f16 = false) {
@@ -250,6 +290,59 @@ static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, 
   pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, dst, K, ld_src, rows, col0, interleave, ld_dst ? ld_dst : K, to_f16 ? 1 : 0);
   SI_CHECK_LAUNCH();
   return SI_OK;
+}
+
+// One [K, rows] parameter matrix into rows [row0, row0 + rows) of the packed [N_total, K] weight at
+// `base`: k-contiguous rows, or (as_ring) the ring kernel's fragment stream for problems of up to
+// Mmax tokens.  f16: 16-bit values are stored as fp16.
+template <typename T>
+static si_status pack_weight(const T* src, T* base, int K, int ld_src, int rows, int interleave, int N_total, int row0,
+                             bool as_ring, int64_t Mmax, bool f16, hipStream_t st) {
+  dim3 grid((unsigned)((rows + 31) / 32), (unsigned)((K + 31) / 32));
+  if (as_ring) {
+    const RingShape rs = ring_shape(Mmax, N_total, K);
+    pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, base, K, ld_src, rows, 0, interleave, K, f16 ? 1 : 0, rs.tn, row0, K);
+  } else {
+    pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, base + (size_t)row0 * K, K, ld_src, rows, 0, interleave, K, f16 ? 1 : 0);
+  }
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+
+// The ring kernel (k_conv.h) as a GEMM: M tokens are M one-pixel images, one tap; act is a
+// fragment-order operand buffer (K channels per token), wf the fragment stream packed by
+// pack_weight for (Mmax, N).  Same epilogue contract as gemm_bf16_kernel.
+template <bool F16, class Epi>
+static si_status launch_gemm_ring(const char* stage, const void* act, const void* wf, int64_t M, int64_t Mmax, int N, int K,
+                                  Epi epi, hipStream_t st) {
+  if (M <= 0) return SI_OK;
+  StageScope scope(stage, st);
+  const RingShape rs = ring_shape(Mmax, N, K);
+  constexpr int kBigMin = 400;  // 256-token row tiles for the largest problems only (measured)
+  const int64_t rows2 = (M + 255) / 256;
+  const bool big = rs.tn >= 4 && rows2 * rs.ncol >= kBigMin;
+  ConvArgs a{static_cast<const char*>(act), static_cast<const char*>(wf), M, K, N, 1, 1, rs.ncol,
+             (int)((big ? rows2 : (M + 127) / 128) * rs.ncol), 1, 1, kConvSame, 1};
+  const unsigned grid = (unsigned)((a.ntiles + 7) / 8 * 8);
+  switch (rs.tn * 2 + (big ? 1 : 0)) {
+    case 11: conv3x3_dma_kernel<2, 5, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    case 10: conv3x3_dma_kernel<1, 5, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    case 9: conv3x3_dma_kernel<2, 4, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    case 8: conv3x3_dma_kernel<1, 4, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    case 4: conv3x3_dma_kernel<1, 2, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    default: conv3x3_dma_kernel<1, 1, 6, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+  }
+  SI_CHECK_LAUNCH();
+  return SI_OK;
+}
+
+template <typename T, bool F16, class Epi>
+static si_status launch_gemm_sel(const char* stage, bool as_ring, const T* A, int64_t lda, const T* Wp, int64_t M, int64_t Mmax,
+                                 int N, int K, Epi epi, hipStream_t st) {
+  if constexpr (sizeof(T) == 2) {
+    if (as_ring) return launch_gemm_ring<F16>(stage, A, Wp, M, Mmax, N, K, epi, st);
+  }
+  return launch_gemm<T, F16>(stage, A, lda, Wp, M, N, K, epi, st);
 }
 
 template <typename T>
@@ -266,13 +359,14 @@ static si_status launch_attention(const char* stage, const AttnArgs& a, hipStrea
 // Matrix-core attention (bf16, head dimension 64): v is first copied with keys contiguous.
 static si_status launch_attention_mfma(const char* stage, const bf16* q, int64_t ldq, const bf16* k, int64_t ldk,
                                        const bf16* vt, bf16* o, int64_t ldo, int S, int Nq, int Nk, int Nkp, int heads,
-                                       int kv_div, float scale, hipStream_t st) {
+                                       int kv_div, float scale, hipStream_t st, int o_frag = 0) {
   if (S <= 0 || Nq <= 0) return SI_OK;
   StageScope scope(stage, st);
   AttnMfmaArgs a;
   a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.o = o; a.ldo = ldo;
   a.Nq = Nq; a.Nk = Nk; a.Nkp = Nkp; a.heads = heads; a.kv_div = kv_div;
   a.scale_log2 = scale * 1.4426950408889634f;
+  a.o_frag = o_frag;
   // 8 wavefronts share the key / value stages when that still leaves several workgroups for every CU
   const int64_t wg8 = (int64_t)((Nq + 255) / 256) * heads * S;
   if (wg8 >= 1024) {
@@ -297,10 +391,14 @@ static si_status launch_transpose_v(const char* stage, const bf16* src, int64_t 
 
 template <typename T>
 static si_status launch_layer_norm(const char* stage, const float* h, T* a, int64_t M, int D, const void* g, const void* b,
-                                   float eps, const float* pe, int Pw, int Fw, int f0, hipStream_t st) {
+                                   float eps, const float* pe, int Pw, int Fw, int f0, hipStream_t st, bool frag = false) {
   StageScope scope(stage, st);
-  layer_norm_kernel<T><<<(unsigned)((M + 3) / 4), 256, 0, st>>>(h, a, M, D, static_cast<const T*>(g), static_cast<const T*>(b),
-                                                                   eps, pe, Pw, Fw, f0);
+  const unsigned blocks = (unsigned)((M + 3) / 4);
+  if (frag && sizeof(T) == 2)
+    layer_norm_kernel<T, sizeof(T) == 2><<<blocks, 256, 0, st>>>(h, a, M, D, static_cast<const T*>(g), static_cast<const T*>(b), eps,
+                                                                 pe, Pw, Fw, f0);
+  else
+    layer_norm_kernel<T><<<blocks, 256, 0, st>>>(h, a, M, D, static_cast<const T*>(g), static_cast<const T*>(b), eps, pe, Pw, Fw, f0);
   SI_CHECK_LAUNCH();
   return SI_OK;
 }
@@ -411,6 +509,11 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   const bool fused_ffn = p.fused_nb > 0, fused_attn = p.fused_attn;
   constexpr int kSplit = 1;
   constexpr bool kF16 = sizeof(T) == 2;  // proj_in / proj_out run on fp16 operands for 16-bit storage
+  // operand buffers in fragment order + ring kernel; the attention outputs too where the matrix-core
+  // attention kernel writes them and a staged GEMM (not the FFN-half kernel) reads them
+  const bool ring = p.ring;
+  const bool self_frag = ring && p.attn_mfma, cross_frag = ring && p.attn_mfma && !fused_ffn;
+  const int64_t Mx = p.Mmax;
   auto cT = [](const void* q) { return static_cast<const T*>(q); };
 
   // ---- once per call: weight re-layout, frame embedding table (skipped when the caller vouches that
@@ -418,24 +521,22 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   if (!packed) {
     StageScope scope("pack_weights", st);
     if (!fused_attn) {
-      for (int h2 = 0; h2 < kSplit; ++h2)
-        SI_TRY(launch_pack<T>(cT(w->w_in), w_in + (size_t)h2 * C, C, D, D, 0, 0, st, kSplit * C, kF16));
-      SI_TRY(launch_pack<T>(cT(w->wq), wqkv, D, D, D, 0, 0, st));
-      SI_TRY(launch_pack<T>(cT(w->wk), wqkv + (size_t)D * D, D, D, D, 0, 0, st));
-      SI_TRY(launch_pack<T>(cT(w->wv), wqkv + (size_t)2 * D * D, D, D, D, 0, 0, st));
-      if (spatial || !fused_ffn) SI_TRY(launch_pack<T>(cT(w->wo), wo, D, D, D, 0, 0, st));
+      SI_TRY(pack_weight<T>(cT(w->w_in), w_in, C, D, D, 0, D, 0, ring, Mx, kF16, st));
+      SI_TRY(pack_weight<T>(cT(w->wq), wqkv, D, D, D, 0, 3 * D, 0, ring, Mx, false, st));
+      SI_TRY(pack_weight<T>(cT(w->wk), wqkv, D, D, D, 0, 3 * D, D, ring, Mx, false, st));
+      SI_TRY(pack_weight<T>(cT(w->wv), wqkv, D, D, D, 0, 3 * D, 2 * D, ring, Mx, false, st));
+      if (spatial || !fused_ffn) SI_TRY(pack_weight<T>(cT(w->wo), wo, D, D, D, 0, D, 0, self_frag, Mx, false, st));
     }
     if (spatial) {
-      SI_TRY(launch_pack<T>(cT(w->wq2), wq2, D, D, D, 0, 0, st));
+      SI_TRY(pack_weight<T>(cT(w->wq2), wq2, D, D, D, 0, D, 0, ring, Mx, false, st));
       SI_TRY(launch_pack<T>(cT(w->wk2), wkv2, p.Cc, D, D, 0, 0, st));
       SI_TRY(launch_pack<T>(cT(w->wv2), wkv2 + (size_t)D * p.Cc, p.Cc, D, D, 0, 0, st));
-      if (!fused_ffn) SI_TRY(launch_pack<T>(cT(w->wo2), wo2, D, D, D, 0, 0, st));
+      if (!fused_ffn) SI_TRY(pack_weight<T>(cT(w->wo2), wo2, D, D, D, 0, D, 0, cross_frag, Mx, false, st));
     }
     if (!fused_ffn) {
-      for (int h2 = 0; h2 < kSplit; ++h2)
-        SI_TRY(launch_pack<T>(cT(w->w_out), w_out + (size_t)h2 * D, D, C, C, 0, 0, st, kSplit * D, kF16));
-      SI_TRY(launch_pack<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 0, 4 * D, st));
-      SI_TRY(launch_pack<T>(cT(w->w2), w2, 4 * D, D, D, 0, 0, st));
+      SI_TRY(pack_weight<T>(cT(w->w_out), w_out, D, C, C, 0, C, 0, ring, Mx, kF16, st));
+      SI_TRY(pack_weight<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 4 * D, 8 * D, 0, ring, Mx, false, st));
+      SI_TRY(pack_weight<T>(cT(w->w2), w2, 4 * D, D, D, 0, D, 0, ring, Mx, false, st));
     } else if constexpr (sizeof(T) == 2) {
       if (p.fused_nb == 2) SI_TRY(pack_fused_streams<2>(p, w, ws, pe, st));
       else SI_TRY(pack_fused_streams<10>(p, w, ws, pe, st));
@@ -513,32 +614,33 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       {  // slice-in: window -> GroupNorm -> token rows
         StageScope scope("slice_in", st);
         dim3 grid((unsigned)((win.Pw + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * win.Fw));
-        if constexpr (sizeof(T) == 2)
-          window_to_tokens_f16_kernel<<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
-        else
+        if constexpr (sizeof(T) == 2) {
+          if (ring) window_to_tokens_f16_kernel<true><<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
+          else window_to_tokens_f16_kernel<false><<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
+        } else
           window_to_tokens_kernel<T><<<grid, 256, 0, st>>>(X, stats, cT(w->gn_g), cT(w->gn_b), a, win);
         SI_CHECK_LAUNCH();
       }
       {
         EpiResidual<T> epi{h, (int64_t)D, cT(w->b_in), 0, nullptr};
-        SI_TRY((launch_gemm<T, kF16>("proj_in", a, (int64_t)kSplit * C, w_in, M, D, kSplit * C, epi, st)));
+        SI_TRY((launch_gemm_sel<T, kF16>("proj_in", ring, a, (int64_t)C, w_in, M, Mx, D, C, epi, st)));
       }
-      SI_TRY(launch_layer_norm<T>("ln1", h, a, M, D, w->ln1_g, w->ln1_b, w->ln_eps, pe, win.Pw, win.Fw, win.f0, st));
+      SI_TRY(launch_layer_norm<T>("ln1", h, a, M, D, w->ln1_g, w->ln1_b, w->ln_eps, pe, win.Pw, win.Fw, win.f0, st, ring));
       bool self_done = false;
       if constexpr (sizeof(T) == 2) {
         if (p.attn_mfma) {  // spatial: sequence (b, f) = rows (b*Fw + f)*Pw + i; the projection writes V transposed
           bf16* vt = reinterpret_cast<bf16*>(vt_lane);
           EpiStoreQKVt epi{big, (int64_t)3 * D, vt, D, win.Pw};
-          SI_TRY(launch_gemm<T>("qkv", a, (int64_t)D, wqkv, M, 3 * D, D, epi, st));
+          SI_TRY((launch_gemm_sel<T, false>("qkv", ring, a, (int64_t)D, wqkv, M, Mx, 3 * D, D, epi, st)));
           SI_TRY(launch_attention_mfma("self_attn", big, (int64_t)3 * D, big + D, (int64_t)3 * D, vt, a, (int64_t)D, p.B * win.Fw,
-                                       win.Pw, win.Pw, win.Pw, p.heads, 1, scale, st));
+                                       win.Pw, win.Pw, win.Pw, p.heads, 1, scale, st, self_frag ? D : 0));
           self_done = true;
         }
       }
       if (!self_done) {
         {
           EpiStore<T> epi{big, (int64_t)3 * D, nullptr};
-          SI_TRY(launch_gemm<T>("qkv", a, (int64_t)D, wqkv, M, 3 * D, D, epi, st));
+          SI_TRY((launch_gemm_sel<T, false>("qkv", ring, a, (int64_t)D, wqkv, M, Mx, 3 * D, D, epi, st)));
         }
         AttnArgs at;
         at.q = big; at.k = big + D; at.v = big + 2 * D; at.o = a;
@@ -556,20 +658,20 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       }
       if (spatial || !fused_ffn) {  // otherwise the FFN-half kernel applies W_o itself
         EpiResidual<T> epi{h, (int64_t)D, cT(w->bo), 1, nullptr};
-        SI_TRY(launch_gemm<T>("attn_out", a, (int64_t)D, wo, M, D, D, epi, st));
+        SI_TRY((launch_gemm_sel<T, false>("attn_out", self_frag, a, (int64_t)D, wo, M, Mx, D, D, epi, st)));
       }
       if (spatial) {
-        SI_TRY(launch_layer_norm<T>("ln2", h, a, M, D, w->ln2_g, w->ln2_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st));
+        SI_TRY(launch_layer_norm<T>("ln2", h, a, M, D, w->ln2_g, w->ln2_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st, ring));
         {
           EpiStore<T> epi{big, (int64_t)D, nullptr};
-          SI_TRY(launch_gemm<T>("q2", a, (int64_t)D, wq2, M, D, D, epi, st));
+          SI_TRY((launch_gemm_sel<T, false>("q2", ring, a, (int64_t)D, wq2, M, Mx, D, D, epi, st)));
         }
         bool cross_done = false;
         if constexpr (sizeof(T) == 2) {
           if (p.attn_mfma) {  // keys / values: the context rows of the batch entry, shared by its frames
             SI_TRY(launch_attention_mfma("cross_attn", big, (int64_t)D, ctxkv, (int64_t)2 * D,
                                          reinterpret_cast<const bf16*>(ws + p.off_ctxvt), a, (int64_t)D, p.B * win.Fw, win.Pw,
-                                         p.Mc, p.Mcp, p.heads, win.Fw, scale, st));
+                                         p.Mc, p.Mcp, p.heads, win.Fw, scale, st, cross_frag ? D : 0));
             cross_done = true;
           }
         }
@@ -585,7 +687,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         }
         if (!fused_ffn) {
           EpiResidual<T> epi{h, (int64_t)D, cT(w->bo2), 1, nullptr};
-          SI_TRY(launch_gemm<T>("cross_out", a, (int64_t)D, wo2, M, D, D, epi, st));
+          SI_TRY((launch_gemm_sel<T, false>("cross_out", cross_frag, a, (int64_t)D, wo2, M, Mx, D, D, epi, st)));
         }
       }
     }
@@ -604,18 +706,32 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         continue;
       }
     }
-    SI_TRY(launch_layer_norm<T>("ln3", h, a, M, D, w->ln3_g, w->ln3_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st));
-    {
-      EpiGeglu<T> epi{big, (int64_t)4 * D, cT(w->b1), 4 * D};
-      SI_TRY(launch_gemm<T>("ff1_geglu", a, (int64_t)D, w1, M, 8 * D, D, epi, st));
+    SI_TRY(launch_layer_norm<T>("ln3", h, a, M, D, w->ln3_g, w->ln3_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st, ring));
+    bool ffn_done = false;
+    if constexpr (sizeof(T) == 2) {
+      if (ring) {  // GEGLU output, the final residual stream and the slice-out all in / from fragment order
+        EpiGeglu<T, true> e1{big, (int64_t)4 * D, cT(w->b1), 4 * D};
+        SI_TRY((launch_gemm_ring<false>("ff1_geglu", a, w1, M, Mx, 8 * D, D, e1, st)));
+        EpiResidual<T, true> e2{h, (int64_t)D, cT(w->b2), 1, a};  // also leaves the final h as fp16 in `a`
+        SI_TRY((launch_gemm_ring<false>("ff2", big, w2, M, Mx, D, 4 * D, e2, st)));
+        EpiSliceOutRows e3{X, OUT, cT(w->b_out), win};
+        SI_TRY((launch_gemm_ring<true>("proj_out", a, w_out, M, Mx, C, D, e3, st)));
+        ffn_done = true;
+      }
     }
-    {
-      EpiResidual<T> epi{h, (int64_t)D, cT(w->b2), 1, a};  // also leaves the final h as T in `a`
-      SI_TRY(launch_gemm<T>("ff2", big, (int64_t)4 * D, w2, M, D, 4 * D, epi, st));
-    }
-    {
-      EpiSliceOut<T> epi{X, OUT, cT(w->b_out), win};
-      SI_TRY((launch_gemm<T, kF16>("proj_out", a, (int64_t)kSplit * D, w_out, M, C, kSplit * D, epi, st)));
+    if (!ffn_done) {
+      {
+        EpiGeglu<T> epi{big, (int64_t)4 * D, cT(w->b1), 4 * D};
+        SI_TRY(launch_gemm<T>("ff1_geglu", a, (int64_t)D, w1, M, 8 * D, D, epi, st));
+      }
+      {
+        EpiResidual<T> epi{h, (int64_t)D, cT(w->b2), 1, a};  // also leaves the final h as T in `a`
+        SI_TRY(launch_gemm<T>("ff2", big, (int64_t)4 * D, w2, M, D, 4 * D, epi, st));
+      }
+      {
+        EpiSliceOut<T> epi{X, OUT, cT(w->b_out), win};
+        SI_TRY((launch_gemm<T, kF16>("proj_out", a, (int64_t)kSplit * D, w_out, M, C, kSplit * D, epi, st)));
+      }
     }
   }
   if (lanes >= 2) {  // join: the caller's stream continues after all lanes
