@@ -371,4 +371,61 @@ __global__ __launch_bounds__(256) void pack_transpose_kernel(const T* __restrict
   }
 }
 
+// pack_transpose_kernel for 16-bit elements with 64 x 64 tiles: every thread has 8 reads in flight
+// (4 bytes where two destination rows are neighbours in the source) and writes whole 16-byte
+// granules (8 consecutive k of one row) -- 128 bytes per row per tile in the k-contiguous layout,
+// 512 contiguous bytes per 32 rows in a fragment stream.  Requires K % 8 == 0, ld_dst % 8 == 0 and a
+// 16-byte aligned destination; same arguments otherwise (col0 = 0).
+__global__ __launch_bounds__(256) void pack_transpose16_kernel(const unsigned short* __restrict__ src,
+                                                               unsigned short* __restrict__ dst, int K, int ld_src, int rows,
+                                                               int interleave, int ld_dst, int to_f16, int frag_tn,
+                                                               int frag_row0, int frag_K) {
+  __shared__ unsigned short tile[64][66];  // [k][r]
+  const int tid = threadIdx.x;
+  const int r0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+  const int rp = 2 * (tid % 32);  // the thread's pair of destination rows within the tile
+  const bool pair = interleave == 0 && (ld_src & 1) == 0 && (reinterpret_cast<uintptr_t>(src) & 3) == 0 && r0 + rp + 1 < rows;
+  unsigned v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int k = k0 + tid / 32 + 8 * i, r = r0 + rp;
+    v[i] = 0u;
+    if (k < K) {
+      const unsigned short* row = src + (int64_t)k * ld_src;
+      if (pair) {
+        v[i] = *reinterpret_cast<const unsigned*>(row + r);
+      } else {
+        if (r < rows) v[i] = row[interleave > 0 ? (r >> 1) : r];
+        if (r + 1 < rows) v[i] |= (unsigned)row[interleave > 0 ? interleave + (r >> 1) : r + 1] << 16;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *reinterpret_cast<unsigned*>(&tile[tid / 32 + 8 * i][rp]) = v[i];
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int g = tid + 256 * j;
+    // fragment stream: consecutive lanes take consecutive rows (consecutive granules of a fragment);
+    // k-contiguous rows: consecutive lanes take consecutive granules of one row
+    const int rl = frag_tn > 0 ? g % 64 : g / 8, k8 = frag_tn > 0 ? g / 64 : g % 8;
+    const int r = r0 + rl, k = k0 + 8 * k8;
+    if (r >= rows || k >= K) continue;
+    unsigned short e[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      e[q] = tile[8 * k8 + q][rl];
+      if (to_f16)
+        e[q] = __builtin_bit_cast(unsigned short, (_Float16)__builtin_amdgcn_fmed3f(__uint_as_float((unsigned)e[q] << 16), -65504.f, 65504.f));
+    }
+    uint4 o;
+    o.x = e[0] | ((unsigned)e[1] << 16);
+    o.y = e[2] | ((unsigned)e[3] << 16);
+    o.z = e[4] | ((unsigned)e[5] << 16);
+    o.w = e[6] | ((unsigned)e[7] << 16);
+    const int64_t at = frag_tn > 0 ? weight_fragment_index(frag_row0 + r, k, frag_K, frag_tn) : (int64_t)r * ld_dst + k;
+    *reinterpret_cast<uint4*>(dst + at) = o;
+  }
+}
+
 }  // namespace si

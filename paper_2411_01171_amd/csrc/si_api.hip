@@ -285,9 +285,17 @@ static si_status launch_gemm_sel(const char* stage, bool as_ring, const T* A, in
 
 template <typename T>
 static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, int col0, int interleave, hipStream_t st,
-                             int ld_dst = 0, bool to_f16 = false) {
-  dim3 grid((unsigned)((rows + 31) / 32), (unsigned)((K + 31) / 32));
-  pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, dst, K, ld_src, rows, col0, interleave, ld_dst ? ld_dst : K, to_f16 ? 1 : 0);
+                             int ld_dst = 0, bool to_f16 = false, int frag_tn = 0, int frag_row0 = 0) {
+  if (!ld_dst) ld_dst = K;
+  if (sizeof(T) == 2 && col0 == 0 && K % 8 == 0 && ld_dst % 8 == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+    dim3 grid((unsigned)((rows + 63) / 64), (unsigned)((K + 63) / 64));
+    pack_transpose16_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const unsigned short*>(src), reinterpret_cast<unsigned short*>(dst),
+                                                  K, ld_src, rows, interleave, ld_dst, to_f16 ? 1 : 0, frag_tn, frag_row0, K);
+  } else {
+    dim3 grid((unsigned)((rows + 31) / 32), (unsigned)((K + 31) / 32));
+    pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, dst, K, ld_src, rows, col0, interleave, ld_dst, to_f16 ? 1 : 0, frag_tn,
+                                                   frag_row0, K);
+  }
   SI_CHECK_LAUNCH();
   return SI_OK;
 }
@@ -298,15 +306,8 @@ static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, 
 template <typename T>
 static si_status pack_weight(const T* src, T* base, int K, int ld_src, int rows, int interleave, int N_total, int row0,
                              bool as_ring, int64_t Mmax, bool f16, hipStream_t st) {
-  dim3 grid((unsigned)((rows + 31) / 32), (unsigned)((K + 31) / 32));
-  if (as_ring) {
-    const RingShape rs = ring_shape(Mmax, N_total, K);
-    pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, base, K, ld_src, rows, 0, interleave, K, f16 ? 1 : 0, rs.tn, row0, K);
-  } else {
-    pack_transpose_kernel<T><<<grid, 256, 0, st>>>(src, base + (size_t)row0 * K, K, ld_src, rows, 0, interleave, K, f16 ? 1 : 0);
-  }
-  SI_CHECK_LAUNCH();
-  return SI_OK;
+  if (as_ring) return launch_pack<T>(src, base, K, ld_src, rows, 0, interleave, st, K, f16, ring_shape(Mmax, N_total, K).tn, row0);
+  return launch_pack<T>(src, base + (size_t)row0 * K, K, ld_src, rows, 0, interleave, st, K, f16);
 }
 
 // The ring kernel (k_conv.h) as a GEMM: M tokens are M one-pixel images, one tap; act is a

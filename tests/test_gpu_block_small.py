@@ -72,6 +72,22 @@ def test_spatial_head_dim_64_bf16(hw, M):
     _check(spec, x, w, ctx, 1)
 
 
+@pytest.mark.parametrize("kind,slice_len", [("temporal", 37), ("spatial", 2)])
+def test_fragment_order_path_with_alu_attention_bf16(kind, slice_len):
+    """C = D = 128 with head dimension 32: the projections and the FFN run on the ring kernel over
+    fragment-order operands (ragged windows: 5*37 and 2*2*45 tokens, a last window of another length)
+    while the attention kernels read and write token rows."""
+    if kind == "temporal":
+        spec = tiny_spec(wl.TEMPORAL, B=1, C=128, F=5, H=9, W=11, heads=4, dim_head=32, groups=8, pe=True, dtype="bf16")
+        ctx = None
+    else:
+        spec = tiny_spec(wl.SPATIAL, B=2, C=128, F=3, H=5, W=9, heads=4, dim_head=32, groups=8, M=6, Cc=16, dtype="bf16")
+        ctx = wl.make_context(spec)
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, ctx, slice_len)
+
+
 def test_spatial_head_dim_64_peaky_bf16():
     """Scaled-up queries and keys: the running maximum of the online softmax moves between key tiles."""
     spec = tiny_spec(wl.SPATIAL, B=1, C=128, F=2, H=12, W=16, heads=2, dim_head=64, groups=8, M=9, Cc=16, dtype="bf16")
