@@ -24,7 +24,7 @@ struct ResPlan {
   size_t weights_bytes, total_bytes;
 };
 
-static void conv_column_tiles(int O, int* TN, int* ncol);
+static void conv_column_tiles(int O, int64_t rows_in_flight, int* TN, int* ncol);
 
 static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w, int64_t slice_len, ResPlan* p) {
   if (!x || !w) return SI_ERR_NULL;
@@ -72,7 +72,7 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
   p->lane_stride = off - p->off_a;
   for (int l = 1; l < p->lanes; ++l) take(p->lane_stride);
   const size_t act_end = off;
-  conv_column_tiles(p->Co, &p->TN, &p->ncol);
+  conv_column_tiles(p->Co, (p->Mmax + 127) / 128 * p->lanes, &p->TN, &p->ncol);
   const size_t per_ktile = (size_t)p->ncol * 2 * p->TN * 1024;  // bytes of one 32-channel k-tile over all column tiles
   p->off_w1 = take(per_ktile * 9 * (C / 32));
   p->off_w2 = take(per_ktile * 9 * (Co / 32));
@@ -89,13 +89,25 @@ static void launch_conv_tile(const ConvArgs& a, Epi epi, hipStream_t st) {
 }
 
 // Column tiles of the convolution kernel: the candidate width that pads the output channels least,
-// the wider one on a tie.
-static void conv_column_tiles(int O, int* TN, int* ncol) {
+// the wider one on a tie.  rows_in_flight = 128-token row tiles of the windows in flight: while the
+// launches together leave CUs without a workgroup, a narrower tile (4 or 2 blocks of 32 channels,
+// never one: measured slower throughout) that pads at most a tenth more takes its place (down-
+// sampling of a 72 x 128 map at 320 channels: 2 x 72 workgroups of 160 channels -> 2 x 180 of 64).
+static void conv_column_tiles(int O, int64_t rows_in_flight, int* TN, int* ncol) {
   *TN = 1;
   *ncol = (O + 31) / 32;
   for (int tn : {2, 4, 5}) {
     const int nc = (O + 32 * tn - 1) / (32 * tn);
     if (nc * tn <= *ncol * *TN) {
+      *TN = tn;
+      *ncol = nc;
+    }
+  }
+  for (int tn : {4, 2}) {
+    if (rows_in_flight * *ncol >= 256) break;
+    if (tn >= *TN) continue;
+    const int nc = (O + 32 * tn - 1) / (32 * tn);
+    if (nc * tn * 10 <= *ncol * *TN * 11) {
       *TN = tn;
       *ncol = nc;
     }
@@ -297,7 +309,9 @@ static si_status make_resample_plan(const si_tensor5* x, int32_t kind, int64_t s
   p->Mi_max = (int64_t)p->B * p->slice_len * p->Pi;
   if ((double)p->Mi_max * p->C * 2.0 + 4096.0 >= 4294967296.0) return SI_ERR_SHAPE;  // 32-bit operand offsets
   if ((int64_t)p->B * p->slice_len * p->Po >= (1LL << 31) / 16) return SI_ERR_SHAPE;
-  conv_column_tiles(p->C, &p->TN, &p->ncol);
+  const int64_t n_slices = (p->F + p->slice_len - 1) / p->slice_len;
+  p->lanes = n_slices >= 8 ? 2 : 1;
+  conv_column_tiles(p->C, ((int64_t)p->B * p->slice_len * p->Po + 127) / 128 * p->lanes, &p->TN, &p->ncol);
   size_t off = 0;
   auto take = [&](size_t bytes) {
     const size_t o = off;
@@ -305,8 +319,6 @@ static si_status make_resample_plan(const si_tensor5* x, int32_t kind, int64_t s
     return o;
   };
   p->off_a = take(kActZeroBytes + (size_t)((p->Mi_max + 31) / 32 * 32) * p->C * 2);
-  const int64_t n_slices = (p->F + p->slice_len - 1) / p->slice_len;
-  p->lanes = n_slices >= 8 ? 2 : 1;
   p->lane_stride = off - p->off_a;
   if (p->lanes == 2) take(p->lane_stride);
   const size_t act_end = off;
