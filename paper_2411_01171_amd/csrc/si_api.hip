@@ -69,17 +69,22 @@ static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t
 #define SI_LANES3_MIN 12
 #endif
 
-// Column tiles of the ring kernel used as a GEMM on up to Mmax tokens x N columns over K: the widest
-// tile (5, 4, 2 or 1 blocks of 32 columns) that pads N by at most a tenth and still gives enough
-// workgroups of 128 tokens, else the narrowest such tile.  Enough (measured): one per CU when the
-// k loop is long (K > 512: the tile's reuse of the activation rows then outweighs the idle tail of
-// the last round of workgroups), 400 for short k loops.  Weight packing and launch use the same
-// (Mmax, N, K).
+// Column tiles of the ring kernel used as a GEMM on windows of up to Mmax tokens (`lanes` of them in
+// flight) x N columns over K: the widest tile (5, 4, 2 or 1 blocks of 32 columns) that pads N by at
+// most a tenth and still gives enough workgroups of 128 tokens, else the narrowest such tile.
+// Enough (measured): for long k loops (K > 512) one workgroup per CU over the windows in flight --
+// the tile's reuse of the activation rows then outweighs the idle tail of the last round of
+// workgroups; for short k loops 400 in the launch itself.  Weight packing and launch use the same
+// arguments.
+struct RingDims {
+  int64_t Mmax;
+  int lanes;
+};
 struct RingShape {
   int tn, ncol;
 };
-static RingShape ring_shape(int64_t Mmax, int N, int K) {
-  const int64_t rows = (Mmax + 127) / 128;
+static RingShape ring_shape(RingDims d, int N, int K) {
+  const int64_t rows = (d.Mmax + 127) / 128 * (K > 512 ? d.lanes : 1);
   const int min_wg = K > 512 ? 256 : 400;
   RingShape best{1, (N + 31) / 32};
   for (int tn : {5, 4, 2, 1}) {
@@ -216,7 +221,7 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   // re-laid-out weights ([N, K]; fragment streams pad N to whole column tiles)
   auto wbytes = [&](size_t N, size_t K) {
     if (!p->ring) return N * K * es;
-    const RingShape rs = ring_shape(p->Mmax, (int)N, (int)K);
+    const RingShape rs = ring_shape(RingDims{p->Mmax, p->lanes}, (int)N, (int)K);
     return (size_t)rs.ncol * rs.tn * 32 * K * es;
   };
   p->off_w_in = take(wbytes(Dz, split * C));
@@ -280,7 +285,7 @@ static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T
 
 // as_ring: A is a fragment-order buffer and Wp a fragment stream -> ring kernel; else rows of lda.
 template <typename T, bool F16, class Epi>
-static si_status launch_gemm_sel(const char* stage, bool as_ring, const T* A, int64_t lda, const T* Wp, int64_t M, int64_t Mmax,
+static si_status launch_gemm_sel(const char* stage, bool as_ring, const T* A, int64_t lda, const T* Wp, int64_t M, RingDims Mmax,
                                  int N, int K, Epi epi, hipStream_t st);
 
 template <typename T>
@@ -305,7 +310,7 @@ static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, 
 // Mmax tokens.  f16: 16-bit values are stored as fp16.
 template <typename T>
 static si_status pack_weight(const T* src, T* base, int K, int ld_src, int rows, int interleave, int N_total, int row0,
-                             bool as_ring, int64_t Mmax, bool f16, hipStream_t st) {
+                             bool as_ring, RingDims Mmax, bool f16, hipStream_t st) {
   if (as_ring) return launch_pack<T>(src, base, K, ld_src, rows, 0, interleave, st, K, f16, ring_shape(Mmax, N_total, K).tn, row0);
   return launch_pack<T>(src, base + (size_t)row0 * K, K, ld_src, rows, 0, interleave, st, K, f16);
 }
@@ -314,7 +319,7 @@ static si_status pack_weight(const T* src, T* base, int K, int ld_src, int rows,
 // fragment-order operand buffer (K channels per token), wf the fragment stream packed by
 // pack_weight for (Mmax, N).  Same epilogue contract as gemm_bf16_kernel.
 template <bool F16, class Epi>
-static si_status launch_gemm_ring(const char* stage, const void* act, const void* wf, int64_t M, int64_t Mmax, int N, int K,
+static si_status launch_gemm_ring(const char* stage, const void* act, const void* wf, int64_t M, RingDims Mmax, int N, int K,
                                   Epi epi, hipStream_t st) {
   if (M <= 0) return SI_OK;
   StageScope scope(stage, st);
@@ -338,7 +343,7 @@ static si_status launch_gemm_ring(const char* stage, const void* act, const void
 }
 
 template <typename T, bool F16, class Epi>
-static si_status launch_gemm_sel(const char* stage, bool as_ring, const T* A, int64_t lda, const T* Wp, int64_t M, int64_t Mmax,
+static si_status launch_gemm_sel(const char* stage, bool as_ring, const T* A, int64_t lda, const T* Wp, int64_t M, RingDims Mmax,
                                  int N, int K, Epi epi, hipStream_t st) {
   if constexpr (sizeof(T) == 2) {
     if (as_ring) return launch_gemm_ring<F16>(stage, A, Wp, M, Mmax, N, K, epi, st);
@@ -514,7 +519,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   // attention kernel writes them and a staged GEMM (not the FFN-half kernel) reads them
   const bool ring = p.ring;
   const bool self_frag = ring && p.attn_mfma, cross_frag = ring && p.attn_mfma && !fused_ffn;
-  const int64_t Mx = p.Mmax;
+  const RingDims Mx{p.Mmax, p.lanes};
   auto cT = [](const void* q) { return static_cast<const T*>(q); };
 
   // ---- once per call: weight re-layout, frame embedding table (skipped when the caller vouches that
