@@ -10,6 +10,10 @@
 //                           doubling -- as an implicit GEMM on the matrix cores; both operands arrive
 //                           in MFMA fragment order by direct global->LDS loads through a multi-stage
 //                           ring                                                             [MFMA bound]
+//                           With one tap on one-pixel images (ntaps = 1, H = W = 1) the same kernel
+//                           is a plain GEMM over M tokens: the transformer blocks' projections and
+//                           FFN use it that way on fragment-order operands (weights packed by
+//                           pack_transpose16_kernel, k_norm.h).
 //   pack_conv_kernel        [O, C, 3, 3] bf16 kernel -> fragment stream in the order the kernel reads
 //   temb_proj_kernel        e[b, o] = b_t[o] + sum_k SiLU(temb[b, k]) * W_t[k, o]
 //   window_to_tokens_silu_kernel  slice window -> SiLU(GroupNorm1) (or a plain copy) -> operand in

@@ -194,7 +194,6 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->ring = p->dtype == SI_BF16 && p->C % 32 == 0 && D % 32 == 0 &&
             (double)p->Mmax * (double)(4 * D > p->C ? 4 * D : p->C) * 2.0 + 4096.0 < 4294967296.0;
   // one slice's intermediates
-  const size_t split = 1;  // proj_in / proj_out operands of the bf16 staged path travel as fp16, same bytes as bf16
   if (p->fused_attn) {  // one kernel per window: only the parked residual stream (128 rows per workgroup)
     const int64_t npos = 4 * (32 / p->F);
     const int64_t wgs = ((int64_t)p->B * p->slice_len + npos - 1) / npos;
@@ -204,7 +203,7 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   } else {
     // fragment-order operand buffers carry a 256-byte head and whole 32-token blocks
     const size_t pad = p->ring ? kActZeroBytes : 0, Mp = p->ring ? (size_t)((p->Mmax + 31) / 32 * 32) : (size_t)p->Mmax;
-    p->off_a = take(pad + Mp * (C > Dz ? C : Dz) * split * es);
+    p->off_a = take(pad + Mp * (C > Dz ? C : Dz) * es);
     p->off_h = take((size_t)p->Mmax * Dz * sizeof(float));
     p->off_big = take(pad + Mp * 4 * Dz * es);
   }
@@ -224,7 +223,7 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     const RingShape rs = ring_shape(RingDims{p->Mmax, p->lanes}, (int)N, (int)K);
     return (size_t)rs.ncol * rs.tn * 32 * K * es;
   };
-  p->off_w_in = take(wbytes(Dz, split * C));
+  p->off_w_in = take(wbytes(Dz, C));
   p->off_wqkv = take(wbytes(3 * Dz, Dz));
   p->off_wo = take(wbytes(Dz, Dz));
   const bool sp = p->kind == SI_BLOCK_SPATIAL;
@@ -233,7 +232,7 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_wo2 = take(sp ? wbytes(Dz, Dz) : 0);
   p->off_w1 = take(wbytes(8 * Dz, Dz));
   p->off_w2 = take(wbytes(Dz, 4 * Dz));
-  p->off_w_out = take(wbytes(C, split * Dz));
+  p->off_w_out = take(wbytes(C, Dz));
   p->off_ffn_stream = take(p->fused_nb && !p->fused_attn ? (size_t)stream_bytes(14 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->off_attn_stream = take(p->fused_attn ? (size_t)stream_bytes(18 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->weights_bytes = off - act_end;
@@ -513,7 +512,6 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   const int C = p.C, D = p.D;
   const bool spatial = p.kind == SI_BLOCK_SPATIAL;
   const bool fused_ffn = p.fused_nb > 0, fused_attn = p.fused_attn;
-  constexpr int kSplit = 1;
   constexpr bool kF16 = sizeof(T) == 2;  // proj_in / proj_out run on fp16 operands for 16-bit storage
   // operand buffers in fragment order + ring kernel; the attention outputs too where the matrix-core
   // attention kernel writes them and a staged GEMM (not the FFN-half kernel) reads them
@@ -736,7 +734,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       }
       {
         EpiSliceOut<T> epi{X, OUT, cT(w->b_out), win};
-        SI_TRY((launch_gemm<T, kF16>("proj_out", a, (int64_t)kSplit * D, w_out, M, C, kSplit * D, epi, st)));
+        SI_TRY((launch_gemm<T, kF16>("proj_out", a, (int64_t)D, w_out, M, C, D, epi, st)));
       }
     }
   }
