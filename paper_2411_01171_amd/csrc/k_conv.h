@@ -54,6 +54,10 @@ struct ConvArgs {
                     // source ((y+dy)/2, (x+dx)/2) when (y+dy, x+dx) lies inside the output map)
   int mode;
   int ntaps;        // 9, or 1: the centre tap only (a 1x1 convolution; the kernel stream then holds one tap)
+  int col_major;    // tile order within an XCD's share: 0 = the column tiles of a row tile are neighbours (the
+                    // activation rows stay in that XCD's L2, every XCD streams the whole kernel), 1 = the row
+                    // tiles of a column tile are (the kernel columns stay, the activations stream): the
+                    // operand that is streamed by all 8 XCDs should be the smaller one
 };
 
 // acc[m, o] = sum_{tap, c} a[m + dy*W + dx, c] * w[o, c, tap] over the taps whose source pixel lies
@@ -81,8 +85,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi
   const int chunk = (a.ntiles + 7) / 8;
   const int tile = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
   if (tile >= a.ntiles) return;
-  const int col = tile % a.ncol;
-  const int64_t m0 = (int64_t)(tile / a.ncol) * (128 * TM);
+  const int nrow = a.ntiles / a.ncol;
+  const int col = a.col_major ? tile / nrow : tile % a.ncol;
+  const int64_t m0 = (int64_t)(a.col_major ? tile % nrow : tile / a.ncol) * (128 * TM);
 
   const int tid = threadIdx.x, lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);

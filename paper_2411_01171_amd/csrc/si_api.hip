@@ -327,7 +327,8 @@ static si_status launch_gemm_ring(const char* stage, const void* act, const void
   const int64_t rows2 = (M + 255) / 256;
   const bool big = rs.tn >= 4 && rows2 * rs.ncol >= kBigMin;
   ConvArgs a{static_cast<const char*>(act), static_cast<const char*>(wf), M, K, N, 1, 1, rs.ncol,
-             (int)((big ? rows2 : (M + 127) / 128) * rs.ncol), 1, 1, kConvSame, 1};
+             (int)((big ? rows2 : (M + 127) / 128) * rs.ncol), 1, 1, kConvSame, 1,
+             M < N ? 1 : 0};  // the smaller operand is the one every XCD streams
   const unsigned grid = (unsigned)((a.ntiles + 7) / 8 * 8);
   switch (rs.tn * 2 + (big ? 1 : 0)) {
     case 11: conv3x3_dma_kernel<2, 5, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
