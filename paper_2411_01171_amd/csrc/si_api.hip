@@ -282,11 +282,6 @@ static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T
   return SI_OK;
 }
 
-// as_ring: A is a fragment-order buffer and Wp a fragment stream -> ring kernel; else rows of lda.
-template <typename T, bool F16, class Epi>
-static si_status launch_gemm_sel(const char* stage, bool as_ring, const T* A, int64_t lda, const T* Wp, int64_t M, RingDims Mmax,
-                                 int N, int K, Epi epi, hipStream_t st);
-
 template <typename T>
 static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, int col0, int interleave, hipStream_t st,
                              int ld_dst = 0, bool to_f16 = false, int frag_tn = 0, int frag_row0 = 0) {
@@ -342,6 +337,7 @@ static si_status launch_gemm_ring(const char* stage, const void* act, const void
   return SI_OK;
 }
 
+// as_ring: A is a fragment-order buffer and Wp a fragment stream -> ring kernel; else rows of lda.
 template <typename T, bool F16, class Epi>
 static si_status launch_gemm_sel(const char* stage, bool as_ring, const T* A, int64_t lda, const T* Wp, int64_t M, RingDims Mmax,
                                  int N, int K, Epi epi, hipStream_t st) {
