@@ -318,9 +318,12 @@ static si_status launch_gemm_ring(const char* stage, const void* act, const void
   if (M <= 0) return SI_OK;
   StageScope scope(stage, st);
   const RingShape rs = ring_shape(Mmax, N, K);
-  constexpr int kBigMin = 400;  // 256-token row tiles for the largest problems only (measured)
+  // 256-token row tiles for the largest problems only: 400 workgroups over the windows in flight
+  // (measured: cfg3's ff1 with three windows in flight gains 4 % per step although one launch
+  // alone is slower, 31 -> 43 us)
+  constexpr int kBigMin = 400;
   const int64_t rows2 = (M + 255) / 256;
-  const bool big = rs.tn >= 4 && rows2 * rs.ncol >= kBigMin;
+  const bool big = rs.tn >= 4 && rows2 * rs.ncol * Mmax.lanes >= kBigMin;
   ConvArgs a{static_cast<const char*>(act), static_cast<const char*>(wf), M, K, N, 1, 1, rs.ncol,
              (int)((big ? rows2 : (M + 127) / 128) * rs.ncol), 1, 1, kConvSame, 1,
              M < N ? 1 : 0};  // the smaller operand is the one every XCD streams
