@@ -72,9 +72,10 @@ static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t
 // Column tiles of the ring kernel used as a GEMM on windows of up to Mmax tokens (`lanes` of them in
 // flight) x N columns over K: the widest tile (5, 4, 2 or 1 blocks of 32 columns) that pads N by at
 // most a tenth and still gives enough workgroups of 128 tokens, else the narrowest such tile.
-// Enough (measured): for long k loops (K > 512) one workgroup per CU over the windows in flight --
-// the tile's reuse of the activation rows then outweighs the idle tail of the last round of
-// workgroups; for short k loops 400 in the launch itself.  Weight packing and launch use the same
+// Enough (measured): for long k loops (K > 512) 330 workgroups over the windows in flight, and never
+// the 32-column tile if a wider one fits (64-column tiles beat both the wider and the narrower ones
+// whenever the wider ones leave fewer: cfg5's N = 1280 at 2048 tokens, cfg3's N = 640 at 2048 to
+// 8192 tokens); for short k loops 400 in the launch itself.  Weight packing and launch use the same
 // arguments.
 struct RingDims {
   int64_t Mmax;
@@ -85,12 +86,15 @@ struct RingShape {
 };
 static RingShape ring_shape(RingDims d, int N, int K) {
   const int64_t rows = (d.Mmax + 127) / 128 * (K > 512 ? d.lanes : 1);
-  const int min_wg = K > 512 ? 256 : 400;
+  const int min_wg = K > 512 ? 330 : 400;
   RingShape best{1, (N + 31) / 32};
+  bool found = false;
   for (int tn : {5, 4, 2, 1}) {
     const int nc = (N + 32 * tn - 1) / (32 * tn);
     if ((int64_t)nc * tn * 32 * 10 > (int64_t)N * 11) continue;  // too much padding
+    if (tn == 1 && K > 512 && found) break;
     best = RingShape{tn, nc};
+    found = true;
     if (rows * nc >= min_wg) break;
   }
   return best;
