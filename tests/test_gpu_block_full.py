@@ -79,6 +79,15 @@ def test_cfg3_spatial():
     _assert_bf16("cfg3", *_spatial_sampled(wl.CONFIGS["cfg3"], frames=[0, 7, 15]))
 
 
+@pytest.mark.parametrize("slice_len", [2, 5, 16])
+def test_cfg3_spatial_other_slice_lengths(slice_len):
+    """The staged path picks its GEMM tiles from the window's tokens and the windows in flight:
+    2 frames per slice (two windows in flight, 64-column tiles), 5 (ragged last window of one frame)
+    and the unsliced run (256-token row tiles) take other kernels than the default one-frame slices."""
+    spec = wl.scaled(wl.CONFIGS["cfg3"], slice_len=slice_len)
+    _assert_bf16(f"cfg3/slice{slice_len}", *_spatial_sampled(spec, frames=[0, 9, 15]))
+
+
 def test_cfg4_svdxt_spatial():
     _assert_bf16("cfg4s", *_spatial_sampled(wl.CONFIGS["cfg4s"], frames=[24]))
 
@@ -93,3 +102,17 @@ def test_cfg5_spatial():
 
 def test_cfg5_temporal():
     _assert_bf16("cfg5t", *_temporal_sampled(wl.CONFIGS["cfg5t"]))
+
+
+@pytest.mark.parametrize("slice_len", [1, 16])
+def test_cfg5_spatial_other_slice_lengths(slice_len):
+    """One frame per slice (16 windows of 512 tokens, three in flight) and the unsliced run."""
+    spec = wl.scaled(wl.CONFIGS["cfg5s"], slice_len=slice_len)
+    _assert_bf16(f"cfg5s/slice{slice_len}", *_spatial_sampled(spec, frames=[0, 8, 15]))
+
+
+@pytest.mark.parametrize("slice_len", [24, 256])
+def test_cfg5_temporal_other_slice_lengths(slice_len):
+    """24 positions per slice (11 windows, the last one of 16 positions, two in flight) and unsliced."""
+    spec = wl.scaled(wl.CONFIGS["cfg5t"], slice_len=slice_len)
+    _assert_bf16(f"cfg5t/slice{slice_len}", *_temporal_sampled(spec))
