@@ -23,7 +23,37 @@ def device_weights(spec: wl.BlockSpec, w: dict) -> si.BlockWeights:
                            gn_eps=spec.gn_eps, ln_eps=spec.ln_eps, add_sin_pe=spec.add_sin_pe)
 
 
+GUARD_BYTES = 4096
+
+
+def guarded(nbytes_or_like, dtype=None):
+    """Device buffer with GUARD_BYTES of 0xFF bytes (NaN in bf16 / fp32) before and after it.
+
+    Returns (whole uint8 buffer, view of the middle).  With a tensor argument the middle has its
+    shape and dtype and is filled with NaN; with a byte count it is raw uint8."""
+    if isinstance(nbytes_or_like, int):
+        n, like = nbytes_or_like, None
+    else:
+        like = nbytes_or_like
+        n = like.numel() * like.element_size()
+    pad = (-n) % 256
+    buf = torch.full((GUARD_BYTES + n + pad + GUARD_BYTES,), 0xFF, dtype=torch.uint8, device="cuda")
+    mid = buf[GUARD_BYTES:GUARD_BYTES + n]
+    if like is not None:
+        mid = mid.view(like.dtype).view(like.shape)
+    return buf, mid
+
+
+def guards_intact(buf, n) -> bool:
+    """True when the bytes before and after the n-byte middle of a guarded() buffer still hold 0xFF."""
+    head = buf[:GUARD_BYTES]
+    tail = buf[GUARD_BYTES + n:]
+    return bool((head == 0xFF).all().item()) and bool((tail == 0xFF).all().item())
+
+
 def run_block(spec: wl.BlockSpec, x: np.ndarray, w: dict, ctx, slice_len=None, return_torch=False):
+    """One si_block_forward call; `out` starts as NaN and both `out` and the workspace sit between
+    guard bands that the call must leave untouched."""
     xd = to_dev(x, spec.dtype)
     cd = None if ctx is None else to_dev(ctx, spec.dtype)
     wd = device_weights(spec, w)
@@ -31,12 +61,14 @@ def run_block(spec: wl.BlockSpec, x: np.ndarray, w: dict, ctx, slice_len=None, r
     sl = spec.slice_len if slice_len is None else slice_len
     nbytes = si.si_workspace_bytes(xd, wd, cd, axis, sl)
     assert nbytes > 0, "si_workspace_bytes rejected the arguments"
-    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    out = torch.full_like(xd, float("nan"))
+    ws_buf, ws = guarded(nbytes)
+    out_buf, out = guarded(xd)
     si.si_block_forward(xd, wd, cd, out, axis, sl, ws)
     torch.cuda.synchronize()
+    assert guards_intact(out_buf, out.numel() * out.element_size()), "write outside `out`"
+    assert guards_intact(ws_buf, nbytes), "write outside the workspace"
     if return_torch:
-        return out
+        return out.clone()
     return out.float().cpu().numpy().astype(np.float64)
 
 

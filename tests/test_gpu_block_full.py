@@ -1,11 +1,21 @@
-"""Full-size configurations in the launch configuration the benchmark times,
-checked against the oracle on sampled outputs.
+"""Full-size configurations in the launch configuration the benchmark times.
+
+cfg2, cfg3 and both cfg5 blocks: the WHOLE output tensor is compared with the
+oracle's unsliced forward, element by element.  The oracle's pass over one of
+these tensors is computed once per process and shared by the tests that run the
+same input at other slice lengths.
+
+cfg4 (9216 keys per frame: one oracle frame costs seconds, the tensor has 50):
+the oracle evaluates sampled frames / positions chosen so that every window in
+flight (every lane), the first, the last and the ragged window are compared;
+in addition the whole output at the default slicing is compared with the GPU's
+own unsliced run (Eq. 1: slicing leaves the result unchanged), which ties every
+element that the oracle did not visit to ones computed by the same kernels in a
+single window on a single stream.
 
 A temporal block's output at position p depends on x[:, :, :, p] and on the
 GroupNorm statistics of the whole frame only; a spatial block's output frame
-(b, f) depends on x[b, :, f] only.  The oracle therefore evaluates sampled
-positions (with GroupNorm taken over the full tensor) or sampled frames one by
-one; samples straddle slice and tile boundaries and include the last element.
+(b, f) depends on x[b, :, f] only -- that is what makes sampling exact.
 """
 import numpy as np
 import pytest
@@ -17,102 +27,152 @@ pytestmark = pytest.mark.gpu
 
 BF16_MAX_ABS, BF16_REL_L2 = 2e-2, 5e-3
 
-
-def _sample_positions(P, slice_len, n_random, seed):
-    rng = np.random.default_rng(seed)
-    fixed = {0, 1, 31, 32, 63, 64, 127, 128, P - 1, P - 2}
-    for s in range(slice_len, P, slice_len):
-        fixed.update({s - 1, s})
-    fixed = {p for p in fixed if 0 <= p < P}
-    if len(fixed) > 40:
-        fixed = set(sorted(fixed)[:20] + sorted(fixed)[-20:])
-    fixed.update(int(p) for p in rng.integers(0, P, n_random))
-    return np.array(sorted(fixed))
+_cache = {}
 
 
-def _temporal_sampled(spec, n_random=24):
-    from gpu_helpers import run_block
-    x, w = wl.make_x(spec), wl.make_weights(spec)
-    out = run_block(spec, x, w, None)
-    assert np.all(np.isfinite(out))
-    B, C, F, H, W = x.shape
-    P = H * W
-    sel = _sample_positions(P, spec.slice_len, n_random, spec.seed)
-    xhat = oracle.group_norm_ref(x, spec.gn_groups, spec.gn_eps, w["gn_g"], w["gn_b"]).reshape(B, C, F, 1, P)
-    xs = x.reshape(B, C, F, 1, P)[..., sel]
-    ref = oracle.block_forward_ref(xs, w, spec, None, xhat=xhat[..., sel])
-    got = out.reshape(B, C, F, 1, P)[..., sel]
-    return got, ref, xs, out
+def _inputs(name):
+    """Seeded inputs of a named configuration and the oracle's whole-tensor result (cached)."""
+    if name not in _cache:
+        spec = wl.CONFIGS[name]
+        x, w, ctx = wl.make_x(spec), wl.make_weights(spec), wl.make_context(spec)
+        _cache[name] = (x, w, ctx, oracle.block_forward_ref(x, w, spec, ctx))
+    return _cache[name]
 
 
-def _spatial_sampled(spec, frames):
-    from gpu_helpers import run_block
-    x, w, ctx = wl.make_x(spec), wl.make_weights(spec), wl.make_context(spec)
-    out = run_block(spec, x, w, ctx)
-    assert np.all(np.isfinite(out))
-    got, ref, xs = [], [], []
-    for f in frames:
-        xf = x[:, :, f:f + 1]
-        ref.append(oracle.block_forward_ref(xf, w, spec, ctx))
-        got.append(out[:, :, f:f + 1])
-        xs.append(xf)
-    return np.concatenate(got, 2), np.concatenate(ref, 2), np.concatenate(xs, 2), out
-
-
-def _assert_bf16(name, got, ref, xs, out):
+def _report(name, got, ref, xs, out=None):
     from gpu_helpers import errors
     e = errors(got, ref, xs)
-    e["max_out_full"] = float(np.max(np.abs(out)))
+    d = np.abs(got - ref)
     i = np.unravel_index(np.argmax(np.abs(ref)), ref.shape)
-    e["err_at_argmax"] = float(abs(got[i] - ref[i]))
+    e["err_at_argmax_ref"] = float(d[i])
+    big = np.abs(ref) >= 4.0
+    e["n_ref_ge_4"] = int(big.sum())
+    e["max_abs_where_ref_ge_4"] = float(d[big].max()) if big.any() else 0.0
+    e["max_abs_where_ref_lt_4"] = float(d[~big].max())
+    e["n_compared"] = int(ref.size)
+    if out is not None:
+        e["max_out_full"] = float(np.max(np.abs(out)))
     print(name, e)
     assert e["max_abs"] <= BF16_MAX_ABS, e
     assert e["rel_l2"] <= BF16_REL_L2, e
     assert e["rel_l2_branch"] <= 2e-2, e
 
 
-def test_cfg2_animatediff_temporal():
-    _assert_bf16("cfg2", *_temporal_sampled(wl.CONFIGS["cfg2"]))
+def _whole(name, slice_len=None):
+    from gpu_helpers import run_block
+    spec = wl.CONFIGS[name]
+    x, w, ctx, ref = _inputs(name)
+    out = run_block(spec, x, w, ctx, slice_len)
+    assert np.all(np.isfinite(out)), "output has NaN/Inf or unwritten elements"
+    _report(f"{name}/slice{slice_len or spec.slice_len}/whole", out, ref, x)
 
 
-def test_cfg3_spatial():
-    _assert_bf16("cfg3", *_spatial_sampled(wl.CONFIGS["cfg3"], frames=[0, 7, 15]))
+def test_cfg2_animatediff_temporal_whole_tensor():
+    _whole("cfg2")
+
+
+@pytest.mark.parametrize("slice_len", [257, 4096])
+def test_cfg2_other_slice_lengths_whole_tensor(slice_len):
+    """257 positions per slice: 16 windows (two in flight on two streams, workgroup tiles of 8
+    positions that do not divide the window, a ragged last window of 241); 4096: unsliced."""
+    _whole("cfg2", slice_len)
+
+
+def test_cfg3_spatial_whole_tensor():
+    _whole("cfg3")
 
 
 @pytest.mark.parametrize("slice_len", [2, 5, 16])
-def test_cfg3_spatial_other_slice_lengths(slice_len):
+def test_cfg3_other_slice_lengths_whole_tensor(slice_len):
     """The staged path picks its GEMM tiles from the window's tokens and the windows in flight:
     2 frames per slice (two windows in flight, 64-column tiles), 5 (ragged last window of one frame)
     and the unsliced run (256-token row tiles) take other kernels than the default one-frame slices."""
-    spec = wl.scaled(wl.CONFIGS["cfg3"], slice_len=slice_len)
-    _assert_bf16(f"cfg3/slice{slice_len}", *_spatial_sampled(spec, frames=[0, 9, 15]))
+    _whole("cfg3", slice_len)
 
 
-def test_cfg4_svdxt_spatial():
-    _assert_bf16("cfg4s", *_spatial_sampled(wl.CONFIGS["cfg4s"], frames=[24]))
-
-
-def test_cfg4_svdxt_temporal():
-    _assert_bf16("cfg4t", *_temporal_sampled(wl.CONFIGS["cfg4t"]))
-
-
-def test_cfg5_spatial():
-    _assert_bf16("cfg5s", *_spatial_sampled(wl.CONFIGS["cfg5s"], frames=[0, 3, 4, 15]))
-
-
-def test_cfg5_temporal():
-    _assert_bf16("cfg5t", *_temporal_sampled(wl.CONFIGS["cfg5t"]))
+def test_cfg5_spatial_whole_tensor():
+    _whole("cfg5s")
 
 
 @pytest.mark.parametrize("slice_len", [1, 16])
-def test_cfg5_spatial_other_slice_lengths(slice_len):
+def test_cfg5_spatial_other_slice_lengths_whole_tensor(slice_len):
     """One frame per slice (16 windows of 512 tokens, three in flight) and the unsliced run."""
-    spec = wl.scaled(wl.CONFIGS["cfg5s"], slice_len=slice_len)
-    _assert_bf16(f"cfg5s/slice{slice_len}", *_spatial_sampled(spec, frames=[0, 8, 15]))
+    _whole("cfg5s", slice_len)
+
+
+def test_cfg5_temporal_whole_tensor():
+    _whole("cfg5t")
 
 
 @pytest.mark.parametrize("slice_len", [24, 256])
-def test_cfg5_temporal_other_slice_lengths(slice_len):
+def test_cfg5_temporal_other_slice_lengths_whole_tensor(slice_len):
     """24 positions per slice (11 windows, the last one of 16 positions, two in flight) and unsliced."""
-    spec = wl.scaled(wl.CONFIGS["cfg5t"], slice_len=slice_len)
-    _assert_bf16(f"cfg5t/slice{slice_len}", *_temporal_sampled(spec))
+    _whole("cfg5t", slice_len)
+
+
+# ----------------------------------------------------------------------------- cfg4: samples + sliced == unsliced
+
+def _same_as_unsliced(spec, x, w, ctx, out_t):
+    """The whole output at the default slicing against the GPU's own unsliced run."""
+    import torch
+    from gpu_helpers import run_block
+    extent = spec.F if spec.slice_axis == wl.AXIS_F else spec.H * spec.W
+    full_t = run_block(spec, x, w, ctx, extent, return_torch=True)
+    diff = (out_t.float() - full_t.float()).abs()
+    n_diff = int((diff != 0).sum().item())
+    print(spec.name, "sliced vs unsliced: differing elements", n_diff, "of", diff.numel(), "max", float(diff.max().item()))
+    # the same per-token arithmetic in another window: identical bits, or (where a kernel's tile
+    # shape changes the order in which partial sums meet) at most one rounding step of the storage type
+    assert torch.equal(out_t, full_t) or float((diff / full_t.float().abs().clamp_min(1.0)).max().item()) <= 2.0 ** -7
+    return n_diff
+
+
+def test_cfg4_svdxt_spatial_sampled_frames_and_unsliced():
+    from gpu_helpers import run_block
+    spec = wl.CONFIGS["cfg4s"]
+    x, w, ctx = wl.make_x(spec), wl.make_weights(spec), wl.make_context(spec)
+    out_t = run_block(spec, x, w, ctx, return_torch=True)
+    out = out_t.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(out))
+    # 25 one-frame windows on three streams: frames 0, 1, 2 are the first window of each lane,
+    # 13 the middle (lane 1), 23 lane 2's last, 24 the last window (lane 0)
+    frames = [0, 1, 2, 13, 23, 24]
+    got, ref, xs = [], [], []
+    for f in frames:
+        xf = x[:, :, f:f + 1]
+        ref.append(oracle.block_forward_ref(xf, w, spec, ctx))
+        got.append(out[:, :, f:f + 1])
+        xs.append(xf)
+    _report("cfg4s/frames" + str(frames), np.concatenate(got, 2), np.concatenate(ref, 2), np.concatenate(xs, 2), out)
+    _same_as_unsliced(spec, x, w, ctx, out_t)
+
+
+def _positions_over_windows(P, slice_len, per_window, seed):
+    """Positions in every window: its first and last two, tile edges after its start, random ones."""
+    rng = np.random.default_rng(seed)
+    sel = set()
+    for s0 in range(0, P, slice_len):
+        s1 = min(s0 + slice_len, P)
+        sel.update({s0, s0 + 1, s1 - 2, s1 - 1})
+        sel.update(p for p in (s0 + 3, s0 + 4, s0 + 127, s0 + 128) if p < s1)
+        sel.update(int(p) for p in rng.integers(s0, s1, per_window))
+    return np.array(sorted(p for p in sel if 0 <= p < P))
+
+
+def test_cfg4_svdxt_temporal_sampled_positions_and_unsliced():
+    from gpu_helpers import run_block
+    spec = wl.CONFIGS["cfg4t"]
+    x, w = wl.make_x(spec), wl.make_weights(spec)
+    out_t = run_block(spec, x, w, None, return_torch=True)
+    out = out_t.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(out))
+    B, C, F, H, W = x.shape
+    P = H * W
+    sel = _positions_over_windows(P, spec.slice_len, 72, spec.seed)   # 8 windows (two lanes) x ~80 positions
+    assert len(sel) >= 512
+    xhat = oracle.group_norm_ref(x, spec.gn_groups, spec.gn_eps, w["gn_g"], w["gn_b"]).reshape(B, C, F, 1, P)
+    xs = x.reshape(B, C, F, 1, P)[..., sel]
+    ref = oracle.block_forward_ref(xs, w, spec, None, xhat=xhat[..., sel])
+    got = out.reshape(B, C, F, 1, P)[..., sel]
+    _report(f"cfg4t/{len(sel)} positions", got, ref, xs, out)
+    _same_as_unsliced(spec, x, w, None, out_t)

@@ -122,6 +122,51 @@ def test_head_dim_40_and_25_frames_bf16():
     _check(spec, x, w, None, 10)
 
 
+# ---- D = 320: the register-resident kernels at the width the full-size configurations use, on
+# shapes those configurations do not reach
+
+@pytest.mark.parametrize("slice_len", [35, 20])
+def test_temporal_320_odd_positions_bf16(slice_len):
+    """C = 320, 8 heads x 40, H*W = 35: windows that are not multiples of 4 positions take the scalar
+    slice-in / slice-out; 20 positions per slice leaves a ragged last window of 15."""
+    spec = tiny_spec(wl.TEMPORAL, B=2, C=320, F=16, H=5, W=7, heads=8, dim_head=40, groups=32, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.03)
+    _check(spec, x, w, None, slice_len)
+
+
+def test_temporal_320_three_batches_tiles_straddle_bf16():
+    """C = 320, B = 3, F = 8 (16 positions per workgroup), 136 positions per batch entry: workgroup
+    tiles straddle batch entries (two sets of statistics per workgroup) and the last tile is ragged."""
+    spec = tiny_spec(wl.TEMPORAL, B=3, C=320, F=8, H=8, W=17, heads=5, dim_head=64, groups=32, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.03)
+    _check(spec, x, w, None, 136)
+
+
+@pytest.mark.parametrize("heads,dim_head", [(8, 40), (5, 64)])
+def test_temporal_320_25_frames_ragged_window_bf16(heads, dim_head):
+    """C = 320 with 25 frames (one position per wavefront, 7 padding columns), 36 positions in
+    windows of 10: ragged last window of 6, window starts that are not multiples of 4."""
+    spec = tiny_spec(wl.TEMPORAL, B=2, C=320, F=25, H=6, W=6, heads=heads, dim_head=dim_head, groups=32, pe=True,
+                     dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.03)
+    _check(spec, x, w, None, 10)
+
+
+@pytest.mark.parametrize("hw,slice_len", [((9, 11), 1), ((8, 13), 1), ((8, 13), 2)])
+def test_spatial_320_ragged_token_tiles_bf16(hw, slice_len):
+    """C = 320, 5 heads x 64: the fused out-projection / FFN / proj_out kernel on windows of 198, 208
+    and 416 tokens (its 128-token tiles end in a ragged one); 99 positions per frame also take the
+    attention kernel that does not need H*W to be a multiple of 8."""
+    spec = tiny_spec(wl.SPATIAL, B=2, C=320, F=3, H=hw[0], W=hw[1], heads=5, dim_head=64, groups=32, M=7, Cc=24,
+                     dtype="bf16")
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.03)
+    _check(spec, x, w, ctx, slice_len)
+
+
 def test_peaky_softmax_bf16():
     """Queries and keys scaled up so that the softmax is far from uniform."""
     spec = tiny_spec(wl.SPATIAL, B=1, C=64, F=2, H=10, W=10, heads=2, dim_head=32, groups=8, M=7, Cc=16, dtype="bf16")
