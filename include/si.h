@@ -24,6 +24,13 @@
  *     argument validation happens before the first GPU call, so every error
  *     other than SI_ERR_HIP can be provoked on a machine without a GPU.
  *   - Device base pointers must be 16-byte aligned.
+ *   - State the library keeps: per device, up to two auxiliary streams
+ *     (non-blocking, default priority) and three events, created the first
+ *     time a forward call pipelines windows and kept until the process ends;
+ *     calls that pipeline windows on the same device share them, so forward
+ *     calls on one device must not overlap in time from several host threads.
+ *     A small host table remembers which workspaces hold re-laid-out weights
+ *     (SI_FWD_WEIGHTS_PACKED).  Nothing else outlives a call.
  */
 #ifndef SI_H_
 #define SI_H_
@@ -51,7 +58,7 @@ typedef enum { SI_F32 = 0, SI_BF16 = 1 } si_dtype;
 
 /* Temporal blocks attend over the F frames of one spatial position; spatial
  * blocks attend over the H*W positions of one frame and cross-attend to the
- * context tokens (Sec. 3, "temporal layers ... after every spatial layer"). */
+ * context tokens; a temporal block follows every spatial one (Sec. 3). */
 typedef enum { SI_BLOCK_TEMPORAL = 0, SI_BLOCK_SPATIAL = 1 } si_block_kind;
 
 /* Slice axis (Sec. 4.1).  SI_AXIS_F: windows of frames, legal for spatial
@@ -106,8 +113,9 @@ typedef struct {
 } si_block_weights;
 
 /* Bytes of device workspace si_block_forward needs for these arguments: the
- * intermediates of ONE slice (Sec. 4.2.1, "only ... a single sliced
- * sub-feature") plus slice-independent items (GroupNorm statistics, the
+ * intermediates of the slices in flight (Sec. 4.2.1: one sliced sub-feature at
+ * a time; Sec. 4.2.2: up to si_windows_in_flight of them when slices are many
+ * and small) plus slice-independent items (GroupNorm statistics, the
  * re-laid-out weights, the context keys/values).  `ctx` may be NULL for
  * temporal blocks.  Returns 0 if the arguments are invalid (the same checks
  * as si_block_forward, pointers excepted).  Host-only; touches no GPU. */
@@ -119,6 +127,15 @@ size_t si_workspace_bytes(const si_tensor5* x, const si_block_weights* w, const 
  * re-laid-out weights.  Same arguments, same validity rule. */
 size_t si_live_activation_bytes(const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
                                 int32_t axis, int64_t slice_len);
+
+/* Windows that si_block_forward keeps in flight for these arguments (Sec. 4.2.2:
+ * pipelining across slices): 1, or 2 / 3 when the slices are many and small,
+ * each on a stream of its own (the caller's plus library-owned ones, forked
+ * after the once-per-call work and joined before the call's work on `stream`
+ * ends) and with window intermediates of its own.  0 if the arguments are
+ * invalid.  Host-only. */
+int32_t si_windows_in_flight(const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
+                             int32_t axis, int64_t slice_len);
 
 /* Sliced block forward (Sec. 4.1, 4.2.1, Eq. 1).
  *
@@ -147,8 +164,12 @@ si_status si_block_forward(const si_tensor5* x, const si_block_weights* w, const
  *                          re-laid-out weights and the frame table it still holds are used as
  *                          they are and the re-layout pass is skipped (weights are constant
  *                          across diffusion steps).  Everything activation-derived (statistics,
- *                          context keys / values) is recomputed.  A wrong promise gives wrong
- *                          results, not an error.
+ *                          context keys / values) is recomputed.  What the host can see of a
+ *                          broken promise is refused with SI_ERR_ARG before anything is
+ *                          enqueued: a workspace pointer that no re-laying-out call of this
+ *                          process used last with the same shapes, slicing, device and
+ *                          parameter pointers.  Changed values behind the same pointers, or a
+ *                          workspace written in between, give wrong results, not an error.
  * Unknown flag bits -> SI_ERR_ARG.  flags == 0 is si_block_forward. */
 #define SI_FWD_WEIGHTS_PACKED 1u
 si_status si_block_forward_ex(const si_tensor5* x, const si_block_weights* w, const si_context* ctx,
@@ -285,7 +306,9 @@ si_status si_resample_forward(const si_tensor5* x, int32_t kind, const void* w_c
  * a visited diagonal entry below gamma). */
 int32_t si_key_step_search(const float* S, int32_t K, float gamma, int32_t* G_out);
 
-/* Optional per-stage timing for measurement.  When enabled, the forward entry
+/* Measurement aid, not part of the product path: process-wide state, off by
+ * default, not thread-safe, and never to be enabled while other threads call
+ * the library.  Optional per-stage timing.  When enabled, the forward entry
  * points and si_rehash_check record a HIP event pair around every kernel
  * launch, and windows that would otherwise run two at a time on two streams
  * run one after the other on the caller's stream, so that each pair brackets

@@ -118,20 +118,18 @@ def feature_from_tokens_ref(y, kind: str, shape):
     return y.reshape(B, Fr, P, C).transpose(0, 3, 1, 2).reshape(B, C, Fr, H, W)
 
 
-def transformer_ref(t, w, hp, ctx_per_seq=None, frame_index=None):
+def transformer_ref(t, w, hp, ctx_per_seq=None):
     """Steps 2-7 (up to y = h W_out + b_out) on sequences t [S, N, C].
 
-    ctx_per_seq: [S, M, Cc] context of each sequence (spatial blocks).
-    frame_index: [N] frame number of each row (temporal blocks with add_sin_pe)."""
+    ctx_per_seq: [S, M, Cc] context of each sequence (spatial blocks).  Row n of a temporal
+    sequence is frame n (the frame embedding's index)."""
     W = {k: np.asarray(v, F64) for k, v in w.items()}
     t = np.asarray(t, F64)
     h = t @ W["w_in"] + W["b_in"]
     D = h.shape[-1]
     a = layer_norm_ref(h, W["ln1_g"], W["ln1_b"], hp.ln_eps)
     if hp.kind == "temporal" and hp.add_sin_pe:
-        frames = np.arange(h.shape[1]) if frame_index is None else np.asarray(frame_index)
-        pe = sinusoidal_pe_ref(int(frames.max()) + 1, D)
-        a = a + pe[frames][None, :, :]
+        a = a + sinusoidal_pe_ref(h.shape[1], D)[None, :, :]
     o = attention_ref(a @ W["wq"], a @ W["wk"], a @ W["wv"], hp.heads)
     h = h + o @ W["wo"] + W["bo"]
     if hp.kind == "spatial":

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     SiError, lib, library_path, BlockWeights, RehashCache, ResBlockWeights,
     si_resblock_workspace_bytes, si_resblock_live_activation_bytes, si_resblock_forward,
     SI_RESAMPLE_DOWN, SI_RESAMPLE_UP, si_resample_workspace_bytes, si_resample_forward,
-    si_workspace_bytes, si_live_activation_bytes, si_block_forward, si_block_forward_rehash,
+    si_workspace_bytes, si_live_activation_bytes, si_windows_in_flight, si_block_forward, si_block_forward_rehash,
     si_block_forward_ex, SI_FWD_WEIGHTS_PACKED,
     si_rehash_scratch_bytes, si_rehash_check, si_rehash_check_sync, si_key_step_search,
     si_stage_timing_enable, si_stage_timing_read, si_status_str, si_abi_version,

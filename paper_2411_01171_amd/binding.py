@@ -77,6 +77,8 @@ def lib() -> C.CDLL:
     L.si_workspace_bytes.argtypes = [C.POINTER(_Tensor5), C.POINTER(_Weights), C.POINTER(_Context), i32, i64]
     L.si_live_activation_bytes.restype = sz
     L.si_live_activation_bytes.argtypes = L.si_workspace_bytes.argtypes
+    L.si_windows_in_flight.restype = i32
+    L.si_windows_in_flight.argtypes = L.si_workspace_bytes.argtypes
     L.si_block_forward.restype = i32
     L.si_block_forward.argtypes = [C.POINTER(_Tensor5), C.POINTER(_Weights), C.POINTER(_Context), C.POINTER(_Tensor5),
                                    i32, i64, vp, sz, vp]
@@ -190,6 +192,12 @@ def si_live_activation_bytes(x, weights: BlockWeights, ctx, axis: int, slice_len
     xd = _tensor5(x)
     pc, _keep = _pctx(ctx)
     return int(lib().si_live_activation_bytes(C.byref(xd), C.byref(weights.struct), pc, axis, slice_len))
+
+
+def si_windows_in_flight(x, weights: BlockWeights, ctx, axis: int, slice_len: int) -> int:
+    xd = _tensor5(x)
+    pc, _keep = _pctx(ctx)
+    return int(lib().si_windows_in_flight(C.byref(xd), C.byref(weights.struct), pc, axis, slice_len))
 
 
 SI_FWD_WEIGHTS_PACKED = 1

@@ -6,7 +6,7 @@
 // lies outside fp16's normal range (|w| < 6.1e-5 rounds to a multiple of 2^-24, |w| > 65504 overflows).
 // The resampling operators of the same group (stride-2 convolution, nearest doubling + convolution)
 // run on the raw bf16 feature with bf16 operands (exact).
-//   conv3x3_dma_kernel      3x3 convolution, zero padding 1 -- same map, stride 2, or after nearest
+//   ring_mma_kernel      3x3 convolution, zero padding 1 -- same map, stride 2, or after nearest
 //                           doubling -- as an implicit GEMM on the matrix cores; both operands arrive
 //                           in MFMA fragment order by direct global->LDS loads through a multi-stage
 //                           ring                                                             [MFMA bound]
@@ -72,7 +72,7 @@ struct ConvArgs {
 // before every LDS read); no compiler-visible vector-memory load sits inside the k loop.
 // F16: operands are fp16 (v_mfma_f32_32x32x16_f16), else bf16 (v_mfma_f32_32x32x16_bf16).
 template <int TM, int TN, int STAGES, bool F16, class Epi>
-__global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvArgs a, Epi epi) {
+__global__ __launch_bounds__(256, 2) void ring_mma_kernel(ConvArgs a, Epi epi) {
   constexpr int AF = 4 * TM * 2, WFR = 2 * TN;           // fragments per stage
   constexpr int NW = (WFR + 3) / 4;                      // weight loads per wavefront per stage
   constexpr int PER = 2 * TM + NW;                       // loads per wavefront per stage

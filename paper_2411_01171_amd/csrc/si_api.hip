@@ -7,6 +7,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -333,12 +334,12 @@ static si_status launch_gemm_ring(const char* stage, const void* act, const void
              M < N ? 1 : 0};  // the smaller operand is the one every XCD streams
   const unsigned grid = (unsigned)((a.ntiles + 7) / 8 * 8);
   switch (rs.tn * 2 + (big ? 1 : 0)) {
-    case 11: conv3x3_dma_kernel<2, 5, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
-    case 10: conv3x3_dma_kernel<1, 5, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
-    case 9: conv3x3_dma_kernel<2, 4, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
-    case 8: conv3x3_dma_kernel<1, 4, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
-    case 4: conv3x3_dma_kernel<1, 2, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
-    default: conv3x3_dma_kernel<1, 1, 6, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    case 11: ring_mma_kernel<2, 5, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    case 10: ring_mma_kernel<1, 5, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    case 9: ring_mma_kernel<2, 4, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    case 8: ring_mma_kernel<1, 4, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    case 4: ring_mma_kernel<1, 2, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    default: ring_mma_kernel<1, 1, 6, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
   }
   SI_CHECK_LAUNCH();
   return SI_OK;
@@ -752,6 +753,54 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   return SI_OK;
 }
 
+// What the host can verify of a SI_FWD_WEIGHTS_PACKED promise: the last call that re-laid-out weights
+// into this workspace (in this process, on this device) had the same plan -- every offset, tile choice
+// and stream length follows from the fields hashed here -- and the same parameter pointers.  A small
+// table of the most recent workspaces, shared by all callers and guarded by a mutex.
+static uint64_t fnv1a(uint64_t h, const void* data, size_t n) {
+  const unsigned char* b = static_cast<const unsigned char*>(data);
+  for (size_t i = 0; i < n; ++i) h = (h ^ b[i]) * 1099511628211ull;
+  return h;
+}
+static uint64_t pack_fingerprint(const Plan& p, const si_block_weights* w) {
+  int dev = -1;
+  (void)hipGetDevice(&dev);
+  const int64_t f[] = {p.kind, p.dtype, p.B, p.C, p.F, p.H, p.W, p.G, p.heads, p.d, p.Mc, p.Cc, p.axis, p.extent, p.slice_len,
+                       p.Mmax, p.pe, p.fused_nb, p.fused_attn, p.attn_mfma, p.ring, p.lanes, (int64_t)p.weights_bytes,
+                       (int64_t)p.total_bytes, (int64_t)p.off_w_in, (int64_t)p.off_ffn_stream, (int64_t)p.off_attn_stream, dev};
+  uint64_t h = fnv1a(14695981039346656037ull, f, sizeof(f));
+  const void* q[] = {w->gn_g, w->gn_b, w->w_in, w->b_in, w->ln1_g, w->ln1_b, w->wq, w->wk, w->wv, w->wo, w->bo,
+                     w->ln3_g, w->ln3_b, w->w1, w->b1, w->w2, w->b2, w->w_out, w->b_out};
+  h = fnv1a(h, q, sizeof(q));
+  if (p.kind == SI_BLOCK_SPATIAL) {
+    const void* sp[] = {w->ln2_g, w->ln2_b, w->wq2, w->wk2, w->wv2, w->wo2, w->bo2};
+    h = fnv1a(h, sp, sizeof(sp));
+  }
+  return h ? h : 1;
+}
+struct PackRecord {
+  const void* ws;
+  uint64_t fp;
+};
+static std::mutex g_pack_mutex;
+static PackRecord g_pack_table[64];
+static unsigned g_pack_next = 0;
+static void pack_record(const void* ws, uint64_t fp) {
+  std::lock_guard<std::mutex> lock(g_pack_mutex);
+  for (PackRecord& r : g_pack_table)
+    if (r.ws == ws) {
+      r.fp = fp;
+      return;
+    }
+  g_pack_table[g_pack_next++ % 64] = PackRecord{ws, fp};
+}
+static bool pack_matches(const void* ws, uint64_t fp) {
+  std::lock_guard<std::mutex> lock(g_pack_mutex);
+  for (const PackRecord& r : g_pack_table)
+    if (r.ws == ws) return r.fp == fp;
+  return false;
+}
+
 static bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
   const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
   return a0 < b0 + nb && b0 < a0 + na;
@@ -794,6 +843,13 @@ size_t si_live_activation_bytes(const si_tensor5* x, const si_block_weights* w, 
   si::Plan p;
   if (si::make_plan(x, w, ctx, axis, slice_len, &p) != SI_OK) return 0;
   return p.total_bytes - p.weights_bytes;
+}
+
+int32_t si_windows_in_flight(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, int32_t axis,
+                             int64_t slice_len) {
+  si::Plan p;
+  if (si::make_plan(x, w, ctx, axis, slice_len, &p) != SI_OK) return 0;
+  return p.lanes;
 }
 
 // Argument checks shared by the forward entry points; fills the plan.
@@ -841,6 +897,9 @@ si_status si_block_forward_ex(const si_tensor5* x, const si_block_weights* w, co
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
   const bool packed = (flags & SI_FWD_WEIGHTS_PACKED) != 0;
+  const uint64_t fp = si::pack_fingerprint(p, w);
+  if (packed && !si::pack_matches(workspace, fp)) return SI_ERR_ARG;  // nothing enqueued
+  if (!packed) si::pack_record(workspace, fp);
   if (p.dtype == SI_F32) return si::run_block<float>(p, x, w, ctx, out, ws, st, false, packed);
   return si::run_block<si::bf16>(p, x, w, ctx, out, ws, st, false, packed);
 }
@@ -908,6 +967,7 @@ si_status si_block_forward_rehash(const si_tensor5* x, const si_block_weights* w
       return SI_OK;
     }
   }
+  si::pack_record(workspace, si::pack_fingerprint(p, w));
   s = p.dtype == SI_F32 ? si::run_block<float>(p, x, w, ctx, out, ws, st, stats_done)
                         : si::run_block<si::bf16>(p, x, w, ctx, out, ws, st, stats_done);
   if (s != SI_OK) return s;
@@ -986,20 +1046,19 @@ si_status si_rehash_check_sync(const void* feat_t, const void* feat_prev, int64_
 
 int32_t si_key_step_search(const float* S, int32_t K, float gamma, int32_t* G_out) {
   if (!S || !G_out || K < 1 || std::isnan(gamma) || gamma > 1.0f) return -1;
-  // Algorithm 1: i walks upward, j is the last key step (the anchor).
+  // Algorithm 1 as a scan per anchor: a key step stays the anchor for the run of later steps that are
+  // still similar to it; the first step that is not becomes the next key step.  Entries and
+  // threshold are compared as the float values the caller passed (a NaN entry counts as dissimilar).
   int32_t count = 0;
-  G_out[count++] = 0;
-  int32_t i = 0, j = 0;
-  while (i < K) {
-    if (S[(int64_t)i * K + j] >= gamma) {
-      ++i;
-    } else {
-      if (!(S[(int64_t)i * K + i] >= gamma)) return -1;  // the walk could not advance
-      if (G_out[count - 1] != i) G_out[count++] = i;
-      j = i;
-    }
+  for (int32_t anchor = 0;;) {
+    G_out[count++] = anchor;
+    if (!(S[(int64_t)anchor * K + anchor] >= gamma)) return -1;  // a step must at least be similar to itself
+    int32_t next = anchor + 1;
+    while (next < K && S[(int64_t)next * K + anchor] >= gamma) ++next;
+    if (next >= K) break;
+    anchor = next;
   }
-  if (G_out[count - 1] != K - 1) G_out[count++] = K - 1;
+  if (G_out[count - 1] != K - 1) G_out[count++] = K - 1;  // the last step always joins
   return count;
 }
 

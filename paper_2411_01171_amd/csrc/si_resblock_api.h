@@ -85,7 +85,7 @@ static si_status make_res_plan(const si_tensor5* x, const si_resblock_weights* w
 template <int TM, int TN, int STAGES, bool F16, class Epi>
 static void launch_conv_tile(const ConvArgs& a, Epi epi, hipStream_t st) {
   const int grid = (a.ntiles + 7) / 8 * 8;
-  conv3x3_dma_kernel<TM, TN, STAGES, F16, Epi><<<grid, 256, 0, st>>>(a, epi);
+  ring_mma_kernel<TM, TN, STAGES, F16, Epi><<<grid, 256, 0, st>>>(a, epi);
 }
 
 // Column tiles of the convolution kernel: the candidate width that pads the output channels least,

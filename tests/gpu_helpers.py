@@ -7,20 +7,7 @@ import torch
 import paper_2411_01171_amd as si
 import si_workloads as wl
 
-TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
-AXIS = {wl.AXIS_F: si.SI_AXIS_F, wl.AXIS_HW: si.SI_AXIS_HW}
-KIND = {wl.TEMPORAL: si.SI_BLOCK_TEMPORAL, wl.SPATIAL: si.SI_BLOCK_SPATIAL}
-
-
-def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
-    """fp32 array holding storage-rounded values -> device tensor of the storage type (exact)."""
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda").to(TORCH_DTYPE[dtype]).contiguous()
-
-
-def device_weights(spec: wl.BlockSpec, w: dict) -> si.BlockWeights:
-    tensors = {k: to_dev(v, spec.dtype) for k, v in w.items()}
-    return si.BlockWeights(KIND[spec.kind], spec.heads, spec.dim_head, spec.gn_groups, tensors,
-                           gn_eps=spec.gn_eps, ln_eps=spec.ln_eps, add_sin_pe=spec.add_sin_pe)
+from paper_2411_01171_amd.devio import AXIS, KIND, TORCH_DTYPE, device_res_weights, device_weights, to_dev  # noqa: F401
 
 
 GUARD_BYTES = 4096
@@ -82,11 +69,6 @@ def errors(out: np.ndarray, ref: np.ndarray, x: np.ndarray):
         "rel_l2_branch": float(np.linalg.norm(d) / max(np.linalg.norm(branch), 1e-300)),
         "max_ref": float(np.max(np.abs(ref))),
     }
-
-
-def device_res_weights(spec: wl.ResSpec, w: dict) -> si.ResBlockWeights:
-    tensors = {k: to_dev(v, spec.dtype) for k, v in w.items()}
-    return si.ResBlockWeights(spec.gn_groups, tensors, gn_eps=spec.gn_eps, temb_dim=spec.temb_dim, c_out=spec.C_out)
 
 
 def run_resblock(spec: wl.ResSpec, x: np.ndarray, w: dict, temb, slice_len=None) -> np.ndarray:

@@ -221,3 +221,29 @@ def test_key_step_search_random_maps_and_errors():
         si.si_key_step_search([[1.0]], 1.5)
     with pytest.raises(si.SiError):
         si.si_key_step_search([[0.2, 0.1], [0.1, 0.2]], 0.5)     # diagonal below the threshold
+
+
+def test_packed_promise_is_refused_for_a_workspace_that_was_never_packed():
+    """SI_FWD_WEIGHTS_PACKED on a workspace that no re-laying-out call of this process used: the host
+    can see that the promise is broken and refuses before anything is enqueued."""
+    x, w, _, out = _descs()
+    st = si.lib().si_block_forward_ex(C.byref(x), C.byref(w), None, C.byref(out), B.SI_AXIS_HW, 4,
+                                      0x7100000000, 1 << 40, B.SI_FWD_WEIGHTS_PACKED, None)
+    assert st == 7
+    st = si.lib().si_block_forward_ex(C.byref(x), C.byref(w), None, C.byref(out), B.SI_AXIS_HW, 4,
+                                      0x7100000000, 1 << 40, 2, None)          # unknown flag bit
+    assert st == 7
+
+
+def _in_flight(x, w, ctx, axis, slice_len):
+    return si.lib().si_windows_in_flight(C.byref(x), C.byref(w), C.byref(ctx) if ctx is not None else None, axis, slice_len)
+
+
+def test_windows_in_flight_follow_the_slice_count():
+    """One window at a time for a few large slices, two from 8 slices on, three from 12 on (Sec. 4.2.2)."""
+    x, w, _, _ = _descs(H=8, W=12)                                   # 96 positions
+    assert _in_flight(x, w, None, B.SI_AXIS_HW, 96) == 1
+    assert _in_flight(x, w, None, B.SI_AXIS_HW, 24) == 1             # 4 slices
+    assert _in_flight(x, w, None, B.SI_AXIS_HW, 12) == 2             # 8 slices
+    assert _in_flight(x, w, None, B.SI_AXIS_HW, 8) == 3              # 12 slices
+    assert _in_flight(x, w, None, B.SI_AXIS_F, 1) == 0               # invalid: temporal block along frames

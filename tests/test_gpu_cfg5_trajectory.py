@@ -79,8 +79,11 @@ def test_cfg5_trajectory_decisions_and_key_steps():
                 assert D[p, i, j] == oracle.rehash_decision_ref(host[i], host[j], gamma), (p, i, j)
                 assert abs(S[p, i, j] - S_ref[i, j]) < 1e-12
                 min_margin = min(min_margin, abs(S_ref[i, j] - float(np.float32(gamma))))
+        # both walks decide on the float32 map and threshold the C ABI receives
         G = si.si_key_step_search(S[p].tolist(), gamma)
-        assert G == oracle.key_step_search_ref(S_ref, float(np.float32(gamma)), K) or min_margin < 1e-6
+        assert G == oracle.key_step_search_ref(S[p].astype(np.float32), np.float32(gamma), K)
+        if min_margin > 1e-6:       # away from the threshold the float64 oracle map gives the same walk
+            assert G == oracle.key_step_search_ref(S_ref, float(np.float32(gamma)), K)
         assert G[0] == 0 and G[-1] == K - 1
         G_all.append(G)
 
