@@ -20,7 +20,8 @@
 namespace si {
 
 struct AttnMfmaArgs {
-  const bf16* q;   // query i of sequence s: row s*Nq + i, head h at columns [64h, 64h+64)
+  const bf16* q;   // query i of sequence s: row s*Nq + i, head h at columns [64h, 64h+64); pre-scaled by
+                   // softmax scale * log2(e), so that q k^T is the exponent in base 2
   int64_t ldq;
   const bf16* k;   // key j of key sequence ks = s / kv_div: row ks*Nk + j
   int64_t ldk;
@@ -28,7 +29,6 @@ struct AttnMfmaArgs {
   bf16* o;         // output rows like q's
   int64_t ldo;
   int Nq, Nk, Nkp, heads, kv_div;
-  float scale_log2;  // softmax scale * log2(e)
   int o_frag;        // 0: o rows of ldo elements; else o is a fragment-order buffer of that many channels per token
 };
 
@@ -54,66 +54,107 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16* __restrict
   }
 }
 
-// One 64-key stage of the online softmax for this wavefront's 32 queries.  MASKED: keys >= Nk exist
-// in the stage (the last, ragged one) and get a score of -inf.
-template <bool MASKED>
-__device__ __forceinline__ void attn_stage(const u32x4_t* slot, int lane, int g, int key0, int Nk, float c, const bf16x8_t (&qop)[4],
-                                           f32x16_t (&oacc)[2], float& m, float& lsum) {
+// Online softmax, per 32-key tile of this wavefront's 32 queries.  The queries arrive pre-scaled by
+// softmax scale * log2(e) (the projection's epilogue does it before its one rounding), so S^T is in
+// base-2 exponent units.  `minit` holds -m (the lane's reference maximum) in all 16 registers and is
+// the accumulator input of the first score MFMA of a tile: the result registers are s - m and go
+// straight into v_exp_f32.  m is a *lazy* maximum: it is raised (and the output rescaled) only when
+// some lane's partial row sum says that an exponent went beyond kLazyTrigger, so the steady state
+// per tile is 16 exponentials, 8 conversions to bf16 pairs and 8 packed dot products for the row
+// sum -- no maximum, no subtraction, no cross-lane traffic.  lsum is the lane's own half of the row
+// sum (16 of a tile's 32 keys); the two halves meet once, after the last tile.
+constexpr float kLazyTrigger = 256.f;  // 2^8: an exponential this large, or 16 of them each above 2^4
+
+__device__ __forceinline__ float dot2_ones(unsigned packed_bf16x2, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, packed_bf16x2), __builtin_bit_cast(bf16x2_t, 0x3f803f80u), acc,
+                                         false);
+}
+
+struct AttnState {
+  f32x16_t oacc[2];  // O^T, two 32-channel blocks
+  f32x16_t minit;    // -m in every register
+  float lsum;
+};
+
+// keys >= Nk of the tile that starts at key0 get a score of -inf
+__device__ __forceinline__ void attn_mask_tile(f32x16_t& sc, int key0, int Nk, int g) {
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    f32x16_t sc;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) sc[e] = 0.f;
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4)
-      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, slot[(4 * u + s4) * kWave + lane]), qop[s4], sc, 0, 0, 0);
-    if (MASKED) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int i = 8 * (e / 4) + 4 * g + (e % 4);
-        const int key = key0 + 32 * u + 16 * (i / 16) + kappa16(i % 16);
-        if (key >= Nk) sc[e] = -INFINITY;
-      }
-    }
-    float mx = sc[0];
-#pragma unroll
-    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    // the running maximum moves in the first tiles and rarely afterwards: rescale only when some
-    // lane's maximum grew (finite from the first tile on, which always holds a real key)
-    if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {
-      const float mnew = fmaxf(m, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m - mnew) * c);
-      lsum *= alpha;
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[b][e] *= alpha;
-      m = mnew;
-    }
-    const float mc = m * c;
-    float pr[16], rs = 0.f;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      pr[e] = __builtin_amdgcn_exp2f(fmaf(sc[e], c, -mc));
-      rs += pr[e];
-    }
-    rs += __shfl_xor(rs, 32, kWave);
-    lsum += rs;
-    bf16x8_t pop[2];
-    pop[0] = to_operand(&pr[0]);
-    pop[1] = to_operand(&pr[8]);
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, slot[(8 + 4 * u + 2 * b + t) * kWave + lane]),
-                                                          pop[t], oacc[b], 0, 0, 0);
+  for (int e = 0; e < 16; ++e) {
+    const int i = 8 * (e / 4) + 4 * g + (e % 4);
+    const int key = key0 + 16 * (i / 16) + kappa16(i % 16);
+    if (key >= Nk) sc[e] = -INFINITY;
   }
 }
 
+__device__ __forceinline__ void attn_exp_pack(const f32x16_t& sc, float delta, u32x4_t (&pk)[2], float& rs) {
+  unsigned w[8];
+#pragma unroll
+  for (int e = 0; e < 16; e += 2) w[e / 2] = pack_bf16x2(__builtin_amdgcn_exp2f(sc[e] - delta), __builtin_amdgcn_exp2f(sc[e + 1] - delta));
+  rs = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) rs = dot2_ones(w[i], rs);
+  pk[0] = u32x4_t{w[0], w[1], w[2], w[3]};
+  pk[1] = u32x4_t{w[4], w[5], w[6], w[7]};
+}
+
+// Probabilities of one tile (scores sc = s - m) as the bf16 column operand pk of O^T += V^T P^T.
+// Rare path: the reference maximum rises by delta -- the output so far and the row sum shrink by
+// 2^-delta, and score tiles that were already taken against the old reference (l0, l1, l2; NULL =
+// none) move by -delta.
+__device__ __forceinline__ void attn_softmax_tile(f32x16_t& sc, u32x4_t (&pk)[2], AttnState& st, f32x16_t* l0, f32x16_t* l1,
+                                                  f32x16_t* l2) {
+  float rs;
+  attn_exp_pack(sc, 0.f, pk, rs);
+  if (__builtin_amdgcn_ballot_w64(rs > kLazyTrigger) != 0) {
+    float mx = sc[0];
+#pragma unroll
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));  // both halves of the row agree on the new reference
+    const float delta = fmaxf(mx, 0.f);
+    const float alpha = __builtin_amdgcn_exp2f(-delta);
+    st.lsum *= alpha;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) st.oacc[b][e] *= alpha;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) st.minit[e] -= delta;
+    attn_exp_pack(sc, delta, pk, rs);
+    f32x16_t* later[3] = {l0, l1, l2};
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+      if (later[i]) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) (*later[i])[e] -= delta;
+      }
+  }
+  st.lsum += rs;
+}
+
+// S^T of the stage's two tiles against minit; kf: the 8 K fragments (tile u: kf[4u .. 4u+3]).  The
+// two chains are interleaved so that no MFMA waits for the one issued just before it.
+__device__ __forceinline__ void attn_scores(const u32x4_t (&kf)[8], const bf16x8_t (&qop)[4], const f32x16_t& minit, f32x16_t (&sc)[2]) {
+  sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[0]), qop[0], minit, 0, 0, 0);
+  sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[4]), qop[0], minit, 0, 0, 0);
+#pragma unroll
+  for (int s4 = 1; s4 < 4; ++s4) {
+    sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[s4]), qop[s4], sc[0], 0, 0, 0);
+    sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[4 + s4]), qop[s4], sc[1], 0, 0, 0);
+  }
+}
+
+// O^T += V^T P^T for tile u; vf: the stage's 8 V^T fragments (tile u, channel block b, k-step t: vf[4u + 2b + t])
+__device__ __forceinline__ void attn_pv(const u32x4_t (&vf)[8], int u, const u32x4_t (&pk)[2], f32x16_t (&oacc)[2]) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+      oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf[4 * u + 2 * b + t]), __builtin_bit_cast(bf16x8_t, pk[t]),
+                                                        oacc[b], 0, 0, 0);
+}
+
 template <int NW>
-__global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attn_mfma_kernel(AttnMfmaArgs a) {
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(AttnMfmaArgs a) {
   constexpr int NS = kAttnStages, FR = 16;  // fragments per stage: 8 of K (2 tiles x 4 k-steps), 8 of V^T (2 tiles x 2 blocks x 2 k-steps)
   constexpr int PER = FR / NW;              // stage loads per lane
   static_assert(NW == 4 || NW == 8, "wavefronts per workgroup");
@@ -177,28 +218,84 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void attn_mfma_kernel(Att
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the query loads; nothing the compiler tracks stays pending in the loop
 
-  f32x16_t oacc[2];
+  AttnState as;
 #pragma unroll
   for (int b = 0; b < 2; ++b)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[b][e] = 0.f;
-  float m = -INFINITY, lsum = 0.f;
-  const float c = a.scale_log2;
+    for (int e = 0; e < 16; ++e) as.oacc[b][e] = 0.f;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) as.minit[e] = 0.f;
+  as.lsum = 0.f;
 
-  for (int st = 0; st < nst; ++st) {
-    // own loads of stage st have landed: at most the batches of the next NS - 2 stages stay in flight
-    {
-      const int younger = nst - 1 - st;
-      if (NS >= 4 && younger >= 2) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(2 * PER));
-      else if (younger >= 1) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(PER));
-      else __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(0));
-    }
-    __syncthreads();  // stage st is visible to all; everybody has left stage st - 1, whose slot is loaded next
+  // own loads of stage st have landed (at most the batches of the next NS - 2 stages stay in flight),
+  // then the barrier: stage st is visible to all and everybody has left stage st - 1, whose slot the
+  // load issued next overwrites
+  auto open_stage = [&](int st) {
+    const int younger = nst - 1 - st;
+    if (NS >= 4 && younger >= 2) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(2 * PER));
+    else if (younger >= 1) __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(PER));
+    else __builtin_amdgcn_s_waitcnt(WeightPipe<4>::wait_imm(0));
+    __syncthreads();
     issue(st + NS - 1);
-    const u32x4_t* slot = ring[st % NS];
-    if (st < nfull) attn_stage<false>(slot, lane, g, 64 * st, a.Nk, c, qop, oacc, m, lsum);
-    else attn_stage<true>(slot, lane, g, 64 * st, a.Nk, c, qop, oacc, m, lsum);
+  };
+
+  // Software pipeline over stages: while the matrix cores form the scores of stage st, the vector
+  // ALUs exponentiate the first tile of stage st - 1; O^T += V^T P^T of that tile then runs under the
+  // exponentials of the second one.  The V^T fragments of a stage are taken out of LDS before the
+  // next barrier, because that barrier frees their slot.
+  u32x4_t kf[8], vf[8];
+  f32x16_t scp[2], scn[2];  // scores of the previous / the new stage
+  open_stage(0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) kf[i] = ring[0][i * kWave + lane];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) vf[i] = ring[0][(8 + i) * kWave + lane];
+  attn_scores(kf, qop, as.minit, scp);
+  {  // the first tile sets the reference maximum (key 0 always exists, so it is finite)
+    if (nfull == 0) {
+      attn_mask_tile(scp[0], 0, a.Nk, g);
+      attn_mask_tile(scp[1], 32, a.Nk, g);
+    }
+    float mx = scp[0][0];
+#pragma unroll
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, scp[0][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      as.minit[e] = -mx;
+      scp[0][e] -= mx;
+      scp[1][e] -= mx;
+    }
   }
+  for (int st = 1; st < nst; ++st) {
+    open_stage(st);
+    const u32x4_t* slot = ring[st % NS];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) kf[i] = slot[i * kWave + lane];
+    u32x4_t pk[2];
+    attn_scores(kf, qop, as.minit, scn);
+    attn_softmax_tile(scp[0], pk, as, &scp[1], &scn[0], &scn[1]);
+    attn_pv(vf, 0, pk, as.oacc);
+    attn_softmax_tile(scp[1], pk, as, &scn[0], &scn[1], nullptr);
+    attn_pv(vf, 1, pk, as.oacc);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vf[i] = slot[(8 + i) * kWave + lane];
+    scp[0] = scn[0];
+    scp[1] = scn[1];
+  }
+  {  // drain: the last stage's tiles (the only ones that can hold keys past the end)
+    if (nfull < nst && nst > 1) {
+      attn_mask_tile(scp[0], 64 * (nst - 1), a.Nk, g);
+      attn_mask_tile(scp[1], 64 * (nst - 1) + 32, a.Nk, g);
+    }
+    u32x4_t pk[2];
+    attn_softmax_tile(scp[0], pk, as, &scp[1], nullptr, nullptr);
+    attn_pv(vf, 0, pk, as.oacc);
+    attn_softmax_tile(scp[1], pk, as, nullptr, nullptr, nullptr);
+    attn_pv(vf, 1, pk, as.oacc);
+  }
+  const float lsum = as.lsum + __shfl_xor(as.lsum, 32, kWave);  // the two halves of the row
+  f32x16_t(&oacc)[2] = as.oacc;
 
   // ---- O^T / l: register 4q + j of block b is head channel 32b + 8q + 4g + j of this lane's query
   if (qvalid) {

@@ -27,28 +27,30 @@ struct EpiStore {
   T* out;
   int64_t ld;
   const T* bias;
+  float scale = 1.f;  // applied to acc + bias before the one rounding (the matrix-core attention's query scale)
   __device__ __forceinline__ void operator()(int64_t m, int n0, const float (&v)[4]) const {
     T* p = out + m * ld + n0;
     if constexpr (sizeof(T) == 2) {
       uint2 pk;
-      pk.x = (unsigned)float_to_bf16_bits(v[0] + param_or(bias, n0 + 0, 0.f)) |
-             ((unsigned)float_to_bf16_bits(v[1] + param_or(bias, n0 + 1, 0.f)) << 16);
-      pk.y = (unsigned)float_to_bf16_bits(v[2] + param_or(bias, n0 + 2, 0.f)) |
-             ((unsigned)float_to_bf16_bits(v[3] + param_or(bias, n0 + 3, 0.f)) << 16);
+      pk.x = (unsigned)float_to_bf16_bits((v[0] + param_or(bias, n0 + 0, 0.f)) * scale) |
+             ((unsigned)float_to_bf16_bits((v[1] + param_or(bias, n0 + 1, 0.f)) * scale) << 16);
+      pk.y = (unsigned)float_to_bf16_bits((v[2] + param_or(bias, n0 + 2, 0.f)) * scale) |
+             ((unsigned)float_to_bf16_bits((v[3] + param_or(bias, n0 + 3, 0.f)) * scale) << 16);
       *reinterpret_cast<uint2*>(p) = pk;
     } else {
       float4 o;
-      o.x = v[0] + param_or(bias, n0 + 0, 0.f);
-      o.y = v[1] + param_or(bias, n0 + 1, 0.f);
-      o.z = v[2] + param_or(bias, n0 + 2, 0.f);
-      o.w = v[3] + param_or(bias, n0 + 3, 0.f);
+      o.x = (v[0] + param_or(bias, n0 + 0, 0.f)) * scale;
+      o.y = (v[1] + param_or(bias, n0 + 1, 0.f)) * scale;
+      o.z = (v[2] + param_or(bias, n0 + 2, 0.f)) * scale;
+      o.w = (v[3] + param_or(bias, n0 + 3, 0.f)) * scale;
       *reinterpret_cast<float4*>(p) = o;
     }
   }
 };
 
 // q/k/v projection for the matrix-core attention kernel: columns [0, 2D) (queries, keys) are stored
-// row-major as EpiStore does; the value columns go straight to the transposed copy the kernel reads,
+// row-major as EpiStore does, the queries multiplied by qscale (softmax scale * log2(e)) in fp32 before
+// their one rounding; the value columns go straight to the transposed copy the kernel reads,
 // vt[(s*D + c)*Pw + key] for token m = s*Pw + key (keys contiguous), and are not stored row-major.
 struct EpiStoreQKVt {
   static constexpr bool kRows8 = false;
@@ -56,11 +58,13 @@ struct EpiStoreQKVt {
   int64_t ld;
   bf16* vt;
   int D, Pw;
+  float qscale;
   __device__ __forceinline__ void operator()(int64_t m, int n0, const float (&v)[4]) const {
     if (n0 < 2 * D) {
+      const float sc = n0 < D ? qscale : 1.f;
       uint2 pk;
-      pk.x = (unsigned)float_to_bf16_bits(v[0]) | ((unsigned)float_to_bf16_bits(v[1]) << 16);
-      pk.y = (unsigned)float_to_bf16_bits(v[2]) | ((unsigned)float_to_bf16_bits(v[3]) << 16);
+      pk.x = (unsigned)float_to_bf16_bits(v[0] * sc) | ((unsigned)float_to_bf16_bits(v[1] * sc) << 16);
+      pk.y = (unsigned)float_to_bf16_bits(v[2] * sc) | ((unsigned)float_to_bf16_bits(v[3] * sc) << 16);
       *reinterpret_cast<uint2*>(out + m * ld + n0) = pk;
     } else {
       const int mi = (int)m, s = mi / Pw, key = mi - s * Pw;

@@ -369,13 +369,12 @@ static si_status launch_attention(const char* stage, const AttnArgs& a, hipStrea
 // Matrix-core attention (bf16, head dimension 64): v is first copied with keys contiguous.
 static si_status launch_attention_mfma(const char* stage, const bf16* q, int64_t ldq, const bf16* k, int64_t ldk,
                                        const bf16* vt, bf16* o, int64_t ldo, int S, int Nq, int Nk, int Nkp, int heads,
-                                       int kv_div, float scale, hipStream_t st, int o_frag = 0) {
+                                       int kv_div, hipStream_t st, int o_frag = 0) {
   if (S <= 0 || Nq <= 0) return SI_OK;
   StageScope scope(stage, st);
   AttnMfmaArgs a;
   a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.o = o; a.ldo = ldo;
   a.Nq = Nq; a.Nk = Nk; a.Nkp = Nkp; a.heads = heads; a.kv_div = kv_div;
-  a.scale_log2 = scale * 1.4426950408889634f;
   a.o_frag = o_frag;
   // 8 wavefronts share the key / value stages when that still leaves several workgroups for every CU
   const int64_t wg8 = (int64_t)((Nq + 255) / 256) * heads * S;
@@ -567,6 +566,9 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
 
   // ---- Feature Slicer windows; one operator group per window (Eq. 1)
   const float scale = 1.0f / sqrtf((float)p.d);
+  // the matrix-core attention kernel exponentiates in base 2 and takes its queries pre-scaled: the
+  // projections that feed it fold softmax scale * log2(e) into q before q's one rounding
+  const float qscale2 = scale * 1.4426950408889634f;
   hipStream_t const st_main = st;
   T* const a_base = a;
   float* const h_base = h;
@@ -639,10 +641,10 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       if constexpr (sizeof(T) == 2) {
         if (p.attn_mfma) {  // spatial: sequence (b, f) = rows (b*Fw + f)*Pw + i; the projection writes V transposed
           bf16* vt = reinterpret_cast<bf16*>(vt_lane);
-          EpiStoreQKVt epi{big, (int64_t)3 * D, vt, D, win.Pw};
+          EpiStoreQKVt epi{big, (int64_t)3 * D, vt, D, win.Pw, qscale2};
           SI_TRY((launch_gemm_sel<T, false>("qkv", ring, a, (int64_t)D, wqkv, M, Mx, 3 * D, D, epi, st)));
           SI_TRY(launch_attention_mfma("self_attn", big, (int64_t)3 * D, big + D, (int64_t)3 * D, vt, a, (int64_t)D, p.B * win.Fw,
-                                       win.Pw, win.Pw, win.Pw, p.heads, 1, scale, st, self_frag ? D : 0));
+                                       win.Pw, win.Pw, win.Pw, p.heads, 1, st, self_frag ? D : 0));
           self_done = true;
         }
       }
@@ -672,7 +674,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       if (spatial) {
         SI_TRY(launch_layer_norm<T>("ln2", h, a, M, D, w->ln2_g, w->ln2_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st, ring));
         {
-          EpiStore<T> epi{big, (int64_t)D, nullptr};
+          EpiStore<T> epi{big, (int64_t)D, nullptr, p.attn_mfma ? qscale2 : 1.f};
           SI_TRY((launch_gemm_sel<T, false>("q2", ring, a, (int64_t)D, wq2, M, Mx, D, D, epi, st)));
         }
         bool cross_done = false;
@@ -680,7 +682,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
           if (p.attn_mfma) {  // keys / values: the context rows of the batch entry, shared by its frames
             SI_TRY(launch_attention_mfma("cross_attn", big, (int64_t)D, ctxkv, (int64_t)2 * D,
                                          reinterpret_cast<const bf16*>(ws + p.off_ctxvt), a, (int64_t)D, p.B * win.Fw, win.Pw,
-                                         p.Mc, p.Mcp, p.heads, win.Fw, scale, st, cross_frag ? D : 0));
+                                         p.Mc, p.Mcp, p.heads, win.Fw, st, cross_frag ? D : 0));
             cross_done = true;
           }
         }
