@@ -202,6 +202,25 @@ si_status si_rehash_check_sync(const void* feat_t, const void* feat_prev, int64_
                                float thresh, void* scratch, void* result_dev, void* stream,
                                double* cos_host, int32_t* decision_host);
 
+/* si_rehash_check for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * partial sums live in a device array inside the library
+ * (SI_REHASH_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead
+ * of a caller-provided scratch buffer; the call allocates nothing.  Same
+ * arguments, results and error codes as si_rehash_check otherwise; n larger than
+ * SI_REHASH_STATIC_MAX_N -> SI_ERR_SHAPE (nothing enqueued).  All calls on one
+ * GPU share the array: calls that overlap in time on one GPU (two streams, two
+ * threads) race and give wrong results; calls on one stream, or otherwise
+ * ordered, are safe, and nothing has to be cleared between them.
+ * si_init_device resolves the array's address on the current device ahead of
+ * time (optional; otherwise the first call on a device does it), e.g. before a
+ * graph capture begins.  Returns SI_OK or SI_ERR_HIP. */
+#define SI_REHASH_STATIC_SCRATCH_BYTES 49152
+#define SI_REHASH_STATIC_MAX_N (1LL << 33)
+si_status si_init_device(void);
+si_status si_rehash_check_static(const void* feat_t, const void* feat_prev, int64_t n, int32_t dtype,
+                                 float thresh, double* cos_dev, int32_t* decision_dev, void* stream);
+
 /* Anchor of the one-pass Step Rehash walk around one block: input and output
  * of the last step at which the block was computed.  x_key and y_key are
  * caller-owned device buffers of the feature's size and dtype, 16-byte

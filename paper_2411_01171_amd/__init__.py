@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     si_workspace_bytes, si_live_activation_bytes, si_windows_in_flight, si_block_forward, si_block_forward_rehash,
     si_block_forward_ex, SI_FWD_WEIGHTS_PACKED,
     si_rehash_scratch_bytes, si_rehash_check, si_rehash_check_sync, si_key_step_search,
+    si_init_device, si_rehash_check_static,
     si_stage_timing_enable, si_stage_timing_read, si_status_str, si_abi_version,
 )

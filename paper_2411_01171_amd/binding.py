@@ -104,6 +104,10 @@ def lib() -> C.CDLL:
     L.si_rehash_check_sync.restype = i32
     L.si_rehash_check_sync.argtypes = [vp, vp, i64, i32, C.c_float, vp, vp, vp,
                                        C.POINTER(C.c_double), C.POINTER(i32)]
+    L.si_init_device.restype = i32
+    L.si_init_device.argtypes = []
+    L.si_rehash_check_static.restype = i32
+    L.si_rehash_check_static.argtypes = [vp, vp, i64, i32, C.c_float, vp, vp, vp]
     L.si_key_step_search.restype = i32
     L.si_key_step_search.argtypes = [C.POINTER(C.c_float), i32, C.c_float, C.POINTER(i32)]
     L.si_stage_timing_enable.restype = None
@@ -331,6 +335,25 @@ def si_rehash_check(feat_t, feat_prev, thresh: float, cos_dev, decision_dev, scr
                                scratch.data_ptr(), _stream_ptr(stream))
     if st != 0:
         raise SiError(st, "si_rehash_check")
+
+
+def si_init_device() -> None:
+    st = lib().si_init_device()
+    if st != 0:
+        raise SiError(st, "si_init_device")
+
+
+def si_rehash_check_static(feat_t, feat_prev, thresh: float, cos_dev, decision_dev, stream=None) -> None:
+    """si_rehash_check without a scratch argument: the partial sums live in the library's device array."""
+    if feat_t.numel() != feat_prev.numel() or feat_t.dtype != feat_prev.dtype:
+        raise ValueError("features must have the same size and dtype")
+    if not (feat_t.is_contiguous() and feat_prev.is_contiguous()):
+        raise ValueError("features must be contiguous")
+    st = lib().si_rehash_check_static(feat_t.data_ptr(), feat_prev.data_ptr(), feat_t.numel(), _dtype_code(feat_t),
+                                      thresh, None if cos_dev is None else cos_dev.data_ptr(), decision_dev.data_ptr(),
+                                      _stream_ptr(stream))
+    if st != 0:
+        raise SiError(st, "si_rehash_check_static")
 
 
 def si_rehash_check_sync(feat_t, feat_prev, thresh: float, scratch, result_dev, stream=None) -> Tuple[float, int]:

@@ -1046,6 +1046,8 @@ si_status si_rehash_check_sync(const void* feat_t, const void* feat_prev, int64_
   return SI_OK;
 }
 
+#include "si_static_scratch.h"
+
 int32_t si_key_step_search(const float* S, int32_t K, float gamma, int32_t* G_out) {
   if (!S || !G_out || K < 1 || std::isnan(gamma) || gamma > 1.0f) return -1;
   // Algorithm 1 as a scan per anchor: a key step stays the anchor for the run of later steps that are
