@@ -63,12 +63,11 @@ struct StageScope {
 
 // ----------------------------------------------------------------------------- plan
 
+constexpr int kMaxLanes = 3;  // windows in flight at most (measured: a fourth window in flight gains nothing at 25 slices
+                              // and 7 % at 16, where it would take the live bytes past a quarter of the unsliced run's)
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-#ifndef SI_LANES3_MIN
-#define SI_LANES3_MIN 12
-#endif
 
 // Column tiles of the ring kernel used as a GEMM on windows of up to Mmax tokens (`lanes` of them in
 // flight) x N columns over K: the widest tile (5, 4, 2 or 1 blocks of 32 columns) that pads N by at
@@ -214,11 +213,13 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   }
   p->off_vt = take(p->attn_mfma ? (size_t)p->Mmax * Dz * es : 0);  // values of the window, keys contiguous
   // Cross-slice pipelining (Sec. 4.2.2): with many small slices the kernels of one slice leave CUs
-  // idle (under-filled grids, partial last rounds), so two slices (from 8 slices on) or three (from
-  // 12 on) run at a time, each on a stream and with intermediates of its own: their buffers together
-  // still stay within a quarter of the unsliced footprint.
+  // idle (under-filled grids, partial last rounds), so several windows run at a time, each on a
+  // stream and with intermediates of its own: as many as keep the window intermediates in flight
+  // within a quarter of what the unsliced run needs for them (one per four slices, at most
+  // kMaxLanes).  The slice-independent items (statistics, frame table, context keys / values) come
+  // on top in either case.
   const int64_t n_slices = (p->extent + p->slice_len - 1) / p->slice_len;
-  p->lanes = n_slices >= SI_LANES3_MIN ? 3 : n_slices >= 8 ? 2 : 1;
+  p->lanes = (int)(n_slices / 4 < 1 ? 1 : n_slices / 4 > kMaxLanes ? kMaxLanes : n_slices / 4);
   p->lane_stride = off - p->off_a;
   for (int l = 1; l < p->lanes; ++l) take(p->lane_stride);
   const size_t act_end = off;
@@ -450,26 +451,40 @@ static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, ch
   return SI_OK;
 }
 
-// Auxiliary stream and fork / join events for two slices in flight, one set per device, created on
+// Auxiliary streams and fork / join events for windows in flight, one set per device, created on
 // first use (default priority) and kept for the life of the process.  Calls that overlap on one
 // device share them and must not run concurrently from several host threads.
 struct AuxStream {
-  hipStream_t stream = nullptr, stream2 = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr, join2 = nullptr;
+  hipStream_t s[kMaxLanes - 1] = {};   // lane l >= 1 runs on s[l - 1]; lane 0 on the caller's stream
+  hipEvent_t fork = nullptr, join[kMaxLanes - 1] = {};
 };
 static si_status aux_stream(AuxStream** out) {
   static AuxStream per_device[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SI_ERR_HIP;
   AuxStream& a = per_device[dev];
-  if (!a.stream) {
-    if (hipStreamCreateWithFlags(&a.stream, hipStreamNonBlocking) != hipSuccess) return SI_ERR_HIP;
+  if (!a.fork) {
+    for (int l = 0; l < kMaxLanes - 1; ++l) {
+      if (hipStreamCreateWithFlags(&a.s[l], hipStreamNonBlocking) != hipSuccess) return SI_ERR_HIP;
+      if (hipEventCreateWithFlags(&a.join[l], hipEventDisableTiming) != hipSuccess) return SI_ERR_HIP;
+    }
     if (hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess) return SI_ERR_HIP;
-    if (hipEventCreateWithFlags(&a.join, hipEventDisableTiming) != hipSuccess) return SI_ERR_HIP;
-    if (hipStreamCreateWithFlags(&a.stream2, hipStreamNonBlocking) != hipSuccess) return SI_ERR_HIP;
-    if (hipEventCreateWithFlags(&a.join2, hipEventDisableTiming) != hipSuccess) return SI_ERR_HIP;
   }
   *out = &a;
+  return SI_OK;
+}
+// fork: the other lanes start after what the caller's stream has enqueued so far
+static si_status lanes_fork(AuxStream* aux, int lanes, hipStream_t st_main) {
+  if (hipEventRecord(aux->fork, st_main) != hipSuccess) return SI_ERR_HIP;
+  for (int l = 1; l < lanes; ++l)
+    if (hipStreamWaitEvent(aux->s[l - 1], aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
+  return SI_OK;
+}
+// join: the caller's stream continues after all lanes
+static si_status lanes_join(AuxStream* aux, int lanes, hipStream_t st_main) {
+  for (int l = 1; l < lanes; ++l)
+    if (hipEventRecord(aux->join[l - 1], aux->s[l - 1]) != hipSuccess || hipStreamWaitEvent(st_main, aux->join[l - 1], 0) != hipSuccess)
+      return SI_ERR_HIP;
   return SI_OK;
 }
 
@@ -578,16 +593,14 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   const int lanes = g_timing ? 1 : p.lanes;
   if (lanes >= 2) {  // fork: the other lanes start after the once-per-call work above
     SI_TRY(aux_stream(&aux));
-    if (hipEventRecord(aux->fork, st_main) != hipSuccess || hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess)
-      return SI_ERR_HIP;
-    if (lanes == 3 && hipStreamWaitEvent(aux->stream2, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
+    SI_TRY(lanes_fork(aux, lanes, st_main));
   }
   for (int64_t s0 = 0; s0 < p.extent; s0 += p.slice_len) {
     const int64_t s1 = s0 + p.slice_len < p.extent ? s0 + p.slice_len : p.extent;
     // this slice's lane: stream and intermediates (the names below shadow the first lane's)
     const int lane_id = (int)((s0 / p.slice_len) % lanes);
     const size_t lane_off = (size_t)lane_id * p.lane_stride;
-    hipStream_t st = lane_id == 0 ? st_main : lane_id == 1 ? aux->stream : aux->stream2;
+    hipStream_t st = lane_id == 0 ? st_main : aux->s[lane_id - 1];
     T* a = reinterpret_cast<T*>(reinterpret_cast<char*>(a_base) + lane_off);
     float* h = reinterpret_cast<float*>(reinterpret_cast<char*>(h_base) + lane_off);
     T* big = reinterpret_cast<T*>(reinterpret_cast<char*>(big_base) + lane_off);
@@ -745,13 +758,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       }
     }
   }
-  if (lanes >= 2) {  // join: the caller's stream continues after all lanes
-    if (hipEventRecord(aux->join, aux->stream) != hipSuccess || hipStreamWaitEvent(st_main, aux->join, 0) != hipSuccess)
-      return SI_ERR_HIP;
-    if (lanes == 3 &&
-        (hipEventRecord(aux->join2, aux->stream2) != hipSuccess || hipStreamWaitEvent(st_main, aux->join2, 0) != hipSuccess))
-      return SI_ERR_HIP;
-  }
+  if (lanes >= 2) SI_TRY(lanes_join(aux, lanes, st_main));
   return SI_OK;
 }
 

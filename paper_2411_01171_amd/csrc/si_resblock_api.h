@@ -189,16 +189,14 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
   const int lanes = g_timing ? 1 : p.lanes;  // per-stage timing: one window at a time
   if (lanes >= 2) {
     SI_TRY(aux_stream(&aux));
-    if (hipEventRecord(aux->fork, st0) != hipSuccess) return SI_ERR_HIP;
-    if (hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
-    if (lanes == 3 && hipStreamWaitEvent(aux->stream2, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
+    SI_TRY(lanes_fork(aux, lanes, st0));
   }
 
   // ---- the frame windows (Sec. 4.1): each goes through the whole group and lands in its window of out
   int widx = 0;
   for (int64_t f0 = 0; f0 < p.F; f0 += p.slice_len, ++widx) {
     const int lane_id = widx % lanes;
-    hipStream_t st = lane_id == 0 ? st0 : lane_id == 1 ? aux->stream : aux->stream2;
+    hipStream_t st = lane_id == 0 ? st0 : aux->s[lane_id - 1];
     char* lane_ws = ws + (size_t)lane_id * p.lane_stride;
     _Float16* a = reinterpret_cast<_Float16*>(lane_ws + p.off_a);
     _Float16* h = reinterpret_cast<_Float16*>(lane_ws + p.off_h);
@@ -271,14 +269,7 @@ static si_status run_resblock(const ResPlan& p, const si_tensor5* x, const si_re
       SI_TRY(launch_conv3x3<true>("conv2", frag_h ? h : a, w2, M, Co, p.TN, p.ncol, p.H, p.W, p.H, p.W, kConvSame, epi, st));
     }
   }
-  if (lanes >= 2) {
-    if (hipEventRecord(aux->join, aux->stream) != hipSuccess) return SI_ERR_HIP;
-    if (hipStreamWaitEvent(st0, aux->join, 0) != hipSuccess) return SI_ERR_HIP;
-    if (lanes == 3) {
-      if (hipEventRecord(aux->join2, aux->stream2) != hipSuccess) return SI_ERR_HIP;
-      if (hipStreamWaitEvent(st0, aux->join2, 0) != hipSuccess) return SI_ERR_HIP;
-    }
-  }
+  if (lanes >= 2) SI_TRY(lanes_join(aux, lanes, st0));
   return SI_OK;
 }
 
@@ -346,13 +337,12 @@ static si_status run_resample(const ResamplePlan& p, const si_tensor5* x, const 
   const int lanes = g_timing ? 1 : p.lanes;
   if (lanes == 2) {
     SI_TRY(aux_stream(&aux));
-    if (hipEventRecord(aux->fork, st0) != hipSuccess) return SI_ERR_HIP;
-    if (hipStreamWaitEvent(aux->stream, aux->fork, 0) != hipSuccess) return SI_ERR_HIP;
+    SI_TRY(lanes_fork(aux, lanes, st0));
   }
   int widx = 0;
   for (int64_t f0 = 0; f0 < p.F; f0 += p.slice_len, ++widx) {
     const int lane_id = lanes == 2 ? widx & 1 : 0;
-    hipStream_t st = lane_id ? aux->stream : st0;
+    hipStream_t st = lane_id ? aux->s[0] : st0;
     unsigned short* a = reinterpret_cast<unsigned short*>(ws + p.off_a + (size_t)lane_id * p.lane_stride);
     const int Fw = (int)((f0 + p.slice_len <= p.F) ? p.slice_len : p.F - f0);
     Window win_in{p.B, C, p.F, p.Pi, (int)f0, Fw, 0, (int)p.Pi, 1};
@@ -367,10 +357,7 @@ static si_status run_resample(const ResamplePlan& p, const si_tensor5* x, const 
     SI_TRY(launch_conv3x3<false>(p.mode == kConvStride2 ? "conv_down" : "conv_up", a, wf, (int64_t)p.B * Fw * p.Po, C, p.TN,
                                  p.ncol, p.Ho, p.Wo, p.Hi, p.Wi, p.mode, epi, st));
   }
-  if (lanes == 2) {
-    if (hipEventRecord(aux->join, aux->stream) != hipSuccess) return SI_ERR_HIP;
-    if (hipStreamWaitEvent(st0, aux->join, 0) != hipSuccess) return SI_ERR_HIP;
-  }
+  if (lanes == 2) SI_TRY(lanes_join(aux, lanes, st0));
   return SI_OK;
 }
 
