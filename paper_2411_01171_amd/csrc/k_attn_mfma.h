@@ -177,34 +177,61 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   const unsigned vvoff = (unsigned)(((int64_t)r * a.Nkp + 8 * g) * 2);
   const char* kb = reinterpret_cast<const char*>(a.k + (int64_t)ks * a.Nk * a.ldk + h * 64);
   const char* vb = reinterpret_cast<const char*>(a.vt + ((int64_t)ks * a.heads * 64 + h * 64) * a.Nkp);
-  auto issue = [&](int st) {
-    if (st < nst) {
-      const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(ring[st % NS]);
+  // Full stages are issued in order, so every fragment's source is a running scalar pointer that
+  // advances by a fixed stride per stage (64 key rows of K; 64 keys = 128 bytes of a V^T row), and
+  // the ring slot is a running scalar too: a stage's loads cost a few scalar additions.
+  const int64_t kstride = (int64_t)64 * a.ldk * 2;
+  const char* kcur[PER / 2];
+  const char* vcur[PER / 2];
+  unsigned loff[PER];
 #pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        const int id = wave_s + NW * i;  // scalar; K for i < PER / 2
-        const unsigned l = dst + (unsigned)(id * kWave * 16);
-        if (st < nfull) {
-          const char* sb = i < PER / 2
-                               ? kb + ((int64_t)(64 * st + 32 * (id / 4)) * a.ldk + 16 * (id % 4)) * 2
-                               : vb + ((int64_t)(32 * (((id - 8) / 2) % 2)) * a.Nkp + 64 * st + 32 * ((id - 8) / 4) + 16 * (id % 2)) * 2;
-          // assembly for the same reason as in WeightPipe::issue: completion is awaited explicitly
-          asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(i < PER / 2 ? kvoff : vvoff), "s"(sb), "s"(l) : "memory");
-        } else {
-          const bf16* src;
-          if (i < PER / 2) {
-            int key = 64 * st + 32 * (id / 4) + kap;
-            key = key < a.Nk ? key : a.Nk - 1;
-            src = reinterpret_cast<const bf16*>(kb) + (int64_t)key * a.ldk + 16 * (id % 4) + 8 * g;
-          } else {
-            int k0 = 64 * st + 32 * ((id - 8) / 4) + 16 * (id % 2) + 8 * g;  // groups of 8 keys past the row's end hold masked keys only
-            k0 = k0 < a.Nkp - 8 ? k0 : a.Nkp - 8;
-            src = reinterpret_cast<const bf16*>(vb) + (int64_t)(32 * (((id - 8) / 2) % 2) + r) * a.Nkp + k0;
-          }
-          asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
-        }
-      }
+  for (int i = 0; i < PER / 2; ++i) {
+    const int idk = wave_s + NW * i, idv = wave_s + NW * (i + PER / 2), j = idv - 8;
+    kcur[i] = kb + ((int64_t)(32 * (idk / 4)) * a.ldk + 16 * (idk % 4)) * 2;
+    vcur[i] = vb + ((int64_t)(32 * ((j / 2) % 2)) * a.Nkp + 32 * (j / 4) + 16 * (idv % 2)) * 2;
+    loff[i] = (unsigned)(idk * kWave * 16);
+    loff[PER / 2 + i] = (unsigned)(idv * kWave * 16);
+  }
+  const unsigned ring_lds = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(&ring[0][0]);
+  constexpr unsigned kSlotBytes = FR * kWave * 16;
+  unsigned islot = ring_lds;  // LDS address of the slot the next issued stage lands in
+  auto next_slot = [&]() { islot = islot + kSlotBytes == ring_lds + NS * kSlotBytes ? ring_lds : islot + kSlotBytes; };
+  auto issue_full = [&]() {
+#pragma unroll
+    for (int i = 0; i < PER / 2; ++i) {
+      // assembly for the same reason as in WeightPipe::issue: completion is awaited explicitly
+      asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(kvoff), "s"(kcur[i]), "s"(islot + loff[i]) : "memory");
+      kcur[i] += kstride;
     }
+#pragma unroll
+    for (int i = 0; i < PER / 2; ++i) {
+      asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vvoff), "s"(vcur[i]), "s"(islot + loff[PER / 2 + i]) : "memory");
+      vcur[i] += 128;
+    }
+    next_slot();
+  };
+  // the ragged last stage: per-lane clamped addresses
+  auto issue_ragged = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int id = wave_s + NW * i;
+      const bf16* src;
+      if (i < PER / 2) {
+        int key = 64 * st + 32 * (id / 4) + kap;
+        key = key < a.Nk ? key : a.Nk - 1;
+        src = reinterpret_cast<const bf16*>(kb) + (int64_t)key * a.ldk + 16 * (id % 4) + 8 * g;
+      } else {
+        int k0 = 64 * st + 32 * ((id - 8) / 4) + 16 * (id % 2) + 8 * g;  // groups of 8 keys past the row's end hold masked keys only
+        k0 = k0 < a.Nkp - 8 ? k0 : a.Nkp - 8;
+        src = reinterpret_cast<const bf16*>(vb) + (int64_t)(32 * (((id - 8) / 2) % 2) + r) * a.Nkp + k0;
+      }
+      asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(islot + loff[i]) : "memory");
+    }
+    next_slot();
+  };
+  auto issue = [&](int st) {
+    if (st < nfull) issue_full();
+    else if (st < nst) issue_ragged(st);
   };
 #pragma unroll
   for (int st = 0; st < NS - 1; ++st) issue(st);
@@ -244,32 +271,35 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   // exponentials of the second one.  The V^T fragments of a stage are taken out of LDS before the
   // next barrier, because that barrier frees their slot.
   u32x4_t kf[8], vf[8];
-  f32x16_t scp[2], scn[2];  // scores of the previous / the new stage
+  f32x16_t scA[2], scB[2];  // scores of the previous / the new stage, roles alternating
   open_stage(0);
 #pragma unroll
   for (int i = 0; i < 8; ++i) kf[i] = ring[0][i * kWave + lane];
 #pragma unroll
   for (int i = 0; i < 8; ++i) vf[i] = ring[0][(8 + i) * kWave + lane];
-  attn_scores(kf, qop, as.minit, scp);
+  attn_scores(kf, qop, as.minit, scA);
   {  // the first tile sets the reference maximum (key 0 always exists, so it is finite)
     if (nfull == 0) {
-      attn_mask_tile(scp[0], 0, a.Nk, g);
-      attn_mask_tile(scp[1], 32, a.Nk, g);
+      attn_mask_tile(scA[0], 0, a.Nk, g);
+      attn_mask_tile(scA[1], 32, a.Nk, g);
     }
-    float mx = scp[0][0];
+    float mx = scA[0][0];
 #pragma unroll
-    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, scp[0][e]);
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, scA[0][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       as.minit[e] = -mx;
-      scp[0][e] -= mx;
-      scp[1][e] -= mx;
+      scA[0][e] -= mx;
+      scA[1][e] -= mx;
     }
   }
-  for (int st = 1; st < nst; ++st) {
+  const u32x4_t* slot = ring[0];  // slot of the stage whose scores are being formed
+  auto next_ring = [&]() { slot = slot + FR * kWave == &ring[0][0] + NS * FR * kWave ? &ring[0][0] : slot + FR * kWave; };
+  // one stage: scores of stage st into scn while scp (stage st - 1) is exponentiated and multiplied into O^T
+  auto stage_body = [&](int st, f32x16_t(&scp)[2], f32x16_t(&scn)[2]) {
     open_stage(st);
-    const u32x4_t* slot = ring[st % NS];
+    next_ring();
 #pragma unroll
     for (int i = 0; i < 8; ++i) kf[i] = slot[i * kWave + lane];
     u32x4_t pk[2];
@@ -280,10 +310,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
     attn_pv(vf, 1, pk, as.oacc);
 #pragma unroll
     for (int i = 0; i < 8; ++i) vf[i] = slot[(8 + i) * kWave + lane];
-    scp[0] = scn[0];
-    scp[1] = scn[1];
-  }
-  {  // drain: the last stage's tiles (the only ones that can hold keys past the end)
+  };
+  // drain: the last stage's tiles (the only ones that can hold keys past the end)
+  auto drain = [&](f32x16_t(&scp)[2]) {
     if (nfull < nst && nst > 1) {
       attn_mask_tile(scp[0], 64 * (nst - 1), a.Nk, g);
       attn_mask_tile(scp[1], 64 * (nst - 1) + 32, a.Nk, g);
@@ -293,6 +322,17 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
     attn_pv(vf, 0, pk, as.oacc);
     attn_softmax_tile(scp[1], pk, as, nullptr, nullptr, nullptr);
     attn_pv(vf, 1, pk, as.oacc);
+  };
+  int st = 1;
+  for (; st + 1 < nst; st += 2) {
+    stage_body(st, scA, scB);
+    stage_body(st + 1, scB, scA);
+  }
+  if (st < nst) {
+    stage_body(st, scA, scB);
+    drain(scB);
+  } else {
+    drain(scA);
   }
   const float lsum = as.lsum + __shfl_xor(as.lsum, 32, kWave);  // the two halves of the row
   f32x16_t(&oacc)[2] = as.oacc;
