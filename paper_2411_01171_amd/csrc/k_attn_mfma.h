@@ -30,6 +30,7 @@ struct AttnMfmaArgs {
   int64_t ldo;
   int Nq, Nk, Nkp, heads, kv_div;
   int o_frag;        // 0: o rows of ldo elements; else o is a fragment-order buffer of that many channels per token
+  int nqt, ntiles;   // query tiles per (sequence, head) pair; nqt * heads * sequences (the grid is 8 * ceil(ntiles / 8))
 };
 
 constexpr int kAttnStages = 3;  // 48 KiB of LDS: three 4-wavefront workgroups per CU
@@ -162,8 +163,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int r = lane % 32, g = lane / 32;
-  const int h = blockIdx.y, s = blockIdx.z, ks = s / a.kv_div;
-  const int qi = (blockIdx.x * NW + wave) * 32 + r;
+  // XCD-aware order: workgroups go to the 8 XCDs round-robin, and every XCD has an L2 of its own.
+  // The work list (query tiles of one (sequence, head) pair after the other) is cut into 8
+  // contiguous chunks, one per XCD, so that the keys and values of a pair are fetched into one L2
+  // (two for a pair that straddles a chunk boundary) instead of into all eight.
+  const int chunk = (a.ntiles + 7) / 8;
+  const int work = (int)(blockIdx.x % 8) * chunk + (int)(blockIdx.x / 8);
+  if (work >= a.ntiles) return;
+  const int qtile = work % a.nqt, pair = work / a.nqt;
+  const int h = pair % a.heads, s = pair / a.heads, ks = s / a.kv_div;
+  const int qi = (qtile * NW + wave) * 32 + r;
   const bool qvalid = qi < a.Nq;
   const int nst = (a.Nk + 63) / 64;
   const int nfull = a.Nk / 64;  // stages without missing keys (Nkp >= Nk: their V^T groups are in-row too)

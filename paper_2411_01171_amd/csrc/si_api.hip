@@ -380,11 +380,13 @@ static si_status launch_attention_mfma(const char* stage, const bf16* q, int64_t
   // 8 wavefronts share the key / value stages when that still leaves several workgroups for every CU
   const int64_t wg8 = (int64_t)((Nq + 255) / 256) * heads * S;
   if (wg8 >= 1024) {
-    dim3 grid((unsigned)((Nq + 255) / 256), (unsigned)heads, (unsigned)S);
-    attn_mfma_kernel<8><<<grid, 512, 0, st>>>(a);
+    a.nqt = (Nq + 255) / 256;
+    a.ntiles = a.nqt * heads * S;
+    attn_mfma_kernel<8><<<(unsigned)((a.ntiles + 7) / 8 * 8), 512, 0, st>>>(a);
   } else {
-    dim3 grid((unsigned)((Nq + 127) / 128), (unsigned)heads, (unsigned)S);
-    attn_mfma_kernel<4><<<grid, 256, 0, st>>>(a);
+    a.nqt = (Nq + 127) / 128;
+    a.ntiles = a.nqt * heads * S;
+    attn_mfma_kernel<4><<<(unsigned)((a.ntiles + 7) / 8 * 8), 256, 0, st>>>(a);
   }
   SI_CHECK_LAUNCH();
   return SI_OK;
