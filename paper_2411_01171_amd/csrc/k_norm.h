@@ -328,6 +328,74 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float* __restrict
   }
 }
 
+// Row LayerNorm into the ring kernels' fragment order (bf16 blocks with D % 32 == 0): one wavefront
+// per 8 consecutive rows.  Lane (r = lane % 8, q = lane / 8) owns the channel quads q, q + 8, ... of
+// row r, so a load instruction covers 128 contiguous bytes of each of the 8 rows (all of them in
+// flight before the first use) and a store instruction writes four complete 128-byte pieces of the
+// fragment-order buffer (8 tokens x 16 bytes each).  Row sums meet over the 8 lanes of a row
+// (lane ^ 8, 16, 32).  NQ = D / 32 quads per lane.  Same arithmetic per element as layer_norm_kernel.
+template <int NQ>
+__global__ __launch_bounds__(64) void layer_norm_frag_kernel(const float* __restrict__ h, bf16* __restrict__ a, int64_t M,
+                                                             const bf16* __restrict__ gamma, const bf16* __restrict__ beta, float eps,
+                                                             const float* __restrict__ pe, int Pw, int Fw, int f0) {
+  constexpr int D = 32 * NQ;
+  const int lane = threadIdx.x, r = lane % 8, q = lane / 8;
+  const int64_t m = (int64_t)blockIdx.x * 8 + r;
+  const int64_t ml = m < M ? m : M - 1;  // rows past the end repeat the last one and are not stored
+  const float4* row = reinterpret_cast<const float4*>(h + ml * D) + q;
+  float4 v[NQ];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) v[i] = row[8 * i];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+  s += __shfl_xor(s, 8, kWave);
+  s += __shfl_xor(s, 16, kWave);
+  s += __shfl_xor(s, 32, kWave);
+  const float mean = s / (float)D;
+  float qs = 0.f;
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const float dx = v[i].x - mean, dy = v[i].y - mean, dz = v[i].z - mean, dw = v[i].w - mean;
+    qs += (dx * dx + dy * dy) + (dz * dz + dw * dw);
+  }
+  qs += __shfl_xor(qs, 8, kWave);
+  qs += __shfl_xor(qs, 16, kWave);
+  qs += __shfl_xor(qs, 32, kWave);
+  const float rstd = rsqrtf(qs / (float)D + eps);
+  const float* perow = pe ? pe + (int64_t)(f0 + (int)((ml / Pw) % Fw)) * D : nullptr;
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const int c = 4 * (q + 8 * i);
+    const float in[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+    float ga[4] = {1.f, 1.f, 1.f, 1.f}, be[4] = {0.f, 0.f, 0.f, 0.f}, pv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (gamma) {  // four consecutive 16-bit values: one 8-byte load (c % 4 == 0, 16-byte aligned base)
+      const uint2 w2 = *reinterpret_cast<const uint2*>(gamma + c);
+      ga[0] = __uint_as_float(w2.x << 16); ga[1] = __uint_as_float(w2.x & 0xffff0000u);
+      ga[2] = __uint_as_float(w2.y << 16); ga[3] = __uint_as_float(w2.y & 0xffff0000u);
+    }
+    if (beta) {
+      const uint2 w2 = *reinterpret_cast<const uint2*>(beta + c);
+      be[0] = __uint_as_float(w2.x << 16); be[1] = __uint_as_float(w2.x & 0xffff0000u);
+      be[2] = __uint_as_float(w2.y << 16); be[3] = __uint_as_float(w2.y & 0xffff0000u);
+    }
+    if (perow) {
+      const float4 p4 = *reinterpret_cast<const float4*>(perow + c);
+      pv[0] = p4.x; pv[1] = p4.y; pv[2] = p4.z; pv[3] = p4.w;
+    }
+    float y[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      y[e] = (in[e] - mean) * rstd * ga[e] + be[e];
+      if (perow) y[e] += pv[e];
+    }
+    uint2 pk;
+    pk.x = (unsigned)float_to_bf16_bits(y[0]) | ((unsigned)float_to_bf16_bits(y[1]) << 16);
+    pk.y = (unsigned)float_to_bf16_bits(y[2]) | ((unsigned)float_to_bf16_bits(y[3]) << 16);
+    if (m < M) *reinterpret_cast<uint2*>(a + act_offset(m, c, D)) = pk;
+  }
+}
+
 // dst[r * ld_dst + k] = src[k * ld_src + col(r)] for r in [0, rows): the k-contiguous
 // layout the GEMM kernels read (ld_dst > K lets two copies sit side by side for
 // operands that arrive as high/low pairs).  col(r) = col0 + r, or, with `interleave` > 0

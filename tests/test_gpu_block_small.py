@@ -167,6 +167,32 @@ def test_spatial_320_ragged_token_tiles_bf16(hw, slice_len):
     _check(spec, x, w, ctx, slice_len)
 
 
+@pytest.mark.parametrize("kind,C,heads", [("spatial", 640, 10), ("temporal", 640, 10), ("spatial", 1280, 20), ("temporal", 1280, 20)])
+def test_wide_blocks_small_windows_bf16(kind, C, heads):
+    """C = 640 / 1280 (the staged path of the deep levels) on a few dozen tokens with random norm
+    gains, shifts and biases: windows of 27 and 18 tokens (no multiple of a 32-token block or of the
+    8 rows a LayerNorm wavefront takes), a ragged last window."""
+    if kind == "spatial":
+        spec = tiny_spec(wl.SPATIAL, B=1, C=C, F=3, H=3, W=9, heads=heads, dim_head=64, groups=32, M=5, Cc=24, dtype="bf16")
+        ctx, sl = wl.make_context(spec), 2
+    else:
+        spec = tiny_spec(wl.TEMPORAL, B=1, C=C, F=3, H=3, W=5, heads=heads, dim_head=64, groups=32, pe=True, dtype="bf16")
+        ctx, sl = None, 9
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.02)
+    _check(spec, x, w, ctx, sl)
+
+
+def test_wide_temporal_block_large_ragged_window_bf16():
+    """C = 640 on one window of 3 x 2731 = 8193 tokens: large enough for the eight-rows-per-wavefront
+    LayerNorm (with the frame embedding and random gains / shifts), and one row past a multiple of 8,
+    of 32 and of every GEMM tile."""
+    spec = tiny_spec(wl.TEMPORAL, B=1, C=640, F=3, H=1, W=2731, heads=10, dim_head=64, groups=32, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.02)
+    _check(spec, x, w, None, 2731)
+
+
 def test_peaky_softmax_bf16():
     """Queries and keys scaled up so that the softmax is far from uniform."""
     spec = tiny_spec(wl.SPATIAL, B=1, C=64, F=2, H=10, W=10, heads=2, dim_head=32, groups=8, M=7, Cc=16, dtype="bf16")
