@@ -444,13 +444,24 @@ __global__ __launch_bounds__(256) void pack_transpose_kernel(const T* __restrict
 // granules (8 consecutive k of one row) -- 128 bytes per row per tile in the k-contiguous layout,
 // 512 contiguous bytes per 32 rows in a fragment stream.  Requires K % 8 == 0, ld_dst % 8 == 0 and a
 // 16-byte aligned destination; same arguments otherwise (col0 = 0).
-__global__ __launch_bounds__(256) void pack_transpose16_kernel(const unsigned short* __restrict__ src,
-                                                               unsigned short* __restrict__ dst, int K, int ld_src, int rows,
-                                                               int interleave, int ld_dst, int to_f16, int frag_tn,
-                                                               int frag_row0, int frag_K) {
-  __shared__ unsigned short tile[64][66];  // [k][r]
+// One matrix of a batch: the arguments of pack_transpose16_kernel plus the matrix's range of blocks.
+struct PackJob {
+  const unsigned short* src;
+  unsigned short* dst;
+  int K, ld_src, rows, interleave, ld_dst, to_f16, frag_tn, frag_row0, frag_K;
+  int block0, blocks_x;  // first block of the matrix in the batch's grid; blocks along its rows
+};
+constexpr int kPackBatchMax = 16;
+struct PackBatch {
+  PackJob job[kPackBatchMax];
+  int n, blocks;
+};
+
+__device__ __forceinline__ void pack_transpose16_tile(unsigned short (*tile)[66], const unsigned short* __restrict__ src,
+                                                      unsigned short* __restrict__ dst, int K, int ld_src, int rows, int interleave,
+                                                      int ld_dst, int to_f16, int frag_tn, int frag_row0, int frag_K, int bx, int by) {
   const int tid = threadIdx.x;
-  const int r0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+  const int r0 = bx * 64, k0 = by * 64;
   const int rp = 2 * (tid % 32);  // the thread's pair of destination rows within the tile
   const bool pair = interleave == 0 && (ld_src & 1) == 0 && (reinterpret_cast<uintptr_t>(src) & 3) == 0 && r0 + rp + 1 < rows;
   unsigned v[8];
@@ -494,6 +505,26 @@ __global__ __launch_bounds__(256) void pack_transpose16_kernel(const unsigned sh
     const int64_t at = frag_tn > 0 ? weight_fragment_index(frag_row0 + r, k, frag_K, frag_tn) : (int64_t)r * ld_dst + k;
     *reinterpret_cast<uint4*>(dst + at) = o;
   }
+}
+
+__global__ __launch_bounds__(256) void pack_transpose16_kernel(const unsigned short* __restrict__ src,
+                                                               unsigned short* __restrict__ dst, int K, int ld_src, int rows,
+                                                               int interleave, int ld_dst, int to_f16, int frag_tn,
+                                                               int frag_row0, int frag_K) {
+  __shared__ unsigned short tile[64][66];  // [k][r]
+  pack_transpose16_tile(tile, src, dst, K, ld_src, rows, interleave, ld_dst, to_f16, frag_tn, frag_row0, frag_K, blockIdx.x, blockIdx.y);
+}
+
+// All the matrices of a block's weight re-layout in one launch: block b works on the matrix whose
+// block range holds b.
+__global__ __launch_bounds__(256) void pack_transpose16_batch_kernel(PackBatch b) {
+  __shared__ unsigned short tile[64][66];
+  int j = 0;
+  while (j + 1 < b.n && (int)blockIdx.x >= b.job[j + 1].block0) ++j;
+  const PackJob& q = b.job[j];
+  const int local = (int)blockIdx.x - q.block0;
+  pack_transpose16_tile(tile, q.src, q.dst, q.K, q.ld_src, q.rows, q.interleave, q.ld_dst, q.to_f16, q.frag_tn, q.frag_row0, q.frag_K,
+                        local % q.blocks_x, local / q.blocks_x);
 }
 
 }  // namespace si

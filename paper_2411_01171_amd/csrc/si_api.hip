@@ -288,11 +288,19 @@ static si_status launch_gemm(const char* stage, const T* A, int64_t lda, const T
   return SI_OK;
 }
 
+// batch: collect eligible matrices instead of launching; flush_pack launches them all at once
 template <typename T>
 static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, int col0, int interleave, hipStream_t st,
-                             int ld_dst = 0, bool to_f16 = false, int frag_tn = 0, int frag_row0 = 0) {
+                             int ld_dst = 0, bool to_f16 = false, int frag_tn = 0, int frag_row0 = 0, PackBatch* batch = nullptr) {
   if (!ld_dst) ld_dst = K;
   if (sizeof(T) == 2 && col0 == 0 && K % 8 == 0 && ld_dst % 8 == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+    if (batch && batch->n < kPackBatchMax) {
+      const int bx = (rows + 63) / 64, by = (K + 63) / 64;
+      batch->job[batch->n++] = PackJob{reinterpret_cast<const unsigned short*>(src), reinterpret_cast<unsigned short*>(dst), K, ld_src,
+                                       rows, interleave, ld_dst, to_f16 ? 1 : 0, frag_tn, frag_row0, K, batch->blocks, bx};
+      batch->blocks += bx * by;
+      return SI_OK;
+    }
     dim3 grid((unsigned)((rows + 63) / 64), (unsigned)((K + 63) / 64));
     pack_transpose16_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const unsigned short*>(src), reinterpret_cast<unsigned short*>(dst),
                                                   K, ld_src, rows, interleave, ld_dst, to_f16 ? 1 : 0, frag_tn, frag_row0, K);
@@ -310,9 +318,16 @@ static si_status launch_pack(const T* src, T* dst, int K, int ld_src, int rows, 
 // Mmax tokens.  f16: 16-bit values are stored as fp16.
 template <typename T>
 static si_status pack_weight(const T* src, T* base, int K, int ld_src, int rows, int interleave, int N_total, int row0,
-                             bool as_ring, RingDims Mmax, bool f16, hipStream_t st) {
-  if (as_ring) return launch_pack<T>(src, base, K, ld_src, rows, 0, interleave, st, K, f16, ring_shape(Mmax, N_total, K).tn, row0);
-  return launch_pack<T>(src, base + (size_t)row0 * K, K, ld_src, rows, 0, interleave, st, K, f16);
+                             bool as_ring, RingDims Mmax, bool f16, hipStream_t st, PackBatch* batch = nullptr) {
+  if (as_ring)
+    return launch_pack<T>(src, base, K, ld_src, rows, 0, interleave, st, K, f16, ring_shape(Mmax, N_total, K).tn, row0, batch);
+  return launch_pack<T>(src, base + (size_t)row0 * K, K, ld_src, rows, 0, interleave, st, K, f16, 0, 0, batch);
+}
+static si_status flush_pack(const PackBatch& batch, hipStream_t st) {
+  if (batch.n == 0) return SI_OK;
+  pack_transpose16_batch_kernel<<<(unsigned)batch.blocks, 256, 0, st>>>(batch);
+  SI_CHECK_LAUNCH();
+  return SI_OK;
 }
 
 // The ring kernel (k_conv.h) as a GEMM: M tokens are M one-pixel images, one tap; act is a
@@ -560,27 +575,32 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   // the workspace still holds them), GroupNorm statistics, context K/V
   if (!packed) {
     StageScope scope("pack_weights", st);
+    PackBatch pb;
+    pb.n = 0;
+    pb.blocks = 0;
+    PackBatch* const pbp = &pb;
     if (!fused_attn) {
-      SI_TRY(pack_weight<T>(cT(w->w_in), w_in, C, D, D, 0, D, 0, ring, Mx, kF16, st));
-      SI_TRY(pack_weight<T>(cT(w->wq), wqkv, D, D, D, 0, 3 * D, 0, ring, Mx, false, st));
-      SI_TRY(pack_weight<T>(cT(w->wk), wqkv, D, D, D, 0, 3 * D, D, ring, Mx, false, st));
-      SI_TRY(pack_weight<T>(cT(w->wv), wqkv, D, D, D, 0, 3 * D, 2 * D, ring, Mx, false, st));
-      if (spatial || !fused_ffn) SI_TRY(pack_weight<T>(cT(w->wo), wo, D, D, D, 0, D, 0, self_frag, Mx, false, st));
+      SI_TRY(pack_weight<T>(cT(w->w_in), w_in, C, D, D, 0, D, 0, ring, Mx, kF16, st, pbp));
+      SI_TRY(pack_weight<T>(cT(w->wq), wqkv, D, D, D, 0, 3 * D, 0, ring, Mx, false, st, pbp));
+      SI_TRY(pack_weight<T>(cT(w->wk), wqkv, D, D, D, 0, 3 * D, D, ring, Mx, false, st, pbp));
+      SI_TRY(pack_weight<T>(cT(w->wv), wqkv, D, D, D, 0, 3 * D, 2 * D, ring, Mx, false, st, pbp));
+      if (spatial || !fused_ffn) SI_TRY(pack_weight<T>(cT(w->wo), wo, D, D, D, 0, D, 0, self_frag, Mx, false, st, pbp));
     }
     if (spatial) {
-      SI_TRY(pack_weight<T>(cT(w->wq2), wq2, D, D, D, 0, D, 0, ring, Mx, false, st));
-      SI_TRY(launch_pack<T>(cT(w->wk2), wkv2, p.Cc, D, D, 0, 0, st));
-      SI_TRY(launch_pack<T>(cT(w->wv2), wkv2 + (size_t)D * p.Cc, p.Cc, D, D, 0, 0, st));
-      if (!fused_ffn) SI_TRY(pack_weight<T>(cT(w->wo2), wo2, D, D, D, 0, D, 0, cross_frag, Mx, false, st));
+      SI_TRY(pack_weight<T>(cT(w->wq2), wq2, D, D, D, 0, D, 0, ring, Mx, false, st, pbp));
+      SI_TRY(launch_pack<T>(cT(w->wk2), wkv2, p.Cc, D, D, 0, 0, st, 0, false, 0, 0, pbp));
+      SI_TRY(launch_pack<T>(cT(w->wv2), wkv2 + (size_t)D * p.Cc, p.Cc, D, D, 0, 0, st, 0, false, 0, 0, pbp));
+      if (!fused_ffn) SI_TRY(pack_weight<T>(cT(w->wo2), wo2, D, D, D, 0, D, 0, cross_frag, Mx, false, st, pbp));
     }
     if (!fused_ffn) {
-      SI_TRY(pack_weight<T>(cT(w->w_out), w_out, D, C, C, 0, C, 0, ring, Mx, kF16, st));
-      SI_TRY(pack_weight<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 4 * D, 8 * D, 0, ring, Mx, false, st));
-      SI_TRY(pack_weight<T>(cT(w->w2), w2, 4 * D, D, D, 0, D, 0, ring, Mx, false, st));
+      SI_TRY(pack_weight<T>(cT(w->w_out), w_out, D, C, C, 0, C, 0, ring, Mx, kF16, st, pbp));
+      SI_TRY(pack_weight<T>(cT(w->w1), w1, D, 8 * D, 8 * D, 4 * D, 8 * D, 0, ring, Mx, false, st, pbp));
+      SI_TRY(pack_weight<T>(cT(w->w2), w2, 4 * D, D, D, 0, D, 0, ring, Mx, false, st, pbp));
     } else if constexpr (sizeof(T) == 2) {
       if (p.fused_nb == 2) SI_TRY(pack_fused_streams<2>(p, w, ws, pe, st));
       else SI_TRY(pack_fused_streams<10>(p, w, ws, pe, st));
     }
+    SI_TRY(flush_pack(pb, st));
     if (pe && !(fused_ffn && sizeof(T) == 2)) {
       pe_table_kernel<<<(p.F * D + 255) / 256, 256, 0, st>>>(pe, p.F, D);
       SI_CHECK_LAUNCH();
