@@ -139,6 +139,7 @@ struct StreamDesc {
   const bf16 *w1, *w2;
   float* pe;
   int F;
+  int extra_sub;  // sub-chunks that another kernel appends behind these (they share the stream's pitch)
 };
 template <int NB>
 __global__ __launch_bounds__(256) void pack_stream_kernel(StreamDesc sd, u32x4_t* __restrict__ dst) {
@@ -189,7 +190,7 @@ __global__ __launch_bounds__(256) void pack_stream_kernel(StreamDesc sd, u32x4_t
   o.y = e[2] | ((unsigned)e[3] << 16);
   o.z = e[4] | ((unsigned)e[5] << 16);
   o.w = e[6] | ((unsigned)e[7] << 16);
-  dst[idx * stream_pitch_u4(total_sub) + (int64_t)sub * kWave + lane] = o;
+  dst[idx * stream_pitch_u4(total_sub + sd.extra_sub) + (int64_t)sub * kWave + lane] = o;
 }
 
 // ----------------------------------------------------------------------------- weight stream pipeline
@@ -240,20 +241,24 @@ struct WeightPipe {
   }
   static __device__ __forceinline__ void issue(const u32x4_t* stream, u32x4_t* ring0, int sub, int total, int64_t pitch,
                                                unsigned voff, int wave_s) {
-    if (sub < total) {
-      const char* sbase = reinterpret_cast<const char*>(stream) + (int64_t)sub * (kWave * 16);
-      // LDS byte address of this wavefront's first fragment in the slot, wave-uniform (goes to M0)
-      const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)ring0 +
-                           (unsigned)((sub % kRingSlots) * (SUB * kWave * 16) + wave_s * (kWave * 16));
+    if (sub < total) issue_at(stream, ring0, sub, sub, pitch, voff, wave_s);
+  }
+  // Sub-chunk `src_sub` of the stream into the ring slot of step `step` (the two differ where a
+  // kernel splices sub-chunks from elsewhere in the stream into its sequence of steps).
+  static __device__ __forceinline__ void issue_at(const u32x4_t* stream, u32x4_t* ring0, int src_sub, int step, int64_t pitch,
+                                                  unsigned voff, int wave_s) {
+    const char* sbase = reinterpret_cast<const char*>(stream) + (int64_t)src_sub * (kWave * 16);
+    // LDS byte address of this wavefront's first fragment in the slot, wave-uniform (goes to M0)
+    const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)ring0 +
+                         (unsigned)((step % kRingSlots) * (SUB * kWave * 16) + wave_s * (kWave * 16));
 #pragma unroll
-      for (int i = 0; i < PER_THREAD; ++i) {
-        const char* sb = sbase + (int64_t)(4 * i) * pitch * 16;
-        const unsigned l = dst + (unsigned)(4 * i * kWave * 16);
-        // Issued as assembly so that the compiler's wait-count pass does not place a full vector-memory
-        // wait in front of every later LDS read; completion is awaited explicitly when a step closes.
-        // M0 is reserved by the compiler and used by nothing else in these kernels.
-        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sb), "s"(l) : "memory");
-      }
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const char* sb = sbase + (int64_t)(4 * i) * pitch * 16;
+      const unsigned l = dst + (unsigned)(4 * i * kWave * 16);
+      // Issued as assembly so that the compiler's wait-count pass does not place a full vector-memory
+      // wait in front of every later LDS read; completion is awaited explicitly when a step closes.
+      // M0 is reserved by the compiler and used by nothing else in these kernels.
+      asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sb), "s"(l) : "memory");
     }
   }
 };
@@ -270,16 +275,70 @@ struct FfnHalfArgs {
   const bf16* x;
   bf16* out;
   Window win;
+  // CROSS only (spatial blocks, heads of 64): `o` / b_o belong to the self-attention; then LN2, the
+  // query projection, attention over the context tokens and its out-projection (b_o2) run here too.
+  const bf16 *ln2_g, *ln2_b, *b_o2;
+  int64_t pitch;          // the stream's pitch in 16-byte units (it also carries the context fragments)
+  int ctx_sub0;           // first context sub-chunk of batch entry 0; kCrossSub per batch entry
+  int Mc;                 // context tokens (<= 32 * kCrossTiles)
+  int tokens_per_batch;   // a multiple of 128: a workgroup's tokens share one context
+  float qscale;           // softmax scale * log2(e)
 };
 
+// Attention over the context inside the FFN-half kernel: up to 3 tiles of 32 keys, heads of 64
+// channels.  Per head 24 MFMAs, in this order (= the order of the head's fragments in the stream):
+//   j < 12:  S^T[kt] += K[kt, ks] q[ks]         ks = j / 3 (16 head channels), kt = j % 3 (32 keys)
+//   j >= 12: O^T[cb] += V^T[cb, kk] P^T[kk]     kk = (j - 12) / 2 (16 keys), cb = (j - 12) % 2 (32 channels)
+// so a batch entry's context is 24 * heads fragments = kCrossSub sub-chunks of SUB at 5 heads.
+constexpr int kCrossTiles = 3, kCrossOps = 8 * kCrossTiles;
+
+// Context keys / values [B*Mc, 2D] (keys in columns [0, D), values in [D, 2D)) -> the fragments
+// above, appended to a fragment stream as sub-chunks sub0 + (NH * kCrossOps / SUB) * b + ...
+// Keys past Mc are zero (their scores are masked, their probabilities zero).  One wavefront per fragment.
 template <int NB>
+__global__ __launch_bounds__(256) void pack_ctx_stream_kernel(const bf16* __restrict__ kv, int B, int Mc, u32x4_t* __restrict__ dst,
+                                                              int64_t pitch, int sub0) {
+  constexpr int D = 32 * NB, SUB = 2 * NB, NH = D / 64, PERB = NH * kCrossOps;
+  static_assert(PERB % SUB == 0, "whole sub-chunks per batch entry");
+  const int fidx = blockIdx.x * 4 + threadIdx.x / kWave;
+  if (fidx >= B * PERB) return;
+  const int lane = threadIdx.x % kWave, r = lane % 32, g = lane / 32;
+  const int b = fidx / PERB, i = fidx % PERB, hd = i / kCrossOps, j = i % kCrossOps;
+  unsigned short e[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    int key, col;
+    if (j < 4 * kCrossTiles) {
+      key = 32 * (j % kCrossTiles) + r;
+      col = 64 * hd + 16 * (j / kCrossTiles) + frag_k(g, t);
+    } else {
+      const int jj = j - 4 * kCrossTiles;
+      key = 16 * (jj / 2) + frag_k(g, t);
+      col = D + 64 * hd + 32 * (jj % 2) + r;
+    }
+    e[t] = key < Mc ? kv[((int64_t)b * Mc + key) * (2 * D) + col].v : (unsigned short)0;
+  }
+  u32x4_t o;
+  o.x = e[0] | ((unsigned)e[1] << 16);
+  o.y = e[2] | ((unsigned)e[3] << 16);
+  o.z = e[4] | ((unsigned)e[5] << 16);
+  o.w = e[6] | ((unsigned)e[7] << 16);
+  const int sub = sub0 + (PERB / SUB) * b + i / SUB;
+  dst[(i % SUB) * pitch + (int64_t)sub * kWave + lane] = o;
+}
+
+template <int NB, bool CROSS = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void ffn_half_kernel(FfnHalfArgs a) {
   constexpr int D = 32 * NB, SUB = 2 * NB, NC = 4 * NB;  // SUB fragments per sub-chunk (= k-steps over D)
   constexpr int NSLOT = kRingSlots, FIFO = NB;
-  constexpr int TOTAL_SUB = NB + 3 * NC + NB;
+  // CROSS: W_o, W_q2 blocks | the batch entry's context fragments | W_o2 blocks, FFN, W_out blocks
+  constexpr int kCrossSub = CROSS ? (D / 64) * kCrossOps / SUB : 0, kSplice = 2 * NB;
+  constexpr int TOTAL_SUB = (CROSS ? 2 * NB : 0) + kCrossSub + NB + 3 * NC + NB;  // steps
   static_assert(NB % 2 == 0, "NB must be even");  // whole fragments per wavefront per sub-chunk
+  static_assert(!CROSS || ((D / 64) * kCrossOps) % SUB == 0, "context fragments fill whole sub-chunks");
   __shared__ u32x4_t ring[NSLOT][SUB * kWave];
   __shared__ float t_g[D], t_b[D], t_b2[D], t_bout[D], t_bo[D], t_b1[8 * D];
+  __shared__ float t_g2[CROSS ? D : 1], t_bl2[CROSS ? D : 1], t_bo2[CROSS ? D : 1];
   __shared__ __attribute__((aligned(16))) float stage[4][32][36];  // slice-out transpose, one patch per wavefront
 
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -322,17 +381,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     t_b2[i] = param_or(a.b2, i, 0.f);
     t_bout[i] = param_or(a.b_out, i, 0.f);
     t_bo[i] = param_or(a.b_o, i, 0.f);
+    if constexpr (CROSS) {
+      t_g2[i] = param_or(a.ln2_g, i, 1.f);
+      t_bl2[i] = param_or(a.ln2_b, i, 0.f);
+      t_bo2[i] = param_or(a.b_o2, i, 0.f);
+    }
   }
   for (int i = tid; i < 8 * D; i += 256) t_b1[i] = param_or(a.b1, i, 0.f);
 
   // ---- weight stream: the first three sub-chunks go straight into the ring
   using Pipe = WeightPipe<SUB>;
-  const int64_t pitch = stream_pitch_u4(TOTAL_SUB);
+  const int64_t pitch = CROSS ? a.pitch : stream_pitch_u4(TOTAL_SUB);
   const unsigned pipe_voff = Pipe::pipe_voff(lane, wave, pitch);
   const int pipe_wave = __builtin_amdgcn_readfirstlane(wave);
+  // the workgroup's context sub-chunks (all of its tokens belong to one batch entry)
+  const int ctx_sub = CROSS ? a.ctx_sub0 + kCrossSub * (int)(((int64_t)blockIdx.x * 128) / a.tokens_per_batch) : 0;
+  // loads of step G: the stream's sub-chunk G, except that the context sub-chunks are spliced in
+  // behind the first kSplice steps
+  auto issue_step = [&](int G) {
+    if (G >= TOTAL_SUB) return;
+    int src = G;
+    if constexpr (CROSS) {
+      if (G >= kSplice) src = G < kSplice + kCrossSub ? ctx_sub + (G - kSplice) : G - kCrossSub;
+    }
+    Pipe::issue_at(a.stream, ring[0], src, G, pitch, pipe_voff, pipe_wave);
+  };
   int cur = 0;  // sub-chunk being consumed; loads run at cur + 3
 #pragma unroll
-  for (int i = 0; i < NSLOT - 1; ++i) Pipe::issue(a.stream, ring[0], i, TOTAL_SUB, pitch, pipe_voff, pipe_wave);
+  for (int i = 0; i < NSLOT - 1; ++i) issue_step(i);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): also the residual / attention rows loaded above
   __syncthreads();  // tables and the first three sub-chunks are in LDS
 
@@ -344,7 +420,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // One pipeline step around the MFMAs of sub-chunk `cur` (see WeightPipe).
 #define SI_STEP_OPEN()                                                           \
   __builtin_amdgcn_sched_barrier(0);                                             \
-  Pipe::issue(a.stream, ring[0], cur + NSLOT - 1, TOTAL_SUB, pitch, pipe_voff, pipe_wave); \
+  issue_step(cur + NSLOT - 1);                                                   \
   const u32x4_t* slot_c = ring[cur % NSLOT];                                     \
   const u32x4_t* slot_n = ring[(cur + 1) % NSLOT];                               \
   (void)slot_c; (void)slot_n
@@ -365,25 +441,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #define SI_REFILL(f)                                                                                 \
   fifo[(f) % FIFO] = __builtin_bit_cast(bf16x8_t, (f) < FIFO ? slot_c[((f) + FIFO) * kWave + lane]   \
                                                              : slot_n[((f)-FIFO) * kWave + lane])
-  // ---- h += o W_o + b_o: NB steps, one 32-column block of the residual each
-#define SI_WO_BLOCK(nb)                                                                          \
+  // ---- h += o W + b: NB steps, one 32-column block of the residual each (OPS: the k-steps of o as
+  // column operands, TB: the bias table)
+#define SI_WO_BLOCK(nb, OPS, TB)                                                                 \
   {                                                                                                 \
     SI_STEP_OPEN();                                                                                \
     _Pragma("unroll") for (int s = 0; s < SUB; ++s) {                                               \
-      hacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), aop[s], hacc[nb], 0, 0, 0);    \
+      hacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), OPS[s], hacc[nb], 0, 0, 0);    \
       SI_REFILL(s);                                                                                 \
       __builtin_amdgcn_sched_barrier(0);                                                            \
     }                                                                                               \
     SI_STEP_CLOSE();                                                                               \
     _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                   \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) hacc[nb][4 * q + j] += t_bo[32 * (nb) + 8 * q + 4 * g + j]; \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) hacc[nb][4 * q + j] += TB[32 * (nb) + 8 * q + 4 * g + j]; \
   }
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) SI_WO_BLOCK(nb)
-#undef SI_WO_BLOCK
+  for (int nb = 0; nb < NB; ++nb) SI_WO_BLOCK(nb, aop, t_bo)
 
-  // ---- LN3 over the row (this lane holds half of it, lane ^ 32 the other half); aop becomes its output
-  {
+  // LayerNorm over the row (this lane holds half of it, lane ^ 32 the other half); aop becomes its output
+  auto layer_norm_row = [&](const float* tg, const float* tb) {
     float s = 0.f;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -409,11 +485,119 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int n = 32 * nb + 16 * hf + frag_k(g, e);
-          v[e] = (hacc[nb][8 * hf + e] - mean) * rstd * t_g[n] + t_b[n];
+          v[e] = (hacc[nb][8 * hf + e] - mean) * rstd * tg[n] + tb[n];
         }
         aop[2 * nb + hf] = to_operand(v);
       }
+  };
+
+  if constexpr (CROSS) {
+    // ---- LN2, then q = LN2(h) W_q2 * scale * log2(e): block nb of the result is k-steps 2nb, 2nb + 1
+    // of the score contraction's column operand (head nb / 2)
+    layer_norm_row(t_g2, t_bl2);
+    bf16x8_t xop[SUB];  // the queries; head by head replaced by the attention output
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      f32x16_t qa;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) qa[e] = 0.f;
+      {
+        SI_STEP_OPEN();
+#pragma unroll
+        for (int s = 0; s < SUB; ++s) {
+          qa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), aop[s], qa, 0, 0, 0);
+          SI_REFILL(s);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        SI_STEP_CLOSE();
+      }
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = qa[8 * hf + e] * a.qscale;
+        xop[2 * nb + hf] = to_operand(v);
+      }
+    }
+    // ---- attention over the context, head by head (see kCrossOps); scores, probabilities and the
+    // output stay in registers: keys are the rows of S^T, so a lane holds 16 of a tile's 32 keys of
+    // its token and lane ^ 32 the other 16
+    f32x16_t sc[kCrossTiles], oc[2];
+    bf16x8_t pk[2 * kCrossTiles];
+    float inv_l = 0.f;
+    static_for<kCrossSub>([&](auto C6) {
+      constexpr int c6 = decltype(C6)::value;
+      SI_STEP_OPEN();
+      static_for<SUB>([&](auto S20) {
+        constexpr int s = decltype(S20)::value, i = SUB * c6 + s, hd = i / kCrossOps, j = i % kCrossOps;
+        if constexpr (j < 4 * kCrossTiles) {
+          constexpr int ks = j / kCrossTiles, kt = j % kCrossTiles;
+          if constexpr (ks == 0) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[kt][e] = 0.f;
+          }
+          sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), xop[4 * hd + ks], sc[kt], 0, 0, 0);
+        } else {
+          constexpr int jj = j - 4 * kCrossTiles, kk = jj / 2, cb = jj % 2;
+          if constexpr (jj == 0) {  // softmax over the keys (register 4q + j of tile kt: key 32kt + 8q + 4g + j)
+            float mx = -INFINITY;
+#pragma unroll
+            for (int kt = 0; kt < kCrossTiles; ++kt)
+#pragma unroll
+              for (int e = 0; e < 16; ++e) {
+                if (32 * kt + 8 * (e / 4) + 4 * g + (e % 4) >= a.Mc) sc[kt][e] = -INFINITY;
+                mx = fmaxf(mx, sc[kt][e]);
+              }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));  // key 0 exists: finite
+            float l = 0.f;
+#pragma unroll
+            for (int kt = 0; kt < kCrossTiles; ++kt) {
+#pragma unroll
+              for (int e = 0; e < 16; ++e) {
+                sc[kt][e] = __builtin_amdgcn_exp2f(sc[kt][e] - mx);
+                l += sc[kt][e];
+              }
+#pragma unroll
+              for (int hf = 0; hf < 2; ++hf) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = sc[kt][8 * hf + e];
+                pk[2 * kt + hf] = to_operand(v);
+              }
+            }
+            l += __shfl_xor(l, 32, kWave);
+            inv_l = 1.0f / l;
+          }
+          if constexpr (kk == 0) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oc[cb][e] = 0.f;
+          }
+          oc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(SI_FRAG(s), pk[kk], oc[cb], 0, 0, 0);
+          if constexpr (jj == 4 * kCrossTiles - 1) {  // the head's output replaces its queries
+#pragma unroll
+            for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+              for (int hf = 0; hf < 2; ++hf) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = oc[b2][8 * hf + e] * inv_l;
+                xop[4 * hd + 2 * b2 + hf] = to_operand(v);
+              }
+          }
+        }
+        SI_REFILL(s);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      SI_STEP_CLOSE();
+    });
+    // ---- h += o2 W_o2 + b_o2
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) SI_WO_BLOCK(nb, xop, t_bo2)
   }
+#undef SI_WO_BLOCK
+
+  // ---- LN3
+  layer_norm_row(t_g, t_b);
 
   // A step issues, per fragment: one MFMA, the fragment's FIFO refill, and one stage of the GEGLU
   // group that rides along (a handful of independent vector-ALU instructions that execute while

@@ -111,6 +111,8 @@ struct Plan {
   bool pe;
   int fused_nb;     // > 0: register-resident FFN half with D = 32*fused_nb
   bool fused_attn;  // register-resident attention half as well (temporal blocks)
+  bool post_fused;  // spatial: everything behind the self-attention (its out-projection, LN2, query projection,
+                    // attention over the context, FFN half) in one register-resident kernel
   bool attn_mfma;   // matrix-core attention kernel for the staged spatial path (bf16, head dimension 64)
   bool ring;        // staged bf16 GEMMs run on the fragment-order ring kernel (operands in fragment order)
   int lanes;        // slices in flight (many small slices: 2 or 3, each on a stream of its own)
@@ -122,6 +124,9 @@ struct Plan {
   size_t off_a, off_h, off_big, off_ffn_stream, off_attn_stream;
   size_t weights_bytes, total_bytes;
 };
+
+// sub-chunks of context fragments per batch entry in the post-attention kernel's stream
+static int post_ctx_sub(const Plan& p) { return (p.D / 64) * kCrossOps / (2 * p.fused_nb); }
 
 static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const si_context* ctx, int32_t axis,
                            int64_t slice_len, Plan* p) {
@@ -193,6 +198,10 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     p->fused_attn = p->kind == SI_BLOCK_TEMPORAL && tp >= 1 && dh_ok && (int64_t)p->F * p->G <= kAttnMaxStats &&
                     (p->B <= 2 || last_len >= 128);
   }
+  // a workgroup's 128 tokens share one context (P % 128 == 0: frames are whole workgroups), heads of 64
+  // channels (two 32-channel blocks), at most kCrossTiles key tiles
+  p->post_fused = p->fused_nb == 10 && p->kind == SI_BLOCK_SPATIAL && p->attn_mfma && p->d == 64 && P % 128 == 0 &&
+                  p->Mc <= 32 * kCrossTiles;
   // Ring GEMMs: 16-bit storage, every contraction length a multiple of the 32-wide k-tile, operand
   // buffers addressable with 32-bit byte offsets.
   p->ring = p->dtype == SI_BF16 && p->C % 32 == 0 && D % 32 == 0 &&
@@ -239,7 +248,9 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_w1 = take(wbytes(8 * Dz, Dz));
   p->off_w2 = take(wbytes(Dz, 4 * Dz));
   p->off_w_out = take(wbytes(C, Dz));
-  p->off_ffn_stream = take(p->fused_nb && !p->fused_attn ? (size_t)stream_bytes(14 * p->fused_nb, 2 * p->fused_nb) : 0);
+  // post_fused: + W_o and W_q2 blocks and, per batch entry, the context fragments (24 per head)
+  const int ffn_sub = 14 * p->fused_nb + (p->post_fused ? 2 * p->fused_nb + post_ctx_sub(*p) * p->B : 0);
+  p->off_ffn_stream = take(p->fused_nb && !p->fused_attn ? (size_t)stream_bytes(ffn_sub, 2 * p->fused_nb) : 0);
   p->off_attn_stream = take(p->fused_attn ? (size_t)stream_bytes(18 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->weights_bytes = off - act_end;
   p->total_bytes = off;
@@ -468,6 +479,10 @@ static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, ch
         for (int blk = 0; blk < nbg; ++blk) sd.b[n++] = BlockDesc{cB(mats[kind]), D, gi * gw + 32 * blk};
     }
   }
+  if (p.post_fused) {  // self-attention out-projection and the query projection of the context attention
+    for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->wo), D, 32 * nb};
+    for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->wq2), D, 32 * nb};
+  }
   // FFN half: out-projection of the last attention, FFN, proj_out
   for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(spatial ? w->wo2 : w->wo), D, 32 * nb};
   sd.n_pre = n;
@@ -475,6 +490,7 @@ static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, ch
   sd.n_post = NB;
   sd.w1 = cB(w->w1); sd.w2 = cB(w->w2);
   sd.pe = pe; sd.F = p.F;
+  sd.extra_sub = p.post_fused ? post_ctx_sub(p) * p.B : 0;
   const int total = sd.n_pre + 12 * NB + sd.n_post;
   u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + (p.fused_attn ? p.off_attn_stream : p.off_ffn_stream));
   const int frag_wgs = (total * 2 * NB + 3) / 4, pe_wgs = pe ? (p.F * D + 255) / 256 : 0;
@@ -567,7 +583,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
   // operand buffers in fragment order + ring kernel; the attention outputs too where the matrix-core
   // attention kernel writes them and a staged GEMM (not the FFN-half kernel) reads them
   const bool ring = p.ring;
-  const bool self_frag = ring && p.attn_mfma, cross_frag = ring && p.attn_mfma && !fused_ffn;
+  const bool self_frag = ring && p.attn_mfma && !p.post_fused, cross_frag = ring && p.attn_mfma && !fused_ffn;
   const RingDims Mx{p.Mmax, p.lanes};
   auto cT = [](const void* q) { return static_cast<const T*>(q); };
 
@@ -584,10 +600,11 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
       SI_TRY(pack_weight<T>(cT(w->wq), wqkv, D, D, D, 0, 3 * D, 0, ring, Mx, false, st, pbp));
       SI_TRY(pack_weight<T>(cT(w->wk), wqkv, D, D, D, 0, 3 * D, D, ring, Mx, false, st, pbp));
       SI_TRY(pack_weight<T>(cT(w->wv), wqkv, D, D, D, 0, 3 * D, 2 * D, ring, Mx, false, st, pbp));
-      if (spatial || !fused_ffn) SI_TRY(pack_weight<T>(cT(w->wo), wo, D, D, D, 0, D, 0, self_frag, Mx, false, st, pbp));
+      if ((spatial || !fused_ffn) && !p.post_fused)
+        SI_TRY(pack_weight<T>(cT(w->wo), wo, D, D, D, 0, D, 0, self_frag, Mx, false, st, pbp));
     }
     if (spatial) {
-      SI_TRY(pack_weight<T>(cT(w->wq2), wq2, D, D, D, 0, D, 0, ring, Mx, false, st, pbp));
+      if (!p.post_fused) SI_TRY(pack_weight<T>(cT(w->wq2), wq2, D, D, D, 0, D, 0, ring, Mx, false, st, pbp));
       SI_TRY(launch_pack<T>(cT(w->wk2), wkv2, p.Cc, D, D, 0, 0, st, 0, false, 0, 0, pbp));
       SI_TRY(launch_pack<T>(cT(w->wv2), wkv2 + (size_t)D * p.Cc, p.Cc, D, D, 0, 0, st, 0, false, 0, 0, pbp));
       if (!fused_ffn) SI_TRY(pack_weight<T>(cT(w->wo2), wo2, D, D, D, 0, D, 0, cross_frag, Mx, false, st, pbp));
@@ -611,7 +628,15 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     EpiStore<T> epi{ctxkv, (int64_t)2 * D, nullptr};
     SI_TRY(launch_gemm<T>("ctx_kv", cT(ctx->ptr), (int64_t)p.Cc, wkv2, (int64_t)p.B * p.Mc, 2 * D, p.Cc, epi, st));
     if constexpr (sizeof(T) == 2) {
-      if (p.attn_mfma)
+      if (p.post_fused) {  // the context as fragments behind the post-attention kernel's weight stream
+        StageScope scope("ctx_frags", st);
+        const int n_main = 16 * p.fused_nb, per_b = post_ctx_sub(p);
+        const int64_t pitch = stream_pitch_u4(n_main + per_b * p.B);
+        const unsigned wgs = (unsigned)((p.B * per_b * 2 * p.fused_nb + 3) / 4);
+        pack_ctx_stream_kernel<10><<<wgs, 256, 0, st>>>(ctxkv, p.B, p.Mc, reinterpret_cast<u32x4_t*>(ws + p.off_ffn_stream), pitch,
+                                                        n_main);
+        SI_CHECK_LAUNCH();
+      } else if (p.attn_mfma)
         SI_TRY(launch_transpose_v("ctx_vt", ctxkv, (int64_t)2 * D, D, reinterpret_cast<bf16*>(ws + p.off_ctxvt), p.B, p.Mc, p.Mcp, D, st));
     }
   }
@@ -717,11 +742,11 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         at.kmap = at.qmap;
         SI_TRY(launch_attention<T>("self_attn", at, st));
       }
-      if (spatial || !fused_ffn) {  // otherwise the FFN-half kernel applies W_o itself
+      if ((spatial || !fused_ffn) && !p.post_fused) {  // otherwise the FFN-half kernel applies W_o itself
         EpiResidual<T> epi{h, (int64_t)D, cT(w->bo), 1, nullptr};
         SI_TRY((launch_gemm_sel<T, false>("attn_out", self_frag, a, (int64_t)D, wo, M, Mx, D, D, epi, st)));
       }
-      if (spatial) {
+      if (spatial && !p.post_fused) {
         SI_TRY(launch_layer_norm<T>("ln2", h, a, M, D, w->ln2_g, w->ln2_b, w->ln_eps, nullptr, win.Pw, win.Fw, win.f0, st, ring));
         {
           EpiStore<T> epi{big, (int64_t)D, nullptr, p.attn_mfma ? qscale2 : 1.f};
@@ -754,14 +779,22 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     }
     if constexpr (sizeof(T) == 2) {
       if (fused_ffn) {  // h += a W_o + b_o, LN3, GEGLU FFN, proj_out, residual, slice-out
-        StageScope scope("ffn_half_fused", st);
+        StageScope scope(p.post_fused ? "post_attn_fused" : "ffn_half_fused", st);
         FfnHalfArgs fa;
         fa.h = h; fa.o = a; fa.M = M; fa.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_ffn_stream);
-        fa.b_o = cT(spatial ? w->bo2 : w->bo);
+        fa.b_o = cT(spatial && !p.post_fused ? w->bo2 : w->bo);
         fa.ln_g = cT(w->ln3_g); fa.ln_b = cT(w->ln3_b); fa.b1 = cT(w->b1); fa.b2 = cT(w->b2); fa.b_out = cT(w->b_out);
         fa.ln_eps = w->ln_eps; fa.x = X; fa.out = OUT; fa.win = win;
+        fa.ln2_g = fa.ln2_b = fa.b_o2 = nullptr;
+        fa.pitch = 0; fa.ctx_sub0 = 0; fa.Mc = 0; fa.tokens_per_batch = 128; fa.qscale = 0.f;
         const unsigned blocks = (unsigned)((M + 127) / 128);
-        if (p.fused_nb == 2) ffn_half_kernel<2><<<blocks, 256, 0, st>>>(fa);
+        if (p.post_fused) {  // `a` holds the self-attention output; the kernel goes on from there
+          fa.ln2_g = cT(w->ln2_g); fa.ln2_b = cT(w->ln2_b); fa.b_o2 = cT(w->bo2);
+          fa.ctx_sub0 = 16 * p.fused_nb;
+          fa.pitch = stream_pitch_u4(fa.ctx_sub0 + post_ctx_sub(p) * p.B);
+          fa.Mc = p.Mc; fa.tokens_per_batch = (int)(win.Fw * win.Pw); fa.qscale = qscale2;
+          ffn_half_kernel<10, true><<<blocks, 256, 0, st>>>(fa);
+        } else if (p.fused_nb == 2) ffn_half_kernel<2><<<blocks, 256, 0, st>>>(fa);
         else ffn_half_kernel<10><<<blocks, 256, 0, st>>>(fa);
         SI_CHECK_LAUNCH();
         continue;
@@ -812,7 +845,7 @@ static uint64_t pack_fingerprint(const Plan& p, const si_block_weights* w) {
   int dev = -1;
   (void)hipGetDevice(&dev);
   const int64_t f[] = {p.kind, p.dtype, p.B, p.C, p.F, p.H, p.W, p.G, p.heads, p.d, p.Mc, p.Cc, p.axis, p.extent, p.slice_len,
-                       p.Mmax, p.pe, p.fused_nb, p.fused_attn, p.attn_mfma, p.ring, p.lanes, (int64_t)p.weights_bytes,
+                       p.Mmax, p.pe, p.fused_nb, p.fused_attn, p.post_fused, p.attn_mfma, p.ring, p.lanes, (int64_t)p.weights_bytes,
                        (int64_t)p.total_bytes, (int64_t)p.off_w_in, (int64_t)p.off_ffn_stream, (int64_t)p.off_attn_stream, dev};
   uint64_t h = fnv1a(14695981039346656037ull, f, sizeof(f));
   const void* q[] = {w->gn_g, w->gn_b, w->w_in, w->b_in, w->ln1_g, w->ln1_b, w->wq, w->wk, w->wv, w->wo, w->bo,

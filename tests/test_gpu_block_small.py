@@ -167,6 +167,19 @@ def test_spatial_320_ragged_token_tiles_bf16(hw, slice_len):
     _check(spec, x, w, ctx, slice_len)
 
 
+@pytest.mark.parametrize("B,hw,M,slice_len", [(2, (8, 16), 77, 1), (3, (16, 16), 5, 2), (2, (8, 16), 96, 3), (1, (8, 32), 33, 1)])
+def test_spatial_320_whole_tile_frames_bf16(B, hw, M, slice_len):
+    """C = 320, 5 heads x 64, frames of 128 / 256 positions: everything behind the self-attention runs
+    in one kernel per window, context attention included (77 context tokens: a ragged third key tile;
+    5: one tile, mostly masked; 96: three full tiles; 33: one key in the second tile); B = 3 with two
+    frames per slice: workgroups of one window read three different contexts, ragged last window."""
+    spec = tiny_spec(wl.SPATIAL, B=B, C=320, F=3, H=hw[0], W=hw[1], heads=5, dim_head=64, groups=32, M=M, Cc=24,
+                     dtype="bf16")
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.03)
+    _check(spec, x, w, ctx, slice_len)
+
+
 @pytest.mark.parametrize("kind,C,heads", [("spatial", 640, 10), ("temporal", 640, 10), ("spatial", 1280, 20), ("temporal", 1280, 20)])
 def test_wide_blocks_small_windows_bf16(kind, C, heads):
     """C = 640 / 1280 (the staged path of the deep levels) on a few dozen tokens with random norm
