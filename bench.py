@@ -55,6 +55,8 @@ def stage_work(spec, stage, M, window_tokens_per_seq=None):
         return "flop", 2.0 * M * (C * D + 3 * D * D) + 4.0 * M * spec.F * D
     if stage == "ffn_half_fused":       # attention out-projection, W1, W2, proj_out
         return "flop", 2.0 * M * (D * D + 8 * D * D + 4 * D * D + D * C)
+    if stage == "pre_attn_fused":       # proj_in and the q / k / v projections
+        return "flop", 2.0 * M * (C * D + 3 * D * D)
     if stage == "post_attn_fused":      # self-attention out-projection, query projection, context attention and
         # its out-projection, W1, W2, proj_out
         return "flop", 2.0 * M * (3 * D * D + 8 * D * D + 4 * D * D + D * C) + 4.0 * M * spec.ctx_tokens * D

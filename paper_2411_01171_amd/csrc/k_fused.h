@@ -128,6 +128,7 @@ __host__ __device__ inline int64_t stream_bytes(int total_sub, int sub) { return
 struct BlockDesc {
   const bf16* src;
   int ld, col0;
+  int f16;  // store the values as fp16 (operands of an fp16 contraction)
 };
 
 // Whole fragment stream in one launch: n_pre block sub-chunks, the FFN's 12*NB sub-chunks, n_post
@@ -136,6 +137,7 @@ struct BlockDesc {
 struct StreamDesc {
   BlockDesc b[64];  // pre blocks first, then post blocks
   int n_pre, n_post;
+  int n_ffn;  // 12 * NB, or 0 for a stream of blocks only
   const bf16 *w1, *w2;
   float* pe;
   int F;
@@ -144,7 +146,7 @@ struct StreamDesc {
 template <int NB>
 __global__ __launch_bounds__(256) void pack_stream_kernel(StreamDesc sd, u32x4_t* __restrict__ dst) {
   constexpr int D = 32 * NB, SUB = 2 * NB, NC = 4 * NB;
-  const int total_sub = sd.n_pre + 3 * NC + sd.n_post;
+  const int total_sub = sd.n_pre + sd.n_ffn + sd.n_post;
   const int frag_wgs = (total_sub * SUB + 3) / 4;
   if ((int)blockIdx.x >= frag_wgs) {  // frame table
     const int idx = ((int)blockIdx.x - frag_wgs) * 256 + threadIdx.x;
@@ -161,10 +163,10 @@ __global__ __launch_bounds__(256) void pack_stream_kernel(StreamDesc sd, u32x4_t
   const int lane = threadIdx.x % kWave, r = lane % 32, g = lane / 32;
   const int sub = fidx / SUB, idx = fidx % SUB;
   const bf16* src;
-  int ld, n, k0;
-  if (sub < sd.n_pre || sub >= sd.n_pre + 3 * NC) {
-    const BlockDesc d = sd.b[sub < sd.n_pre ? sub : sub - 3 * NC];
-    src = d.src; ld = d.ld; n = d.col0 + r; k0 = 16 * idx;
+  int ld, n, k0, f16 = 0;
+  if (sub < sd.n_pre || sub >= sd.n_pre + sd.n_ffn) {
+    const BlockDesc d = sd.b[sub < sd.n_pre ? sub : sub - sd.n_ffn];
+    src = d.src; ld = d.ld; n = d.col0 + r; k0 = 16 * idx; f16 = d.f16;
   } else {
     const int fs = sub - sd.n_pre;
     int kind, c;  // kind 0: V, 1: G, 2: W2
@@ -184,7 +186,10 @@ __global__ __launch_bounds__(256) void pack_stream_kernel(StreamDesc sd, u32x4_t
   }
   unsigned short e[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) e[i] = src[(int64_t)(k0 + frag_k(g, i)) * ld + n].v;
+  for (int i = 0; i < 8; ++i) {
+    e[i] = src[(int64_t)(k0 + frag_k(g, i)) * ld + n].v;
+    if (f16) e[i] = __builtin_bit_cast(unsigned short, (_Float16)__builtin_amdgcn_fmed3f(bf16_bits_to_float(e[i]), -65504.f, 65504.f));
+  }
   u32x4_t o;
   o.x = e[0] | ((unsigned)e[1] << 16);
   o.y = e[2] | ((unsigned)e[3] << 16);
@@ -283,7 +288,16 @@ struct FfnHalfArgs {
   int Mc;                 // context tokens (<= 32 * kCrossTiles)
   int tokens_per_batch;   // a multiple of 128: a workgroup's tokens share one context
   float qscale;           // softmax scale * log2(e)
+  int h_tiled;            // h is in the workgroup-tile order that spatial_pre_kernel writes (h_tile_index)
 };
+
+// Residual stream between two register-resident kernels of the same tiling (workgroup = 128 tokens,
+// wavefront = 32, lane = (token r, half g), result quad q of 32-channel block nb): index of the
+// lane's float4 -- 64 lanes of a wavefront are 1 KiB contiguous.
+template <int NB>
+__host__ __device__ __forceinline__ int64_t h_tile_index(int64_t tile, int nb, int q, int wave, int lane) {
+  return ((((int64_t)tile * NB + nb) * 4 + q) * 4 + wave) * kWave + lane;
+}
 
 // Attention over the context inside the FFN-half kernel: up to 3 tiles of 32 keys, heads of 64
 // channels.  Per head 24 MFMAs, in this order (= the order of the head's fragments in the stream):
@@ -355,7 +369,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (live) v = *reinterpret_cast<const float4*>(hrow + 32 * nb + 8 * q + 4 * g);
+        if (CROSS && a.h_tiled) v = reinterpret_cast<const float4*>(a.h)[h_tile_index<NB>(blockIdx.x, nb, q, wave, lane)];
+        else if (live) v = *reinterpret_cast<const float4*>(hrow + 32 * nb + 8 * q + 4 * g);
         hacc[nb][4 * q + 0] = v.x; hacc[nb][4 * q + 1] = v.y; hacc[nb][4 * q + 2] = v.z; hacc[nb][4 * q + 3] = v.w;
       }
   }

@@ -16,6 +16,7 @@
 #include "k_fused.h"
 #include "k_fused_attn.h"
 #include "k_fused_block.h"
+#include "k_fused_pre.h"
 #include "k_attn_mfma.h"
 #include "k_conv.h"
 #include "k_gemm.h"
@@ -121,7 +122,7 @@ struct Plan {
   // workspace offsets (bytes)
   size_t off_stats, off_rehash, off_pe, off_ctxkv, off_ctxvt, off_vt;
   size_t off_w_in, off_wqkv, off_wo, off_wq2, off_wkv2, off_wo2, off_w1, off_w2, off_w_out;
-  size_t off_a, off_h, off_big, off_ffn_stream, off_attn_stream;
+  size_t off_a, off_h, off_big, off_ffn_stream, off_attn_stream, off_pre_stream;
   size_t weights_bytes, total_bytes;
 };
 
@@ -252,6 +253,8 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   const int ffn_sub = 14 * p->fused_nb + (p->post_fused ? 2 * p->fused_nb + post_ctx_sub(*p) * p->B : 0);
   p->off_ffn_stream = take(p->fused_nb && !p->fused_attn ? (size_t)stream_bytes(ffn_sub, 2 * p->fused_nb) : 0);
   p->off_attn_stream = take(p->fused_attn ? (size_t)stream_bytes(18 * p->fused_nb, 2 * p->fused_nb) : 0);
+  // post_fused: the kernel in front of the self-attention takes W_in, W_q, W_k, W_v as a stream of its own
+  p->off_pre_stream = take(p->post_fused ? (size_t)stream_bytes(4 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->weights_bytes = off - act_end;
   p->total_bytes = off;
   return SI_OK;
@@ -472,30 +475,43 @@ static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, ch
   int n = 0;
   if (p.fused_attn) {  // attention half: W_in blocks, then per head group q, k, v blocks
     const int gw = lcm_int(p.d, 32), nbg = gw / 32, ng = D / gw;
-    for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->w_in), D, 32 * nb};
+    for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->w_in), D, 32 * nb, 0};
     for (int gi = 0; gi < ng; ++gi) {
       const void* mats[3] = {w->wq, w->wk, w->wv};
       for (int kind = 0; kind < 3; ++kind)
-        for (int blk = 0; blk < nbg; ++blk) sd.b[n++] = BlockDesc{cB(mats[kind]), D, gi * gw + 32 * blk};
+        for (int blk = 0; blk < nbg; ++blk) sd.b[n++] = BlockDesc{cB(mats[kind]), D, gi * gw + 32 * blk, 0};
     }
   }
   if (p.post_fused) {  // self-attention out-projection and the query projection of the context attention
-    for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->wo), D, 32 * nb};
-    for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->wq2), D, 32 * nb};
+    for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->wo), D, 32 * nb, 0};
+    for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->wq2), D, 32 * nb, 0};
   }
   // FFN half: out-projection of the last attention, FFN, proj_out
-  for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(spatial ? w->wo2 : w->wo), D, 32 * nb};
+  for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(spatial ? w->wo2 : w->wo), D, 32 * nb, 0};
   sd.n_pre = n;
-  for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->w_out), p.C, 32 * nb};
+  for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->w_out), p.C, 32 * nb, 0};
   sd.n_post = NB;
   sd.w1 = cB(w->w1); sd.w2 = cB(w->w2);
   sd.pe = pe; sd.F = p.F;
   sd.extra_sub = p.post_fused ? post_ctx_sub(p) * p.B : 0;
+  sd.n_ffn = 12 * NB;
   const int total = sd.n_pre + 12 * NB + sd.n_post;
   u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + (p.fused_attn ? p.off_attn_stream : p.off_ffn_stream));
   const int frag_wgs = (total * 2 * NB + 3) / 4, pe_wgs = pe ? (p.F * D + 255) / 256 : 0;
   pack_stream_kernel<NB><<<frag_wgs + pe_wgs, 256, 0, st>>>(sd, stream);
   SI_CHECK_LAUNCH();
+  if (p.post_fused) {  // the stream of the kernel in front of the self-attention: W_in (as fp16), W_q, W_k, W_v
+    StreamDesc pd;
+    int k = 0;
+    for (int nb = 0; nb < NB; ++nb) pd.b[k++] = BlockDesc{cB(w->w_in), D, 32 * nb, 1};
+    const void* mats[3] = {w->wq, w->wk, w->wv};
+    for (int kind = 0; kind < 3; ++kind)
+      for (int nb = 0; nb < NB; ++nb) pd.b[k++] = BlockDesc{cB(mats[kind]), D, 32 * nb, 0};
+    pd.n_pre = k; pd.n_post = 0; pd.n_ffn = 0; pd.extra_sub = 0;
+    pd.w1 = pd.w2 = nullptr; pd.pe = nullptr; pd.F = 0;
+    pack_stream_kernel<NB><<<(k * 2 * NB + 3) / 4, 256, 0, st>>>(pd, reinterpret_cast<u32x4_t*>(ws + p.off_pre_stream));
+    SI_CHECK_LAUNCH();
+  }
   return SI_OK;
 }
 
@@ -595,7 +611,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     pb.n = 0;
     pb.blocks = 0;
     PackBatch* const pbp = &pb;
-    if (!fused_attn) {
+    if (!fused_attn && !p.post_fused) {
       SI_TRY(pack_weight<T>(cT(w->w_in), w_in, C, D, D, 0, D, 0, ring, Mx, kF16, st, pbp));
       SI_TRY(pack_weight<T>(cT(w->wq), wqkv, D, D, D, 0, 3 * D, 0, ring, Mx, false, st, pbp));
       SI_TRY(pack_weight<T>(cT(w->wk), wqkv, D, D, D, 0, 3 * D, D, ring, Mx, false, st, pbp));
@@ -696,7 +712,24 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         continue;
       }
     }
-    if (!fused_attn) {
+    if constexpr (sizeof(T) == 2) {
+      if (p.post_fused) {  // slice-in, proj_in, LN1, q / k / v in one kernel, then the self-attention
+        {
+          StageScope scope("pre_attn_fused", st);
+          SpatialPreArgs pa;
+          pa.x = X; pa.stats = stats;
+          pa.gn_g = cT(w->gn_g); pa.gn_b = cT(w->gn_b); pa.b_in = cT(w->b_in); pa.ln_g = cT(w->ln1_g); pa.ln_b = cT(w->ln1_b);
+          pa.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_pre_stream);
+          pa.h = h; pa.qk = big; pa.vt = reinterpret_cast<bf16*>(vt_lane);
+          pa.M = M; pa.ln_eps = w->ln_eps; pa.qscale = qscale2; pa.win = win;
+          spatial_pre_kernel<10><<<(unsigned)(M / 128), 256, 0, st>>>(pa);
+          SI_CHECK_LAUNCH();
+        }
+        SI_TRY(launch_attention_mfma("self_attn", big, (int64_t)3 * D, big + D, (int64_t)3 * D, reinterpret_cast<bf16*>(vt_lane), a,
+                                     (int64_t)D, p.B * win.Fw, win.Pw, win.Pw, win.Pw, p.heads, 1, st, 0));
+      }
+    }
+    if (!fused_attn && !p.post_fused) {
       {  // slice-in: window -> GroupNorm -> token rows
         StageScope scope("slice_in", st);
         dim3 grid((unsigned)((win.Pw + 63) / 64), (unsigned)((C + 63) / 64), (unsigned)(p.B * win.Fw));
@@ -786,13 +819,14 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         fa.ln_g = cT(w->ln3_g); fa.ln_b = cT(w->ln3_b); fa.b1 = cT(w->b1); fa.b2 = cT(w->b2); fa.b_out = cT(w->b_out);
         fa.ln_eps = w->ln_eps; fa.x = X; fa.out = OUT; fa.win = win;
         fa.ln2_g = fa.ln2_b = fa.b_o2 = nullptr;
-        fa.pitch = 0; fa.ctx_sub0 = 0; fa.Mc = 0; fa.tokens_per_batch = 128; fa.qscale = 0.f;
+        fa.pitch = 0; fa.ctx_sub0 = 0; fa.Mc = 0; fa.tokens_per_batch = 128; fa.qscale = 0.f; fa.h_tiled = 0;
         const unsigned blocks = (unsigned)((M + 127) / 128);
         if (p.post_fused) {  // `a` holds the self-attention output; the kernel goes on from there
           fa.ln2_g = cT(w->ln2_g); fa.ln2_b = cT(w->ln2_b); fa.b_o2 = cT(w->bo2);
           fa.ctx_sub0 = 16 * p.fused_nb;
           fa.pitch = stream_pitch_u4(fa.ctx_sub0 + post_ctx_sub(p) * p.B);
           fa.Mc = p.Mc; fa.tokens_per_batch = (int)(win.Fw * win.Pw); fa.qscale = qscale2;
+          fa.h_tiled = 1;
           ffn_half_kernel<10, true><<<blocks, 256, 0, st>>>(fa);
         } else if (p.fused_nb == 2) ffn_half_kernel<2><<<blocks, 256, 0, st>>>(fa);
         else ffn_half_kernel<10><<<blocks, 256, 0, st>>>(fa);
