@@ -154,7 +154,16 @@ __device__ __forceinline__ void attn_pv(const u32x4_t (&vf)[8], int u, const u32
                                                         oacc[b], 0, 0, 0);
 }
 
-template <int NW>
+// FRAGIN: the operands arrive, and the output leaves, as MFMA fragments written by the register-
+// resident kernels around this one (1 KiB = 64 lanes x 16 bytes each, so every load and store of a
+// wavefront is one contiguous KiB).  Nq % (32 NW) == 0, Nk % 64 == 0, kv_div == 1.
+//   q: [(sequence, head)][32-query tile][k-step 0..3]        lane (query r, half g): channels 16 ks + frag_k(g, e)
+//   k: [(sequence, head)][64-key stage][16 fragments]        in the order of a stage's ring slot: 8 of K
+//      (tile u, k-step: lane (key r, g), same channels), then 8 of V^T (tile u, block b, 16-key step t:
+//      lane (channel r, g), keys 16 t + frag_k(g, e)) -- keys in natural order, no permutation: the
+//      result registers of S^T, packed pairwise, are already in the k-order of these V^T fragments
+//   o: [32-token tile][k-step 0 .. 4 heads - 1 over the block width]   the column operand of the next contraction
+template <int NW, bool FRAGIN = false>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(AttnMfmaArgs a) {
   constexpr int NS = kAttnStages, FR = 16;  // fragments per stage: 8 of K (2 tiles x 4 k-steps), 8 of V^T (2 tiles x 2 blocks x 2 k-steps)
   constexpr int PER = FR / NW;              // stage loads per lane
@@ -182,22 +191,25 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   // Address = scalar base (stage, fragment) + per-lane byte offset; the ragged last stage clamps
   // per lane instead (keys past the end are masked, so what they load only has to be finite).
   const int kap = 16 * (r / 16) + kappa16(r % 16);
-  const unsigned kvoff = (unsigned)(((int64_t)kap * a.ldk + 8 * g) * 2);
-  const unsigned vvoff = (unsigned)(((int64_t)r * a.Nkp + 8 * g) * 2);
+  const unsigned kvoff = FRAGIN ? (unsigned)(lane * 16) : (unsigned)(((int64_t)kap * a.ldk + 8 * g) * 2);
+  const unsigned vvoff = FRAGIN ? (unsigned)(lane * 16) : (unsigned)(((int64_t)r * a.Nkp + 8 * g) * 2);
   const char* kb = reinterpret_cast<const char*>(a.k + (int64_t)ks * a.Nk * a.ldk + h * 64);
   const char* vb = reinterpret_cast<const char*>(a.vt + ((int64_t)ks * a.heads * 64 + h * 64) * a.Nkp);
+  // FRAGIN: the pair's stage blocks, 16 KiB per stage
+  const char* fb = reinterpret_cast<const char*>(a.k) + ((int64_t)(ks * a.heads + h) * nst) * (16 * 1024);
   // Full stages are issued in order, so every fragment's source is a running scalar pointer that
   // advances by a fixed stride per stage (64 key rows of K; 64 keys = 128 bytes of a V^T row), and
   // the ring slot is a running scalar too: a stage's loads cost a few scalar additions.
-  const int64_t kstride = (int64_t)64 * a.ldk * 2;
+  const int64_t kstride = FRAGIN ? 16 * 1024 : (int64_t)64 * a.ldk * 2;
+  const int64_t vstride = FRAGIN ? 16 * 1024 : 128;
   const char* kcur[PER / 2];
   const char* vcur[PER / 2];
   unsigned loff[PER];
 #pragma unroll
   for (int i = 0; i < PER / 2; ++i) {
     const int idk = wave_s + NW * i, idv = wave_s + NW * (i + PER / 2), j = idv - 8;
-    kcur[i] = kb + ((int64_t)(32 * (idk / 4)) * a.ldk + 16 * (idk % 4)) * 2;
-    vcur[i] = vb + ((int64_t)(32 * ((j / 2) % 2)) * a.Nkp + 32 * (j / 4) + 16 * (idv % 2)) * 2;
+    kcur[i] = FRAGIN ? fb + idk * 1024 : kb + ((int64_t)(32 * (idk / 4)) * a.ldk + 16 * (idk % 4)) * 2;
+    vcur[i] = FRAGIN ? fb + idv * 1024 : vb + ((int64_t)(32 * ((j / 2) % 2)) * a.Nkp + 32 * (j / 4) + 16 * (idv % 2)) * 2;
     loff[i] = (unsigned)(idk * kWave * 16);
     loff[PER / 2 + i] = (unsigned)(idv * kWave * 16);
   }
@@ -215,7 +227,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
 #pragma unroll
     for (int i = 0; i < PER / 2; ++i) {
       asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vvoff), "s"(vcur[i]), "s"(islot + loff[PER / 2 + i]) : "memory");
-      vcur[i] += 128;
+      vcur[i] += vstride;
     }
     next_slot();
   };
@@ -240,14 +252,19 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   };
   auto issue = [&](int st) {
     if (st < nfull) issue_full();
-    else if (st < nst) issue_ragged(st);
+    else if (!FRAGIN && st < nst) issue_ragged(st);
   };
 #pragma unroll
   for (int st = 0; st < NS - 1; ++st) issue(st);
 
   // ---- this lane's query as column operand (head channels in natural order, as K's fragments)
   bf16x8_t qop[4];
-  {
+  if constexpr (FRAGIN) {
+    const u32x4_t* qf = reinterpret_cast<const u32x4_t*>(a.q) +
+                        (((int64_t)(s * a.heads + h) * (a.Nq / 32) + qtile * NW + wave) * 4) * kWave + lane;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) qop[s4] = __builtin_bit_cast(bf16x8_t, qf[s4 * kWave]);
+  } else {
     const bf16* qrow = a.q + ((int64_t)s * a.Nq + (qvalid ? qi : a.Nq - 1)) * a.ldq + h * 64 + 8 * g;
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) qop[s4] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(qrow + 16 * s4));
@@ -347,7 +364,22 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   f32x16_t(&oacc)[2] = as.oacc;
 
   // ---- O^T / l: register 4q + j of block b is head channel 32b + 8q + 4g + j of this lane's query
-  if (qvalid) {
+  if constexpr (FRAGIN) {
+    const float inv = 1.0f / lsum;
+    const int64_t tile = (int64_t)s * (a.Nq / 32) + qtile * NW + wave;
+    u32x4_t* of = reinterpret_cast<u32x4_t*>(a.o) + (tile * (a.heads * 4) + 4 * h) * kWave + lane;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        u32x4_t v;
+        v.x = pack_bf16x2(oacc[b][8 * hf + 0] * inv, oacc[b][8 * hf + 1] * inv);
+        v.y = pack_bf16x2(oacc[b][8 * hf + 2] * inv, oacc[b][8 * hf + 3] * inv);
+        v.z = pack_bf16x2(oacc[b][8 * hf + 4] * inv, oacc[b][8 * hf + 5] * inv);
+        v.w = pack_bf16x2(oacc[b][8 * hf + 6] * inv, oacc[b][8 * hf + 7] * inv);
+        of[(2 * b + hf) * kWave] = v;
+      }
+  } else if (qvalid) {
     const float inv = 1.0f / lsum;
     const int64_t m = (int64_t)s * a.Nq + qi;
     bf16* orow = a.o + m * a.ldo + h * 64 + 4 * g;

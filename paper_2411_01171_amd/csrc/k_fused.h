@@ -288,7 +288,8 @@ struct FfnHalfArgs {
   int Mc;                 // context tokens (<= 32 * kCrossTiles)
   int tokens_per_batch;   // a multiple of 128: a workgroup's tokens share one context
   float qscale;           // softmax scale * log2(e)
-  int h_tiled;            // h is in the workgroup-tile order that spatial_pre_kernel writes (h_tile_index)
+  int h_tiled;            // h is in the workgroup-tile order that spatial_pre_kernel writes (h_tile_index) and o
+                          // holds the attention kernel's output fragments ([32-token tile][k-step][lane])
 };
 
 // Residual stream between two register-resident kernels of the same tiling (workgroup = 128 tokens,
@@ -380,6 +381,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const bf16* orow = a.o + (live ? m : 0) * D;
 #pragma unroll
     for (int s2 = 0; s2 < SUB; ++s2) {
+      if (CROSS && a.h_tiled) {  // fragments as the attention kernel leaves them: [32-token tile][k-step][lane]
+        aop[s2] = __builtin_bit_cast(bf16x8_t, reinterpret_cast<const u32x4_t*>(a.o)[(((int64_t)blockIdx.x * 4 + wave) * SUB + s2) * kWave + lane]);
+        continue;
+      }
       uint2 lo = make_uint2(0, 0), hi = make_uint2(0, 0);
       if (live) {
         lo = *reinterpret_cast<const uint2*>(orow + 16 * s2 + 4 * g);

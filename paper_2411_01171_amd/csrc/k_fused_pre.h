@@ -5,9 +5,10 @@
 // weights arrive as a fragment stream through the LDS ring.  The x operand is gathered straight
 // from the feature tensor: for one channel the 32 tokens of a wavefront are 64 contiguous bytes.
 // proj_in runs on fp16 operands (the normalised input is bounded; three more significand bits than
-// bf16), everything behind LN1 on bf16.  V is formed transposed (activations as the row operand),
-// so a lane holds 4 consecutive keys of one channel: 8-byte stores into the keys-contiguous copy
-// that the attention kernel streams.
+// bf16), everything behind LN1 on bf16.  q, k and v leave as the MFMA fragments that the attention
+// kernel consumes (attn_mfma_kernel, FRAGIN): a result block's register halves, packed to bf16, are
+// such fragments as they stand -- for v with the operands swapped (activations as the row operand),
+// which yields V^T.  Every store of a wavefront is one contiguous KiB.
 #pragma once
 #include "k_fused.h"
 
@@ -19,8 +20,9 @@ struct SpatialPreArgs {
   const bf16 *gn_g, *gn_b, *b_in, *ln_g, *ln_b;
   const u32x4_t* stream;  // W_in blocks (fp16), then W_q, W_k, W_v blocks: 4 * NB sub-chunks
   float* h;               // residual stream, workgroup-tile order (h_tile_index)
-  bf16* qk;               // [M, 3D] rows: q * qscale in columns [0, D), k in [D, 2D)
-  bf16* vt;               // [sequence][D][Pw]: values, keys contiguous
+  u32x4_t* qf;            // q * qscale as fragments: [(sequence, head)][32-query tile][k-step 0..3][lane]
+  u32x4_t* kvf;           // k and v^T as fragments: [(sequence, head)][64-key stage][16][lane], the attention
+                          // kernel's stage order (attn_mfma_kernel, FRAGIN)
   int64_t M;              // tokens of the window, a multiple of 128; sequence (b, f) = rows (b*Fw + f)*Pw + i
   float ln_eps, qscale;
   Window win;             // p0 == 0, Pw == P, P % 128 == 0
@@ -42,7 +44,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int64_t m0 = (int64_t)blockIdx.x * 128;
   const int seq = (int)(m0 / w.Pw), b = seq / w.Fw, f = w.f0 + seq % w.Fw;
   const int key0 = (int)(m0 % w.Pw) + wave * 32;  // first position of this wavefront inside its frame
-  const int64_t m = m0 + wave * 32 + r;
 
   {  // GroupNorm of this frame as one multiply-add per channel, and the other per-channel tables
     const int ng = w.C / w.G;
@@ -169,8 +170,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
   }
 
-  // ---- q (scaled) and k: rows of the token; 4 consecutive channels per store
-  bf16* qrow = a.qk + m * (3 * D) + 4 * g;
+  // ---- q (scaled) and k: a result block's two register halves are two fragments as they are (lane =
+  // token, elements = channels 16 ks + frag_k(g, e) of the head) -- one contiguous KiB per store
+  constexpr int NH = D / 64;
+  const int tile = key0 / 32, tiles = w.Pw / 32;  // this wavefront's 32 tokens inside their sequence
+  u32x4_t* const qdst = a.qf + ((int64_t)seq * NH * tiles + tile) * 4 * kWave + lane;
+  u32x4_t* const kvdst = a.kvf + (((int64_t)seq * NH * (tiles / 2) + tile / 2) * 16 + 4 * (tile % 2)) * kWave + lane;
 #pragma unroll
   for (int blk = 0; blk < 2 * NB; ++blk) {
     f32x16_t acc;
@@ -187,17 +192,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       SI_STEP_CLOSE();
     }
     const float sc = blk < NB ? a.qscale : 1.f;
+    const int nb = blk % NB, hd = nb / 2;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      uint2 v;
-      v.x = pack_bf16x2(acc[4 * q + 0] * sc, acc[4 * q + 1] * sc);
-      v.y = pack_bf16x2(acc[4 * q + 2] * sc, acc[4 * q + 3] * sc);
-      *reinterpret_cast<uint2*>(qrow + 32 * blk + 8 * q) = v;  // block NB + nb of k lands at column D + 32 nb
+    for (int hf = 0; hf < 2; ++hf) {
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = acc[8 * hf + e] * sc;
+      const u32x4_t o = __builtin_bit_cast(u32x4_t, to_operand(v));
+      const int ks = 2 * (nb % 2) + hf;
+      if (blk < NB) qdst[((int64_t)hd * tiles * 4 + ks) * kWave] = o;
+      else kvdst[((int64_t)hd * (tiles / 2) * 16 + ks) * kWave] = o;
     }
   }
 
-  // ---- V^T: activations as the row operand, so lane = channel 32nb + r, register 4q + j = token 8q + 4g + j
-  bf16* vrow = a.vt + ((int64_t)seq * D + r) * w.Pw + key0 + 4 * g;
+  // ---- V^T: activations as the row operand, so lane = channel 32nb + r, register 4q + j = token 8q + 4g + j:
+  // the two register halves are the V^T fragments of 16-key steps 0 and 1 (keys 16 t + frag_k(g, e))
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     f32x16_t acc;
@@ -214,11 +223,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       SI_STEP_CLOSE();
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      uint2 v;
-      v.x = pack_bf16x2(acc[4 * q + 0], acc[4 * q + 1]);
-      v.y = pack_bf16x2(acc[4 * q + 2], acc[4 * q + 3]);
-      *reinterpret_cast<uint2*>(vrow + (int64_t)(32 * nb) * w.Pw + 8 * q) = v;
+    for (int hf = 0; hf < 2; ++hf) {
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = acc[8 * hf + e];
+      kvdst[((int64_t)(nb / 2) * (tiles / 2) * 16 + 8 + 2 * (nb % 2) + hf) * kWave] = __builtin_bit_cast(u32x4_t, to_operand(v));
     }
   }
 #undef SI_REFILL

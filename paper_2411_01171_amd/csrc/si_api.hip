@@ -720,13 +720,21 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
           pa.x = X; pa.stats = stats;
           pa.gn_g = cT(w->gn_g); pa.gn_b = cT(w->gn_b); pa.b_in = cT(w->b_in); pa.ln_g = cT(w->ln1_g); pa.ln_b = cT(w->ln1_b);
           pa.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_pre_stream);
-          pa.h = h; pa.qk = big; pa.vt = reinterpret_cast<bf16*>(vt_lane);
+          pa.h = h; pa.qf = reinterpret_cast<u32x4_t*>(big); pa.kvf = reinterpret_cast<u32x4_t*>(big + M * D);
           pa.M = M; pa.ln_eps = w->ln_eps; pa.qscale = qscale2; pa.win = win;
           spatial_pre_kernel<10><<<(unsigned)(M / 128), 256, 0, st>>>(pa);
           SI_CHECK_LAUNCH();
         }
-        SI_TRY(launch_attention_mfma("self_attn", big, (int64_t)3 * D, big + D, (int64_t)3 * D, reinterpret_cast<bf16*>(vt_lane), a,
-                                     (int64_t)D, p.B * win.Fw, win.Pw, win.Pw, win.Pw, p.heads, 1, st, 0));
+        {  // operands and output as fragments (q: M*D values at big, k / v^T stage blocks behind them)
+          StageScope scope("self_attn", st);
+          AttnMfmaArgs aa;
+          aa.q = big; aa.ldq = 0; aa.k = big + M * D; aa.ldk = 0; aa.vt = nullptr; aa.o = a; aa.ldo = 0;
+          aa.Nq = aa.Nk = aa.Nkp = win.Pw; aa.heads = p.heads; aa.kv_div = 1; aa.o_frag = 0;
+          aa.nqt = win.Pw / 128;
+          aa.ntiles = aa.nqt * p.heads * p.B * win.Fw;
+          attn_mfma_kernel<4, true><<<(unsigned)((aa.ntiles + 7) / 8 * 8), 256, 0, st>>>(aa);
+          SI_CHECK_LAUNCH();
+        }
       }
     }
     if (!fused_attn && !p.post_fused) {
