@@ -78,27 +78,31 @@ __device__ constexpr float kGeluC[kGeluDeg + 1] = {
 //   value = UV[e] + bv[off(e)], gate = UG[e] + bg[off(e)], gv[e] = value * gate * Phi(gate)
 // off(e): column of result register e relative to the lane's first column (see frag_k).
 __host__ __device__ constexpr int reg_col(int e) { return 16 * (e / 8) + ((e % 8) < 4 ? (e % 8) : (e % 8) + 4); }
-constexpr int kGeluStages = kGeluDeg + 9;
+constexpr int kGeluStages = kGeluDeg + 11;
 
+// Stage 0 only issues the LDS reads of the group's biases; they are consumed three stages (three
+// MFMAs) later, so no stage waits for a read issued just before it.
 template <int E0, int G>
 struct GegluGroup {
-  float x[G], v[G], xc[G], t[G], p[G];
+  float x[G], v[G], xc[G], t[G], p[G], bgr[G], bvr[G];
   __device__ __forceinline__ void stage(int s, const f32x16_t& UV, const f32x16_t& UG, const float* bv, const float* bg,
                                         float* gv) {
 #pragma unroll
     for (int i = 0; i < G; ++i) {
       const int e = E0 + i;
-      if (s == 0) x[i] = UG[e];
-      else if (s == 1) v[i] = UV[e];
-      else if (s == 2) x[i] += bg[reg_col(e)];
-      else if (s == 3) v[i] += bv[reg_col(e)];
-      else if (s == 4) xc[i] = __builtin_amdgcn_fmed3f(x[i], -kGeluClamp, kGeluClamp);
-      else if (s == 5) t[i] = xc[i] * xc[i];
-      else if (s == 6) p[i] = fmaf(kGeluC[kGeluDeg], t[i], kGeluC[kGeluDeg - 1]);
-      else if (s >= 7 && s < 6 + kGeluDeg) p[i] = fmaf(p[i], t[i], kGeluC[kGeluDeg + 5 - s]);
-      else if (s == 6 + kGeluDeg) p[i] = fmaf(p[i], xc[i], 0.5f);  // Phi(gate)
-      else if (s == 7 + kGeluDeg) x[i] = x[i] * v[i];
-      else if (s == 8 + kGeluDeg) gv[e] = x[i] * p[i];
+      if (s == 0) bgr[i] = bg[reg_col(e)];
+      else if (s == 1) bvr[i] = bv[reg_col(e)];
+      else if (s == 2) x[i] = UG[e];
+      else if (s == 3) v[i] = UV[e];
+      else if (s == 4) x[i] += bgr[i];
+      else if (s == 5) v[i] += bvr[i];
+      else if (s == 6) xc[i] = __builtin_amdgcn_fmed3f(x[i], -kGeluClamp, kGeluClamp);
+      else if (s == 7) t[i] = xc[i] * xc[i];
+      else if (s == 8) p[i] = fmaf(kGeluC[kGeluDeg], t[i], kGeluC[kGeluDeg - 1]);
+      else if (s >= 9 && s < 8 + kGeluDeg) p[i] = fmaf(p[i], t[i], kGeluC[kGeluDeg + 7 - s]);
+      else if (s == 8 + kGeluDeg) p[i] = fmaf(p[i], xc[i], 0.5f);  // Phi(gate)
+      else if (s == 9 + kGeluDeg) x[i] = x[i] * v[i];
+      else if (s == 10 + kGeluDeg) gv[e] = x[i] * p[i];
     }
   }
 };
