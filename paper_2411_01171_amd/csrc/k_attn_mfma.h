@@ -30,7 +30,14 @@ struct AttnMfmaArgs {
   int64_t ldo;
   int Nq, Nk, Nkp, heads, kv_div;
   int o_frag;        // 0: o rows of ldo elements; else o is a fragment-order buffer of that many channels per token
-  int nqt, ntiles;   // query tiles per (sequence, head) pair; nqt * heads * sequences (the grid is 8 * ceil(ntiles / 8))
+  int nqt, ntiles;   // query tiles per (sequence, head) pair; nqt * heads * sequences * ksplit (the grid is 8 * ceil(ntiles / 8))
+  // FRAGIN only.  ksplit == 2: a workgroup takes one half of the keys; half kh leaves its output,
+  // normalised by its own row sum, in o (kh = 0) / o2 (kh = 1) and, per lane, (reference maximum,
+  // row sum) in ml[(kh * tiles + tile) * 64 + lane] -- whoever reads o merges the halves.
+  int ksplit;
+  bf16* o2;
+  float2* ml;
+  int64_t tiles32;   // 32-query tiles of all sequences
 };
 
 constexpr int kAttnStages = 3;  // 48 KiB of LDS: three 4-wavefront workgroups per CU
@@ -179,12 +186,14 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   const int chunk = (a.ntiles + 7) / 8;
   const int work = (int)(blockIdx.x % 8) * chunk + (int)(blockIdx.x / 8);
   if (work >= a.ntiles) return;
-  const int qtile = work % a.nqt, pair = work / a.nqt;
+  const int ksplit = FRAGIN ? a.ksplit : 1;
+  // work list: the query tiles of one (pair, key half) after the other
+  const int qtile = work % a.nqt, kh = (work / a.nqt) % ksplit, pair = work / (a.nqt * ksplit);
   const int h = pair % a.heads, s = pair / a.heads, ks = s / a.kv_div;
   const int qi = (qtile * NW + wave) * 32 + r;
   const bool qvalid = qi < a.Nq;
-  const int nst = (a.Nk + 63) / 64;
-  const int nfull = a.Nk / 64;  // stages without missing keys (Nkp >= Nk: their V^T groups are in-row too)
+  const int nst = (a.Nk + 63) / 64 / ksplit;  // stages of this workgroup (FRAGIN: Nk % (64 ksplit) == 0)
+  const int nfull = FRAGIN ? nst : a.Nk / 64;  // stages without missing keys (Nkp >= Nk: their V^T groups are in-row too)
 
   // ---- stage loads: fragment ids wave + NW*i, i < PER.  id < 8: K, tile u = id / 4, k-step id % 4;
   // id >= 8: V^T, tile u = (id - 8) / 4, channel block ((id - 8) / 2) % 2, k-step id % 2.
@@ -196,7 +205,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   const char* kb = reinterpret_cast<const char*>(a.k + (int64_t)ks * a.Nk * a.ldk + h * 64);
   const char* vb = reinterpret_cast<const char*>(a.vt + ((int64_t)ks * a.heads * 64 + h * 64) * a.Nkp);
   // FRAGIN: the pair's stage blocks, 16 KiB per stage
-  const char* fb = reinterpret_cast<const char*>(a.k) + ((int64_t)(ks * a.heads + h) * nst) * (16 * 1024);
+  const char* fb = reinterpret_cast<const char*>(a.k) + ((int64_t)((ks * a.heads + h) * ksplit + kh) * nst) * (16 * 1024);
   // Full stages are issued in order, so every fragment's source is a running scalar pointer that
   // advances by a fixed stride per stage (64 key rows of K; 64 keys = 128 bytes of a V^T row), and
   // the ring slot is a running scalar too: a stage's loads cost a few scalar additions.
@@ -367,7 +376,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   if constexpr (FRAGIN) {
     const float inv = 1.0f / lsum;
     const int64_t tile = (int64_t)s * (a.Nq / 32) + qtile * NW + wave;
-    u32x4_t* of = reinterpret_cast<u32x4_t*>(a.o) + (tile * (a.heads * 4) + 4 * h) * kWave + lane;
+    u32x4_t* of = reinterpret_cast<u32x4_t*>(kh ? a.o2 : a.o) + (tile * (a.heads * 4) + 4 * h) * kWave + lane;
+    if (ksplit > 1) a.ml[(((int64_t)kh * a.heads + h) * a.tiles32 + tile) * kWave + lane] = make_float2(-as.minit[0], lsum);
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll

@@ -292,6 +292,9 @@ struct FfnHalfArgs {
   int Mc;                 // context tokens (<= 32 * kCrossTiles)
   int tokens_per_batch;   // a multiple of 128: a workgroup's tokens share one context
   float qscale;           // softmax scale * log2(e)
+  const bf16* o2;         // with h_tiled, or NULL: the attention ran in two key halves; o / o2 hold each half's
+  const float2* ml;       // output and ml[(half * heads + head) * tiles32 + tile][lane] its (reference maximum in
+  int64_t tiles32;        // base-2 exponent units, row sum); the halves are merged as the operands are loaded
   int h_tiled;            // h is in the workgroup-tile order that spatial_pre_kernel writes (h_tile_index) and o
                           // holds the attention kernel's output fragments ([32-token tile][k-step][lane])
 };
@@ -383,10 +386,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   bf16x8_t aop[SUB];
   {
     const bf16* orow = a.o + (live ? m : 0) * D;
+    // two key halves: softmax weights of the halves per head, w = l 2^(m - max m) / sum of the same
+    float w0[CROSS ? NB / 2 : 1], w1[CROSS ? NB / 2 : 1];
+    const int64_t t32 = (int64_t)blockIdx.x * 4 + wave;
+    if (CROSS && a.h_tiled && a.o2) {
+#pragma unroll
+      for (int hd = 0; hd < NB / 2; ++hd) {
+        const float2 p0 = a.ml[((int64_t)hd * a.tiles32 + t32) * kWave + lane];
+        const float2 p1 = a.ml[((int64_t)(NB / 2 + hd) * a.tiles32 + t32) * kWave + lane];
+        const float mx = fmaxf(p0.x, p1.x);
+        const float a0 = p0.y * __builtin_amdgcn_exp2f(p0.x - mx), a1 = p1.y * __builtin_amdgcn_exp2f(p1.x - mx);
+        const float inv = 1.0f / (a0 + a1);
+        w0[hd] = a0 * inv;
+        w1[hd] = a1 * inv;
+      }
+    }
 #pragma unroll
     for (int s2 = 0; s2 < SUB; ++s2) {
       if (CROSS && a.h_tiled) {  // fragments as the attention kernel leaves them: [32-token tile][k-step][lane]
-        aop[s2] = __builtin_bit_cast(bf16x8_t, reinterpret_cast<const u32x4_t*>(a.o)[(((int64_t)blockIdx.x * 4 + wave) * SUB + s2) * kWave + lane]);
+        const u32x4_t f0 = reinterpret_cast<const u32x4_t*>(a.o)[(t32 * SUB + s2) * kWave + lane];
+        if (a.o2) {
+          const u32x4_t f1 = reinterpret_cast<const u32x4_t*>(a.o2)[(t32 * SUB + s2) * kWave + lane];
+          const float u0 = w0[CROSS ? s2 / 4 : 0], u1 = w1[CROSS ? s2 / 4 : 0];
+          const unsigned x0[4] = {f0.x, f0.y, f0.z, f0.w}, x1[4] = {f1.x, f1.y, f1.z, f1.w};
+          float v[8];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            v[2 * i] = u0 * __uint_as_float(x0[i] << 16) + u1 * __uint_as_float(x1[i] << 16);
+            v[2 * i + 1] = u0 * __uint_as_float(x0[i] & 0xffff0000u) + u1 * __uint_as_float(x1[i] & 0xffff0000u);
+          }
+          aop[s2] = to_operand(v);
+        } else {
+          aop[s2] = __builtin_bit_cast(bf16x8_t, f0);
+        }
         continue;
       }
       uint2 lo = make_uint2(0, 0), hi = make_uint2(0, 0);

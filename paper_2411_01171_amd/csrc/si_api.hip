@@ -406,6 +406,7 @@ static si_status launch_attention_mfma(const char* stage, const bf16* q, int64_t
   a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.o = o; a.ldo = ldo;
   a.Nq = Nq; a.Nk = Nk; a.Nkp = Nkp; a.heads = heads; a.kv_div = kv_div;
   a.o_frag = o_frag;
+  a.ksplit = 1; a.o2 = nullptr; a.ml = nullptr; a.tiles32 = 0;
   // 8 wavefronts share the key / value stages when that still leaves several workgroups for every CU
   const int64_t wg8 = (int64_t)((Nq + 255) / 256) * heads * S;
   if (wg8 >= 1024) {
@@ -712,6 +713,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         continue;
       }
     }
+    int ksplit = 1;
     if constexpr (sizeof(T) == 2) {
       if (p.post_fused) {  // slice-in, proj_in, LN1, q / k / v in one kernel, then the self-attention
         {
@@ -731,7 +733,16 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
           aa.q = big; aa.ldq = 0; aa.k = big + M * D; aa.ldk = 0; aa.vt = nullptr; aa.o = a; aa.ldo = 0;
           aa.Nq = aa.Nk = aa.Nkp = win.Pw; aa.heads = p.heads; aa.kv_div = 1; aa.o_frag = 0;
           aa.nqt = win.Pw / 128;
-          aa.ntiles = aa.nqt * p.heads * p.B * win.Fw;
+          // two key halves per query tile when one workgroup per tile would leave the last round of
+          // workgroups (2 per CU) less than half full; the halves' statistics live in the (otherwise
+          // unused) transposed-value buffer, the second half's output behind q, k, v
+          const int64_t wgs1 = (int64_t)aa.nqt * p.heads * p.B * win.Fw;
+          aa.ksplit = (win.Pw % 256 == 0 && wgs1 > 512 && wgs1 % 512 > 0 && wgs1 % 512 <= 256) ? 2 : 1;
+          ksplit = aa.ksplit;
+          aa.o2 = big + 3 * M * D;
+          aa.ml = reinterpret_cast<float2*>(vt_lane);
+          aa.tiles32 = M / 32;
+          aa.ntiles = (int)(wgs1 * aa.ksplit);
           attn_mfma_kernel<4, true><<<(unsigned)((aa.ntiles + 7) / 8 * 8), 256, 0, st>>>(aa);
           SI_CHECK_LAUNCH();
         }
@@ -828,6 +839,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         fa.ln_eps = w->ln_eps; fa.x = X; fa.out = OUT; fa.win = win;
         fa.ln2_g = fa.ln2_b = fa.b_o2 = nullptr;
         fa.pitch = 0; fa.ctx_sub0 = 0; fa.Mc = 0; fa.tokens_per_batch = 128; fa.qscale = 0.f; fa.h_tiled = 0;
+        fa.o2 = nullptr; fa.ml = nullptr; fa.tiles32 = 0;
         const unsigned blocks = (unsigned)((M + 127) / 128);
         if (p.post_fused) {  // `a` holds the self-attention output; the kernel goes on from there
           fa.ln2_g = cT(w->ln2_g); fa.ln2_b = cT(w->ln2_b); fa.b_o2 = cT(w->bo2);
@@ -835,6 +847,9 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
           fa.pitch = stream_pitch_u4(fa.ctx_sub0 + post_ctx_sub(p) * p.B);
           fa.Mc = p.Mc; fa.tokens_per_batch = (int)(win.Fw * win.Pw); fa.qscale = qscale2;
           fa.h_tiled = 1;
+          if (ksplit == 2) {
+            fa.o2 = big + 3 * M * D; fa.ml = reinterpret_cast<const float2*>(vt_lane); fa.tiles32 = M / 32;
+          }
           ffn_half_kernel<10, true><<<blocks, 256, 0, st>>>(fa);
         } else if (p.fused_nb == 2) ffn_half_kernel<2><<<blocks, 256, 0, st>>>(fa);
         else ffn_half_kernel<10><<<blocks, 256, 0, st>>>(fa);

@@ -180,6 +180,18 @@ def test_spatial_320_whole_tile_frames_bf16(B, hw, M, slice_len):
     _check(spec, x, w, ctx, slice_len)
 
 
+@pytest.mark.parametrize("slice_len", [26, 13])
+def test_spatial_320_attention_in_two_key_halves_bf16(slice_len):
+    """C = 320, 26 frames of 256 positions.  Unsliced, the self-attention has 520 workgroups of 128
+    queries -- one full round of the chip plus a few -- so it runs as two key halves per query tile
+    whose outputs are merged by the kernel behind it; 13 frames per slice: 260 workgroups, no split."""
+    spec = tiny_spec(wl.SPATIAL, B=2, C=320, F=26, H=16, W=16, heads=5, dim_head=64, groups=32, M=7, Cc=24,
+                     dtype="bf16")
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.03)
+    _check(spec, x, w, ctx, slice_len)
+
+
 @pytest.mark.parametrize("kind,C,heads", [("spatial", 640, 10), ("temporal", 640, 10), ("spatial", 1280, 20), ("temporal", 1280, 20)])
 def test_wide_blocks_small_windows_bf16(kind, C, heads):
     """C = 640 / 1280 (the staged path of the deep levels) on a few dozen tokens with random norm
