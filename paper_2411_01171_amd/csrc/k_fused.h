@@ -216,6 +216,13 @@ __global__ __launch_bounds__(256) void pack_stream_kernel(StreamDesc sd, u32x4_t
 #define SI_RING_SLOTS 4
 #endif
 constexpr int kRingSlots = SI_RING_SLOTS;
+// The barrier that closes a step of the ring.  What it orders is (1) every wavefront's own
+// global->LDS loads of sub-chunk cur + 2, awaited through vmcnt just before, and (2) the reads of
+// the slot that the loads issued right after it overwrite -- the slot of the step before, whose
+// last reads were consumed (hence complete) ten MFMAs ago.  LDS reads issued in the step that
+// closes target slots that stay untouched for two more steps, so they need not have returned: a
+// bare s_barrier, without the wait for all LDS traffic that __syncthreads() adds.
+#define SI_RING_BARRIER() __builtin_amdgcn_s_barrier()
 static_assert(kRingSlots >= 4 && kRingSlots <= 6, "ring depth");
 template <int SUB>
 struct WeightPipe {
@@ -484,14 +491,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   __builtin_amdgcn_sched_barrier(0);                                             \
   Pipe::template wait_step<0>(cur, TOTAL_SUB);                                   \
   ++cur;                                                                         \
-  __syncthreads()
+  SI_RING_BARRIER()
   // as above when EXTRA (0 or 2) further loads were issued after this step's weight loads
 #define SI_STEP_CLOSE_EXTRA(EXTRA)                                               \
   __builtin_amdgcn_sched_barrier(0);                                             \
   if ((EXTRA) == 2) Pipe::template wait_step<2>(cur, TOTAL_SUB);                 \
   else Pipe::template wait_step<0>(cur, TOTAL_SUB);                              \
   ++cur;                                                                         \
-  __syncthreads()
+  SI_RING_BARRIER()
   // fragment f of the current sub-chunk, and its replacement FIFO fragments further down the stream
 #define SI_FRAG(f) fifo[(f) % FIFO]
 #define SI_REFILL(f)                                                                                 \

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   __builtin_amdgcn_sched_barrier(0);             \
   Pipe::template wait_step<0>(cur, TOTAL_SUB);   \
   ++cur;                                         \
-  __syncthreads()
+  SI_RING_BARRIER()
 #define SI_FRAG(f) fifo[(f) % FIFO]
 #define SI_REFILL(f)                                                                                 \
   fifo[(f) % FIFO] = __builtin_bit_cast(bf16x8_t, (f) < FIFO ? slot_c[((f) + FIFO) * kWave + lane]   \
