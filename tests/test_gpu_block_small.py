@@ -270,6 +270,7 @@ def test_deterministic():
 
 
 @pytest.mark.parametrize("cfg,kw", [("cfg2", dict(H=8, W=8, slice_len=24)), ("cfg3", dict(C=64, F=3, H=8, W=8, heads=1, dim_head=64, ctx_tokens=5, ctx_dim=16)),
+                                    ("cfg4s", dict(F=3, H=8, W=16, ctx_tokens=5, ctx_dim=16)),   # the three-kernel spatial window
                                     ("cfg1", dict())])
 def test_packed_weights_flag_reuses_the_workspace(cfg, kw):
     """A second call that promises unchanged weights skips the re-layout and must give the same bits, also for another input."""
@@ -296,3 +297,28 @@ def test_packed_weights_flag_reuses_the_workspace(cfg, kw):
         assert torch.equal(out, ref)
     with pytest.raises(si.SiError):
         si.si_block_forward_ex(xa, wd, ctx, out, axis, spec.slice_len, ws, 8)             # unknown flag
+
+
+def test_packed_weights_flag_takes_a_new_context():
+    """The three-kernel spatial window keeps the context's keys / values as fragments behind the
+    weight fragments: a call that promises unchanged weights must still re-derive them from the
+    context it is given."""
+    import torch
+    import paper_2411_01171_amd as si
+    from gpu_helpers import AXIS, device_weights, to_dev
+    spec = wl.scaled(wl.CONFIGS["cfg4s"], F=2, H=8, W=16, ctx_tokens=7, ctx_dim=16)
+    x = to_dev(wl.make_x(spec), spec.dtype)
+    ctx1 = to_dev(wl.make_context(spec), spec.dtype)
+    ctx2 = to_dev(wl.make_context(spec, seed=spec.seed + 3), spec.dtype)
+    assert not torch.equal(ctx1, ctx2)
+    wd = device_weights(spec, wl.make_weights(spec, randomize_affine=True))
+    axis = AXIS[spec.slice_axis]
+    ws = torch.empty(si.si_workspace_bytes(x, wd, ctx1, axis, spec.slice_len), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty_like(ws)
+    ref2, out = torch.empty_like(x), torch.empty_like(x)
+    si.si_block_forward(x, wd, ctx2, ref2, axis, spec.slice_len, ws2)
+    si.si_block_forward(x, wd, ctx1, out, axis, spec.slice_len, ws)                        # packs, context 1
+    assert not torch.equal(out, ref2)
+    si.si_block_forward_ex(x, wd, ctx2, out, axis, spec.slice_len, ws, si.SI_FWD_WEIGHTS_PACKED)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref2)
