@@ -27,18 +27,24 @@ struct TemporalBlockArgs {
   const bf16 *gn_g, *gn_b, *b_in, *ln1_g, *ln1_b, *b_o, *ln3_g, *ln3_b, *b1, *b2, *b_out;
   const float* pe;      // [F, D] frame embedding or NULL
   const u32x4_t* stream;  // W_in blocks; per head group q, k, v blocks; W_o blocks; FFN; W_out blocks
-  float* hpark;         // scratch: gridDim.x * 128 * D floats
+  float* hpark;         // scratch: gridDim.x * 128 * D floats.  SPLIT: the residual stream after proj_in as rows
+                        // [tokens, D] (token m = (b*F + f)*Pw + position) + 4 KiB that idle lanes write to
+  bf16* o_rows;         // SPLIT: the attention output [tokens, D] (heads concatenated)
   float ln_eps, scale;
   Window win;           // temporal window: all F frames, positions [p0, p0 + Pw)
 };
 
-template <int NB, int DH>
+// SPLIT: the kernel ends behind the attention and leaves the residual stream and the attention
+// output as token rows; ffn_half_kernel (k_fused.h) takes the window on from there with its
+// wavefronts' 32 columns all in use -- worth it when F leaves many of this kernel's 32 columns per
+// wavefront empty (F = 25: 7 of 32), because three quarters of the window's MFMAs lie behind the cut.
+template <int NB, int DH, bool SPLIT = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void temporal_block_kernel(TemporalBlockArgs a) {
   constexpr int D = 32 * NB, SUB = 2 * NB, NC = 4 * NB, NSLOT = kRingSlots, FIFO = NB;
   constexpr int GW = lcm_int(DH, 32);        // columns per head group
   constexpr int NBG = GW / 32, HG = GW / DH;  // blocks / heads per group
   constexpr int NG = D / GW;
-  constexpr int TOTAL_SUB = 4 * NB + NB + 3 * NC + NB;
+  constexpr int TOTAL_SUB = SPLIT ? 4 * NB : 4 * NB + NB + 3 * NC + NB;
   constexpr int XLD = D + 8;  // padded row of the staged x tile (bf16 elements)
   static_assert(NB % 2 == 0 && D % GW == 0 && DH % 8 == 0, "shape");
   constexpr int SLOT_BYTES = SUB * kWave * 16, XS_BYTES = 128 * XLD * 2;
@@ -69,6 +75,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   // this lane's token: sequence, frame, row of the window's token order m = (b*F + f)*Pw + pl
   const int my_pp = tcol / F, my_f = tcol % F;
+  // SPLIT: row of this lane's token, or (padding column, sequence past the end) a dump row
+  const int64_t my_seq = seq_wg + wave * TP + my_pp;
+  const bool row_live = tcol < TP * F && my_seq < nseq;
+  const int64_t my_row = row_live ? ((my_seq / w.Pw) * F + my_f) * w.Pw + my_seq % w.Pw : 0;
 
   // ---- weight stream (see WeightPipe): sub-chunks 0 and 1 now, sub-chunk 2 once the x tile has left LDS
   using Pipe = WeightPipe<SUB>;
@@ -213,6 +223,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const unsigned l = park_lds + (unsigned)((((nb) % 2) * 16 + q) * (kWave * 16));                  \
     asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"((unsigned)(lane * 16)), "s"(sb), "s"(l) : "memory"); \
   }
+  float4* const hdump = reinterpret_cast<float4*>(a.hpark + (int64_t)w.B * F * w.Pw * D) + tid;
 #define SI_PROJ_IN_BLOCK(nb)                                                                         \
   {                                                                                                  \
     SI_STEP_OPEN();                                                                                  \
@@ -232,8 +243,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       const float4 bb = *reinterpret_cast<const float4*>(&t_bin[32 * (nb) + 8 * q + 4 * g]);         \
       hacc[nb][4 * q + 0] += bb.x; hacc[nb][4 * q + 1] += bb.y;                                      \
       hacc[nb][4 * q + 2] += bb.z; hacc[nb][4 * q + 3] += bb.w;                                      \
-      park[((nb) * 4 + q) * kWave] =                                                                 \
-          make_float4(hacc[nb][4 * q + 0], hacc[nb][4 * q + 1], hacc[nb][4 * q + 2], hacc[nb][4 * q + 3]); \
+      /* always 4 stores per block (the closing waits count them): idle lanes write to the dump area */ \
+      float4* hdst = !SPLIT ? park + ((nb) * 4 + q) * kWave                                          \
+                     : row_live ? reinterpret_cast<float4*>(a.hpark + my_row * D + 32 * (nb) + 8 * q + 4 * g) : hdump; \
+      *hdst = make_float4(hacc[nb][4 * q + 0], hacc[nb][4 * q + 1], hacc[nb][4 * q + 2], hacc[nb][4 * q + 3]); \
     }                                                                                                \
   }
 #pragma unroll
@@ -328,7 +341,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           }
         }
       }
-      if (gi == NG - 1) {  // no more steps until the out-projection: its first two blocks' residual sets out now
+      if (!SPLIT && gi == NG - 1) {  // no more steps until the out-projection: its first two blocks' residual sets out now
         SI_PARK_FETCH(0)
         if (NB > 1) { SI_PARK_FETCH(1) }
       }
@@ -400,6 +413,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #undef SI_BLOCK_WCOLS
 #undef SI_BLOCK_WROWS
 
+  if constexpr (SPLIT) {  // the attention output as token rows: k-step s holds columns 16s + {4g..4g+3, 8+4g..8+4g+3}
+    if (row_live) {
+      bf16* orow = a.o_rows + my_row * D + 4 * g;
+#pragma unroll
+      for (int s = 0; s < SUB; ++s) {
+        *reinterpret_cast<uint2*>(orow + 16 * s) = make_uint2(oop[s].x, oop[s].y);
+        *reinterpret_cast<uint2*>(orow + 16 * s + 8) = make_uint2(oop[s].z, oop[s].w);
+      }
+    }
+    return;
+  }
   // ---- h = h0 + o W_o + b_o: NB steps form one 32-column block of o W_o each; the parked residual
   // block (fetched two steps ahead) and the bias are added behind the step
 #pragma unroll

@@ -112,6 +112,8 @@ struct Plan {
   bool pe;
   int fused_nb;     // > 0: register-resident FFN half with D = 32*fused_nb
   bool fused_attn;  // register-resident attention half as well (temporal blocks)
+  bool attn_split;  // fused_attn, cut behind the attention: the FFN half runs as a kernel of its own on dense
+                    // token tiles (F leaves many of a wavefront's 32 columns empty in the one-kernel form)
   bool post_fused;  // spatial: everything behind the self-attention (its out-projection, LN2, query projection,
                     // attention over the context, FFN half) in one register-resident kernel
   bool attn_mfma;   // matrix-core attention kernel for the staged spatial path (bf16, head dimension 64)
@@ -189,6 +191,7 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   // which path: register-resident kernels need bf16, C == D = 64 or 320 (instantiated widths)
   p->fused_nb = 0;
   p->fused_attn = false;
+  p->attn_split = false;
   if (p->dtype == SI_BF16 && p->C == p->D && (D == 64 || D == 320)) {
     p->fused_nb = (int)(D / 32);
     const int tp = p->F <= 32 ? 32 / p->F : 0;
@@ -198,6 +201,8 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     const int64_t last_len = p->extent % p->slice_len ? p->extent % p->slice_len : p->slice_len;
     p->fused_attn = p->kind == SI_BLOCK_TEMPORAL && tp >= 1 && dh_ok && (int64_t)p->F * p->G <= kAttnMaxStats &&
                     (p->B <= 2 || last_len >= 128);
+    // columns of a wavefront that hold no token in the one-kernel form: 32 - floor(32 / F) * F
+    p->attn_split = p->fused_attn && (32 - tp * p->F) * 100 >= 15 * 32;
   }
   // a workgroup's 128 tokens share one context (P % 128 == 0: frames are whole workgroups), heads of 64
   // channels (two 32-channel blocks), at most kCrossTiles key tiles
@@ -211,8 +216,9 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   if (p->fused_attn) {  // one kernel per window: only the parked residual stream (128 rows per workgroup)
     const int64_t npos = 4 * (32 / p->F);
     const int64_t wgs = ((int64_t)p->B * p->slice_len + npos - 1) / npos;
-    p->off_a = take(0);
-    p->off_h = take((size_t)wgs * 128 * Dz * sizeof(float));
+    // attn_split: the attention output and the residual stream as token rows (+ 4 KiB that idle lanes write to)
+    p->off_a = take(p->attn_split ? (size_t)p->Mmax * Dz * es : 0);
+    p->off_h = take(p->attn_split ? (size_t)p->Mmax * Dz * sizeof(float) + 4096 : (size_t)wgs * 128 * Dz * sizeof(float));
     p->off_big = take(0);
   } else {
     // fragment-order operand buffers carry a 256-byte head and whole 32-token blocks
@@ -251,8 +257,8 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->off_w_out = take(wbytes(C, Dz));
   // post_fused: + W_o and W_q2 blocks and, per batch entry, the context fragments (24 per head)
   const int ffn_sub = 14 * p->fused_nb + (p->post_fused ? 2 * p->fused_nb + post_ctx_sub(*p) * p->B : 0);
-  p->off_ffn_stream = take(p->fused_nb && !p->fused_attn ? (size_t)stream_bytes(ffn_sub, 2 * p->fused_nb) : 0);
-  p->off_attn_stream = take(p->fused_attn ? (size_t)stream_bytes(18 * p->fused_nb, 2 * p->fused_nb) : 0);
+  p->off_ffn_stream = take(p->fused_nb && (!p->fused_attn || p->attn_split) ? (size_t)stream_bytes(ffn_sub, 2 * p->fused_nb) : 0);
+  p->off_attn_stream = take(p->fused_attn ? (size_t)stream_bytes((p->attn_split ? 4 : 18) * p->fused_nb, 2 * p->fused_nb) : 0);
   // post_fused: the kernel in front of the self-attention takes W_in, W_q, W_k, W_v as a stream of its own
   p->off_pre_stream = take(p->post_fused ? (size_t)stream_bytes(4 * p->fused_nb, 2 * p->fused_nb) : 0);
   p->weights_bytes = off - act_end;
@@ -474,7 +480,23 @@ static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, ch
   const bool spatial = p.kind == SI_BLOCK_SPATIAL;
   StreamDesc sd;
   int n = 0;
-  if (p.fused_attn) {  // attention half: W_in blocks, then per head group q, k, v blocks
+  if (p.attn_split) {  // the attention half's blocks as a stream of their own (with the frame table)
+    StreamDesc ad;
+    int k = 0;
+    const int gw = lcm_int(p.d, 32), nbg = gw / 32, ng = D / gw;
+    for (int nb = 0; nb < NB; ++nb) ad.b[k++] = BlockDesc{cB(w->w_in), D, 32 * nb, 0};
+    for (int gi = 0; gi < ng; ++gi) {
+      const void* mats[3] = {w->wq, w->wk, w->wv};
+      for (int kind = 0; kind < 3; ++kind)
+        for (int blk = 0; blk < nbg; ++blk) ad.b[k++] = BlockDesc{cB(mats[kind]), D, gi * gw + 32 * blk, 0};
+    }
+    ad.n_pre = k; ad.n_post = 0; ad.n_ffn = 0; ad.extra_sub = 0;
+    ad.w1 = ad.w2 = nullptr; ad.pe = pe; ad.F = p.F;
+    const int pe_wgs = pe ? (p.F * D + 255) / 256 : 0;
+    pack_stream_kernel<NB><<<(k * 2 * NB + 3) / 4 + pe_wgs, 256, 0, st>>>(ad, reinterpret_cast<u32x4_t*>(ws + p.off_attn_stream));
+    SI_CHECK_LAUNCH();
+    pe = nullptr;  // written
+  } else if (p.fused_attn) {  // attention half: W_in blocks, then per head group q, k, v blocks
     const int gw = lcm_int(p.d, 32), nbg = gw / 32, ng = D / gw;
     for (int nb = 0; nb < NB; ++nb) sd.b[n++] = BlockDesc{cB(w->w_in), D, 32 * nb, 0};
     for (int gi = 0; gi < ng; ++gi) {
@@ -497,7 +519,7 @@ static si_status pack_fused_streams(const Plan& p, const si_block_weights* w, ch
   sd.extra_sub = p.post_fused ? post_ctx_sub(p) * p.B : 0;
   sd.n_ffn = 12 * NB;
   const int total = sd.n_pre + 12 * NB + sd.n_post;
-  u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + (p.fused_attn ? p.off_attn_stream : p.off_ffn_stream));
+  u32x4_t* stream = reinterpret_cast<u32x4_t*>(ws + (p.fused_attn && !p.attn_split ? p.off_attn_stream : p.off_ffn_stream));
   const int frag_wgs = (total * 2 * NB + 3) / 4, pe_wgs = pe ? (p.F * D + 255) / 256 : 0;
   pack_stream_kernel<NB><<<frag_wgs + pe_wgs, 256, 0, st>>>(sd, stream);
   SI_CHECK_LAUNCH();
@@ -695,22 +717,28 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
     const int64_t M = (int64_t)p.B * win.Fw * win.Pw;
 
     if constexpr (sizeof(T) == 2) {
-      if (fused_attn) {  // the whole operator group of the window in one kernel
-        StageScope scope("temporal_block_fused", st);
+      if (fused_attn) {  // the whole operator group of the window in one kernel (attn_split: up to the attention)
+        StageScope scope(p.attn_split ? "attn_half_fused" : "temporal_block_fused", st);
         TemporalBlockArgs ta;
         ta.x = X; ta.out = OUT; ta.stats = stats;
         ta.gn_g = cT(w->gn_g); ta.gn_b = cT(w->gn_b); ta.b_in = cT(w->b_in);
         ta.ln1_g = cT(w->ln1_g); ta.ln1_b = cT(w->ln1_b); ta.b_o = cT(w->bo);
         ta.ln3_g = cT(w->ln3_g); ta.ln3_b = cT(w->ln3_b); ta.b1 = cT(w->b1); ta.b2 = cT(w->b2); ta.b_out = cT(w->b_out);
         ta.pe = pe; ta.stream = reinterpret_cast<const u32x4_t*>(ws + p.off_attn_stream);
-        ta.hpark = h; ta.ln_eps = w->ln_eps; ta.scale = scale; ta.win = win;
+        ta.hpark = h; ta.o_rows = a; ta.ln_eps = w->ln_eps; ta.scale = scale; ta.win = win;
         const int npos = 4 * (32 / p.F);
         const unsigned blocks = (unsigned)(((int64_t)p.B * win.Pw + npos - 1) / npos);
-        if (p.fused_nb == 2) temporal_block_kernel<2, 32><<<blocks, 256, 0, st>>>(ta);
-        else if (p.d == 40) temporal_block_kernel<10, 40><<<blocks, 256, 0, st>>>(ta);
-        else temporal_block_kernel<10, 64><<<blocks, 256, 0, st>>>(ta);
+        if (p.attn_split) {
+          if (p.fused_nb == 2) temporal_block_kernel<2, 32, true><<<blocks, 256, 0, st>>>(ta);
+          else if (p.d == 40) temporal_block_kernel<10, 40, true><<<blocks, 256, 0, st>>>(ta);
+          else temporal_block_kernel<10, 64, true><<<blocks, 256, 0, st>>>(ta);
+        } else {
+          if (p.fused_nb == 2) temporal_block_kernel<2, 32><<<blocks, 256, 0, st>>>(ta);
+          else if (p.d == 40) temporal_block_kernel<10, 40><<<blocks, 256, 0, st>>>(ta);
+          else temporal_block_kernel<10, 64><<<blocks, 256, 0, st>>>(ta);
+        }
         SI_CHECK_LAUNCH();
-        continue;
+        if (!p.attn_split) continue;
       }
     }
     int ksplit = 1;
@@ -902,7 +930,7 @@ static uint64_t pack_fingerprint(const Plan& p, const si_block_weights* w) {
   int dev = -1;
   (void)hipGetDevice(&dev);
   const int64_t f[] = {p.kind, p.dtype, p.B, p.C, p.F, p.H, p.W, p.G, p.heads, p.d, p.Mc, p.Cc, p.axis, p.extent, p.slice_len,
-                       p.Mmax, p.pe, p.fused_nb, p.fused_attn, p.post_fused, p.attn_mfma, p.ring, p.lanes, (int64_t)p.weights_bytes,
+                       p.Mmax, p.pe, p.fused_nb, p.fused_attn, p.attn_split, p.post_fused, p.attn_mfma, p.ring, p.lanes, (int64_t)p.weights_bytes,
                        (int64_t)p.total_bytes, (int64_t)p.off_w_in, (int64_t)p.off_ffn_stream, (int64_t)p.off_attn_stream, dev};
   uint64_t h = fnv1a(14695981039346656037ull, f, sizeof(f));
   const void* q[] = {w->gn_g, w->gn_b, w->w_in, w->b_in, w->ln1_g, w->ln1_b, w->wq, w->wk, w->wv, w->wo, w->bo,
