@@ -302,8 +302,8 @@ struct FfnHalfArgs {
   const bf16* o2;         // with h_tiled, or NULL: the attention ran in two key halves; o / o2 hold each half's
   const float2* ml;       // output and ml[(half * heads + head) * tiles32 + tile][lane] its (reference maximum in
   int64_t tiles32;        // base-2 exponent units, row sum); the halves are merged as the operands are loaded
-  int h_tiled;            // h is in the workgroup-tile order that spatial_pre_kernel writes (h_tile_index) and o
-                          // holds the attention kernel's output fragments ([32-token tile][k-step][lane])
+  int h_tiled;            // h is in workgroup-tile order (h_tile_index) and o holds the attention output as
+                          // fragments ([32-token tile][k-step][lane]), as the kernels in front of this one leave them
 };
 
 // Residual stream between two register-resident kernels of the same tiling (workgroup = 128 tokens,
@@ -384,8 +384,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (CROSS && a.h_tiled) v = reinterpret_cast<const float4*>(a.h)[h_tile_index<NB>(blockIdx.x, nb, q, wave, lane)];
-        else if (live) v = *reinterpret_cast<const float4*>(hrow + 32 * nb + 8 * q + 4 * g);
+        if (a.h_tiled) {
+          if (live) v = reinterpret_cast<const float4*>(a.h)[h_tile_index<NB>(blockIdx.x, nb, q, wave, lane)];
+        } else if (live) v = *reinterpret_cast<const float4*>(hrow + 32 * nb + 8 * q + 4 * g);
         hacc[nb][4 * q + 0] = v.x; hacc[nb][4 * q + 1] = v.y; hacc[nb][4 * q + 2] = v.z; hacc[nb][4 * q + 3] = v.w;
       }
   }
@@ -410,9 +411,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
 #pragma unroll
     for (int s2 = 0; s2 < SUB; ++s2) {
-      if (CROSS && a.h_tiled) {  // fragments as the attention kernel leaves them: [32-token tile][k-step][lane]
-        const u32x4_t f0 = reinterpret_cast<const u32x4_t*>(a.o)[(t32 * SUB + s2) * kWave + lane];
-        if (a.o2) {
+      if (a.h_tiled) {  // fragments as the attention kernel leaves them: [32-token tile][k-step][lane]
+        const u32x4_t f0 = live ? reinterpret_cast<const u32x4_t*>(a.o)[(t32 * SUB + s2) * kWave + lane] : u32x4_t{0, 0, 0, 0};
+        if (CROSS && a.o2) {
           const u32x4_t f1 = reinterpret_cast<const u32x4_t*>(a.o2)[(t32 * SUB + s2) * kWave + lane];
           const float u0 = w0[CROSS ? s2 / 4 : 0], u1 = w1[CROSS ? s2 / 4 : 0];
           const unsigned x0[4] = {f0.x, f0.y, f0.z, f0.w}, x1[4] = {f1.x, f1.y, f1.z, f1.w};

@@ -27,9 +27,10 @@ struct TemporalBlockArgs {
   const bf16 *gn_g, *gn_b, *b_in, *ln1_g, *ln1_b, *b_o, *ln3_g, *ln3_b, *b1, *b2, *b_out;
   const float* pe;      // [F, D] frame embedding or NULL
   const u32x4_t* stream;  // W_in blocks; per head group q, k, v blocks; W_o blocks; FFN; W_out blocks
-  float* hpark;         // scratch: gridDim.x * 128 * D floats.  SPLIT: the residual stream after proj_in as rows
-                        // [tokens, D] (token m = (b*F + f)*Pw + position) + 4 KiB that idle lanes write to
-  bf16* o_rows;         // SPLIT: the attention output [tokens, D] (heads concatenated)
+  float* hpark;         // scratch: gridDim.x * 128 * D floats.  SPLIT: the residual stream after proj_in of the
+                        // window's tokens m = (b*F + f)*Pw + position in the FFN-half kernel's workgroup-tile
+                        // order (h_tile_index; whole 128-token tiles) + 4 KiB that idle lanes write to
+  bf16* o_rows;         // SPLIT: the attention output as that kernel's operand fragments [m / 32][k-step][lane]
   float ln_eps, scale;
   Window win;           // temporal window: all F frames, positions [p0, p0 + Pw)
 };
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const unsigned l = park_lds + (unsigned)((((nb) % 2) * 16 + q) * (kWave * 16));                  \
     asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"((unsigned)(lane * 16)), "s"(sb), "s"(l) : "memory"); \
   }
-  float4* const hdump = reinterpret_cast<float4*>(a.hpark + (int64_t)w.B * F * w.Pw * D) + tid;
+  float4* const hdump = reinterpret_cast<float4*>(a.hpark + ((int64_t)w.B * F * w.Pw + 127) / 128 * 128 * D) + tid;
 #define SI_PROJ_IN_BLOCK(nb)                                                                         \
   {                                                                                                  \
     SI_STEP_OPEN();                                                                                  \
@@ -245,7 +246,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       hacc[nb][4 * q + 2] += bb.z; hacc[nb][4 * q + 3] += bb.w;                                      \
       /* always 4 stores per block (the closing waits count them): idle lanes write to the dump area */ \
       float4* hdst = !SPLIT ? park + ((nb) * 4 + q) * kWave                                          \
-                     : row_live ? reinterpret_cast<float4*>(a.hpark + my_row * D + 32 * (nb) + 8 * q + 4 * g) : hdump; \
+                     : row_live ? reinterpret_cast<float4*>(a.hpark) +                                \
+                                      h_tile_index<NB>(my_row / 128, nb, q, (int)(my_row % 128) / 32, 32 * g + (int)(my_row % 32)) \
+                                : hdump;                                                             \
       *hdst = make_float4(hacc[nb][4 * q + 0], hacc[nb][4 * q + 1], hacc[nb][4 * q + 2], hacc[nb][4 * q + 3]); \
     }                                                                                                \
   }
@@ -413,14 +416,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #undef SI_BLOCK_WCOLS
 #undef SI_BLOCK_WROWS
 
-  if constexpr (SPLIT) {  // the attention output as token rows: k-step s holds columns 16s + {4g..4g+3, 8+4g..8+4g+3}
+  if constexpr (SPLIT) {  // the attention output: oop[s] is the lane's 16 bytes of fragment (token tile, k-step s)
     if (row_live) {
-      bf16* orow = a.o_rows + my_row * D + 4 * g;
+      u32x4_t* of = reinterpret_cast<u32x4_t*>(a.o_rows) + (my_row / 32) * SUB * kWave + 32 * g + (int)(my_row % 32);
 #pragma unroll
-      for (int s = 0; s < SUB; ++s) {
-        *reinterpret_cast<uint2*>(orow + 16 * s) = make_uint2(oop[s].x, oop[s].y);
-        *reinterpret_cast<uint2*>(orow + 16 * s + 8) = make_uint2(oop[s].z, oop[s].w);
-      }
+      for (int s = 0; s < SUB; ++s) of[s * kWave] = oop[s];
     }
     return;
   }

@@ -217,8 +217,9 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
     const int64_t npos = 4 * (32 / p->F);
     const int64_t wgs = ((int64_t)p->B * p->slice_len + npos - 1) / npos;
     // attn_split: the attention output and the residual stream as token rows (+ 4 KiB that idle lanes write to)
-    p->off_a = take(p->attn_split ? (size_t)p->Mmax * Dz * es : 0);
-    p->off_h = take(p->attn_split ? (size_t)p->Mmax * Dz * sizeof(float) + 4096 : (size_t)wgs * 128 * Dz * sizeof(float));
+    const size_t Mt = (size_t)((p->Mmax + 127) / 128 * 128);  // whole 128-token tiles
+    p->off_a = take(p->attn_split ? Mt * Dz * es : 0);
+    p->off_h = take(p->attn_split ? Mt * Dz * sizeof(float) + 4096 : (size_t)wgs * 128 * Dz * sizeof(float));
     p->off_big = take(0);
   } else {
     // fragment-order operand buffers carry a 256-byte head and whole 32-token blocks
@@ -868,6 +869,7 @@ static si_status run_block(const Plan& p, const si_tensor5* x, const si_block_we
         fa.ln2_g = fa.ln2_b = fa.b_o2 = nullptr;
         fa.pitch = 0; fa.ctx_sub0 = 0; fa.Mc = 0; fa.tokens_per_batch = 128; fa.qscale = 0.f; fa.h_tiled = 0;
         fa.o2 = nullptr; fa.ml = nullptr; fa.tiles32 = 0;
+        if (p.attn_split) fa.h_tiled = 1;  // the attention half leaves tile-order residual rows and operand fragments
         const unsigned blocks = (unsigned)((M + 127) / 128);
         if (p.post_fused) {  // `a` holds the self-attention output; the kernel goes on from there
           fa.ln2_g = cT(w->ln2_g); fa.ln2_b = cT(w->ln2_b); fa.b_o2 = cT(w->bo2);

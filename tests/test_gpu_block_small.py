@@ -115,6 +115,18 @@ def test_temporal_32_frames_bf16():
     _check(spec, x, w, None, 24)
 
 
+@pytest.mark.parametrize("slice_len", [24, 7])
+def test_temporal_11_frames_cut_behind_the_attention_bf16(slice_len):
+    """F = 11: two positions per wavefront leave 10 of 32 MFMA columns empty, so the window kernel
+    ends behind the attention and the FFN half runs on dense token tiles (C = 64: 2 x 11 x 24 = 528
+    tokens per window, the last tile ragged; 7 positions per slice: windows smaller than a tile and
+    a ragged last window of 5)."""
+    spec = tiny_spec(wl.TEMPORAL, B=2, C=64, F=11, H=6, W=8, heads=2, dim_head=32, groups=8, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, None, slice_len)
+
+
 def test_head_dim_40_and_25_frames_bf16():
     spec = tiny_spec(wl.TEMPORAL, B=1, C=80, F=25, H=6, W=6, heads=2, dim_head=40, groups=4, pe=True, dtype="bf16")
     x = wl.make_x(spec)
