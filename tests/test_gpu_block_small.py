@@ -127,6 +127,15 @@ def test_temporal_11_frames_cut_behind_the_attention_bf16(slice_len):
     _check(spec, x, w, None, slice_len)
 
 
+def test_temporal_11_frames_three_batches_cut_behind_the_attention_bf16():
+    """As above with B = 3 and one window of 144 positions: workgroups of the attention half straddle
+    batch entries, and the dense token tiles of the FFN half straddle frames and batch entries."""
+    spec = tiny_spec(wl.TEMPORAL, B=3, C=64, F=11, H=12, W=12, heads=2, dim_head=32, groups=8, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, None, 144)
+
+
 def test_head_dim_40_and_25_frames_bf16():
     spec = tiny_spec(wl.TEMPORAL, B=1, C=80, F=25, H=6, W=6, heads=2, dim_head=40, groups=4, pe=True, dtype="bf16")
     x = wl.make_x(spec)
