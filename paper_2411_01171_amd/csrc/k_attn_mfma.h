@@ -202,8 +202,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma_kernel(Att
   const int kap = 16 * (r / 16) + kappa16(r % 16);
   const unsigned kvoff = FRAGIN ? (unsigned)(lane * 16) : (unsigned)(((int64_t)kap * a.ldk + 8 * g) * 2);
   const unsigned vvoff = FRAGIN ? (unsigned)(lane * 16) : (unsigned)(((int64_t)r * a.Nkp + 8 * g) * 2);
-  const char* kb = reinterpret_cast<const char*>(a.k + (int64_t)ks * a.Nk * a.ldk + h * 64);
-  const char* vb = reinterpret_cast<const char*>(a.vt + ((int64_t)ks * a.heads * 64 + h * 64) * a.Nkp);
+  // row-major operands (not FRAGIN): this (sequence, head)'s key rows and transposed value rows
+  const char* kb = FRAGIN ? nullptr : reinterpret_cast<const char*>(a.k + (int64_t)ks * a.Nk * a.ldk + h * 64);
+  const char* vb = FRAGIN ? nullptr : reinterpret_cast<const char*>(a.vt + ((int64_t)ks * a.heads * 64 + h * 64) * a.Nkp);
   // FRAGIN: the pair's stage blocks, 16 KiB per stage
   const char* fb = reinterpret_cast<const char*>(a.k) + ((int64_t)((ks * a.heads + h) * ksplit + kh) * nst) * (16 * 1024);
   // Full stages are issued in order, so every fragment's source is a running scalar pointer that
