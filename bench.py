@@ -565,8 +565,8 @@ def main():
                          "collected around this command can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path shards without changing the kernel; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path would shard over slices and batch entries "
+              "without changing a kernel); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     if args.workload.startswith("res"):
