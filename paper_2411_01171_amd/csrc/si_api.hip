@@ -181,9 +181,6 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   };
   // slice-independent activation-derived items
   p->off_stats = take((size_t)p->B * p->F * p->G * 2 * sizeof(float));
-  // similarity partials of the fused statistics + rehash pass (3 doubles per block), then {cos, decision}
-  p->off_rehash = take((size_t)p->B * p->F * p->G * 3 * sizeof(double) + 16);
-  p->off_pe = take(p->pe ? (size_t)p->F * Dz * sizeof(float) : 0);
   p->off_ctxkv = take((size_t)p->B * p->Mc * 2 * Dz * es);
   p->attn_mfma = p->dtype == SI_BF16 && p->kind == SI_BLOCK_SPATIAL && p->d == 64 && P % 8 == 0;
   p->Mcp = (p->Mc + 7) / 8 * 8;
@@ -239,7 +236,14 @@ static si_status make_plan(const si_tensor5* x, const si_block_weights* w, const
   p->lanes = (int)(n_slices / 4 < 1 ? 1 : n_slices / 4 > kMaxLanes ? kMaxLanes : n_slices / 4);
   p->lane_stride = off - p->off_a;
   for (int l = 1; l < p->lanes; ++l) take(p->lane_stride);
+  // Similarity partials of the fused statistics + rehash pass (3 doubles per block), then {cos, decision}:
+  // written and read back before the first window starts, so they lie in the first window's intermediates
+  // when those are large enough.
+  const size_t rehash_bytes = (size_t)p->B * p->F * p->G * 3 * sizeof(double) + 16;
+  p->off_rehash = rehash_bytes <= p->lane_stride ? p->off_a : take(rehash_bytes);
   const size_t act_end = off;
+  // frame position table (a function of F and D only: written with the weight re-layout)
+  p->off_pe = take(p->pe ? (size_t)p->F * Dz * sizeof(float) : 0);
   // re-laid-out weights ([N, K]; fragment streams pad N to whole column tiles)
   auto wbytes = [&](size_t N, size_t K) {
     if (!p->ring) return N * K * es;
@@ -396,6 +400,16 @@ template <typename T>
 static si_status launch_attention(const char* stage, const AttnArgs& a, hipStream_t st) {
   if (a.S <= 0 || a.Nq <= 0) return SI_OK;
   StageScope scope(stage, st);
+  if constexpr (sizeof(T) == 2) {
+    // self-attention over a short sequence (temporal blocks): one wavefront per (sequence, head)
+    const bool rows16 = a.ldq % 8 == 0 && a.ldk % 8 == 0 && a.ldv % 8 == 0 && a.ldo % 8 == 0 && aligned16(a.q) && aligned16(a.k) &&
+                        aligned16(a.v) && aligned16(a.o);
+    if (a.d == 64 && a.Nq == a.Nk && a.Nk <= 32 && rows16) {
+      attn_short_kernel<64><<<(unsigned)(((int64_t)a.S * a.heads + 3) / 4), 256, 0, st>>>(a);
+      SI_CHECK_LAUNCH();
+      return SI_OK;
+    }
+  }
   constexpr int QB = 4;
   dim3 grid((unsigned)((a.Nq + 4 * QB - 1) / (4 * QB)), (unsigned)a.heads, (unsigned)a.S);
   attn_valu_kernel<T, QB><<<grid, 256, 0, st>>>(a);

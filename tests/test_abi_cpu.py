@@ -185,7 +185,8 @@ def test_workspace_scales_with_the_slice():
     lib = si.lib()
     full = lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 4096)
     quarter = lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 1024)
-    assert 0 < quarter < full and quarter / full < 0.2505
+    # a quarter of the window intermediates plus the slice-independent GroupNorm statistics (8 KiB here)
+    assert 0 < quarter < full and quarter / full < 0.2501
     assert lib.si_workspace_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 1024) > quarter
     # slice_len beyond the extent behaves as unsliced
     assert lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 10**9) == full

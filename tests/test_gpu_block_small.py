@@ -229,6 +229,20 @@ def test_wide_blocks_small_windows_bf16(kind, C, heads):
     _check(spec, x, w, ctx, sl)
 
 
+@pytest.mark.parametrize("F", [1, 16, 17, 32, 33])
+def test_wide_temporal_block_sequence_lengths_bf16(F):
+    """Temporal block on the staged path (C = 128, two heads of 64 channels) at sequence lengths around
+    what one wavefront of the short-sequence attention kernel holds: a single frame, an even and an odd
+    count, the 32-frame limit, and one frame past it (the general attention kernel); the softmax is
+    sharpened so that a misplaced key or probability shows."""
+    spec = tiny_spec(wl.TEMPORAL, B=2, C=128, F=F, H=3, W=7, heads=2, dim_head=64, groups=8, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.02)
+    w["wq"] = wl.round_to_storage(w["wq"] * 8.0, "bf16")
+    w["wk"] = wl.round_to_storage(w["wk"] * 8.0, "bf16")
+    _check(spec, x, w, None, 10)
+
+
 def test_wide_temporal_block_large_ragged_window_bf16():
     """C = 640 on one window of 3 x 2731 = 8193 tokens: large enough for the eight-rows-per-wavefront
     LayerNorm (with the frame embedding and random gains / shifts), and one row past a multiple of 8,
