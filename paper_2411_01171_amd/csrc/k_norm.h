@@ -328,6 +328,83 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float* __restrict
   }
 }
 
+// Row LayerNorm into the ring kernels' fragment order for windows of few rows (bf16, D % 8 == 0,
+// D <= 2048): one wavefront per row as in layer_norm_kernel (as many wavefronts as rows), eight
+// consecutive rows per workgroup.  The eight normalised rows meet in LDS, and the workgroup writes
+// them as whole 128-byte pieces of the fragment-order buffer (8 tokens x the 16 bytes of one
+// 8-channel granule) instead of 16-byte pieces per row; gain and shift are read four at a time.
+// Same arithmetic per element as layer_norm_kernel.
+__global__ __launch_bounds__(512) void layer_norm_rows8_kernel(const float* __restrict__ h, bf16* __restrict__ a, int64_t M, int D,
+                                                               const bf16* __restrict__ gamma, const bf16* __restrict__ beta, float eps,
+                                                               const float* __restrict__ pe, int Pw, int Fw, int f0) {
+  constexpr int LDR = 2048 + 8;  // 16-bit elements per LDS row: 16-byte aligned rows that rotate over the banks
+  __shared__ __attribute__((aligned(16))) unsigned short tile[8][LDR];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int64_t m0 = (int64_t)blockIdx.x * 8, m = m0 + wave;
+  if (m < M) {
+    const float4* row = reinterpret_cast<const float4*>(h + m * D);
+    const int nv = D / 4;
+    float4 r[8];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int v = lane + i * kWave;
+      if (v < nv) {
+        r[i] = row[v];
+        s += (r[i].x + r[i].y) + (r[i].z + r[i].w);
+      }
+    }
+    const float mean = wave_sum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int v = lane + i * kWave;
+      if (v < nv) {
+        const float dx = r[i].x - mean, dy = r[i].y - mean, dz = r[i].z - mean, dw = r[i].w - mean;
+        q += (dx * dx + dy * dy) + (dz * dz + dw * dw);
+      }
+    }
+    const float rstd = rsqrtf(wave_sum(q) / (float)D + eps);
+    const float* perow = pe ? pe + (int64_t)(f0 + (int)((m / Pw) % Fw)) * D : nullptr;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int v = lane + i * kWave;
+      if (v < nv) {
+        const float in[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+        float g[4] = {1.f, 1.f, 1.f, 1.f}, b[4] = {0.f, 0.f, 0.f, 0.f};
+        if (gamma) {
+          const uint2 raw = *reinterpret_cast<const uint2*>(gamma + v * 4);
+          g[0] = __uint_as_float(raw.x << 16); g[1] = __uint_as_float(raw.x & 0xffff0000u);
+          g[2] = __uint_as_float(raw.y << 16); g[3] = __uint_as_float(raw.y & 0xffff0000u);
+        }
+        if (beta) {
+          const uint2 raw = *reinterpret_cast<const uint2*>(beta + v * 4);
+          b[0] = __uint_as_float(raw.x << 16); b[1] = __uint_as_float(raw.x & 0xffff0000u);
+          b[2] = __uint_as_float(raw.y << 16); b[3] = __uint_as_float(raw.y & 0xffff0000u);
+        }
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = (in[e] - mean) * rstd * g[e] + b[e];
+        if (perow) {
+          const float4 pv = *reinterpret_cast<const float4*>(perow + v * 4);
+          y[0] += pv.x; y[1] += pv.y; y[2] += pv.z; y[3] += pv.w;
+        }
+        uint2 pk;
+        pk.x = (unsigned)float_to_bf16_bits(y[0]) | ((unsigned)float_to_bf16_bits(y[1]) << 16);
+        pk.y = (unsigned)float_to_bf16_bits(y[2]) | ((unsigned)float_to_bf16_bits(y[3]) << 16);
+        *reinterpret_cast<uint2*>(&tile[wave][v * 4]) = pk;
+      }
+    }
+  }
+  __syncthreads();
+  const int items = (D / 8) * 8;  // (8-channel granule, row) pairs; the 8 rows of a granule are 128 contiguous bytes
+  for (int idx = threadIdx.x; idx < items; idx += 512) {
+    const int c8 = idx / 8, t = idx % 8;
+    if (m0 + t < M)
+      *reinterpret_cast<uint4*>(a + act_offset(m0 + t, c8 * 8, D)) = *reinterpret_cast<const uint4*>(&tile[t][c8 * 8]);
+  }
+}
+
 // Row LayerNorm into the ring kernels' fragment order (bf16 blocks with D % 32 == 0): one wavefront
 // per 8 consecutive rows.  Lane (r = lane % 8, q = lane / 8) owns the channel quads q, q + 8, ... of
 // row r, so a load instruction covers 128 contiguous bytes of each of the 8 rows (all of them in
