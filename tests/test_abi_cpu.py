@@ -192,6 +192,29 @@ def test_workspace_scales_with_the_slice():
     assert lib.si_live_activation_bytes(C.byref(x), C.byref(w), None, B.SI_AXIS_HW, 10**9) == full
 
 
+def test_live_bytes_of_the_five_configurations():
+    """Sliced / unsliced live activation bytes at each configuration's default slicing: the window
+    intermediates in flight never exceed a quarter of the unsliced run's; the slice-independent items
+    (GroupNorm statistics, context keys / values) come on top, which shows where the plan sits
+    exactly at a quarter (4 slices one at a time, 8 slices two at a time)."""
+    import si_workloads as wl
+    lib = si.lib()
+    bound = {"cfg1": 0.26, "cfg2": 0.2501, "cfg3": 0.19, "cfg4s": 0.121, "cfg4t": 0.2501, "cfg5s": 0.256, "cfg5t": 0.2501}
+    for name, spec in wl.CONFIGS.items():
+        spatial = spec.kind == wl.SPATIAL
+        dt = B.SI_F32 if spec.dtype == "f32" else B.SI_BF16
+        x, w, _, _ = _descs(kind=B.SI_BLOCK_SPATIAL if spatial else B.SI_BLOCK_TEMPORAL, dtype=dt, Bn=spec.B, Cn=spec.C, F=spec.F,
+                            H=spec.H, W=spec.W, heads=spec.heads, dh=spec.dim_head, groups=spec.gn_groups)
+        w.add_sin_pe = int(spec.add_sin_pe)
+        ctx = B._Context(0x10000 + (3 << 30), dt, spec.B, spec.ctx_tokens, spec.ctx_dim) if spatial else None
+        pc = C.byref(ctx) if ctx is not None else None
+        axis = B.SI_AXIS_F if spatial else B.SI_AXIS_HW
+        sliced = lib.si_live_activation_bytes(C.byref(x), C.byref(w), pc, axis, spec.slice_len)
+        full = lib.si_live_activation_bytes(C.byref(x), C.byref(w), pc, axis, 10**9)
+        assert 0 < sliced < full, name
+        assert sliced / full <= bound[name], (name, sliced / full)
+
+
 def test_rehash_check_validation():
     lib = si.lib()
     fake = 0x10000
