@@ -253,6 +253,48 @@ def test_wide_temporal_block_large_ragged_window_bf16():
     _check(spec, x, w, None, 2731)
 
 
+OPTIONAL = ("gn_g", "gn_b", "b_in", "ln1_g", "ln1_b", "bo", "ln2_g", "ln2_b", "bo2", "ln3_g", "ln3_b", "b1", "b2", "b_out")
+
+
+@pytest.mark.parametrize("case", ["fused_temporal", "three_kernel_spatial", "staged_spatial", "staged_temporal", "fp32"])
+def test_null_optional_parameters_mean_identity(case):
+    """A NULL bias means zero, a NULL norm gain one and a NULL norm shift zero: with gains of one and
+    shifts / biases of zero the output must not change by a bit when those vectors are left out, on
+    every kernel family (register-resident temporal window, three-kernel spatial window, staged
+    path at C = 640, fp32 path)."""
+    from gpu_helpers import run_block
+    if case == "fused_temporal":
+        spec = tiny_spec(wl.TEMPORAL, B=2, C=320, F=8, H=4, W=9, heads=8, dim_head=40, groups=32, pe=True, dtype="bf16")
+        sl = 20
+    elif case == "three_kernel_spatial":
+        spec = tiny_spec(wl.SPATIAL, B=1, C=320, F=2, H=16, W=16, heads=5, dim_head=64, groups=32, M=7, Cc=24, dtype="bf16")
+        sl = 1
+    elif case == "staged_spatial":
+        spec = tiny_spec(wl.SPATIAL, B=1, C=640, F=2, H=5, W=7, heads=10, dim_head=64, groups=32, M=5, Cc=24, dtype="bf16")
+        sl = 1
+    elif case == "staged_temporal":
+        spec = tiny_spec(wl.TEMPORAL, B=1, C=640, F=5, H=3, W=7, heads=10, dim_head=64, groups=32, pe=True, dtype="bf16")
+        sl = 8
+    else:
+        spec = tiny_spec(wl.TEMPORAL, B=1, C=64, F=4, H=4, W=5, heads=2, dim_head=32, groups=8, dtype="f32")
+        sl = 7
+    x = wl.make_x(spec)
+    ctx = wl.make_context(spec)
+    w = wl.make_weights(spec)            # gains 1, shifts and biases 0
+    full = run_block(spec, x, w, ctx, sl)
+    bare = run_block(spec, x, {k: v for k, v in w.items() if k not in OPTIONAL}, ctx, sl)
+    assert np.all(np.isfinite(full))
+    assert np.array_equal(full, bare)
+    # and it is the right answer
+    e_ref = oracle.block_forward_ref(x, w, spec, ctx)
+    from gpu_helpers import errors
+    e = errors(bare, e_ref, x)
+    if spec.dtype == "f32":
+        assert e["rel_l2"] <= F32_REL
+    else:
+        assert e["max_abs"] <= BF16_MAX_ABS and e["rel_l2"] <= BF16_REL_L2
+
+
 def test_peaky_softmax_bf16():
     """Queries and keys scaled up so that the softmax is far from uniform."""
     spec = tiny_spec(wl.SPATIAL, B=1, C=64, F=2, H=10, W=10, heads=2, dim_head=32, groups=8, M=7, Cc=16, dtype="bf16")
