@@ -71,8 +71,15 @@ struct ConvArgs {
 // beyond the last k-tile read the zero block into a slot nobody reads any more.  The loads are inline assembly (the compiler would otherwise wait for all of them
 // before every LDS read); no compiler-visible vector-memory load sits inside the k loop.
 // F16: operands are fp16 (v_mfma_f32_32x32x16_f16), else bf16 (v_mfma_f32_32x32x16_bf16).
-template <int TM, int TN, int STAGES, bool F16, class Epi>
-__global__ __launch_bounds__(256, 2) void ring_mma_kernel(ConvArgs a, Epi epi) {
+// WS (wavefront-specialised, 512 threads): wavefronts 4..7 only feed the ring -- wavefront 4 + w issues
+// exactly the loads wavefront w would issue -- and wavefronts 0..3 only read it and run the MFMAs, with
+// the fragments of k-tile kt+1 read from LDS while the MFMAs of k-tile kt run.  The load issue of a
+// stage (which blocks a wavefront while the address unit takes its KiB-sized requests) and the LDS
+// latency then overlap with the MFMAs instead of preceding them, which is what a launch with one
+// workgroup per CU at most lacks.  Both roles pass the same barriers: one per k-tile, then those of
+// the epilogue.
+template <int TM, int TN, int STAGES, bool F16, class Epi, bool WS = false>
+__global__ __launch_bounds__(WS ? 512 : 256, (WS && TM * TN > 2) ? 1 : 2) void ring_mma_kernel(ConvArgs a, Epi epi) {
   constexpr int AF = 4 * TM * 2, WFR = 2 * TN;           // fragments per stage
   constexpr int NW = (WFR + 3) / 4;                      // weight loads per wavefront per stage
   constexpr int PER = 2 * TM + NW;                       // loads per wavefront per stage
@@ -90,7 +97,9 @@ __global__ __launch_bounds__(256, 2) void ring_mma_kernel(ConvArgs a, Epi epi) {
   const int64_t m0 = (int64_t)(a.col_major ? tile % nrow : tile / a.ncol) * (128 * TM);
 
   const int tid = threadIdx.x, lane = tid % kWave;
-  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int wave_id = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int wave = wave_id % 4;  // the quarter of the row tile this wavefront loads (feeding role) or contracts
+  const bool producer = WS && wave_id >= 4;
   const int trow = lane % 32, half = lane / 32;
   const int P = a.H * a.W;
   const int per_tap = a.C / 32, nkt = a.ntaps * per_tap;
@@ -170,33 +179,81 @@ __global__ __launch_bounds__(256, 2) void ring_mma_kernel(ConvArgs a, Epi epi) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-#pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) issue();
   constexpr int kWaitImm = (((STAGES - 2) * PER) & 0xF) | 0x70 | 0xF00 | ((((STAGES - 2) * PER) >> 4) << 14);
-  for (int kt = 0; kt < nkt; ++kt) {
-    // k-tile kt has landed for this wavefront once at most the STAGES-2 younger stages are in flight
-    __builtin_amdgcn_s_waitcnt(kWaitImm);
-    __syncthreads();  // ... and for every wavefront; all have also finished reading k-tile kt-1's slot
-    issue();          // which the stage loaded now reuses
+  struct Frags {
+    u32x4_t wf[2][TN], af[2][TM];
+  };
+  auto read_frags = [&](int kt, Frags& f) {
     const char* slot = ring + (kt % STAGES) * SLOT;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      u32x4_t wf[TN], af[TM];
 #pragma unroll
-      for (int i = 0; i < TN; ++i) wf[i] = *reinterpret_cast<const u32x4_t*>(slot + (AF + ks * TN + i) * 1024 + lane * 16);
+      for (int i = 0; i < TN; ++i) f.wf[ks][i] = *reinterpret_cast<const u32x4_t*>(slot + (AF + ks * TN + i) * 1024 + lane * 16);
 #pragma unroll
-      for (int j = 0; j < TM; ++j) af[j] = *reinterpret_cast<const u32x4_t*>(slot + ((wave * TM + j) * 2 + ks) * 1024 + lane * 16);
+      for (int j = 0; j < TM; ++j) f.af[ks][j] = *reinterpret_cast<const u32x4_t*>(slot + ((wave * TM + j) * 2 + ks) * 1024 + lane * 16);
+    }
+  };
+  auto contract = [&](const Frags& f) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
           if constexpr (F16)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, wf[i]), __builtin_bit_cast(f16x8_t, af[j]),
-                                                               acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, f.wf[ks][i]),
+                                                               __builtin_bit_cast(f16x8_t, f.af[ks][j]), acc[i][j], 0, 0, 0);
           else
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[i]), __builtin_bit_cast(bf16x8_t, af[j]),
-                                                                acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f.wf[ks][i]),
+                                                                __builtin_bit_cast(bf16x8_t, f.af[ks][j]), acc[i][j], 0, 0, 0);
         }
+  };
+  if constexpr (WS) {
+    if (producer) {
+#pragma unroll
+      for (int s = 0; s < STAGES - 1; ++s) issue();
+      for (int kt = 0; kt < nkt; ++kt) {
+        __builtin_amdgcn_s_waitcnt(kWaitImm);  // this wavefront's share of k-tile kt has landed
+        __syncthreads();                       // barrier kt: every share has; k-tile kt-1's slot is no longer read
+        issue();
+      }
+    } else {
+      // barrier kt opens k-tile kt; its fragments are in registers (lgkmcnt(0)) before barrier kt+1 lets
+      // the feeding wavefronts overwrite the slot two stages later
+      constexpr int kLgkm0 = 0xC07F;  // lgkmcnt(0), other counters untouched
+      Frags f0, f1;
+      int kt = 0;
+      if (nkt > 0) {
+        __syncthreads();  // barrier 0
+        read_frags(0, f0);
+      }
+      for (; kt + 2 <= nkt; kt += 2) {
+        __builtin_amdgcn_s_waitcnt(kLgkm0);
+        __syncthreads();  // barrier kt+1
+        read_frags(kt + 1, f1);
+        __builtin_amdgcn_sched_barrier(0);
+        contract(f0);
+        __builtin_amdgcn_s_waitcnt(kLgkm0);
+        if (kt + 2 < nkt) {
+          __syncthreads();  // barrier kt+2
+          read_frags(kt + 2, f0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        contract(f1);
+      }
+      if (kt < nkt) contract(f0);  // odd count: the last k-tile was read behind barrier nkt-1
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue();
+    for (int kt = 0; kt < nkt; ++kt) {
+      // k-tile kt has landed for this wavefront once at most the STAGES-2 younger stages are in flight
+      __builtin_amdgcn_s_waitcnt(kWaitImm);
+      __syncthreads();  // ... and for every wavefront; all have also finished reading k-tile kt-1's slot
+      issue();          // which the stage loaded now reuses
+      Frags f;
+      read_frags(kt, f);
+      contract(f);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0070 | 0xF00);  // vmcnt(0): the padding loads of the last stages
@@ -211,16 +268,19 @@ __global__ __launch_bounds__(256, 2) void ring_mma_kernel(ConvArgs a, Epi epi) {
 #pragma unroll
     for (int i = 0; i < TN; ++i) {
       __syncthreads();  // the ring (first pass) or the previous block's patch is no longer read
+      if (!producer) {
 #pragma unroll
-      for (int j = 0; j < TM; ++j)
+        for (int j = 0; j < TM; ++j)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+          for (int q = 0; q < 4; ++q)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) patch[(q * 8 + half * 4 + r) * LDP + (wave * TM + j) * 32 + trow] = acc[i][j][q * 4 + r];
+            for (int r = 0; r < 4; ++r) patch[(q * 8 + half * 4 + r) * LDP + (wave * TM + j) * 32 + trow] = acc[i][j][q * 4 + r];
+      }
       __syncthreads();
+      constexpr int NT = WS ? 512 : 256;  // the feeding wavefronts take their share of the stores
 #pragma unroll
-      for (int u = 0; u < 2 * TM; ++u) {
-        const int id = tid + u * 256, ch = id / (TOK / 8), t8 = (id % (TOK / 8)) * 8;
+      for (int u = 0; u < 2 * TM * 256 / NT; ++u) {
+        const int id = tid + u * NT, ch = id / (TOK / 8), t8 = (id % (TOK / 8)) * 8;
         const int n = (col * TN + i) * 32 + ch;
         const int64_t m = m0 + t8;
         if (n < a.O && m < a.M) {
@@ -234,6 +294,7 @@ __global__ __launch_bounds__(256, 2) void ring_mma_kernel(ConvArgs a, Epi epi) {
     return;
   }
 
+  if (producer) return;
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
     const int64_t m = tok[j];

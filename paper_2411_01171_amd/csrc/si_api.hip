@@ -374,13 +374,23 @@ static si_status launch_gemm_ring(const char* stage, const void* act, const void
              (int)((big ? rows2 : (M + 127) / 128) * rs.ncol), 1, 1, kConvSame, 1,
              M < N ? 1 : 0};  // the smaller operand is the one every XCD streams
   const unsigned grid = (unsigned)((a.ntiles + 7) / 8 * 8);
+  // Narrow tiles (64 or 32 columns: the N = D projections and ff2) run wavefront-specialised: their
+  // launches have one or two workgroups per CU, too few to hide a workgroup's load issue behind
+  // another's MFMAs (measured per step: cfg3 1.68 -> 1.59 ms, cfg5 spatial 1.33 -> 1.29 ms, cfg5 temporal
+  // 1.12 -> 1.08 ms; the 160-column tiles of q/k/v and ff1 lose with it: two such workgroups no longer
+  // fit a CU's registers).
+  if (!big && rs.tn <= 2) {
+    if (rs.tn == 2) ring_mma_kernel<1, 2, 4, F16, Epi, true><<<grid, 512, 0, st>>>(a, epi);
+    else ring_mma_kernel<1, 1, 6, F16, Epi, true><<<grid, 512, 0, st>>>(a, epi);
+    SI_CHECK_LAUNCH();
+    return SI_OK;
+  }
   switch (rs.tn * 2 + (big ? 1 : 0)) {
     case 11: ring_mma_kernel<2, 5, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
     case 10: ring_mma_kernel<1, 5, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
     case 9: ring_mma_kernel<2, 4, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
     case 8: ring_mma_kernel<1, 4, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
-    case 4: ring_mma_kernel<1, 2, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
-    default: ring_mma_kernel<1, 1, 6, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
+    default: return SI_ERR_ARG;  // ring_shape only gives tiles of 1, 2, 4 or 5 column blocks
   }
   SI_CHECK_LAUNCH();
   return SI_OK;
