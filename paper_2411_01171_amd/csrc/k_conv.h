@@ -24,6 +24,7 @@
 //   gn_silu_{tokens,frag}_kernel  SiLU(GroupNorm2(h)) -> fp16 operand in fragment order (in place
 //                           when h already is)                                               [HBM bound]
 #pragma once
+#include <type_traits>
 #include "si_common.h"
 #include "k_gemm.h"
 
@@ -78,6 +79,11 @@ struct ConvArgs {
 // latency then overlap with the MFMAs instead of preceding them, which is what a launch with one
 // workgroup per CU at most lacks.  Both roles pass the same barriers: one per k-tile, then those of
 // the epilogue.
+template <class Epi, class = void>
+struct epi_block32 : std::false_type {};
+template <class Epi>
+struct epi_block32<Epi, std::enable_if_t<Epi::kBlock32>> : std::true_type {};
+
 template <int TM, int TN, int STAGES, bool F16, class Epi, bool WS = false>
 __global__ __launch_bounds__(WS ? 512 : 256, (WS && TM * TN > 2) ? 1 : 2) void ring_mma_kernel(ConvArgs a, Epi epi) {
   constexpr int AF = 4 * TM * 2, WFR = 2 * TN;           // fragments per stage
@@ -295,6 +301,19 @@ __global__ __launch_bounds__(WS ? 512 : 256, (WS && TM * TN > 2) ? 1 : 2) void r
   }
 
   if (producer) return;
+  if constexpr (epi_block32<Epi>::value) {
+    // whole 32-column blocks go to the epilogue's block form (every lane takes part in its exchange)
+    if (a.O % 32 == 0) {
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+          const int n0 = (col * TN + i) * 32;
+          if (n0 < a.O) epi.block32(tok[j], tok[j] < a.M, n0, acc[i][j], half);
+        }
+      return;
+    }
+  }
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
     const int64_t m = tok[j];

@@ -66,12 +66,7 @@ __device__ __forceinline__ bf16x8_t to_operand(const float* v) {
 // polynomial xc * R(xc^2), xc = clamp(x, -4.2, 4.2), degree 8 in xc^2 (minimax fit of
 // erf(x / sqrt 2) / x on [0, 4.2], |erf error| <= 2.2e-5 everywhere, coefficients pre-halved).
 // No transcendental instructions: the FFN's GELUs share the issue port with the MFMAs.
-constexpr float kGeluClamp = 4.2f;
-constexpr int kGeluDeg = 8;
-__device__ constexpr float kGeluC[kGeluDeg + 1] = {
-    0.5f * 0.7978148460388184f,     0.5f * -0.1327207386493683f,    0.5f * 0.019660256803035736f,
-    0.5f * -0.0022282942663878202f, 0.5f * 0.00018914842803496867f, 0.5f * -1.1521495252964087e-05f,
-    0.5f * 4.6873191195118125e-07f, 0.5f * -1.1266531707576632e-08f, 0.5f * 1.199598614887165e-10f};
+// (kGeluClamp, kGeluDeg, kGeluC: si_common.h)
 
 // GEGLU of G result registers [E0, E0+G) of one chunk, cut into stages of G independent
 // vector-ALU instructions each, so that one stage can be issued behind every MFMA.

@@ -123,6 +123,39 @@ struct EpiGeglu {
   int64_t ld;
   const T* b1;
   int inner;  // 4D
+  // One 32-column result block of the ring kernel at a time (16-bit storage, fragment-order g): the
+  // lane holds, per register quad q, the (value, gate) pairs of output channels 4q + 2*half + {0, 1}
+  // of the block's 16; one lane^32 exchange per two quads leaves each lane with the 8 consecutive
+  // channels of one 16-byte granule (half 0: channels 0..7, half 1: 8..15), so a wavefront's store is
+  // one contiguous KiB of the fragment-order buffer instead of four 4-byte pieces per lane.  The
+  // GELU is the polynomial of the register-resident kernels.  Called by every lane of the wavefront
+  // (the exchange needs them all); rows past the end are not stored.
+  static constexpr bool kBlock32 = FRAG && sizeof(T) == 2;
+  __device__ __forceinline__ void block32(int64_t m, bool mvalid, int n0, const f32x16_t& acc, int half) const {
+    const int j0 = n0 >> 1;  // first of the block's 16 output channels
+    unsigned d[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int j = j0 + 4 * q + 2 * half;
+      float bv0 = 0.f, bv1 = 0.f, bg0 = 0.f, bg1 = 0.f;
+      if (b1) {  // two adjacent 16-bit values per load (j is even, the vector 4-byte aligned)
+        const unsigned wv = *reinterpret_cast<const unsigned*>(b1 + j), wg = *reinterpret_cast<const unsigned*>(b1 + inner + j);
+        bv0 = __uint_as_float(wv << 16); bv1 = __uint_as_float(wv & 0xffff0000u);
+        bg0 = __uint_as_float(wg << 16); bg1 = __uint_as_float(wg & 0xffff0000u);
+      }
+      const float a0 = (acc[4 * q + 0] + bv0) * gelu_poly(acc[4 * q + 1] + bg0);
+      const float a1 = (acc[4 * q + 2] + bv1) * gelu_poly(acc[4 * q + 3] + bg1);
+      d[q] = (unsigned)float_to_bf16_bits(a0) | ((unsigned)float_to_bf16_bits(a1) << 16);
+    }
+    // lanes 32..63 of the first operand change places with lanes 0..31 of the second
+    const auto x = __builtin_amdgcn_permlane32_swap(d[0], d[2], false, false);
+    const auto y = __builtin_amdgcn_permlane32_swap(d[1], d[3], false, false);
+    if (mvalid) {
+      u32x4_t o;
+      o.x = x[0]; o.y = x[1]; o.z = y[0]; o.w = y[1];
+      *reinterpret_cast<u32x4_t*>(reinterpret_cast<unsigned short*>(g) + act_offset(m, j0 + 8 * half, (int)ld)) = o;
+    }
+  }
   __device__ __forceinline__ void operator()(int64_t m, int n0, const float (&v)[4]) const {
     const int j = n0 >> 1;
     const float a0 = (v[0] + param_or(b1, j, 0.f)) * gelu_erf(v[1] + param_or(b1, inner + j, 0.f));

@@ -63,4 +63,21 @@ __device__ __forceinline__ float gelu_erf(float u) {
   return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f));
 }
 
+// Coefficients of Phi(x) - 0.5 = xc * R(xc^2), xc = clamp(x, -4.2, 4.2), R of degree 8 (minimax fit of
+// erf(x / sqrt 2) / x on [0, 4.2], |erf error| <= 2.2e-5 everywhere, coefficients pre-halved).
+constexpr float kGeluClamp = 4.2f;
+constexpr int kGeluDeg = 8;
+__device__ constexpr float kGeluC[kGeluDeg + 1] = {
+    0.5f * 0.7978148460388184f,     0.5f * -0.1327207386493683f,    0.5f * 0.019660256803035736f,
+    0.5f * -0.0022282942663878202f, 0.5f * 0.00018914842803496867f, 0.5f * -1.1521495252964087e-05f,
+    0.5f * 4.6873191195118125e-07f, 0.5f * -1.1266531707576632e-08f, 0.5f * 1.199598614887165e-10f};
+// GELU(x) = x * Phi(x) from that polynomial: 13 full-rate instructions, no transcendental ones
+__device__ __forceinline__ float gelu_poly(float x) {
+  const float xc = __builtin_amdgcn_fmed3f(x, -kGeluClamp, kGeluClamp), t = xc * xc;
+  float p = fmaf(kGeluC[kGeluDeg], t, kGeluC[kGeluDeg - 1]);
+#pragma unroll
+  for (int k = kGeluDeg - 2; k >= 0; --k) p = fmaf(p, t, kGeluC[k]);
+  return x * fmaf(p, xc, 0.5f);
+}
+
 }  // namespace si
