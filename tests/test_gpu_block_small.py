@@ -295,6 +295,15 @@ def test_null_optional_parameters_mean_identity(case):
         assert e["max_abs"] <= BF16_MAX_ABS and e["rel_l2"] <= BF16_REL_L2
 
 
+def test_wide_temporal_block_one_window_of_1953_tokens_bf16():
+    """C = 1280 on one window of 3 x 651 = 1953 tokens (close to a cfg5 window): every tile shape the
+    staged path picks at that size, with a last row tile of 33 tokens (one whole block and one token)."""
+    spec = tiny_spec(wl.TEMPORAL, B=1, C=1280, F=3, H=1, W=651, heads=20, dim_head=64, groups=32, pe=True, dtype="bf16")
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.02)
+    _check(spec, x, w, None, 651)
+
+
 def test_peaky_softmax_bf16():
     """Queries and keys scaled up so that the softmax is far from uniform."""
     spec = tiny_spec(wl.SPATIAL, B=1, C=64, F=2, H=10, W=10, heads=2, dim_head=32, groups=8, M=7, Cc=16, dtype="bf16")
