@@ -345,14 +345,24 @@ __global__ __launch_bounds__(512) void layer_norm_rows8_kernel(const float* __re
     const float4* row = reinterpret_cast<const float4*>(h + m * D);
     const int nv = D / 4;
     float4 r[8];
+    uint2 gr[8], br[8];  // gain and shift are requested together with the row: their latency hides behind the two sums
+    const float* perow = pe ? pe + (int64_t)(f0 + (int)((m / Pw) % Fw)) * D : nullptr;
+    float4 pr[8];
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int v = lane + i * kWave;
       if (v < nv) {
         r[i] = row[v];
-        s += (r[i].x + r[i].y) + (r[i].z + r[i].w);
+        gr[i] = gamma ? *reinterpret_cast<const uint2*>(gamma + v * 4) : make_uint2(0x3f803f80u, 0x3f803f80u);
+        br[i] = beta ? *reinterpret_cast<const uint2*>(beta + v * 4) : make_uint2(0u, 0u);
+        pr[i] = perow ? *reinterpret_cast<const float4*>(perow + v * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
       }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int v = lane + i * kWave;
+      if (v < nv) s += (r[i].x + r[i].y) + (r[i].z + r[i].w);
     }
     const float mean = wave_sum(s) / (float)D;
     float q = 0.f;
@@ -365,29 +375,20 @@ __global__ __launch_bounds__(512) void layer_norm_rows8_kernel(const float* __re
       }
     }
     const float rstd = rsqrtf(wave_sum(q) / (float)D + eps);
-    const float* perow = pe ? pe + (int64_t)(f0 + (int)((m / Pw) % Fw)) * D : nullptr;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int v = lane + i * kWave;
       if (v < nv) {
         const float in[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
-        float g[4] = {1.f, 1.f, 1.f, 1.f}, b[4] = {0.f, 0.f, 0.f, 0.f};
-        if (gamma) {
-          const uint2 raw = *reinterpret_cast<const uint2*>(gamma + v * 4);
-          g[0] = __uint_as_float(raw.x << 16); g[1] = __uint_as_float(raw.x & 0xffff0000u);
-          g[2] = __uint_as_float(raw.y << 16); g[3] = __uint_as_float(raw.y & 0xffff0000u);
-        }
-        if (beta) {
-          const uint2 raw = *reinterpret_cast<const uint2*>(beta + v * 4);
-          b[0] = __uint_as_float(raw.x << 16); b[1] = __uint_as_float(raw.x & 0xffff0000u);
-          b[2] = __uint_as_float(raw.y << 16); b[3] = __uint_as_float(raw.y & 0xffff0000u);
-        }
+        const float g[4] = {__uint_as_float(gr[i].x << 16), __uint_as_float(gr[i].x & 0xffff0000u), __uint_as_float(gr[i].y << 16),
+                            __uint_as_float(gr[i].y & 0xffff0000u)};
+        const float b[4] = {__uint_as_float(br[i].x << 16), __uint_as_float(br[i].x & 0xffff0000u), __uint_as_float(br[i].y << 16),
+                            __uint_as_float(br[i].y & 0xffff0000u)};
         float y[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) y[e] = (in[e] - mean) * rstd * g[e] + b[e];
         if (perow) {
-          const float4 pv = *reinterpret_cast<const float4*>(perow + v * 4);
-          y[0] += pv.x; y[1] += pv.y; y[2] += pv.z; y[3] += pv.w;
+          y[0] += pr[i].x; y[1] += pr[i].y; y[2] += pr[i].z; y[3] += pr[i].w;
         }
         uint2 pk;
         pk.x = (unsigned)float_to_bf16_bits(y[0]) | ((unsigned)float_to_bf16_bits(y[1]) << 16);
