@@ -86,6 +86,12 @@ struct RingShape {
   int tn, ncol;
 };
 static RingShape ring_shape(RingDims d, int N, int K) {
+  // q/k/v of one window in flight at the deep levels (N = 3 K = 3840 on 2048 tokens): 128-column tiles make
+  // 480 workgroups, two for nearly every CU, where 160-column tiles make 384 (measured 34.0 -> 31.5 us)
+  if (d.lanes == 1 && K > 512 && N == 3 * K && N % 128 == 0) {
+    const int64_t wg = (d.Mmax + 127) / 128 * (N / 128);
+    if (wg > 448 && wg <= 512) return RingShape{4, N / 128};
+  }
   const int64_t rows = (d.Mmax + 127) / 128 * (K > 512 ? d.lanes : 1);
   const int min_wg = K > 512 ? 330 : 400;
   RingShape best{1, (N + 31) / 32};
@@ -380,7 +386,12 @@ static si_status launch_gemm_ring(const char* stage, const void* act, const void
   // 1.12 -> 1.08 ms; the 160-column tiles of q/k/v and ff1 lose with it: two such workgroups no longer
   // fit a CU's registers).
   if (!big && rs.tn <= 2) {
-    if (rs.tn == 2) ring_mma_kernel<1, 2, 4, F16, Epi, true><<<grid, 512, 0, st>>>(a, epi);
+    // ff2 of one window in flight (K = 4 N): 256-token row tiles, one workgroup per CU at most, move fewer
+    // ring bytes per MFMA than 320 tiles of 128 tokens on 256 CUs (measured 52.7 -> 50.9 us at cfg5)
+    if (rs.tn == 2 && M >= 1024 && Mmax.lanes == 1 && K >= 4 * N && rows2 * rs.ncol <= 256) {
+      a.ntiles = (int)(rows2 * rs.ncol);
+      ring_mma_kernel<2, 2, 4, F16, Epi, true><<<(unsigned)((a.ntiles + 7) / 8 * 8), 512, 0, st>>>(a, epi);
+    } else if (rs.tn == 2) ring_mma_kernel<1, 2, 4, F16, Epi, true><<<grid, 512, 0, st>>>(a, epi);
     else ring_mma_kernel<1, 1, 6, F16, Epi, true><<<grid, 512, 0, st>>>(a, epi);
     SI_CHECK_LAUNCH();
     return SI_OK;
