@@ -115,10 +115,16 @@ __global__ __launch_bounds__(WS ? 512 : 256, (WS && TM * TN > 2) ? 1 : 2) void r
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
     tok[j] = m0 + (wave * TM + j) * 32 + trow;
-    const int p = (int)(tok[j] % P);
-    img0[j] = (tok[j] / P) * ((int64_t)a.Hi * a.Wi);
-    py[j] = tok[j] < a.M ? p / a.W : -100000;  // far outside: no tap is ever inside
-    px[j] = p % a.W;
+    if (P == 1 && a.Hi == 1 && a.Wi == 1) {  // a GEMM: one-pixel images, token m reads source token m (no 64-bit divisions)
+      img0[j] = tok[j];
+      py[j] = tok[j] < a.M ? 0 : -100000;
+      px[j] = 0;
+    } else {
+      const int p = (int)(tok[j] % P);
+      img0[j] = (tok[j] / P) * ((int64_t)a.Hi * a.Wi);
+      py[j] = tok[j] < a.M ? p / a.W : -100000;  // far outside: no tap is ever inside
+      px[j] = p % a.W;
+    }
   }
   const unsigned ring_lds = (unsigned)(size_t)(__attribute__((address_space(3))) void*)ring;
   const char* wtile = a.wf + (int64_t)col * nkt * (WFR * 1024);
