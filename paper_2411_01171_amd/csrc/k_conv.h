@@ -347,7 +347,7 @@ struct EpiConvEmb {
   const float* e;
   int64_t tokens_per_batch;
   __device__ __forceinline__ void operator()(int64_t m, int n0, const float (&v)[4]) const {
-    const float* er = e ? e + (m / tokens_per_batch) * ld + n0 : nullptr;
+    const float* er = e ? e + (int64_t)((int)m / (int)tokens_per_batch) * ld + n0 : nullptr;
     typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
     f16x4_t o;
 #pragma unroll
@@ -367,7 +367,7 @@ struct EpiConvEmbFrag {
   const float* e;
   int64_t tokens_per_batch;
   __device__ __forceinline__ void operator()(int64_t m, int n0, const float (&v)[4]) const {
-    const float* er = e ? e + (m / tokens_per_batch) * C + n0 : nullptr;
+    const float* er = e ? e + (int64_t)((int)m / (int)tokens_per_batch) * C + n0 : nullptr;
     typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
     f16x4_t o;
 #pragma unroll
@@ -388,9 +388,10 @@ struct EpiSliceOutRows {
   __device__ __forceinline__ void operator()(int64_t, int, const float (&)[4]) const {}
   __device__ __forceinline__ void rows8(int64_t m, int n, const float (&v)[8], int64_t M) const {
     const float bn = param_or(bias, n, 0.f);
-    const int pl = (int)(m % w.Pw);
-    const int64_t bf = m / w.Pw;
-    const int64_t off = (((bf / w.Fw) * w.C + n) * w.F + (w.f0 + (int)(bf % w.Fw))) * w.P + w.p0 + pl;
+    const int mi = (int)m;  // window tokens fit 31 bits: 32-bit divisions
+    const int pl = mi % w.Pw;
+    const int64_t bf = mi / w.Pw;
+    const int64_t off = ((((int64_t)((int)bf / w.Fw)) * w.C + n) * w.F + (w.f0 + (int)bf % w.Fw)) * w.P + w.p0 + pl;
     if (pl + 7 < w.Pw && m + 7 < M && ((w.P | w.p0 | pl) & 7) == 0) {
       const uint4 raw = *reinterpret_cast<const uint4*>(x + off);
       const unsigned xw[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -407,9 +408,9 @@ struct EpiSliceOutRows {
       for (int t = 0; t < 8; ++t) {
         const int64_t mt = m + t;
         if (mt >= M) break;
-        const int plt = (int)(mt % w.Pw);
-        const int64_t bft = mt / w.Pw;
-        const int64_t o2 = (((bft / w.Fw) * w.C + n) * w.F + (w.f0 + (int)(bft % w.Fw))) * w.P + w.p0 + plt;
+        const int plt = (int)mt % w.Pw;
+        const int64_t bft = (int)mt / w.Pw;
+        const int64_t o2 = ((((int64_t)((int)bft / w.Fw)) * w.C + n) * w.F + (w.f0 + (int)bft % w.Fw)) * w.P + w.p0 + plt;
         out[o2] = from_float<bf16>(to_float(x[o2]) + (v[t] + bn));
       }
     }
@@ -426,9 +427,10 @@ struct EpiStoreRows {
   __device__ __forceinline__ void operator()(int64_t, int, const float (&)[4]) const {}
   __device__ __forceinline__ void rows8(int64_t m, int n, const float (&v)[8], int64_t M) const {
     const float bn = param_or(bias, n, 0.f);
-    const int pl = (int)(m % w.Pw);
-    const int64_t bf = m / w.Pw;
-    const int64_t off = (((bf / w.Fw) * w.C + n) * w.F + (w.f0 + (int)(bf % w.Fw))) * w.P + w.p0 + pl;
+    const int mi = (int)m;  // window tokens fit 31 bits: 32-bit divisions
+    const int pl = mi % w.Pw;
+    const int64_t bf = mi / w.Pw;
+    const int64_t off = ((((int64_t)((int)bf / w.Fw)) * w.C + n) * w.F + (w.f0 + (int)bf % w.Fw)) * w.P + w.p0 + pl;
     if (pl + 7 < w.Pw && m + 7 < M && ((w.P | w.p0 | pl) & 7) == 0) {
       unsigned ow[4];
 #pragma unroll
@@ -440,9 +442,9 @@ struct EpiStoreRows {
       for (int t = 0; t < 8; ++t) {
         const int64_t mt = m + t;
         if (mt >= M) break;
-        const int plt = (int)(mt % w.Pw);
-        const int64_t bft = mt / w.Pw;
-        out[(((bft / w.Fw) * w.C + n) * w.F + (w.f0 + (int)(bft % w.Fw))) * w.P + w.p0 + plt] = from_float<bf16>(v[t] + bn);
+        const int plt = (int)mt % w.Pw;
+        const int64_t bft = (int)mt / w.Pw;
+        out[((((int64_t)((int)bft / w.Fw)) * w.C + n) * w.F + (w.f0 + (int)bft % w.Fw)) * w.P + w.p0 + plt] = from_float<bf16>(v[t] + bn);
       }
     }
   }

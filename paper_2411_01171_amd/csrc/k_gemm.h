@@ -179,8 +179,9 @@ struct EpiSliceOut {
   const T* bias;
   Window w;
   __device__ __forceinline__ void operator()(int64_t m, int n0, const float (&v)[4]) const {
-    const int pl = (int)(m % w.Pw);
-    const int bf = (int)(m / w.Pw);
+    const int mi = (int)m;  // window tokens fit 31 bits: 32-bit divisions
+    const int pl = mi % w.Pw;
+    const int bf = mi / w.Pw;
     const int fl = bf % w.Fw, b = bf / w.Fw;
     const int64_t cs = (int64_t)w.F * w.P;
     const int64_t off = (((int64_t)b * w.C + n0) * w.F + (w.f0 + fl)) * w.P + w.p0 + pl;
