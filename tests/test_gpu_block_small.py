@@ -304,6 +304,22 @@ def test_wide_temporal_block_one_window_of_1953_tokens_bf16():
     _check(spec, x, w, None, 651)
 
 
+@pytest.mark.parametrize("kind", ["temporal", "spatial"])
+@pytest.mark.parametrize("C,heads", [(32, 1), (96, 3)])
+def test_short_and_odd_k_loops_bf16(kind, C, heads):
+    """C = D = 32 and 96 on the staged path: contractions of one and of three 32-channel k-tiles (the
+    wavefront-specialised GEMM's prologue-only and odd-count cases), windows with ragged row tiles."""
+    if kind == "temporal":
+        spec = tiny_spec(wl.TEMPORAL, B=2, C=C, F=5, H=6, W=11, heads=heads, dim_head=32, groups=8, pe=True, dtype="bf16")
+        ctx, sl = None, 40
+    else:
+        spec = tiny_spec(wl.SPATIAL, B=2, C=C, F=3, H=6, W=11, heads=heads, dim_head=32, groups=8, M=5, Cc=16, dtype="bf16")
+        ctx, sl = wl.make_context(spec), 2
+    x = wl.make_x(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, ctx, sl)
+
+
 def test_peaky_softmax_bf16():
     """Queries and keys scaled up so that the softmax is far from uniform."""
     spec = tiny_spec(wl.SPATIAL, B=1, C=64, F=2, H=10, W=10, heads=2, dim_head=32, groups=8, M=7, Cc=16, dtype="bf16")
