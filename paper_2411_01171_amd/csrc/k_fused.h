@@ -454,7 +454,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const unsigned pipe_voff = Pipe::pipe_voff(lane, wave, pitch);
   const int pipe_wave = __builtin_amdgcn_readfirstlane(wave);
   // the workgroup's context sub-chunks (all of its tokens belong to one batch entry)
-  const int ctx_sub = CROSS ? a.ctx_sub0 + kCrossSub * (int)(((int64_t)blockIdx.x * 128) / a.tokens_per_batch) : 0;
+  const int ctx_sub = CROSS ? a.ctx_sub0 + kCrossSub * ((int)(blockIdx.x * 128) / a.tokens_per_batch) : 0;
   // loads of step G: the stream's sub-chunk G, except that the context sub-chunks are spliced in
   // behind the first kSplice steps
   auto issue_step = [&](int G) {
@@ -755,8 +755,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const bool vec_ok = (w.Pw % 8 == 0) && (w.p0 % 8 == 0) && (w.P % 8 == 0);
   // element-wise path: this lane's token
   const int64_t mm = live ? m : 0;
-  const int64_t off0 = ((int64_t)(mm / w.Pw / w.Fw) * w.C * w.F + (w.f0 + (int)((mm / w.Pw) % w.Fw))) * w.P + w.p0 +
-                       (int)(mm % w.Pw);
+  const int mmi = (int)mm;  // window tokens fit 31 bits: 32-bit divisions
+  const int64_t off0 = ((int64_t)(mmi / w.Pw / w.Fw) * w.C * w.F + (w.f0 + (mmi / w.Pw) % w.Fw)) * w.P + w.p0 + mmi % w.Pw;
   // vector path: lane-op i in {0,1} -> channel row r_i of the block, token group tg_i (8 tokens)
   int vr[2];
   int64_t voff[2];
@@ -768,8 +768,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int64_t m8 = (int64_t)blockIdx.x * 128 + wave * 32 + 8 * tg;
     vlive[i] = vec_ok && m8 < a.M;
     const int64_t mq = vlive[i] ? m8 : 0;
-    voff[i] = ((int64_t)(mq / w.Pw / w.Fw) * w.C * w.F + (w.f0 + (int)((mq / w.Pw) % w.Fw))) * w.P + w.p0 + (int)(mq % w.Pw) +
-              (int64_t)vr[i] * cs;
+    const int mqi = (int)mq;
+    voff[i] = ((int64_t)(mqi / w.Pw / w.Fw) * w.C * w.F + (w.f0 + (mqi / w.Pw) % w.Fw)) * w.P + w.p0 + mqi % w.Pw + (int64_t)vr[i] * cs;
   }
   u32x4_t xq[3][2];
   // every wavefront issues both loads (dead lanes read the tensor's first bytes): the step-closing

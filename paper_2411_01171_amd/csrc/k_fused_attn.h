@@ -42,7 +42,7 @@ __device__ __forceinline__ void stage_window(const bf16* __restrict__ x, unsigne
   const int j0 = run * U;
   const int64_t seq = seq_wg + j0;
   if (pair >= pairs || seq >= nseq) return;  // runs never straddle the end: nseq % U == 0 when U > 1
-  const int b = (int)(seq / w.Pw), pl = (int)(seq % w.Pw);
+  const int b = (int)seq / w.Pw, pl = (int)seq % w.Pw;  // sequences of a window fit 31 bits
   const int ng = w.C / w.G;
   const float2* st = t_stats + (b - b_first) * kAttnMaxStats + f * w.G;
   const bf16* xp = x + (((int64_t)b * w.C + cl) * F + f) * w.P + w.p0 + pl;

@@ -79,7 +79,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // SPLIT: row of this lane's token, or (padding column, sequence past the end) a dump row
   const int64_t my_seq = seq_wg + wave * TP + my_pp;
   const bool row_live = tcol < TP * F && my_seq < nseq;
-  const int64_t my_row = row_live ? ((my_seq / w.Pw) * F + my_f) * w.Pw + my_seq % w.Pw : 0;
+  const int my_si = (int)my_seq;  // sequences of a window fit 31 bits: 32-bit divisions throughout this kernel
+  const int64_t my_row = row_live ? ((int64_t)(my_si / w.Pw) * F + my_f) * w.Pw + my_si % w.Pw : 0;
 
   // ---- weight stream (see WeightPipe): sub-chunks 0 and 1 now, sub-chunk 2 once the x tile has left LDS
   using Pipe = WeightPipe<SUB>;
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   Pipe::issue(a.stream, ring[0], 1, TOTAL_SUB, pitch, pipe_voff, pipe_wave);
 
   // ---- tables; the staged tile starts as zeros (padding rows and columns stay zero)
-  const int b_first = (int)(seq_wg / w.Pw);
+  const int b_first = (int)seq_wg / w.Pw;
   for (int i = tid; i < D; i += 256) {
     t_gng[i] = param_or(a.gn_g, i, 1.f);
     t_gnb[i] = param_or(a.gn_b, i, 0.f);
@@ -598,7 +599,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int64_t seq = seq_wg + 4 * k;
     plive[i] = vec_ok && id < pieces && seq < nseq;
     const int64_t sq = plive[i] ? seq : 0;
-    const int b = (int)(sq / w.Pw), pl = (int)(sq % w.Pw);
+    const int b = (int)sq / w.Pw, pl = (int)sq % w.Pw;
     poff[i] = plive[i] ? (((int64_t)b * w.C + r) * F + f) * w.P + w.p0 + pl : 0;
     pidx[i] = (r < 32 ? r : 0) * 1024 + f * NPOS + 4 * k;
   }
@@ -657,7 +658,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const int j = id % NPOS, f = (id / NPOS) % F, r = id / (NPOS * F);                           \
         const int64_t seq = seq_wg + j;                                                              \
         if (seq < nseq) {                                                                            \
-          const int64_t off = (((int64_t)(seq / w.Pw) * w.C + 32 * (nb) + r) * F + f) * w.P + w.p0 + (seq % w.Pw); \
+          const int64_t off = (((int64_t)((int)seq / w.Pw) * w.C + 32 * (nb) + r) * F + f) * w.P + w.p0 + ((int)seq % w.Pw); \
           a.out[off].v = float_to_bf16_bits(bf16_bits_to_float(a.x[off].v) + patch[(nb) % 2][r][f * NPOS + j]); \
         }                                                                                            \
       }                                                                                              \

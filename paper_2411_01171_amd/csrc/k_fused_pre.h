@@ -42,8 +42,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int r = lane % 32, g = lane / 32;
   const Window& w = a.win;
   const int64_t m0 = (int64_t)blockIdx.x * 128;
-  const int seq = (int)(m0 / w.Pw), b = seq / w.Fw, f = w.f0 + seq % w.Fw;
-  const int key0 = (int)(m0 % w.Pw) + wave * 32;  // first position of this wavefront inside its frame
+  const int seq = (int)m0 / w.Pw, b = seq / w.Fw, f = w.f0 + seq % w.Fw;  // window tokens fit 31 bits
+  const int key0 = (int)m0 % w.Pw + wave * 32;  // first position of this wavefront inside its frame
 
   {  // GroupNorm of this frame as one multiply-add per channel, and the other per-channel tables
     const int ng = w.C / w.G;
