@@ -72,6 +72,27 @@ def test_spatial_head_dim_64_bf16(hw, M):
     _check(spec, x, w, ctx, 1)
 
 
+@pytest.mark.parametrize("hw,slice_len", [((16, 32), 1), ((24, 32), 2), ((32, 20), 1)])
+def test_spatial_head_dim_64_whole_key_stages_bf16(hw, slice_len):
+    """512, 768 (windows of two frames) and 640 positions: the matrix-core attention kernel runs 8, 12 and
+    10 whole key stages (even and odd counts of its two-stage loop) and 4 to 6 whole query tiles per head."""
+    spec = tiny_spec(wl.SPATIAL, B=1, C=128, F=2, H=hw[0], W=hw[1], heads=2, dim_head=64, groups=8, M=9, Cc=16,
+                     dtype="bf16")
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.05)
+    _check(spec, x, w, ctx, slice_len)
+
+
+def test_spatial_head_dim_64_whole_key_stages_peaky_bf16():
+    """As above with sharpened scores: the reference maximum of the online softmax moves along the 8 stages."""
+    spec = tiny_spec(wl.SPATIAL, B=1, C=128, F=1, H=16, W=32, heads=2, dim_head=64, groups=8, M=9, Cc=16, dtype="bf16")
+    x, ctx = wl.make_x(spec), wl.make_context(spec)
+    w = wl.make_weights(spec, randomize_affine=True, matrix_std=0.02)
+    for k in ("wq", "wk"):
+        w[k] = wl.round_to_storage(w[k] * 8.0, "bf16")
+    _check(spec, x, w, ctx, 1)
+
+
 @pytest.mark.parametrize("kind,slice_len", [("temporal", 37), ("spatial", 2)])
 def test_fragment_order_path_with_alu_attention_bf16(kind, slice_len):
     """C = D = 128 with head dimension 32: the projections and the FFN run on the ring kernel over
