@@ -92,6 +92,14 @@ static RingShape ring_shape(RingDims d, int N, int K) {
     const int64_t wg = (d.Mmax + 127) / 128 * (N / 128);
     if (wg > 448 && wg <= 512) return RingShape{4, N / 128};
   }
+  // one window in flight and a projection whose 64-column tiles would give some CUs two workgroups and most of
+  // them one (N = 1280 on 2048 tokens: 320): 96-column tiles make it one workgroup for nearly every CU (224)
+  if (d.lanes == 1 && K > 512 && N % 32 == 0) {
+    const int64_t rows128 = (d.Mmax + 127) / 128;
+    const int nc3 = (N + 95) / 96;
+    if (rows128 * ((N + 63) / 64) > 256 && rows128 * nc3 <= 256 && rows128 * nc3 > 160 && (int64_t)nc3 * 96 * 10 <= (int64_t)N * 11)
+      return RingShape{3, nc3};
+  }
   const int64_t rows = (d.Mmax + 127) / 128 * (K > 512 ? d.lanes : 1);
   const int min_wg = K > 512 ? 330 : 400;
   RingShape best{1, (N + 31) / 32};
@@ -385,13 +393,14 @@ static si_status launch_gemm_ring(const char* stage, const void* act, const void
   // another's MFMAs (measured per step: cfg3 1.68 -> 1.59 ms, cfg5 spatial 1.33 -> 1.29 ms, cfg5 temporal
   // 1.12 -> 1.08 ms; the 160-column tiles of q/k/v and ff1 lose with it: two such workgroups no longer
   // fit a CU's registers).
-  if (!big && rs.tn <= 2) {
+  if (!big && rs.tn <= 3) {
     // ff2 of one window in flight (K = 4 N): 256-token row tiles, one workgroup per CU at most, move fewer
     // ring bytes per MFMA than 320 tiles of 128 tokens on 256 CUs (measured 52.7 -> 50.9 us at cfg5)
     if (rs.tn == 2 && M >= 1024 && Mmax.lanes == 1 && K >= 4 * N && rows2 * rs.ncol <= 256) {
       a.ntiles = (int)(rows2 * rs.ncol);
       ring_mma_kernel<2, 2, 4, F16, Epi, true><<<(unsigned)((a.ntiles + 7) / 8 * 8), 512, 0, st>>>(a, epi);
-    } else if (rs.tn == 2) ring_mma_kernel<1, 2, 4, F16, Epi, true><<<grid, 512, 0, st>>>(a, epi);
+    } else if (rs.tn == 3) ring_mma_kernel<1, 3, 4, F16, Epi, true><<<grid, 512, 0, st>>>(a, epi);
+    else if (rs.tn == 2) ring_mma_kernel<1, 2, 4, F16, Epi, true><<<grid, 512, 0, st>>>(a, epi);
     else ring_mma_kernel<1, 1, 6, F16, Epi, true><<<grid, 512, 0, st>>>(a, epi);
     SI_CHECK_LAUNCH();
     return SI_OK;
@@ -401,7 +410,7 @@ static si_status launch_gemm_ring(const char* stage, const void* act, const void
     case 10: ring_mma_kernel<1, 5, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
     case 9: ring_mma_kernel<2, 4, 3, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
     case 8: ring_mma_kernel<1, 4, 4, F16, Epi><<<grid, 256, 0, st>>>(a, epi); break;
-    default: return SI_ERR_ARG;  // ring_shape only gives tiles of 1, 2, 4 or 5 column blocks
+    default: return SI_ERR_ARG;  // ring_shape only gives tiles of 1, 2, 3, 4 or 5 column blocks
   }
   SI_CHECK_LAUNCH();
   return SI_OK;
